@@ -1,0 +1,201 @@
+"""ctypes front end of the CPU oracle (oracle/vscan_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+benchmark's CPU-baseline leg, never by the product path.  It contains no
+arithmetic of its own beyond chaining the C functions in the paper's order
+(Sec. 4.1: score -> local/global select -> assign -> merge; Sec. 4.2: score ->
+top-k -> compaction); it marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "vscan_oracle.c")
+_LIB = os.path.join(_HERE, "libvscan_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over independent items)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.vso_threads.restype = ctypes.c_int
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().vso_threads())
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _f64p(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with status {rc}")
+
+
+def default_scale(head_dim: int, scale: float = 0.0) -> float:
+    return float(scale) if scale > 0 else 1.0 / math.sqrt(head_dim)
+
+
+def encoder_scores(q, k, has_cls: int, mode: int, domain: int = 0, scale: float = 0.0):
+    """q, k: [B,C,H,S,dh] -> scores [B,C,N] fp64 (Eq. 1-2 / mean attention received)."""
+    q, qp = _f32(q)
+    k, kp = _f32(k)
+    B, C, H, S, dh = q.shape
+    assert k.shape == q.shape
+    N = S - has_cls
+    out = np.empty((B, C, N), dtype=np.float64)
+    rc = _load().vso_encoder_scores(qp, kp, B, C, H, S, dh, int(has_cls), int(mode), int(domain),
+                                    ctypes.c_double(default_scale(dh, scale)), _f64p(out))
+    _check(rc, "encoder_scores")
+    return out
+
+
+def select(s_local, s_global, gh, gw, wr, wc, kl, kg):
+    """scores [B,C,N] -> kept [B, C*(kl+kg)] int32, ascending per image (Eq. 2-3)."""
+    s_local = np.ascontiguousarray(s_local, dtype=np.float64)
+    s_global = np.ascontiguousarray(s_global, dtype=np.float64)
+    B, C, N = s_global.shape
+    assert N == gh * gw and s_local.shape == s_global.shape
+    kept = np.empty((B, C * (kl + kg)), dtype=np.int32)
+    rc = _load().vso_select(_f64p(s_local), _f64p(s_global), B, C, gh, gw, wr, wc, kl, kg,
+                            kept.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "select")
+    return kept
+
+
+def assign(x, kept):
+    """x [B,T,D], kept [B,K] -> slot of every token [B,T] (highest cosine, first on ties)."""
+    x, xp = _f32(x)
+    kept, kp = _i32(kept)
+    B, T, D = x.shape
+    K = kept.shape[1]
+    out = np.empty((B, T), dtype=np.int32)
+    rc = _load().vso_assign(xp, kp, B, T, D, K, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "assign")
+    return out
+
+
+def merge(x, kept, assign_):
+    """Eq. 4 under a given assignment -> (merged [B,K,D] fp64, counts [B,K])."""
+    x, xp = _f32(x)
+    kept, kp = _i32(kept)
+    assign_, ap = _i32(assign_)
+    B, T, D = x.shape
+    K = kept.shape[1]
+    merged = np.empty((B, K, D), dtype=np.float64)
+    counts = np.empty((B, K), dtype=np.int32)
+    rc = _load().vso_merge(xp, kp, ap, B, T, D, K, _f64p(merged),
+                           counts.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "merge")
+    return merged, counts
+
+
+def cos_pairs(x, u, s):
+    """Cosine similarity of rows u[i], s[i] of x viewed as [rows, D] (flat row indices)."""
+    x, xp = _f32(x)
+    D = x.shape[-1]
+    u = np.ascontiguousarray(u, dtype=np.int64)
+    s = np.ascontiguousarray(s, dtype=np.int64)
+    out = np.empty(u.shape, dtype=np.float64)
+    rc = _load().vso_cos_pairs(xp, D, ctypes.c_int64(u.size),
+                               u.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                               s.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _f64p(out))
+    _check(rc, "cos_pairs")
+    return out
+
+
+def llm_scores(q, k, vis_start, V, domain: int = 0, scale: float = 0.0):
+    """q [B,Hq,Tq,dh], k [B,Hkv,S,dh] -> scores [B,V] fp64 (Eq. 5, head/query mean)."""
+    q, qp = _f32(q)
+    k, kp = _f32(k)
+    B, Hq, Tq, dh = q.shape
+    _, Hkv, S, _ = k.shape
+    out = np.empty((B, V), dtype=np.float64)
+    rc = _load().vso_llm_scores(qp, kp, B, Hq, Hkv, Tq, S, dh, vis_start, V, int(domain),
+                                ctypes.c_double(default_scale(dh, scale)), _f64p(out))
+    _check(rc, "llm_scores")
+    return out
+
+
+def topk(scores, keep):
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    B, V = scores.shape
+    kept = np.empty((B, keep), dtype=np.int32)
+    rc = _load().vso_topk(_f64p(scores), B, V, keep,
+                          kept.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "topk")
+    return kept
+
+
+def compact(t, kept, vis_start, V):
+    """t [B,G,S,W] (or [B,S,W]) -> [B,G,S_out,W]: prefix ++ kept visual ++ tail rows."""
+    t, tp = _f32(t)
+    squeeze = t.ndim == 3
+    if squeeze:
+        t = t[:, None]
+    kept, kp = _i32(kept)
+    B, G, S, W = t.shape
+    keep = kept.shape[1]
+    out = np.empty((B, G, S - V + keep, W), dtype=np.float32)
+    rc = _load().vso_compact(tp, kp, B, G, S, W, vis_start, V, keep,
+                             out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    _check(rc, "compact")
+    return out[:, 0] if squeeze else out
+
+
+def encoder_reduce(shape, q, k, x, q_local=None, k_local=None) -> Dict[str, np.ndarray]:
+    """Sec. 4.1 end to end for an `EncoderShape`-like object (duck-typed)."""
+    s_global = encoder_scores(q, k, shape.has_cls, shape.score_mode, shape.softmax_domain,
+                              shape.scale)
+    if q_local is not None:
+        s_local = encoder_scores(q_local, k_local, shape.has_cls, shape.score_mode,
+                                 shape.softmax_domain, shape.scale)
+    else:
+        s_local = s_global
+    kept = select(s_local, s_global, shape.grid_h, shape.grid_w, shape.win_rows, shape.win_cols,
+                  shape.keep_local, shape.keep_global)
+    a = assign(x, kept)
+    merged, counts = merge(x, kept, a)
+    return {"scores": s_global.reshape(s_global.shape[0], -1),
+            "scores_local": s_local.reshape(s_local.shape[0], -1),
+            "kept": kept, "assign": a, "merged": merged, "counts": counts}
+
+
+def llm_prune(shape, q, k, v, hidden) -> Dict[str, np.ndarray]:
+    """Sec. 4.2 end to end for an `LlmShape`-like object (duck-typed)."""
+    s = llm_scores(q, k, shape.vis_start, shape.vis_len, shape.softmax_domain, shape.scale)
+    kept = topk(s, shape.keep)
+    return {"scores": s, "kept": kept,
+            "k": compact(k, kept, shape.vis_start, shape.vis_len),
+            "v": compact(v, kept, shape.vis_start, shape.vis_len),
+            "hidden": compact(hidden, kept, shape.vis_start, shape.vis_len)}
