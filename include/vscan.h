@@ -1,0 +1,186 @@
+/*
+ * vscan.h - C ABI of the MI355X (gfx950) implementation of VScan's two-stage
+ * visual token reduction (arXiv 2505.22654).
+ *
+ * Stage 1 (Sec. 4.1): score the visual encoder's tokens by attention, keep a
+ * local top-k per window plus a global top-k, assign every dropped token to its
+ * most cosine-similar kept token and average each group (Eq. 1-4).
+ * Stage 2 (Sec. 4.2): at a middle LLM layer score the visual tokens by the
+ * attention of the last instruction token(s), keep the top-k and compact hidden
+ * states and K/V so pruned tokens never reach the cache (Eq. 5, "Remarks on KV
+ * Cache").
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  Tensors are
+ *     contiguous, row-major, 16-byte aligned.  Descriptors are HOST structs.
+ *   - The entry points keep no state between calls and allocate no device
+ *     memory: scratch comes in through `workspace` (size from the matching
+ *     *_workspace_size call).  The only process-wide state is the optional
+ *     measurement aid at the end of this header.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without synchronising.  Calls that
+ *     share a workspace must be ordered on one stream.
+ *   - Return value: VSCAN_OK or a negative error.  On error nothing is enqueued
+ *     and no output is touched.  No exceptions, no abort.
+ *   - Ties are broken towards the lowest index; index outputs are ascending.
+ *   - Floating-point inputs must be finite (NaN ordering is unspecified).
+ */
+#ifndef VSCAN_H
+#define VSCAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VSCAN_VERSION 0x00010000u
+
+enum { VSCAN_F32 = 0, VSCAN_BF16 = 1 };
+
+/* Which attention row scores the encoder tokens (Sec. 4.1 "Global Scan"):
+ * the [CLS] query row (Eq. 1), or, for encoders without [CLS], the mean
+ * attention each token receives from all visual query rows. */
+enum { VSCAN_SCORE_CLS_ROW = 0, VSCAN_SCORE_MEAN_RECEIVED = 1 };
+
+/* Softmax key domain.  VISUAL_ONLY follows Eq. 1 / Eq. 5 as written (K_V holds
+ * visual keys only).  KEYS_ALL normalises over the whole attention row (encoder:
+ * including the [CLS] key; LLM: the causal row of each query) and then takes the
+ * visual slice. */
+enum { VSCAN_KEYS_VISUAL_ONLY = 0, VSCAN_KEYS_ALL = 1 };
+
+enum {
+    VSCAN_OK = 0,
+    VSCAN_ERR_NULL = -1,      /* a required pointer is NULL */
+    VSCAN_ERR_SHAPE = -2,     /* a dimension is non-positive or inconsistent */
+    VSCAN_ERR_BUDGET = -3,    /* a keep budget does not fit */
+    VSCAN_ERR_DTYPE = -4,     /* unknown dtype / mode enum */
+    VSCAN_ERR_ALIGN = -5,     /* a tensor pointer is not 16-byte aligned */
+    VSCAN_ERR_WORKSPACE = -6, /* workspace missing or too small */
+    VSCAN_ERR_HIP = -7,       /* a HIP runtime call failed */
+    VSCAN_ERR_VERSION = -8,   /* struct_size does not match this library */
+    VSCAN_ERR_UNSUPPORTED = -9 /* valid request outside what the kernels cover */
+};
+
+/* ---------------------------------------------------------------------------
+ * Stage 1: vscan_encoder_reduce  (Sec. 4.1, Eq. 1-4)
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    uint32_t struct_size;   /* sizeof(vscan_encoder_desc) */
+    int32_t dtype;          /* of q, k, x, merged: VSCAN_F32 or VSCAN_BF16 */
+    int32_t batch;          /* B images */
+    int32_t n_segments;     /* C crops per image (1 for single-image encoders) */
+    int32_t grid_h, grid_w; /* token grid per segment; N = grid_h * grid_w */
+    int32_t has_cls;        /* 1: q/k have S = N + 1 rows and [CLS] is row 0 */
+    int32_t score_mode;     /* VSCAN_SCORE_* */
+    int32_t softmax_domain; /* VSCAN_KEYS_* */
+    int32_t heads;          /* H */
+    int32_t head_dim;       /* dh, multiple of 8, <= 256 */
+    int32_t feat_dim;       /* D of x, multiple of 8 */
+    int32_t win_rows, win_cols; /* windows per segment along each axis (Eq. 3):
+                                   token (r, c) is in window (r*win_rows/grid_h,
+                                   c*win_cols/grid_w), integer division */
+    int32_t keep_global;    /* |x^g| per segment (Eq. 2) */
+    int32_t keep_local;     /* |x^l| per segment (Eq. 3): floor(keep_local / W) per
+                               window, the remainder is added to keep_global */
+    float scale;            /* logit scale; <= 0 selects 1/sqrt(head_dim) */
+} vscan_encoder_desc;
+
+/* Bytes of workspace vscan_encoder_reduce needs for this descriptor.
+ * `with_local_pair` != 0 sizes for a call that passes q_local / k_local. */
+int vscan_encoder_workspace_size(const vscan_encoder_desc *desc, int with_local_pair,
+                                 size_t *bytes);
+
+/*
+ * q, k        in  [B, C, H, S, dh]  output-layer queries / keys (only the [CLS]
+ *                 query row is read in CLS mode)
+ * q_local,    in  same layout, the shallow-layer pair whose scores drive the
+ * k_local         local scan (Sec. 4.1 "Local Scan", layer l); both NULL = use q, k
+ * x           in  [B, C*N, D]  patch token features (no [CLS] row); cosine
+ *                 similarity and Eq. 4 act on these
+ * kept_idx    out [B, K] int32, K = C*(keep_global+keep_local): image-level token
+ *                 index c*N + r*grid_w + col, ascending
+ * merged      out [B, K, D] in `dtype`: Eq. 4 for every kept token
+ * assign_out  out optional [B, C*N] int32: slot (0..K-1) each token merged into
+ *                 (a kept token reports its own slot)
+ * scores_out  out optional [B, C*N] fp32: the global-scan score S^avg (Eq. 2)
+ */
+int vscan_encoder_reduce(const vscan_encoder_desc *desc, const void *q, const void *k,
+                         const void *q_local, const void *k_local, const void *x,
+                         int32_t *kept_idx, void *merged, int32_t *assign_out,
+                         float *scores_out, void *workspace, size_t workspace_bytes,
+                         void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Stage 2: vscan_llm_prune  (Sec. 4.2, Eq. 5; "Remarks on KV Cache")
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    uint32_t struct_size;   /* sizeof(vscan_llm_desc) */
+    int32_t dtype;          /* of q, k, v, hidden */
+    int32_t batch;          /* B sequences, all of the same layout */
+    int32_t seq_len;        /* S */
+    int32_t vis_start;      /* first visual position */
+    int32_t vis_len;        /* V visual tokens, contiguous */
+    int32_t n_query;        /* Tq scoring queries = the last Tq positions; the paper
+                               uses the last instruction token only (Tq = 1) */
+    int32_t q_heads;        /* Hq */
+    int32_t kv_heads;       /* Hkv, divides Hq; query head h reads kv head h/(Hq/Hkv) */
+    int32_t head_dim;       /* dh, multiple of 8, <= 256 */
+    int32_t hidden;         /* Dh, multiple of 8 */
+    int32_t keep;           /* visual tokens kept per sequence (R2 % of V) */
+    int32_t softmax_domain; /* VSCAN_KEYS_* */
+    int32_t in_place;       /* 1: compact k, v, hidden inside their own buffers */
+    float scale;            /* <= 0 selects 1/sqrt(head_dim) */
+} vscan_llm_desc;
+
+int vscan_llm_workspace_size(const vscan_llm_desc *desc, size_t *bytes);
+
+/*
+ * q           in  [B, Hq, Tq, dh]  layer-k queries of the last Tq positions
+ * k, v        in  [B, Hkv, S, dh]  layer-k keys / values (position-encoded as the
+ *                 attention layer sees them); mutated iff in_place
+ * hidden      in  [B, S, Dh]; mutated iff in_place
+ * kept_idx    out [B, keep] int32, ascending, relative to vis_start
+ * k_out,v_out out [B, Hkv, S_out, dh], hidden_out [B, S_out, Dh],
+ *                 S_out = S - V + keep: rows [0, vis_start) ++ kept visual rows in
+ *                 original order ++ rows [vis_start+V, S).  Must be NULL iff
+ *                 in_place; in place, slab strides stay those of S and rows
+ *                 [S_out, S) of every slab are left unspecified.
+ * scores_out  out optional [B, V] fp32: head- and query-averaged attention
+ */
+int vscan_llm_prune(const vscan_llm_desc *desc, const void *q, void *k, void *v, void *hidden,
+                    int32_t *kept_idx, void *k_out, void *v_out, void *hidden_out,
+                    float *scores_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Measurement aid (not part of the method): per-kernel device time.
+ *
+ * While enabled, every kernel the two entry points launch is bracketed by a pair
+ * of HIP events on its stream.  vscan_profile_read waits for the recorded
+ * events, adds the elapsed times up per kernel name and clears the record.
+ * The switch and the record are process-wide host state; enable it only around
+ * measurement passes (events cost a little launch latency) and do not toggle it
+ * while another thread is inside an entry point.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    char name[32];     /* kernel name, NUL-terminated */
+    int32_t launches;  /* launches recorded since the last read */
+    float total_ms;    /* summed event-to-event device time */
+} vscan_kernel_time;
+
+int vscan_profile_enable(int on);
+/* out: host array of `capacity` entries; *count receives the entries written.
+ * Returns VSCAN_ERR_HIP if an event query fails, VSCAN_ERR_NULL on NULL args. */
+int vscan_profile_read(vscan_kernel_time *out, int capacity, int *count);
+
+/* ---------------------------------------------------------------------------
+ * Misc
+ * ------------------------------------------------------------------------- */
+const char *vscan_status_string(int status);
+uint32_t vscan_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VSCAN_H */

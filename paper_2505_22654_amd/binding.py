@@ -1,0 +1,255 @@
+"""Thin ctypes binding of libvscan.so (include/vscan.h).
+
+Argument marshalling only: every step of the reduction runs in the HIP kernels
+behind the C ABI.  torch is used for device memory and the current stream.
+There is no fallback: if the library is missing the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libvscan.so")
+_lib = None
+
+VSCAN_F32, VSCAN_BF16 = 0, 1
+VSCAN_SCORE_CLS_ROW, VSCAN_SCORE_MEAN_RECEIVED = 0, 1
+VSCAN_KEYS_VISUAL_ONLY, VSCAN_KEYS_ALL = 0, 1
+(VSCAN_OK, VSCAN_ERR_NULL, VSCAN_ERR_SHAPE, VSCAN_ERR_BUDGET, VSCAN_ERR_DTYPE, VSCAN_ERR_ALIGN,
+ VSCAN_ERR_WORKSPACE, VSCAN_ERR_HIP, VSCAN_ERR_VERSION, VSCAN_ERR_UNSUPPORTED) = (
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9)
+
+EXPORTS = ("vscan_encoder_workspace_size", "vscan_encoder_reduce", "vscan_llm_workspace_size",
+           "vscan_llm_prune", "vscan_profile_enable", "vscan_profile_read", "vscan_status_string",
+           "vscan_version")
+
+
+class EncoderDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("batch", ctypes.c_int32), ("n_segments", ctypes.c_int32),
+                ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
+                ("has_cls", ctypes.c_int32), ("score_mode", ctypes.c_int32),
+                ("softmax_domain", ctypes.c_int32), ("heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("feat_dim", ctypes.c_int32),
+                ("win_rows", ctypes.c_int32), ("win_cols", ctypes.c_int32),
+                ("keep_global", ctypes.c_int32), ("keep_local", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+class LlmDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("batch", ctypes.c_int32), ("seq_len", ctypes.c_int32),
+                ("vis_start", ctypes.c_int32), ("vis_len", ctypes.c_int32),
+                ("n_query", ctypes.c_int32), ("q_heads", ctypes.c_int32),
+                ("kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("hidden", ctypes.c_int32), ("keep", ctypes.c_int32),
+                ("softmax_domain", ctypes.c_int32), ("in_place", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+class KernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 32), ("launches", ctypes.c_int32),
+                ("total_ms", ctypes.c_float)]
+
+
+class VscanError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib():
+    """Load libvscan.so; fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2505_22654_amd.build` (no CPU fallback exists)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+        L.vscan_encoder_workspace_size.argtypes = [ctypes.POINTER(EncoderDesc), ctypes.c_int,
+                                                   ctypes.POINTER(ctypes.c_size_t)]
+        L.vscan_encoder_workspace_size.restype = ctypes.c_int
+        L.vscan_encoder_reduce.argtypes = [ctypes.POINTER(EncoderDesc), vp, vp, vp, vp, vp, i32p,
+                                           vp, i32p, f32p, vp, ctypes.c_size_t, vp]
+        L.vscan_encoder_reduce.restype = ctypes.c_int
+        L.vscan_llm_workspace_size.argtypes = [ctypes.POINTER(LlmDesc),
+                                               ctypes.POINTER(ctypes.c_size_t)]
+        L.vscan_llm_workspace_size.restype = ctypes.c_int
+        L.vscan_llm_prune.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, vp, i32p, vp, vp, vp,
+                                      f32p, vp, ctypes.c_size_t, vp]
+        L.vscan_llm_prune.restype = ctypes.c_int
+        L.vscan_profile_enable.argtypes = [ctypes.c_int]
+        L.vscan_profile_enable.restype = ctypes.c_int
+        L.vscan_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int,
+                                         ctypes.POINTER(ctypes.c_int)]
+        L.vscan_profile_read.restype = ctypes.c_int
+        L.vscan_status_string.argtypes = [ctypes.c_int]
+        L.vscan_status_string.restype = ctypes.c_char_p
+        L.vscan_version.restype = ctypes.c_uint32
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().vscan_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().vscan_version())
+
+
+def profile_enable(on: bool) -> None:
+    """Switch per-kernel event timing inside the library on or off."""
+    lib().vscan_profile_enable(int(on))
+
+
+def profile_read() -> Dict[str, Dict[str, float]]:
+    """{kernel name: {"launches": n, "total_ms": t}} since the last read."""
+    buf = (KernelTime * 32)()
+    n = ctypes.c_int(0)
+    rc = lib().vscan_profile_read(buf, 32, ctypes.byref(n))
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_profile_read")
+    return {buf[i].name.decode(): {"launches": int(buf[i].launches),
+                                   "total_ms": float(buf[i].total_ms)} for i in range(n.value)}
+
+
+def _dtype_code(dtype: str) -> int:
+    return {"f32": VSCAN_F32, "bf16": VSCAN_BF16}[dtype]
+
+
+def encoder_desc(shape) -> EncoderDesc:
+    """Descriptor from an `EncoderShape`-like object."""
+    return EncoderDesc(ctypes.sizeof(EncoderDesc), _dtype_code(shape.dtype), shape.batch,
+                       shape.n_segments, shape.grid_h, shape.grid_w, shape.has_cls,
+                       shape.score_mode, shape.softmax_domain, shape.heads, shape.head_dim,
+                       shape.feat_dim, shape.win_rows, shape.win_cols, shape.keep_global,
+                       shape.keep_local, shape.scale)
+
+
+def llm_desc(shape) -> LlmDesc:
+    """Descriptor from an `LlmShape`-like object."""
+    return LlmDesc(ctypes.sizeof(LlmDesc), _dtype_code(shape.dtype), shape.batch, shape.seq_len,
+                   shape.vis_start, shape.vis_len, shape.n_query, shape.q_heads, shape.kv_heads,
+                   shape.head_dim, shape.hidden, shape.keep, shape.softmax_domain, shape.in_place,
+                   shape.scale)
+
+
+def encoder_workspace_size(desc: EncoderDesc, with_local_pair: bool = False) -> int:
+    n = ctypes.c_size_t(0)
+    rc = lib().vscan_encoder_workspace_size(ctypes.byref(desc), int(with_local_pair),
+                                            ctypes.byref(n))
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_encoder_workspace_size")
+    return int(n.value)
+
+
+def llm_workspace_size(desc: LlmDesc) -> int:
+    n = ctypes.c_size_t(0)
+    rc = lib().vscan_llm_workspace_size(ctypes.byref(desc), ctypes.byref(n))
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_llm_workspace_size")
+    return int(n.value)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _torch_dtype(dtype: str):
+    import torch
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+def encoder_reduce(shape, q, k, x, q_local=None, k_local=None, want_assign: bool = False,
+                   want_scores: bool = False, workspace=None, out=None) -> Dict[str, object]:
+    """vscan_encoder_reduce on CUDA tensors q, k [B,C,H,S,dh], x [B,C*N,D].
+
+    Returns kept_idx [B,K] int32 and merged [B,K,D] (plus assign / scores on request).
+    `workspace` (uint8 tensor) and `out` (dict of preallocated outputs) avoid allocation."""
+    import torch
+    desc = encoder_desc(shape)
+    need = encoder_workspace_size(desc, q_local is not None)
+    dev = q.device
+    for t in (q, k, x, q_local, k_local):
+        assert t is None or (t.is_cuda and t.is_contiguous() and t.dtype == _torch_dtype(shape.dtype))
+    B, K, T = shape.batch, shape.keep, shape.tokens_per_image
+    assert tuple(q.shape) == (B, shape.n_segments, shape.heads, shape.rows, shape.head_dim)
+    assert tuple(k.shape) == tuple(q.shape) and tuple(x.shape) == (B, T, shape.feat_dim)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = dict(out) if out else {}
+    if "kept_idx" not in out:
+        out["kept_idx"] = torch.empty((B, K), dtype=torch.int32, device=dev)
+    if "merged" not in out:
+        out["merged"] = torch.empty((B, K, shape.feat_dim), dtype=x.dtype, device=dev)
+    if want_assign and "assign" not in out:
+        out["assign"] = torch.empty((B, T), dtype=torch.int32, device=dev)
+    if want_scores and "scores" not in out:
+        out["scores"] = torch.empty((B, T), dtype=torch.float32, device=dev)
+    rc = lib().vscan_encoder_reduce(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(q_local),
+                                    _ptr(k_local), _ptr(x), _ptr(out["kept_idx"]),
+                                    _ptr(out["merged"]), _ptr(out.get("assign")),
+                                    _ptr(out.get("scores")), _ptr(workspace), workspace.numel(),
+                                    _stream_handle())
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_encoder_reduce")
+    out["workspace"] = workspace
+    return out
+
+
+def llm_prune(shape, q, k, v, hidden, want_scores: bool = False, workspace=None,
+              out=None) -> Dict[str, object]:
+    """vscan_llm_prune on CUDA tensors q [B,Hq,Tq,dh], k, v [B,Hkv,S,dh], hidden [B,S,Dh].
+
+    Out of place it returns k, v, hidden of length S_out; in place (shape.in_place) it
+    mutates the inputs and returns views of their first S_out rows."""
+    import torch
+    desc = llm_desc(shape)
+    need = llm_workspace_size(desc)
+    dev = q.device
+    for t in (q, k, v, hidden):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == _torch_dtype(shape.dtype)
+    B, S, So = shape.batch, shape.seq_len, shape.seq_out
+    assert tuple(q.shape) == (B, shape.q_heads, shape.n_query, shape.head_dim)
+    assert tuple(k.shape) == (B, shape.kv_heads, S, shape.head_dim) and k.shape == v.shape
+    assert tuple(hidden.shape) == (B, S, shape.hidden)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = dict(out) if out else {}
+    if "kept_idx" not in out:
+        out["kept_idx"] = torch.empty((B, shape.keep), dtype=torch.int32, device=dev)
+    if want_scores and "scores" not in out:
+        out["scores"] = torch.empty((B, shape.vis_len), dtype=torch.float32, device=dev)
+    if shape.in_place:
+        ko = vo = ho = None
+    else:
+        ko = out.get("k")
+        vo = out.get("v")
+        ho = out.get("hidden")
+        if ko is None:
+            ko = torch.empty((B, shape.kv_heads, So, shape.head_dim), dtype=k.dtype, device=dev)
+        if vo is None:
+            vo = torch.empty_like(ko)
+        if ho is None:
+            ho = torch.empty((B, So, shape.hidden), dtype=hidden.dtype, device=dev)
+    rc = lib().vscan_llm_prune(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(hidden),
+                               _ptr(out["kept_idx"]), _ptr(ko), _ptr(vo), _ptr(ho),
+                               _ptr(out.get("scores")), _ptr(workspace), workspace.numel(),
+                               _stream_handle())
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_llm_prune")
+    if shape.in_place:
+        out["k"], out["v"], out["hidden"] = k[:, :, :So], v[:, :, :So], hidden[:, :So]
+    else:
+        out["k"], out["v"], out["hidden"] = ko, vo, ho
+    out["workspace"] = workspace
+    return out

@@ -1,0 +1,407 @@
+// C ABI of the VScan reduction library: argument validation, workspace
+// planning and kernel sequencing.  Everything before the first launch is pure
+// host code and never touches the HIP runtime, so descriptor errors are
+// reported identically with or without a device.
+#include "../../include/vscan.h"
+
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "launch.hpp"
+
+namespace {
+
+using namespace vscan;
+
+constexpr size_t kAlign = 256;
+constexpr size_t kLdsBudget = 160 * 1024;
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) & ~(kAlign - 1); }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int elem_bytes(int dtype) { return dtype == VSCAN_BF16 ? 2 : 4; }
+
+struct EncoderPlan {
+    int N, S, BC, T, W, kw, kg, Kseg, K, U;
+    size_t off_head_global, off_head_local, off_lse, off_drop, off_best, off_inv, bytes;
+};
+
+int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
+    if (!d) return VSCAN_ERR_NULL;
+    if (d->struct_size != sizeof(vscan_encoder_desc)) return VSCAN_ERR_VERSION;
+    if (d->dtype != VSCAN_F32 && d->dtype != VSCAN_BF16) return VSCAN_ERR_DTYPE;
+    if (d->score_mode != VSCAN_SCORE_CLS_ROW && d->score_mode != VSCAN_SCORE_MEAN_RECEIVED)
+        return VSCAN_ERR_DTYPE;
+    if (d->softmax_domain != VSCAN_KEYS_VISUAL_ONLY && d->softmax_domain != VSCAN_KEYS_ALL)
+        return VSCAN_ERR_DTYPE;
+    if (d->batch < 0 || d->n_segments < 1 || d->grid_h < 1 || d->grid_w < 1 || d->heads < 1)
+        return VSCAN_ERR_SHAPE;
+    if (d->has_cls != 0 && d->has_cls != 1) return VSCAN_ERR_SHAPE;
+    if (d->score_mode == VSCAN_SCORE_CLS_ROW && !d->has_cls) return VSCAN_ERR_SHAPE;
+    if (d->head_dim < 8 || d->head_dim % 8 || d->head_dim > 256) return VSCAN_ERR_SHAPE;
+    if (d->feat_dim < 8 || d->feat_dim % 8) return VSCAN_ERR_SHAPE;
+    if (d->win_rows < 1 || d->win_cols < 1 || d->win_rows > d->grid_h || d->win_cols > d->grid_w)
+        return VSCAN_ERR_SHAPE;
+    if ((int64_t)d->grid_h * d->grid_w > (1 << 20)) return VSCAN_ERR_SHAPE;
+    if (d->keep_global < 0 || d->keep_local < 0) return VSCAN_ERR_BUDGET;
+    const int es = elem_bytes(d->dtype);
+    p->N = d->grid_h * d->grid_w;
+    p->S = p->N + d->has_cls;
+    p->W = d->win_rows * d->win_cols;
+    p->kw = d->keep_local / p->W;
+    p->kg = d->keep_global + (d->keep_local - p->kw * p->W);
+    p->Kseg = d->keep_global + d->keep_local;
+    if (p->Kseg < 1 || p->Kseg > p->N) return VSCAN_ERR_BUDGET;
+    const int min_window = (d->grid_h / d->win_rows) * (d->grid_w / d->win_cols);
+    if (p->kw > min_window) return VSCAN_ERR_BUDGET;
+    if ((int64_t)d->batch * d->n_segments > (1 << 24)) return VSCAN_ERR_SHAPE;
+    if ((int64_t)d->n_segments * p->N > (1 << 24)) return VSCAN_ERR_SHAPE;
+    p->BC = d->batch * d->n_segments;
+    p->T = d->n_segments * p->N;
+    p->K = d->n_segments * p->Kseg;
+    p->U = p->T - p->K;
+    // limits of the kernels
+    if (d->feat_dim * es > 16 * 1024) return VSCAN_ERR_UNSUPPORTED;
+    if (d->score_mode == VSCAN_SCORE_MEAN_RECEIVED && d->head_dim * es > 512)
+        return VSCAN_ERR_UNSUPPORTED;
+    if (encoder_select_lds_bytes(p->N, with_local) > kLdsBudget) return VSCAN_ERR_UNSUPPORTED;
+    if ((size_t)(16 + 256 + p->S) * sizeof(float) > kLdsBudget) return VSCAN_ERR_UNSUPPORTED;
+
+    const size_t head = align_up((size_t)p->BC * d->heads * p->N * sizeof(float));
+    size_t off = 0;
+    p->off_head_global = off;
+    off += head;
+    p->off_head_local = off;
+    if (with_local) off += head;
+    p->off_lse = off;
+    if (d->score_mode == VSCAN_SCORE_MEAN_RECEIVED) off += head;
+    p->off_drop = off;
+    off += align_up((size_t)d->batch * p->U * sizeof(int32_t));
+    p->off_best = off;
+    off += align_up((size_t)d->batch * p->T * sizeof(uint64_t));
+    p->off_inv = off;
+    off += align_up((size_t)d->batch * p->K * sizeof(float));
+    p->bytes = off ? off : kAlign;
+    return VSCAN_OK;
+}
+
+struct LlmPlan {
+    int rows, k0, nk, S_out;
+    size_t off_part, bytes;
+};
+
+int plan_llm(const vscan_llm_desc *d, LlmPlan *p) {
+    if (!d) return VSCAN_ERR_NULL;
+    if (d->struct_size != sizeof(vscan_llm_desc)) return VSCAN_ERR_VERSION;
+    if (d->dtype != VSCAN_F32 && d->dtype != VSCAN_BF16) return VSCAN_ERR_DTYPE;
+    if (d->softmax_domain != VSCAN_KEYS_VISUAL_ONLY && d->softmax_domain != VSCAN_KEYS_ALL)
+        return VSCAN_ERR_DTYPE;
+    if (d->batch < 0 || d->seq_len < 1 || d->vis_start < 0 || d->vis_len < 1 || d->n_query < 1)
+        return VSCAN_ERR_SHAPE;
+    if ((int64_t)d->vis_start + d->vis_len + d->n_query > d->seq_len) return VSCAN_ERR_SHAPE;
+    if (d->q_heads < 1 || d->kv_heads < 1 || d->q_heads % d->kv_heads) return VSCAN_ERR_SHAPE;
+    if (d->head_dim < 8 || d->head_dim % 8 || d->head_dim > 256) return VSCAN_ERR_SHAPE;
+    if (d->hidden < 8 || d->hidden % 8) return VSCAN_ERR_SHAPE;
+    if (d->in_place != 0 && d->in_place != 1) return VSCAN_ERR_SHAPE;
+    if ((int64_t)d->batch * d->kv_heads > (1 << 24)) return VSCAN_ERR_SHAPE;
+    if (d->keep < 0 || d->keep > d->vis_len) return VSCAN_ERR_BUDGET;
+    const int es = elem_bytes(d->dtype);
+    p->rows = (d->q_heads / d->kv_heads) * d->n_query;
+    p->k0 = d->softmax_domain == VSCAN_KEYS_ALL ? 0 : d->vis_start;
+    p->nk = d->softmax_domain == VSCAN_KEYS_ALL ? d->seq_len : d->vis_len;
+    p->S_out = d->seq_len - d->vis_len + d->keep;
+    if (!llm_score_supported(p->rows, p->nk, d->head_dim * es)) return VSCAN_ERR_UNSUPPORTED;
+    if (llm_select_lds_bytes(d->vis_len) > kLdsBudget) return VSCAN_ERR_UNSUPPORTED;
+    p->off_part = 0;
+    p->bytes = align_up((size_t)d->batch * d->kv_heads * d->vis_len * sizeof(float));
+    if (!p->bytes) p->bytes = kAlign;
+    return VSCAN_OK;
+}
+
+inline float resolve_scale(float scale, int head_dim) {
+    return scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+}
+
+// ---- per-kernel event timing (measurement aid) ------------------------------
+struct ProfRecord {
+    const char *name;
+    hipEvent_t start, stop;
+};
+std::mutex g_prof_mutex;
+std::vector<ProfRecord> g_prof_records;
+bool g_prof_on = false;
+
+struct ProfScope {
+    const char *name;
+    hipStream_t stream;
+    hipEvent_t start = nullptr, stop = nullptr;
+    bool on;
+    ProfScope(const char *n, hipStream_t s) : name(n), stream(s), on(g_prof_on) {
+        if (!on) return;
+        if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess ||
+            hipEventRecord(start, stream) != hipSuccess)
+            on = false;
+    }
+    ~ProfScope() {
+        if (!on) return;
+        if (hipEventRecord(stop, stream) == hipSuccess) {
+            std::lock_guard<std::mutex> lock(g_prof_mutex);
+            g_prof_records.push_back({name, start, stop});
+        }
+    }
+};
+
+#define VSCAN_LAUNCH(name, call)                          \
+    do {                                                  \
+        hipError_t e_;                                    \
+        {                                                 \
+            ProfScope scope_(name, s);                    \
+            e_ = (call);                                  \
+        }                                                 \
+        if (e_ != hipSuccess) return VSCAN_ERR_HIP;       \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int vscan_encoder_workspace_size(const vscan_encoder_desc *desc, int with_local_pair,
+                                 size_t *bytes) {
+    if (!bytes) return VSCAN_ERR_NULL;
+    EncoderPlan p;
+    const int rc = plan_encoder(desc, with_local_pair != 0, &p);
+    if (rc != VSCAN_OK) return rc;
+    *bytes = p.bytes;
+    return VSCAN_OK;
+}
+
+int vscan_encoder_reduce(const vscan_encoder_desc *d, const void *q, const void *k,
+                         const void *q_local, const void *k_local, const void *x,
+                         int32_t *kept_idx, void *merged, int32_t *assign_out, float *scores_out,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    if ((q_local == nullptr) != (k_local == nullptr)) return VSCAN_ERR_NULL;
+    const bool with_local = q_local != nullptr;
+    EncoderPlan p;
+    const int rc = plan_encoder(d, with_local, &p);
+    if (rc != VSCAN_OK) return rc;
+    if (!q || !k || !x || !kept_idx || !merged) return VSCAN_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(x) || !aligned16(merged) ||
+        !aligned16(q_local) || !aligned16(k_local))
+        return VSCAN_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(kept_idx) & 3u) || (reinterpret_cast<uintptr_t>(assign_out) & 3u) ||
+        (reinterpret_cast<uintptr_t>(scores_out) & 3u))
+        return VSCAN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < p.bytes) return VSCAN_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return VSCAN_ERR_ALIGN;
+    if (d->batch == 0) return VSCAN_OK;
+
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+    const bool mean = d->score_mode == VSCAN_SCORE_MEAN_RECEIVED;
+
+    ScoreArgs sa;
+    sa.q = q;
+    sa.k = k;
+    sa.head_scores = reinterpret_cast<float *>(ws + p.off_head_global);
+    sa.lse = reinterpret_cast<float *>(ws + p.off_lse);
+    sa.BC = p.BC;
+    sa.H = d->heads;
+    sa.S = p.S;
+    sa.dh = d->head_dim;
+    sa.N = p.N;
+    sa.has_cls = d->has_cls;
+    sa.domain_all = d->softmax_domain == VSCAN_KEYS_ALL;
+    sa.is_bf16 = d->dtype == VSCAN_BF16;
+    sa.scale = resolve_scale(d->scale, d->head_dim);
+    for (int pair = 0; pair < (with_local ? 2 : 1); ++pair) {
+        if (pair == 1) {
+            sa.q = q_local;
+            sa.k = k_local;
+            sa.head_scores = reinterpret_cast<float *>(ws + p.off_head_local);
+        }
+        if (mean) {
+            VSCAN_LAUNCH("score_mean_lse", launch_score_mean_lse(sa, s));
+            VSCAN_LAUNCH("score_mean_colsum", launch_score_mean_colsum(sa, s));
+        } else {
+            VSCAN_LAUNCH("score_cls", launch_score_cls(sa, s));
+        }
+    }
+
+    EncSelectArgs se;
+    se.head_global = reinterpret_cast<const float *>(ws + p.off_head_global);
+    se.head_local = with_local ? reinterpret_cast<const float *>(ws + p.off_head_local) : nullptr;
+    se.B = d->batch;
+    se.C = d->n_segments;
+    se.H = d->heads;
+    se.gh = d->grid_h;
+    se.gw = d->grid_w;
+    se.wr = d->win_rows;
+    se.wc = d->win_cols;
+    se.kw = p.kw;
+    se.kg = p.kg;
+    se.norm = mean ? 1.0f / ((float)d->heads * (float)p.N) : 1.0f / (float)d->heads;
+    se.kept_idx = kept_idx;
+    se.drop_idx = reinterpret_cast<int32_t *>(ws + p.off_drop);
+    se.best = reinterpret_cast<uint64_t *>(ws + p.off_best);
+    se.scores_out = scores_out;
+    VSCAN_LAUNCH("encoder_select", launch_encoder_select(se, s));
+
+    MergeArgs ma;
+    ma.x = x;
+    ma.kept_idx = kept_idx;
+    ma.drop_idx = se.drop_idx;
+    ma.inv_norm = reinterpret_cast<float *>(ws + p.off_inv);
+    ma.best = se.best;
+    ma.merged = merged;
+    ma.assign_out = assign_out;
+    ma.B = d->batch;
+    ma.T = p.T;
+    ma.D = d->feat_dim;
+    ma.K = p.K;
+    ma.is_bf16 = sa.is_bf16;
+    if (p.U > 0) {
+        VSCAN_LAUNCH("kept_inv_norm", launch_kept_inv_norm(ma, s));
+        VSCAN_LAUNCH("sim_argmax", launch_sim_argmax(ma, s));
+    }
+    VSCAN_LAUNCH("merge", launch_merge(ma, s));
+    return VSCAN_OK;
+}
+
+int vscan_llm_workspace_size(const vscan_llm_desc *desc, size_t *bytes) {
+    if (!bytes) return VSCAN_ERR_NULL;
+    LlmPlan p;
+    const int rc = plan_llm(desc, &p);
+    if (rc != VSCAN_OK) return rc;
+    *bytes = p.bytes;
+    return VSCAN_OK;
+}
+
+int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, void *hidden,
+                    int32_t *kept_idx, void *k_out, void *v_out, void *hidden_out,
+                    float *scores_out, void *workspace, size_t workspace_bytes, void *stream) {
+    LlmPlan p;
+    const int rc = plan_llm(d, &p);
+    if (rc != VSCAN_OK) return rc;
+    if (!q || !k || !v || !hidden || !kept_idx) return VSCAN_ERR_NULL;
+    const bool outs_null = !k_out && !v_out && !hidden_out;
+    const bool outs_all = k_out && v_out && hidden_out;
+    if (d->in_place ? !outs_null : !outs_all) return VSCAN_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(hidden) ||
+        !aligned16(k_out) || !aligned16(v_out) || !aligned16(hidden_out))
+        return VSCAN_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(kept_idx) & 3u) || (reinterpret_cast<uintptr_t>(scores_out) & 3u))
+        return VSCAN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < p.bytes) return VSCAN_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return VSCAN_ERR_ALIGN;
+    if (d->batch == 0) return VSCAN_OK;
+
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+
+    LlmScoreArgs sa;
+    sa.q = q;
+    sa.k = k;
+    sa.part = reinterpret_cast<float *>(ws + p.off_part);
+    sa.B = d->batch;
+    sa.Hq = d->q_heads;
+    sa.Hkv = d->kv_heads;
+    sa.Tq = d->n_query;
+    sa.S = d->seq_len;
+    sa.dh = d->head_dim;
+    sa.vis_start = d->vis_start;
+    sa.V = d->vis_len;
+    sa.domain_all = d->softmax_domain == VSCAN_KEYS_ALL;
+    sa.is_bf16 = d->dtype == VSCAN_BF16;
+    sa.scale = resolve_scale(d->scale, d->head_dim);
+    VSCAN_LAUNCH("llm_score", launch_llm_score(sa, s));
+
+    LlmSelectArgs se;
+    se.part = sa.part;
+    se.B = d->batch;
+    se.Hkv = d->kv_heads;
+    se.V = d->vis_len;
+    se.keep = d->keep;
+    se.norm = 1.0f / ((float)d->n_query * (float)d->q_heads);
+    se.kept_idx = kept_idx;
+    se.scores_out = scores_out;
+    VSCAN_LAUNCH("llm_select", launch_llm_select(se, s));
+
+    CompactArgs ca;
+    ca.k = k;
+    ca.v = v;
+    ca.hidden = hidden;
+    ca.k_out = k_out;
+    ca.v_out = v_out;
+    ca.hidden_out = hidden_out;
+    ca.kept_idx = kept_idx;
+    ca.B = d->batch;
+    ca.Hkv = d->kv_heads;
+    ca.S = d->seq_len;
+    ca.dh = d->head_dim;
+    ca.Dh = d->hidden;
+    ca.vis_start = d->vis_start;
+    ca.V = d->vis_len;
+    ca.keep = d->keep;
+    ca.elem_bytes = elem_bytes(d->dtype);
+    ca.in_place = d->in_place;
+    VSCAN_LAUNCH("compact", launch_compact(ca, s));
+    return VSCAN_OK;
+}
+
+int vscan_profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    g_prof_on = on != 0;
+    return VSCAN_OK;
+}
+
+int vscan_profile_read(vscan_kernel_time *out, int capacity, int *count) {
+    if (!out || !count || capacity < 0) return VSCAN_ERR_NULL;
+    std::vector<ProfRecord> recs;
+    {
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        recs.swap(g_prof_records);
+    }
+    int n = 0, rc = VSCAN_OK;
+    for (const ProfRecord &r : recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) != hipSuccess ||
+            hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+            rc = VSCAN_ERR_HIP;
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+        int i = 0;
+        while (i < n && strcmp(out[i].name, r.name) != 0) ++i;
+        if (i == n) {
+            if (n == capacity) continue;
+            memset(&out[n], 0, sizeof(out[n]));
+            strncpy(out[n].name, r.name, sizeof(out[n].name) - 1);
+            ++n;
+        }
+        out[i].launches += 1;
+        out[i].total_ms += ms;
+    }
+    *count = n;
+    return rc;
+}
+
+const char *vscan_status_string(int status) {
+    switch (status) {
+        case VSCAN_OK: return "ok";
+        case VSCAN_ERR_NULL: return "a required pointer is NULL (or an optional pair is half given)";
+        case VSCAN_ERR_SHAPE: return "a dimension is out of range or inconsistent";
+        case VSCAN_ERR_BUDGET: return "a keep budget does not fit the tokens or windows";
+        case VSCAN_ERR_DTYPE: return "unknown dtype, score mode or softmax domain";
+        case VSCAN_ERR_ALIGN: return "a tensor pointer is not sufficiently aligned";
+        case VSCAN_ERR_WORKSPACE: return "workspace is missing or too small";
+        case VSCAN_ERR_HIP: return "a HIP runtime call failed";
+        case VSCAN_ERR_VERSION: return "descriptor struct_size does not match this library";
+        case VSCAN_ERR_UNSUPPORTED: return "valid request outside the limits of the kernels";
+        default: return "unknown status";
+    }
+}
+
+uint32_t vscan_version(void) { return VSCAN_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,86 @@
+// Host-side launch interface between the C ABI layer and the kernel files.
+// Every launcher enqueues on the given stream and returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace vscan {
+
+// encoder attention scoring (Eq. 1-2)
+struct ScoreArgs {
+    const void *q, *k;    // [BC, H, S, dh]
+    float *head_scores;   // [BC, H, N] un-averaged per-head scores
+    float *lse;           // [BC, H, N] scratch, mean mode only
+    int BC, H, S, dh, N;
+    int has_cls, domain_all, is_bf16;
+    float scale;
+};
+hipError_t launch_score_cls(const ScoreArgs &a, hipStream_t s);
+hipError_t launch_score_mean_lse(const ScoreArgs &a, hipStream_t s);     // pass 1
+hipError_t launch_score_mean_colsum(const ScoreArgs &a, hipStream_t s);  // pass 2
+
+// local + global selection (Eq. 2-3, footnote on priority)
+struct EncSelectArgs {
+    const float *head_global;  // [BC, H, N]
+    const float *head_local;   // [BC, H, N] or NULL (= head_global)
+    int B, C, H, gh, gw, wr, wc;
+    int kw;                    // per window
+    int kg;                    // per segment, remainder of the local budget included
+    float norm;                // 1/H or 1/(H*N)
+    int32_t *kept_idx;         // [B, C*(W*kw+kg)]
+    int32_t *drop_idx;         // [B, C*N - K]
+    uint64_t *best;            // [B, C*N] packed (similarity key, ~slot)
+    float *scores_out;         // optional [B, C*N]
+};
+hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s);
+size_t encoder_select_lds_bytes(int N, int has_local);
+
+// cosine assignment (Sec. 4.1 "Token Merging") and Eq. 4
+struct MergeArgs {
+    const void *x;             // [B, T, D]
+    const int32_t *kept_idx;   // [B, K]
+    const int32_t *drop_idx;   // [B, U]
+    float *inv_norm;           // [B, K] scratch
+    uint64_t *best;            // [B, T]
+    void *merged;              // [B, K, D]
+    int32_t *assign_out;       // optional [B, T]
+    int B, T, D, K, is_bf16;
+};
+hipError_t launch_kept_inv_norm(const MergeArgs &a, hipStream_t s);
+hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s);
+hipError_t launch_merge(const MergeArgs &a, hipStream_t s);
+
+// stage 2 scoring (Eq. 5)
+struct LlmScoreArgs {
+    const void *q;             // [B, Hq, Tq, dh]
+    const void *k;             // [B, Hkv, S, dh]
+    float *part;               // [B, Hkv, V] un-averaged sums over the query rows of a kv head
+    int B, Hq, Hkv, Tq, S, dh, vis_start, V;
+    int domain_all, is_bf16;
+    float scale;
+};
+hipError_t launch_llm_score(const LlmScoreArgs &a, hipStream_t s);
+// rows = (Hq/Hkv)*Tq query rows per kv head, nk = keys in the softmax domain
+bool llm_score_supported(int rows, int nk, int row_bytes);
+
+struct LlmSelectArgs {
+    const float *part;         // [B, Hkv, V]
+    int B, Hkv, V, keep;
+    float norm;                // 1/(Tq*Hq)
+    int32_t *kept_idx;         // [B, keep]
+    float *scores_out;         // optional [B, V]
+};
+hipError_t launch_llm_select(const LlmSelectArgs &a, hipStream_t s);
+size_t llm_select_lds_bytes(int V);
+
+// order-preserving compaction ("Remarks on KV Cache")
+struct CompactArgs {
+    void *k, *v, *hidden;              // sources (and destinations when in_place)
+    void *k_out, *v_out, *hidden_out;  // NULL when in_place
+    const int32_t *kept_idx;           // [B, keep]
+    int B, Hkv, S, dh, Dh, vis_start, V, keep, elem_bytes, in_place;
+};
+hipError_t launch_compact(const CompactArgs &a, hipStream_t s);
+
+}  // namespace vscan

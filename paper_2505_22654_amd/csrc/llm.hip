@@ -1,0 +1,332 @@
+// Stage 2 (Sec. 4.2): text-to-visual attention scoring (Eq. 5) and the
+// order-preserving compaction of hidden states and K/V ("Remarks on KV Cache").
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace vscan {
+
+// ---------------------------------------------------------------------------
+// Scoring.  One workgroup per (sequence, kv head) streams that head's keys once
+// from HBM straight into matrix-core operands and multiplies them with all the
+// query rows sharing the kv head (R = (Hq/Hkv) * Tq rows, padded to 16 per
+// block).  Logits stay in LDS until the row maxima / sums are known, then the
+// normalised rows are summed in a fixed order into
+//   part[b][g][j] = sum_r softmax(row r)_j          (j over the visual span).
+// ---------------------------------------------------------------------------
+constexpr int kScoreDepth = 4;  // 16-key tiles a wave keeps in flight
+
+template <typename T, int NC, int NRB>
+__global__ __launch_bounds__(256) void llm_score_kernel(const T *__restrict__ q,
+                                                        const T *__restrict__ k,
+                                                        float *__restrict__ part, int Hq, int Hkv,
+                                                        int Tq, int S, int dh, int vis_start, int V,
+                                                        int k0, int nk, float sl2) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *rowM = reinterpret_cast<float *>(smem);  // 64
+    float *rowInvL = rowM + 64;                      // 64
+    float *z = rowInvL + 64;                         // [R][nk16]
+
+    const int g_kv = blockIdx.x, b = blockIdx.y;
+    const int group = Hq / Hkv, R = group * Tq;
+    const int nk16 = (nk + 15) & ~15;
+    const int row_bytes = dh * (int)sizeof(T);
+    const unsigned char *qbase = reinterpret_cast<const unsigned char *>(q) +
+                                 ((int64_t)b * Hq + (int64_t)g_kv * group) * Tq * row_bytes;
+    const unsigned char *kbase = reinterpret_cast<const unsigned char *>(k) +
+                                 (((int64_t)b * Hkv + g_kv) * S + k0) * row_bytes;
+    const int lane = lane_id(), l16 = lane & 15, g = lane >> 4, w = wave_id();
+
+    uint4 qfrag[NRB][NC];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int row = rb * 16 + l16;
+            qfrag[rb][c] = load16_guard(qbase, (int64_t)row * row_bytes + 64 * c + 16 * g,
+                                        row < R && 64 * c + 16 * g < row_bytes);
+        }
+
+    const int ntiles = nk16 >> 4;
+    const int my_tiles = ntiles > w ? (ntiles - w + 3) >> 2 : 0;  // tiles w, w+4, ...
+    uint4 ring[kScoreDepth][NC];
+    auto fetch = [&](int n, uint4 *dst) {
+        const int key = (w + 4 * n) * 16 + l16;
+        const bool ok = n < my_tiles && key < nk;
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            dst[c] = load16_guard(kbase, (int64_t)key * row_bytes + 64 * c + 16 * g,
+                                  ok && 64 * c + 16 * g < row_bytes);
+    };
+#pragma unroll
+    for (int d = 0; d < kScoreDepth; ++d) fetch(d, ring[d]);
+
+    for (int n0 = 0; n0 < my_tiles; n0 += kScoreDepth) {
+#pragma unroll
+        for (int d = 0; d < kScoreDepth; ++d) {
+            const int n = n0 + d;
+            if (n < my_tiles) {
+                const int key0 = (w + 4 * n) * 16;
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb) {
+                    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) mma16_chunk<T>(acc, ring[d][c], qfrag[rb][c]);
+                    // acc[r]: key key0 + 4g + r, query row rb*16 + l16
+                    const int row = rb * 16 + l16;
+                    if (row < R) {
+                        const int t = row % Tq;
+                        const int last_pos = S - Tq + t;  // causal limit of this query
+                        float4 o;
+                        float *op = &o.x;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int kk = key0 + 4 * g + r;
+                            op[r] = (kk < nk && k0 + kk <= last_pos) ? acc[r] * sl2 : -INFINITY;
+                        }
+                        *reinterpret_cast<float4 *>(z + (int64_t)row * nk16 + key0 + 4 * g) = o;
+                    }
+                }
+            }
+            fetch(n + kScoreDepth, ring[d]);
+        }
+    }
+    __syncthreads();
+
+    for (int row = w; row < R; row += 4) {
+        const float *zr = z + (int64_t)row * nk16;
+        float m = -INFINITY;
+        for (int j = lane; j < nk16; j += kWave) m = fmaxf(m, zr[j]);
+        m = wave_max(m);
+        float sum = 0.f;
+        for (int j = lane; j < nk16; j += kWave) sum += __builtin_amdgcn_exp2f(zr[j] - m);
+        sum = wave_sum(sum);
+        if (lane == 0) {
+            rowM[row] = m;
+            rowInvL[row] = 1.0f / sum;
+        }
+    }
+    __syncthreads();
+
+    float *out = part + ((int64_t)b * Hkv + g_kv) * V;
+    const int col0 = vis_start - k0;
+    for (int j = threadIdx.x; j < V; j += blockDim.x) {
+        float s = 0.f;
+        for (int row = 0; row < R; ++row)
+            s += __builtin_amdgcn_exp2f(z[(int64_t)row * nk16 + col0 + j] - rowM[row]) *
+                 rowInvL[row];
+        out[j] = s;
+    }
+}
+
+static size_t llm_score_lds(int rows, int nk) {
+    return (size_t)(128 + (int64_t)rows * ((nk + 15) & ~15)) * sizeof(float);
+}
+
+bool llm_score_supported(int rows, int nk, int row_bytes) {
+    return rows <= 64 && row_bytes <= 512 && llm_score_lds(rows, nk) <= 160 * 1024;
+}
+
+template <typename T, int NC, int NRB>
+static hipError_t llm_score_launch(const LlmScoreArgs &a, hipStream_t s) {
+    const int rows = (a.Hq / a.Hkv) * a.Tq;
+    const int k0 = a.domain_all ? 0 : a.vis_start;
+    const int nk = a.domain_all ? a.S : a.V;
+    const size_t smem = llm_score_lds(rows, nk);
+    if (smem > 64 * 1024) {
+        hipError_t e =
+            hipFuncSetAttribute(reinterpret_cast<const void *>(llm_score_kernel<T, NC, NRB>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((llm_score_kernel<T, NC, NRB>), dim3(a.Hkv, a.B), dim3(256), smem, s,
+                       (const T *)a.q, (const T *)a.k, a.part, a.Hq, a.Hkv, a.Tq, a.S, a.dh,
+                       a.vis_start, a.V, k0, nk, a.scale * 1.4426950408889634f);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t llm_score_t(const LlmScoreArgs &a, hipStream_t s) {
+    const int rows = (a.Hq / a.Hkv) * a.Tq;
+    const int nc = (a.dh * (int)sizeof(T) + 63) / 64;
+    if (rows <= 16) {
+        if (nc <= 2) return llm_score_launch<T, 2, 1>(a, s);
+        if (nc <= 4) return llm_score_launch<T, 4, 1>(a, s);
+        return llm_score_launch<T, 8, 1>(a, s);
+    }
+    if (nc <= 2) return llm_score_launch<T, 2, 4>(a, s);
+    if (nc <= 4) return llm_score_launch<T, 4, 4>(a, s);
+    return llm_score_launch<T, 8, 4>(a, s);
+}
+
+hipError_t launch_llm_score(const LlmScoreArgs &a, hipStream_t s) {
+    return a.is_bf16 ? llm_score_t<bf16_t>(a, s) : llm_score_t<float>(a, s);
+}
+
+// ---------------------------------------------------------------------------
+// Compaction.  New row p of a sequence comes from old row
+//   p                          p <  vis_start
+//   vis_start + kept[p - vs]   p <  vis_start + keep
+//   p + (V - keep)             otherwise
+// so sources never lie below destinations.  A "strip" is up to 256 bytes of one
+// row of one slab (K or V: one (sequence, kv head); hidden: one sequence).
+// ---------------------------------------------------------------------------
+struct Strip {
+    unsigned char *src, *dst;  // first byte of row 0 of the strip
+    int64_t src_stride, dst_stride;
+    int width;                 // bytes, multiple of 16, <= 256
+    int b;
+};
+
+__device__ __forceinline__ Strip decode_strip(const CompactArgs &a, int id, int S_out) {
+    const int kv_w = a.dh * a.elem_bytes, hid_w = a.Dh * a.elem_bytes;
+    const int kv_strips = (kv_w + 255) / 256, hid_strips = (hid_w + 255) / 256;
+    const int n_kv = a.B * a.Hkv * kv_strips;
+    Strip s;
+    if (id < 2 * n_kv) {
+        const bool is_v = id >= n_kv;
+        const int r = is_v ? id - n_kv : id;
+        const int slab = r / kv_strips, strip = r - slab * kv_strips;
+        unsigned char *in = reinterpret_cast<unsigned char *>(is_v ? a.v : a.k);
+        unsigned char *out = reinterpret_cast<unsigned char *>(is_v ? a.v_out : a.k_out);
+        s.b = slab / a.Hkv;
+        s.src_stride = kv_w;
+        s.dst_stride = kv_w;
+        s.src = in + (int64_t)slab * a.S * kv_w + strip * 256;
+        s.dst = a.in_place ? s.src : out + (int64_t)slab * S_out * kv_w + strip * 256;
+        s.width = min(256, kv_w - strip * 256);
+    } else {
+        const int r = id - 2 * n_kv;
+        const int b = r / hid_strips, strip = r - b * hid_strips;
+        unsigned char *in = reinterpret_cast<unsigned char *>(a.hidden);
+        unsigned char *out = reinterpret_cast<unsigned char *>(a.hidden_out);
+        s.b = b;
+        s.src_stride = hid_w;
+        s.dst_stride = hid_w;
+        s.src = in + (int64_t)b * a.S * hid_w + strip * 256;
+        s.dst = a.in_place ? s.src : out + (int64_t)b * S_out * hid_w + strip * 256;
+        s.width = min(256, hid_w - strip * 256);
+    }
+    return s;
+}
+
+__device__ __forceinline__ int src_row(const CompactArgs &a, const int32_t *kept_b, int p) {
+    if (p < a.vis_start) return p;
+    if (p < a.vis_start + a.keep)  // clamped: the index comes from device memory
+        return a.vis_start + min(max(kept_b[p - a.vis_start], 0), a.V - 1);
+    return p + (a.V - a.keep);
+}
+
+constexpr int kCompactRpt = 8;                   // rows per thread per tile
+constexpr int kCompactTile = 16 * kCompactRpt;   // rows per tile (16 threads span a row)
+
+// Makes the compiler wait (s_waitcnt vmcnt) until the loads that produced these
+// registers have returned.  A workgroup barrier by itself does not wait for a
+// thread's outstanding global loads, and the in-place walk must not let any thread
+// store over a row another thread is still reading.
+__device__ __forceinline__ void wait_for_loads(const uint4 *regs, int n) {
+#pragma unroll
+    for (int i = 0; i < n; ++i)
+        asm volatile("" ::"v"(regs[i].x), "v"(regs[i].y), "v"(regs[i].z), "v"(regs[i].w));
+}
+
+// In place.  One workgroup walks one strip from the first row that moves to the
+// end.  Per tile: every thread's loads have returned (wait_for_loads), barrier,
+// then the stores.  Tiles are written in ascending order while the next tile's
+// loads are already in flight, which is safe because a tile's stores end below
+// every later tile's sources (source row >= destination row, both ascending).
+__global__ __launch_bounds__(256) void compact_inplace_kernel(CompactArgs a) {
+    __shared__ int red[4];
+    if (a.keep == a.V) return;  // nothing was pruned
+    const int S_out = a.S - a.V + a.keep;
+    const Strip s = decode_strip(a, blockIdx.x, S_out);
+    const int32_t *kept_b = a.kept_idx + (int64_t)s.b * a.keep;
+    const int tid = threadIdx.x;
+
+    // first destination row whose source differs
+    int first = a.keep;
+    for (int i = tid; i < a.keep; i += blockDim.x)
+        if (kept_b[i] != i) {
+            first = i;
+            break;
+        }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) first = min(first, __shfl_xor(first, o, kWave));
+    if (lane_id() == 0) red[wave_id()] = first;
+    __syncthreads();
+    first = min(min(red[0], red[1]), min(red[2], red[3]));
+    const int p0 = a.vis_start + first;
+
+    const int piece = tid & 15, rloc = tid >> 4;
+    const bool col_ok = piece * 16 < s.width;
+    auto load_tile = [&](int tile, uint4 *dst) {
+#pragma unroll
+        for (int i = 0; i < kCompactRpt; ++i) {
+            const int p = p0 + tile * kCompactTile + i * 16 + rloc;
+            const bool ok = col_ok && p < S_out;
+            const int sr = ok ? src_row(a, kept_b, p) : 0;
+            dst[i] = load16_guard(s.src, (int64_t)sr * s.src_stride + piece * 16, ok);
+        }
+    };
+    auto store_tile = [&](int tile, const uint4 *v) {
+#pragma unroll
+        for (int i = 0; i < kCompactRpt; ++i) {
+            const int p = p0 + tile * kCompactTile + i * 16 + rloc;
+            if (col_ok && p < S_out)
+                *reinterpret_cast<uint4 *>(s.dst + (int64_t)p * s.dst_stride + piece * 16) = v[i];
+        }
+    };
+    const int ntiles = (S_out - p0 + kCompactTile - 1) / kCompactTile;
+    if (ntiles <= 0) return;
+    uint4 bufa[kCompactRpt], bufb[kCompactRpt];
+    load_tile(0, bufa);
+    for (int t = 0; t < ntiles; t += 2) {
+        if (t + 1 < ntiles) load_tile(t + 1, bufb);
+        wait_for_loads(bufa, kCompactRpt);
+        __syncthreads();
+        store_tile(t, bufa);
+        if (t + 1 >= ntiles) break;
+        if (t + 2 < ntiles) load_tile(t + 2, bufa);
+        wait_for_loads(bufb, kCompactRpt);
+        __syncthreads();
+        store_tile(t + 1, bufb);
+    }
+}
+
+// Out of place: a plain row gather; grid (strips, row tiles).
+__global__ __launch_bounds__(256) void compact_gather_kernel(CompactArgs a) {
+    const int S_out = a.S - a.V + a.keep;
+    const Strip s = decode_strip(a, blockIdx.x, S_out);
+    const int32_t *kept_b = a.kept_idx + (int64_t)s.b * a.keep;
+    const int piece = threadIdx.x & 15, rloc = threadIdx.x >> 4;
+    if (piece * 16 >= s.width) return;
+    uint4 v[kCompactRpt];
+#pragma unroll
+    for (int i = 0; i < kCompactRpt; ++i) {
+        const int p = blockIdx.y * kCompactTile + i * 16 + rloc;
+        const bool ok = p < S_out;
+        const int sr = ok ? src_row(a, kept_b, p) : 0;
+        v[i] = load16_guard(s.src, (int64_t)sr * s.src_stride + piece * 16, ok);
+    }
+#pragma unroll
+    for (int i = 0; i < kCompactRpt; ++i) {
+        const int p = blockIdx.y * kCompactTile + i * 16 + rloc;
+        if (p < S_out)
+            *reinterpret_cast<uint4 *>(s.dst + (int64_t)p * s.dst_stride + piece * 16) = v[i];
+    }
+}
+
+hipError_t launch_compact(const CompactArgs &a, hipStream_t s) {
+    const int kv_strips = (a.dh * a.elem_bytes + 255) / 256;
+    const int hid_strips = (a.Dh * a.elem_bytes + 255) / 256;
+    const int strips = 2 * a.B * a.Hkv * kv_strips + a.B * hid_strips;
+    if (a.in_place) {
+        hipLaunchKernelGGL(compact_inplace_kernel, dim3(strips), dim3(256), 0, s, a);
+    } else {
+        const int S_out = a.S - a.V + a.keep;
+        dim3 grid(strips, (S_out + kCompactTile - 1) / kCompactTile);
+        hipLaunchKernelGGL(compact_gather_kernel, grid, dim3(256), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace vscan

@@ -1,0 +1,176 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/vscan.h
+declares, sizes workspaces and rejects bad descriptors before touching the GPU.
+
+Every negative call here fails validation, so no kernel is ever launched and the
+fake pointer values are never dereferenced.
+"""
+import ctypes
+import dataclasses
+import os
+import re
+
+import pytest
+
+from paper_2505_22654_amd import binding as vb
+from paper_2505_22654_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000  # aligned, never dereferenced
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "vscan.h")).read()
+    declared = set(re.findall(r"\b(vscan_[a-z_]+)\s*\(", header))
+    assert declared == set(vb.EXPORTS)
+    L = vb.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_version_and_status_strings():
+    assert vb.version() == 0x00010000
+    seen = set()
+    for code in range(0, -10, -1):
+        s = vb.status_string(code)
+        assert s and s != "unknown status" and s not in seen
+        seen.add(s)
+    assert vb.status_string(-99) == "unknown status"
+
+
+def test_descriptor_layout_matches_header():
+    # 17 four-byte fields / 15 four-byte fields, no padding
+    assert ctypes.sizeof(vb.EncoderDesc) == 17 * 4
+    assert ctypes.sizeof(vb.LlmDesc) == 15 * 4
+
+
+def test_workspace_sizes_for_the_benchmark_configs():
+    sizes = {}
+    for i in (1, 2, 3, 4):
+        w = wl.config(i)
+        n = vb.encoder_workspace_size(vb.encoder_desc(w.encoder))
+        n_local = vb.encoder_workspace_size(vb.encoder_desc(w.encoder), True)
+        assert 0 < n < n_local and n % 256 == 0
+        sizes[i] = n
+    assert sizes[1] < sizes[2] < sizes[3]
+    for i in (1, 2, 3, 4, 5):
+        w = wl.config(i)
+        n = vb.llm_workspace_size(vb.llm_desc(w.llm))
+        s = w.llm
+        assert n >= s.batch * s.kv_heads * s.vis_len * 4 and n % 256 == 0
+
+
+def _enc_call(desc, q=FAKE, k=FAKE, ql=None, kl=None, x=FAKE, kept=FAKE, merged=FAKE,
+              ws=FAKE, ws_bytes=1 << 40):
+    return vb.lib().vscan_encoder_reduce(ctypes.byref(desc) if desc is not None else None, q, k,
+                                         ql, kl, x, kept, merged, None, None, ws, ws_bytes, None)
+
+
+def _enc_shape(**kw):
+    return dataclasses.replace(wl.config(1).encoder, **kw)
+
+
+@pytest.mark.parametrize("change,status", [
+    (dict(dtype="f32", batch=-1), vb.VSCAN_ERR_SHAPE),
+    (dict(grid_h=0), vb.VSCAN_ERR_SHAPE),
+    (dict(heads=0), vb.VSCAN_ERR_SHAPE),
+    (dict(head_dim=60), vb.VSCAN_ERR_SHAPE),
+    (dict(head_dim=264), vb.VSCAN_ERR_SHAPE),
+    (dict(feat_dim=1001), vb.VSCAN_ERR_SHAPE),
+    (dict(win_rows=25), vb.VSCAN_ERR_SHAPE),
+    (dict(has_cls=0), vb.VSCAN_ERR_SHAPE),            # [CLS] scoring without a [CLS] row
+    (dict(has_cls=2), vb.VSCAN_ERR_SHAPE),
+    (dict(score_mode=7), vb.VSCAN_ERR_DTYPE),
+    (dict(softmax_domain=-1), vb.VSCAN_ERR_DTYPE),
+    (dict(keep_global=-1), vb.VSCAN_ERR_BUDGET),
+    (dict(keep_global=0, keep_local=0), vb.VSCAN_ERR_BUDGET),
+    (dict(keep_global=570, keep_local=8), vb.VSCAN_ERR_BUDGET),      # more than N
+    (dict(keep_local=4 * 145), vb.VSCAN_ERR_BUDGET),                  # 145 per 144-token window
+    (dict(feat_dim=16384), vb.VSCAN_ERR_UNSUPPORTED),
+    (dict(grid_h=256, grid_w=256, win_rows=1, win_cols=1), vb.VSCAN_ERR_UNSUPPORTED),
+])
+def test_encoder_rejects_bad_descriptors(change, status):
+    desc = vb.encoder_desc(_enc_shape(**change))
+    assert _enc_call(desc) == status
+    n = ctypes.c_size_t(0)
+    assert vb.lib().vscan_encoder_workspace_size(ctypes.byref(desc), 0, ctypes.byref(n)) == status
+
+
+def test_encoder_rejects_bad_pointers_and_workspace():
+    desc = vb.encoder_desc(_enc_shape())
+    need = vb.encoder_workspace_size(desc)
+    assert _enc_call(None) == vb.VSCAN_ERR_NULL
+    bad = vb.encoder_desc(_enc_shape())
+    bad.struct_size = 12
+    assert _enc_call(bad) == vb.VSCAN_ERR_VERSION
+    bad = vb.encoder_desc(_enc_shape())
+    bad.dtype = 5
+    assert _enc_call(bad) == vb.VSCAN_ERR_DTYPE
+    assert _enc_call(desc, q=None) == vb.VSCAN_ERR_NULL
+    assert _enc_call(desc, merged=None) == vb.VSCAN_ERR_NULL
+    assert _enc_call(desc, ql=FAKE, kl=None) == vb.VSCAN_ERR_NULL    # half of the local pair
+    assert _enc_call(desc, x=FAKE + 8) == vb.VSCAN_ERR_ALIGN
+    assert _enc_call(desc, kept=FAKE + 2) == vb.VSCAN_ERR_ALIGN
+    assert _enc_call(desc, ws=None) == vb.VSCAN_ERR_WORKSPACE
+    assert _enc_call(desc, ws_bytes=need - 1) == vb.VSCAN_ERR_WORKSPACE
+    assert _enc_call(desc, ws=FAKE + 4) == vb.VSCAN_ERR_ALIGN
+    # the local pair needs a larger workspace than the plain call
+    assert _enc_call(desc, ql=FAKE, kl=FAKE, ws_bytes=need) == vb.VSCAN_ERR_WORKSPACE
+    assert vb.lib().vscan_encoder_workspace_size(ctypes.byref(desc), 0, None) == vb.VSCAN_ERR_NULL
+
+
+def test_empty_batch_is_a_no_op():
+    desc = vb.encoder_desc(_enc_shape(batch=0))
+    assert _enc_call(desc) == vb.VSCAN_OK
+    ldesc = vb.llm_desc(dataclasses.replace(wl.config(1).llm, batch=0))
+    assert _llm_call(ldesc) == vb.VSCAN_OK
+
+
+def _llm_call(desc, q=FAKE, k=FAKE, v=FAKE, hidden=FAKE, kept=FAKE, ko=FAKE, vo=FAKE, ho=FAKE,
+              ws=FAKE, ws_bytes=1 << 40):
+    return vb.lib().vscan_llm_prune(ctypes.byref(desc) if desc is not None else None, q, k, v,
+                                    hidden, kept, ko, vo, ho, None, ws, ws_bytes, None)
+
+
+def _llm_shape(**kw):
+    return dataclasses.replace(wl.config(1).llm, **kw)
+
+
+@pytest.mark.parametrize("change,status", [
+    (dict(vis_len=0), vb.VSCAN_ERR_SHAPE),
+    (dict(n_query=0), vb.VSCAN_ERR_SHAPE),
+    (dict(n_query=41), vb.VSCAN_ERR_SHAPE),            # queries would overlap the visual span
+    (dict(q_heads=30), vb.VSCAN_ERR_SHAPE),            # not a multiple of kv_heads
+    (dict(head_dim=100), vb.VSCAN_ERR_SHAPE),
+    (dict(hidden=4100), vb.VSCAN_ERR_SHAPE),
+    (dict(in_place=3), vb.VSCAN_ERR_SHAPE),
+    (dict(softmax_domain=2), vb.VSCAN_ERR_DTYPE),
+    (dict(keep=65), vb.VSCAN_ERR_BUDGET),
+    (dict(keep=-1), vb.VSCAN_ERR_BUDGET),
+    (dict(kv_heads=1, n_query=3), vb.VSCAN_ERR_UNSUPPORTED),   # 96 query rows per kv head
+    (dict(prefix=0, vis_len=60000, text=8, keep=10), vb.VSCAN_ERR_UNSUPPORTED),
+])
+def test_llm_rejects_bad_descriptors(change, status):
+    desc = vb.llm_desc(_llm_shape(**change))
+    assert _llm_call(desc) == status
+    n = ctypes.c_size_t(0)
+    assert vb.lib().vscan_llm_workspace_size(ctypes.byref(desc), ctypes.byref(n)) == status
+
+
+def test_llm_rejects_bad_pointers_and_workspace():
+    desc = vb.llm_desc(_llm_shape())
+    need = vb.llm_workspace_size(desc)
+    assert _llm_call(None) == vb.VSCAN_ERR_NULL
+    assert _llm_call(desc, hidden=None) == vb.VSCAN_ERR_NULL
+    assert _llm_call(desc, ko=None) == vb.VSCAN_ERR_NULL             # out of place needs outputs
+    assert _llm_call(desc, v=FAKE + 4) == vb.VSCAN_ERR_ALIGN
+    assert _llm_call(desc, ws_bytes=need - 1) == vb.VSCAN_ERR_WORKSPACE
+    inplace = vb.llm_desc(_llm_shape(in_place=1))
+    assert _llm_call(inplace) == vb.VSCAN_ERR_NULL                   # in place forbids outputs
+    assert _llm_call(inplace, ko=None, vo=None, ho=None, ws=None) == vb.VSCAN_ERR_WORKSPACE
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    monkeypatch.setattr(vb, "_lib", None)
+    monkeypatch.setattr(vb, "LIB_PATH", "/nonexistent/libvscan.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        vb.lib()

@@ -1,0 +1,221 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Rules and tolerances live in tests/parity_utils.py."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import vscan_oracle as vo
+from paper_2505_22654_amd import binding as vb
+from paper_2505_22654_amd import workloads as wl
+from tests import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_encoder(shape, inp, loc=None):
+    q, k, x = (pu.to_device(inp[n], shape.dtype) for n in ("q", "k", "x"))
+    ql = kl = None
+    if loc is not None:
+        ql, kl = pu.to_device(loc["q"], shape.dtype), pu.to_device(loc["k"], shape.dtype)
+    import torch
+    out = vb.encoder_reduce(shape, q, k, x, ql, kl, want_assign=True, want_scores=True)
+    torch.cuda.synchronize()
+    return out
+
+
+def _run_llm(shape, inp):
+    import torch
+    q, k, v, h = (pu.to_device(inp[n], shape.dtype) for n in ("q", "k", "v", "hidden"))
+    out = vb.llm_prune(shape, q, k, v, h, want_scores=True)
+    torch.cuda.synchronize()
+    return out
+
+
+def _enc(dtype=wl.BF16, **kw):
+    base = dict(dtype=dtype, batch=2, n_segments=1, grid_h=12, grid_w=12, has_cls=1, score_mode=0,
+                heads=4, head_dim=32, feat_dim=128, win_rows=2, win_cols=2, keep_global=10,
+                keep_local=8)
+    base.update(kw)
+    return wl.EncoderShape(**base)
+
+
+SMALL_ENCODER = {
+    # several tiles and a ragged tail in every dimension
+    "bf16-ragged": _enc(batch=3, n_segments=2, grid_h=13, grid_w=11, heads=3, head_dim=40,
+                        feat_dim=200, win_rows=3, win_cols=2, keep_global=17, keep_local=13),
+    "f32-ragged": _enc(wl.F32, batch=2, n_segments=3, grid_h=9, grid_w=14, heads=5, head_dim=24,
+                       feat_dim=136, win_rows=2, win_cols=3, keep_global=9, keep_local=12),
+    "bf16-all-keys": _enc(softmax_domain=1, keep_global=30, keep_local=16),
+    "f32-all-keys": _enc(wl.F32, softmax_domain=1),
+    "bf16-one-window": _enc(win_rows=1, win_cols=1, keep_local=5, keep_global=0),
+    "bf16-global-only": _enc(keep_local=0, keep_global=21),
+    "bf16-many-kept": _enc(grid_h=20, grid_w=20, keep_global=150, keep_local=100, feat_dim=264),
+    "bf16-wide-rows": _enc(head_dim=256, feat_dim=1032, heads=2),
+    "f32-keep-one": _enc(wl.F32, keep_global=1, keep_local=0),
+    "bf16-mean": _enc(has_cls=0, score_mode=1, grid_h=15, grid_w=13, head_dim=80, heads=3,
+                      win_rows=3, win_cols=3, keep_global=20, keep_local=18),
+    "bf16-mean-cls-all-keys": _enc(has_cls=1, score_mode=1, softmax_domain=1, grid_h=16,
+                                   grid_w=20, head_dim=64),
+    "bf16-mean-cls": _enc(has_cls=1, score_mode=1, grid_h=11, grid_w=12, head_dim=48),
+    "f32-mean": _enc(wl.F32, has_cls=0, score_mode=1, grid_h=14, grid_w=10, head_dim=40),
+    "bf16-mean-wide": _enc(has_cls=0, score_mode=1, grid_h=18, grid_w=9, head_dim=160, heads=2),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SMALL_ENCODER))
+def test_encoder_small(name):
+    shape = SMALL_ENCODER[name]
+    inp, _, ref, info = pu.screened_encoder_case(shape, seed=1000 + len(name), logit_gain=0.25)
+    out = _run_encoder(shape, inp)
+    rep = pu.check_encoder(shape, inp, ref, out, name)
+    print(name, info, rep)
+
+
+def test_encoder_local_scan_from_shallow_layer_pair():
+    shape = _enc(batch=2, n_segments=2, grid_h=12, grid_w=12, keep_global=12, keep_local=12)
+    inp, loc, ref, info = pu.screened_encoder_case(shape, seed=77, logit_gain=0.25, with_local=True)
+    assert not np.array_equal(ref["scores"], ref["scores_local"])
+    out = _run_encoder(shape, inp, loc)
+    pu.check_encoder(shape, inp, ref, out, "local-pair")
+
+
+def test_encoder_keep_everything_is_identity():
+    shape = _enc(wl.F32, grid_h=8, grid_w=8, keep_global=32, keep_local=32)
+    inp = wl.encoder_inputs(shape, 5)
+    out = _run_encoder(shape, inp)
+    assert np.array_equal(pu.to_host(out["kept_idx"]), np.arange(64)[None].repeat(2, 0))
+    assert np.array_equal(pu.to_host(out["merged"]), inp["x"])
+    assert np.array_equal(pu.to_host(out["assign"]), np.arange(64)[None].repeat(2, 0))
+
+
+def test_encoder_exact_ties():
+    """q = 0 gives every token the same score on both sides: the result must be the first
+    kw row-major tokens of every window, then the lowest remaining indices; duplicated
+    kept rows must send their copies to the lowest slot."""
+    shape = _enc(wl.F32, batch=1, grid_h=8, grid_w=8, win_rows=2, win_cols=2, keep_global=3,
+                 keep_local=8, feat_dim=64)
+    inp = wl.encoder_inputs(shape, 9)
+    inp["q"][:] = 0.0
+    x = inp["x"]
+    x[0, 2] = x[0, 0]        # tokens 0 and 2 are kept (see below) and identical
+    x[0, 40] = x[0, 0]       # a dropped copy -> must go to slot 0, not slot 2
+    ref = vo.encoder_reduce(shape, inp["q"], inp["k"], x)
+    want = sorted([0, 1, 4, 5, 32, 33, 36, 37] + [2, 3, 6])
+    assert ref["kept"].tolist() == [want]
+    out = _run_encoder(shape, inp)
+    assert pu.to_host(out["kept_idx"]).tolist() == [want]
+    assign = pu.to_host(out["assign"])
+    assert assign[0, 40] == 0 and ref["assign"][0, 40] == 0
+    pu.check_encoder(shape, inp, ref, out, "ties")
+
+
+def test_encoder_runs_are_bit_reproducible():
+    shape = SMALL_ENCODER["bf16-ragged"]
+    inp = wl.encoder_inputs(shape, 3, 0.25)
+    a, b = _run_encoder(shape, inp), _run_encoder(shape, inp)
+    for name in ("kept_idx", "merged", "assign", "scores"):
+        assert np.array_equal(pu.to_host(a[name]), pu.to_host(b[name])), name
+
+
+def _llm(dtype=wl.BF16, **kw):
+    base = dict(dtype=dtype, batch=2, prefix=5, vis_len=50, text=9, n_query=1, q_heads=4,
+                kv_heads=4, head_dim=32, hidden=64, keep=20)
+    base.update(kw)
+    return wl.LlmShape(**base)
+
+
+SMALL_LLM = {
+    "bf16-basic": _llm(),
+    "f32-basic": _llm(wl.F32),
+    "bf16-gqa-queries": _llm(batch=3, q_heads=12, kv_heads=4, n_query=3, vis_len=333, text=17,
+                             head_dim=40, hidden=200, keep=111),
+    "f32-gqa": _llm(wl.F32, q_heads=6, kv_heads=2, vis_len=77, head_dim=24, hidden=136, keep=30),
+    "bf16-many-rows": _llm(q_heads=8, kv_heads=2, n_query=8, vis_len=130, text=20, keep=64),
+    "bf16-causal-domain": _llm(softmax_domain=1, n_query=4, q_heads=8, kv_heads=4, text=12),
+    "f32-causal-domain": _llm(wl.F32, softmax_domain=1, n_query=2, text=6),
+    "bf16-in-place": _llm(in_place=1, batch=3, vis_len=300, text=40, keep=100, head_dim=128,
+                          hidden=520),
+    "f32-in-place": _llm(wl.F32, in_place=1, vis_len=200, text=33, keep=7, head_dim=64,
+                         hidden=264),
+    "bf16-keep-all": _llm(keep=50),
+    "bf16-keep-all-in-place": _llm(keep=50, in_place=1),
+    "bf16-keep-none": _llm(keep=0),
+    "bf16-no-prefix": _llm(prefix=0, in_place=1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SMALL_LLM))
+def test_llm_small(name):
+    shape = SMALL_LLM[name]
+    inp, ref, info = pu.screened_llm_case(shape, seed=2000 + len(name))
+    out = _run_llm(shape, inp)
+    rep = pu.check_llm(shape, inp, ref, out, name)
+    print(name, info, rep)
+
+
+@pytest.mark.parametrize("pattern", ["last", "first", "alternate"])
+def test_in_place_compaction_hazards(pattern):
+    """Steer the selection (by planting large keys) to the patterns that stress the
+    write-after-read hazard of in-place compaction, and compare with out-of-place."""
+    shape = _llm(in_place=1, batch=2, prefix=3, vis_len=700, text=300, keep=350, head_dim=128,
+                 hidden=256, q_heads=2, kv_heads=2)
+    inp = wl.llm_inputs(shape, 31)
+    V = shape.vis_len
+    chosen = {"last": np.arange(V - shape.keep, V), "first": np.arange(shape.keep),
+              "alternate": np.arange(0, V, 2)}[pattern]
+    qdir = inp["q"].mean(axis=(1, 2))                      # [B, dh]
+    for b in range(shape.batch):
+        inp["k"][b][:, shape.vis_start + chosen] += wl.round_to_bf16(4.0 * qdir[b])
+    inp["k"] = wl.round_to_bf16(inp["k"])
+    ref = vo.llm_prune(shape, **inp)
+    assert np.array_equal(ref["kept"], chosen[None].repeat(shape.batch, 0))
+    out = _run_llm(shape, inp)
+    pu.check_llm(shape, inp, ref, out, pattern)
+    out2 = _run_llm(dataclasses.replace(shape, in_place=0), inp)
+    for name in ("k", "v", "hidden"):
+        assert np.array_equal(pu.to_host(out[name]), pu.to_host(out2[name]))
+
+
+def test_llm_exact_ties_keep_first_tokens():
+    shape = _llm(wl.F32, keep=13)
+    inp = wl.llm_inputs(shape, 4)
+    inp["k"][:] = 1.0
+    ref = vo.llm_prune(shape, **inp)
+    assert ref["kept"].tolist() == [list(range(13))] * 2
+    out = _run_llm(shape, inp)
+    pu.check_llm(shape, inp, ref, out, "ties")
+
+
+# ----------------------------------------------------------------------------
+# The benchmark configurations at full size
+# ----------------------------------------------------------------------------
+def test_config1_full():
+    w = wl.config(1)
+    inp, _, ref, info = pu.screened_encoder_case(w.encoder, w.seed)
+    print("cfg1 encoder", info, pu.check_encoder(w.encoder, inp, ref, _run_encoder(w.encoder, inp)))
+    inp, ref, info = pu.screened_llm_case(w.llm, w.seed)
+    print("cfg1 llm", info, pu.check_llm(w.llm, inp, ref, _run_llm(w.llm, inp)))
+
+
+@pytest.mark.parametrize("keep", [192, 128, 64])
+def test_config2_full(keep):
+    w = wl.config(2, sweep=keep)
+    inp, _, ref, info = pu.screened_encoder_case(w.encoder, w.seed)
+    print("cfg2 encoder", info, pu.check_encoder(w.encoder, inp, ref, _run_encoder(w.encoder, inp)))
+    inp, ref, info = pu.screened_llm_case(w.llm, w.seed)
+    print("cfg2 llm", info, pu.check_llm(w.llm, inp, ref, _run_llm(w.llm, inp)))
+
+
+def test_config3_full():
+    w = wl.config(3)
+    inp, _, ref, info = pu.screened_encoder_case(w.encoder, w.seed)
+    print("cfg3 encoder", info, pu.check_encoder(w.encoder, inp, ref, _run_encoder(w.encoder, inp)))
+    inp, ref, info = pu.screened_llm_case(w.llm, w.seed)
+    print("cfg3 llm", info, pu.check_llm(w.llm, inp, ref, _run_llm(w.llm, inp)))
+
+
+def test_config4_llm_full():
+    w = wl.config(4)
+    inp, ref, info = pu.screened_llm_case(w.llm, w.seed)
+    print("cfg4 llm", info, pu.check_llm(w.llm, inp, ref, _run_llm(w.llm, inp)))
