@@ -141,7 +141,8 @@ int vscan_llm_workspace_size(const vscan_llm_desc *desc, size_t *bytes);
  * k, v        in  [B, Hkv, S, dh]  layer-k keys / values (position-encoded as the
  *                 attention layer sees them); mutated iff in_place
  * hidden      in  [B, S, Dh]; mutated iff in_place
- * kept_idx    out [B, keep] int32, ascending, relative to vis_start
+ * kept_idx    out [B, keep] int32, ascending, relative to vis_start (may be NULL
+ *                 when keep == 0)
  * k_out,v_out out [B, Hkv, S_out, dh], hidden_out [B, S_out, Dh],
  *                 S_out = S - V + keep: rows [0, vis_start) ++ kept visual rows in
  *                 original order ++ rows [vis_start+V, S).  Must be NULL iff

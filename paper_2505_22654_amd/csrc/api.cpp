@@ -284,7 +284,7 @@ int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, vo
     LlmPlan p;
     const int rc = plan_llm(d, &p);
     if (rc != VSCAN_OK) return rc;
-    if (!q || !k || !v || !hidden || !kept_idx) return VSCAN_ERR_NULL;
+    if (!q || !k || !v || !hidden || (!kept_idx && d->keep > 0)) return VSCAN_ERR_NULL;
     const bool outs_null = !k_out && !v_out && !hidden_out;
     const bool outs_all = k_out && v_out && hidden_out;
     if (d->in_place ? !outs_null : !outs_all) return VSCAN_ERR_NULL;
