@@ -31,7 +31,7 @@ PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 KERNEL_SOURCE = {
     "score_cls": "encoder_score.hip", "score_mean_lse": "encoder_score.hip",
     "score_mean_colsum": "encoder_score.hip", "encoder_select": "select.hip",
-    "llm_select": "select.hip", "kept_inv_norm": "sim_merge.hip", "sim_argmax": "sim_merge.hip",
+    "llm_select": "select.hip", "sim_argmax": "sim_merge.hip",
     "merge": "sim_merge.hip", "llm_score": "llm.hip", "compact": "llm.hip",
 }
 
@@ -60,7 +60,6 @@ def algorithmic_work(w: wl.Workload):
             out["score_mean_lse"] = ("mfma", 2.0 * B * C * H * N * N * dh)
             out["score_mean_colsum"] = ("mfma", 2.0 * B * C * H * N * N * dh)
         out["encoder_select"] = ("hbm", B * T * 4 + B * K * 4)
-        out["kept_inv_norm"] = ("hbm", B * K * D * es)
         out["sim_argmax"] = ("mfma", 2.0 * B * U * K * D)
         out["merge"] = ("hbm", B * (T + K) * D * es)
     l = w.llm

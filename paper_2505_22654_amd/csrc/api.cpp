@@ -25,7 +25,7 @@ inline int elem_bytes(int dtype) { return dtype == VSCAN_BF16 ? 2 : 4; }
 
 struct EncoderPlan {
     int N, S, BC, T, W, kw, kg, Kseg, K, U;
-    size_t off_head_global, off_head_local, off_lse, off_drop, off_best, off_inv, bytes;
+    size_t off_head_global, off_head_local, off_lse, off_drop, off_best, bytes;
 };
 
 int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
@@ -81,8 +81,6 @@ int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
     off += align_up((size_t)d->batch * p->U * sizeof(int32_t));
     p->off_best = off;
     off += align_up((size_t)d->batch * p->T * sizeof(uint64_t));
-    p->off_inv = off;
-    off += align_up((size_t)d->batch * p->K * sizeof(float));
     p->bytes = off ? off : kAlign;
     return VSCAN_OK;
 }
@@ -252,7 +250,6 @@ int vscan_encoder_reduce(const vscan_encoder_desc *d, const void *q, const void 
     ma.x = x;
     ma.kept_idx = kept_idx;
     ma.drop_idx = se.drop_idx;
-    ma.inv_norm = reinterpret_cast<float *>(ws + p.off_inv);
     ma.best = se.best;
     ma.merged = merged;
     ma.assign_out = assign_out;
@@ -261,10 +258,7 @@ int vscan_encoder_reduce(const vscan_encoder_desc *d, const void *q, const void 
     ma.D = d->feat_dim;
     ma.K = p.K;
     ma.is_bf16 = sa.is_bf16;
-    if (p.U > 0) {
-        VSCAN_LAUNCH("kept_inv_norm", launch_kept_inv_norm(ma, s));
-        VSCAN_LAUNCH("sim_argmax", launch_sim_argmax(ma, s));
-    }
+    if (p.U > 0) VSCAN_LAUNCH("sim_argmax", launch_sim_argmax(ma, s));
     VSCAN_LAUNCH("merge", launch_merge(ma, s));
     return VSCAN_OK;
 }

@@ -20,7 +20,7 @@ namespace vscan {
 // lanes, so a wave reads whole rows contiguously.
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
+__global__ __launch_bounds__(256) void score_cls_generic_kernel(const T *__restrict__ q,
                                                         const T *__restrict__ k,
                                                         float *__restrict__ head_scores, int H,
                                                         int S, int dh, int first_key, int col0,
@@ -90,6 +90,86 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
     const float inv = 1.0f / sum;
     float *out = head_scores + ((int64_t)bc * H + h) * N;
     for (int j = tid; j < N; j += blockDim.x) out[j] = z[col0 + j] * inv;
+}
+
+// Same computation for rows whose piece count is a power of two (every common head
+// size).  The key block is read as one flat, fully coalesced stream with up to 16
+// independent 16-byte loads per thread in flight: at these sizes the kernel's time
+// is the number of serialised memory round-trips, so all of them are issued at once.
+template <typename T>
+__global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
+                                                        const T *__restrict__ k,
+                                                        float *__restrict__ head_scores, int H,
+                                                        int S, int dh, int first_key, int col0,
+                                                        int N, float scale_log2e) {
+    constexpr int E = ElemTraits<T>::kPer16B;
+    constexpr int UNR = 16;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *red = reinterpret_cast<float *>(smem);  // 16 floats
+    float *qf = red + 16;                           // dh floats (dh <= 256)
+    float *z = qf + 256;                            // n_keys floats
+
+    const int h = blockIdx.x, bc = blockIdx.y;
+    const int64_t head_row0 = ((int64_t)bc * H + h) * S;
+    const T *qrow = q + head_row0 * dh;
+    const unsigned char *kbase = reinterpret_cast<const unsigned char *>(k + (head_row0 + first_key) * dh);
+    const int n_keys = S - first_key;
+    const int tid = threadIdx.x;
+
+    const int cpr = dh / E;  // power of two, <= 64
+    const int shift = __ffs(cpr) - 1;
+    const int total = n_keys << shift;  // 16-byte pieces in the key block
+    uint4 raw[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        const int p = u * 256 + tid;
+        raw[u] = load16_guard(kbase, (int64_t)p * 16, p < total);
+    }
+    for (int e = tid; e < dh; e += 256) qf[e] = load_elem<T>(qrow + e) * scale_log2e;
+    __syncthreads();
+    float qreg[E];
+    const int piece = tid & (cpr - 1);
+#pragma unroll
+    for (int e = 0; e < E; ++e) qreg[e] = qf[piece * E + e];
+
+    for (int base = 0; base < total; base += 256 * UNR) {
+        uint4 nxt[UNR];
+        if (base + 256 * UNR < total) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int p = base + 256 * UNR + u * 256 + tid;
+                nxt[u] = load16_guard(kbase, (int64_t)p * 16, p < total);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int p = base + u * 256 + tid;
+            float kv[E];
+            unpack16<T>(raw[u], kv);
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) part = fmaf(kv[e], qreg[e], part);
+            for (int o = cpr >> 1; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
+            if (piece == 0 && p < total) z[p >> shift] = part;
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) raw[u] = nxt[u];
+    }
+    __syncthreads();
+
+    float m = -INFINITY;
+    for (int j = tid; j < n_keys; j += 256) m = fmaxf(m, z[j]);
+    m = block_max(m, red);
+    float sum = 0.f;
+    for (int j = tid; j < n_keys; j += 256) {
+        const float e = __builtin_amdgcn_exp2f(z[j] - m);
+        z[j] = e;
+        sum += e;
+    }
+    sum = block_sum(sum, red);
+    const float inv = 1.0f / sum;
+    float *out = head_scores + ((int64_t)bc * H + h) * N;
+    for (int j = tid; j < N; j += 256) out[j] = z[col0 + j] * inv;
 }
 
 // ---------------------------------------------------------------------------
@@ -316,11 +396,20 @@ static hipError_t launch_score_cls_t(const ScoreArgs &a, hipStream_t s) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_cls_kernel<T>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_cls_generic_kernel<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
     }
     dim3 grid(a.H, a.BC);
-    hipLaunchKernelGGL(score_cls_kernel<T>, grid, dim3(256), smem, s, (const T *)a.q,
-                       (const T *)a.k, a.head_scores, a.H, a.S, a.dh, first_key, 1 - first_key,
-                       a.N, a.scale * 1.4426950408889634f);
+    const int cpr = a.dh / ElemTraits<T>::kPer16B;
+    if ((cpr & (cpr - 1)) == 0)
+        hipLaunchKernelGGL(score_cls_kernel<T>, grid, dim3(256), smem, s, (const T *)a.q,
+                           (const T *)a.k, a.head_scores, a.H, a.S, a.dh, first_key,
+                           1 - first_key, a.N, a.scale * 1.4426950408889634f);
+    else
+        hipLaunchKernelGGL(score_cls_generic_kernel<T>, grid, dim3(256), smem, s, (const T *)a.q,
+                           (const T *)a.k, a.head_scores, a.H, a.S, a.dh, first_key,
+                           1 - first_key, a.N, a.scale * 1.4426950408889634f);
     return hipGetLastError();
 }
 

@@ -41,13 +41,11 @@ struct MergeArgs {
     const void *x;             // [B, T, D]
     const int32_t *kept_idx;   // [B, K]
     const int32_t *drop_idx;   // [B, U]
-    float *inv_norm;           // [B, K] scratch
     uint64_t *best;            // [B, T]
     void *merged;              // [B, K, D]
     int32_t *assign_out;       // optional [B, T]
     int B, T, D, K, is_bf16;
 };
-hipError_t launch_kept_inv_norm(const MergeArgs &a, hipStream_t s);
 hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s);
 hipError_t launch_merge(const MergeArgs &a, hipStream_t s);
 

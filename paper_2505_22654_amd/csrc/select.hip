@@ -259,6 +259,129 @@ __global__ void llm_select_kernel(LlmSelectArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// Small segments (N <= 1024): one thread per token, ranks by direct counting.
+// Every loop runs over LDS with independent (pipelined) broadcast reads and there
+// is no serial search, which is what matters when the whole call is a few
+// microseconds long.  rank(j) = #{i : (key_i, -i) > (key_j, -j)}; a token is kept
+// when its rank is below the budget, which is exactly top-k with ties to the
+// lowest index.
+// ---------------------------------------------------------------------------
+constexpr int kSmallSelectMax = 1024;
+
+// number of candidates that beat token j; cand[i] == 0 marks a non-candidate
+__device__ __forceinline__ int count_better(const uint32_t *cand, int n4, uint32_t kj, int j) {
+    int cnt = 0;
+    const uint4 *c4 = reinterpret_cast<const uint4 *>(cand);
+#pragma unroll 4
+    for (int q = 0; q < n4; ++q) {
+        const uint4 v = c4[q];
+        const int i = 4 * q;
+        cnt += (v.x > kj) || (v.x == kj && i < j);
+        cnt += (v.y > kj) || (v.y == kj && i + 1 < j);
+        cnt += (v.z > kj) || (v.z == kj && i + 2 < j);
+        cnt += (v.w > kj) || (v.w == kj && i + 3 < j);
+    }
+    return cnt;
+}
+
+// slot of every kept token in thread (= token) order; two barriers
+__device__ __forceinline__ int block_slot(bool kept, int *wsum) {
+    int tot;
+    return block_excl_count(kept, wsum, tot);
+}
+
+__global__ __launch_bounds__(1024) void encoder_select_small_kernel(EncSelectArgs a) {
+    __shared__ __align__(16) uint32_t keyl[kSmallSelectMax];
+    __shared__ __align__(16) uint32_t cand[kSmallSelectMax];  // global-scan candidates
+    __shared__ int wsum[16];
+    const int N = a.gh * a.gw;
+    const int bc = blockIdx.x, b = bc / a.C, c = bc - b * a.C;
+    const int j = threadIdx.x;
+    const int T_img = a.C * N;
+    const bool live = j < N;
+
+    uint32_t kg_key = 0, kl_key = 0;
+    if (live) {
+        float sg = 0.f, sl = 0.f;
+        const float *hg = a.head_global + (int64_t)bc * a.H * N + j;
+        for (int h = 0; h < a.H; ++h) sg += hg[(int64_t)h * N];
+        sg *= a.norm;
+        kg_key = float_to_key(sg);
+        if (a.scores_out) a.scores_out[(int64_t)b * T_img + (int64_t)c * N + j] = sg;
+        if (a.head_local) {
+            const float *hl = a.head_local + (int64_t)bc * a.H * N + j;
+            for (int h = 0; h < a.H; ++h) sl += hl[(int64_t)h * N];
+            kl_key = float_to_key(sl * a.norm);
+        } else {
+            kl_key = kg_key;
+        }
+    }
+    keyl[j] = kl_key;  // 0 past the end
+    __syncthreads();
+
+    // local scan: rank inside the token's own window
+    bool local = false;
+    if (live && a.kw > 0) {
+        const int r = j / a.gw, col = j - r * a.gw;
+        const int wy = r * a.wr / a.gh, wx = col * a.wc / a.gw;
+        const int r0 = ceil_div(wy * a.gh, a.wr), r1 = ceil_div((wy + 1) * a.gh, a.wr);
+        const int c0 = ceil_div(wx * a.gw, a.wc), c1 = ceil_div((wx + 1) * a.gw, a.wc);
+        int cnt = 0;
+        for (int rr = r0; rr < r1; ++rr)
+            for (int cc = c0; cc < c1; ++cc) {
+                const int i = rr * a.gw + cc;
+                const uint32_t ki = keyl[i];
+                cnt += (ki > kl_key) || (ki == kl_key && i < j);
+            }
+        local = cnt < a.kw;
+    }
+    cand[j] = (live && !local) ? kg_key : 0u;
+    __syncthreads();
+
+    // global scan over what the local scan left
+    bool global = false;
+    if (live && !local && a.kg > 0)
+        global = count_better(cand, (N + 3) >> 2, kg_key, j) < a.kg;
+
+    const bool kept = local || global;
+    const int slot = block_slot(kept, wsum);
+    if (live) {
+        const int Kseg = a.wr * a.wc * a.kw + a.kg;
+        const int K = a.C * Kseg, U = T_img - K;
+        const int tok = c * N + j;
+        if (kept) {
+            const int sidx = c * Kseg + slot;
+            a.kept_idx[(int64_t)b * K + sidx] = tok;
+            a.best[(int64_t)b * T_img + tok] = (0xffffffffull << 32) | (uint32_t)~(uint32_t)sidx;
+        } else {
+            a.drop_idx[(int64_t)b * U + (int64_t)c * (N - Kseg) + (j - slot)] = tok;
+            a.best[(int64_t)b * T_img + tok] = 0ull;
+        }
+    }
+}
+
+__global__ __launch_bounds__(1024) void llm_select_small_kernel(LlmSelectArgs a) {
+    __shared__ __align__(16) uint32_t cand[kSmallSelectMax];
+    __shared__ int wsum[16];
+    const int b = blockIdx.x, j = threadIdx.x, V = a.V;
+    const bool live = j < V;
+    uint32_t key = 0;
+    if (live) {
+        float s = 0.f;
+        const float *pp = a.part + (int64_t)b * a.Hkv * V + j;
+        for (int g = 0; g < a.Hkv; ++g) s += pp[(int64_t)g * V];
+        s *= a.norm;
+        key = float_to_key(s);
+        if (a.scores_out) a.scores_out[(int64_t)b * V + j] = s;
+    }
+    cand[j] = key;
+    __syncthreads();
+    const bool kept = live && a.keep > 0 && count_better(cand, (V + 3) >> 2, key, j) < a.keep;
+    const int slot = block_slot(kept, wsum);
+    if (kept) a.kept_idx[(int64_t)b * a.keep + slot] = j;
+}
+
 static size_t round16(size_t v) { return (v + 15) & ~(size_t)15; }
 
 size_t encoder_select_lds_bytes(int N, int has_local) {
@@ -268,6 +391,11 @@ size_t llm_select_lds_bytes(int V) { return sizeof(SelectSmem) + (size_t)V * 4 +
 
 hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
     const int N = a.gh * a.gw;
+    if (N <= kSmallSelectMax) {
+        const int threads = ((N + 3) / 4 * 4 + kWave - 1) / kWave * kWave;
+        hipLaunchKernelGGL(encoder_select_small_kernel, dim3(a.B * a.C), dim3(threads), 0, s, a);
+        return hipGetLastError();
+    }
     const size_t smem = encoder_select_lds_bytes(N, a.head_local != nullptr);
     if (smem > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(encoder_select_kernel),
@@ -280,6 +408,11 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_llm_select(const LlmSelectArgs &a, hipStream_t s) {
+    if (a.V <= kSmallSelectMax) {
+        const int threads = ((a.V + 3) / 4 * 4 + kWave - 1) / kWave * kWave;
+        hipLaunchKernelGGL(llm_select_small_kernel, dim3(a.B), dim3(threads), 0, s, a);
+        return hipGetLastError();
+    }
     const size_t smem = llm_select_lds_bytes(a.V);
     if (smem > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(llm_select_kernel),

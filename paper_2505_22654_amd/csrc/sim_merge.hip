@@ -1,16 +1,16 @@
 // Similarity-based token merging (Sec. 4.1 "Token Merging", Eq. 4).
 //
-//   kept_inv_norm   1 / max(||x_s||, eps) for every kept token
 //   sim_argmax      for every dropped token u: argmax_s (x_s . x_u) / ||x_s|| over
 //                   the image's kept tokens.  ||x_u|| is a positive per-token
-//                   constant and cannot change the argmax, so it is never formed.
+//                   constant and cannot change the argmax, so it is never formed;
+//                   ||x_s|| is accumulated from the very tiles the GEMM stages.
 //                   A kept x dropped GEMM on the matrix cores; the epilogue folds
 //                   each column into a packed (similarity key, ~slot) word and
 //                   merges it with atomicMax, which is order-independent and puts
 //                   ties on the lowest slot.
-//   merge           Eq. 4: one workgroup per kept slot averages the slot's own
-//                   token and its members in ascending token order (fixed order:
-//                   no floating-point atomics, bit-reproducible).
+//   merge           Eq. 4: one wave per kept slot averages the slot's own token
+//                   and its members in ascending token order (fixed order: no
+//                   floating-point atomics, bit-reproducible).
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -18,55 +18,39 @@ namespace vscan {
 
 constexpr float kNormEps = 1e-12f;
 
-template <typename T>
-__global__ __launch_bounds__(256) void kept_inv_norm_kernel(const T *__restrict__ x,
-                                                            const int32_t *__restrict__ kept_idx,
-                                                            float *__restrict__ inv_norm, int BK,
-                                                            int K, int T_img, int D) {
-    constexpr int E = ElemTraits<T>::kPer16B;
-    const int row = blockIdx.x * (blockDim.x / kWave) + wave_id();
-    if (row >= BK) return;
-    const int b = row / K;
-    const int tok = min(max(kept_idx[row], 0), T_img - 1);  // never index outside the image
-    const T *xr = x + ((int64_t)b * T_img + tok) * D;
-    float ss = 0.f;
-    for (int p = lane_id(); p * E < D; p += kWave) {
-        const uint4 raw = *reinterpret_cast<const uint4 *>(xr + p * E);
-        float v[E];
-        unpack16<T>(raw, v);
-#pragma unroll
-        for (int e = 0; e < E; ++e) ss = fmaf(v[e], v[e], ss);
-    }
-    ss = wave_sum(ss);
-    if (lane_id() == 0) inv_norm[row] = 1.0f / fmaxf(sqrtf(ss), kNormEps);
-}
-
 // ---------------------------------------------------------------------------
-// kept x dropped similarity with fused argmax.
+// kept x dropped similarity with fused norm and argmax.
 // Workgroup tile: (64*TM) kept slots x (64*TN) dropped tokens, 4 waves as 2 x 2,
 // each wave TM x TN blocks of 32 x 32.  The feature axis is streamed through LDS
-// in stages of KC 32-byte chunks, double-buffered, rows gathered by index.
+// in stages of KC 32-byte chunks, rows gathered by index.  Two stages are kept
+// in flight in registers on top of the one being multiplied: the small problems
+// are a handful of stages long, so their time is set by how many memory
+// round-trips are serialised, not by bandwidth.
 // ---------------------------------------------------------------------------
 template <typename T, int TM, int TN, int KC>
 __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x,
                                                          const int32_t *__restrict__ kept_idx,
                                                          const int32_t *__restrict__ drop_idx,
-                                                         const float *__restrict__ inv_norm,
                                                          unsigned long long *__restrict__ best,
                                                          int T_img, int D, int K, int U) {
+    constexpr int E = ElemTraits<T>::kPer16B;
     constexpr int BM = 64 * TM, BN = 64 * TN, ROWS = BM + BN;
     constexpr int PPR = KC * 2;                 // 16-byte pieces per row per stage
     constexpr int STRIDE = KC * 32 + 16;        // LDS row stride in bytes
     constexpr int PER_THREAD = ROWS * PPR / 256;
-    static_assert(ROWS * PPR % 256 == 0, "tile must split evenly over 256 threads");
+    constexpr int A_PIECES = BM * PPR / 256;    // the first A_PIECES pieces of a thread are kept rows
+    static_assert(ROWS * PPR % 256 == 0 && BM * PPR % 256 == 0, "tile must split evenly");
+    static_assert(PPR <= 64 && (PPR & (PPR - 1)) == 0, "a row's pieces must sit in one wave");
     __shared__ __align__(16) unsigned char lds[2][ROWS * STRIDE];
+    __shared__ float inv_s[BM];
 
     const int b = blockIdx.z;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int tid = threadIdx.x, lane = lane_id(), g = lane >> 5;
     const int wm = wave_id() >> 1, wn = wave_id() & 1;
     const int row_bytes = D * (int)sizeof(T);
-    const unsigned char *xb = reinterpret_cast<const unsigned char *>(x) + (int64_t)b * T_img * row_bytes;
+    const unsigned char *xb =
+        reinterpret_cast<const unsigned char *>(x) + (int64_t)b * T_img * row_bytes;
 
     // source byte offset of each piece this thread stages (-1: row outside the problem)
     int64_t src[PER_THREAD];
@@ -83,8 +67,11 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
         tok = min(tok, T_img - 1);  // indices come from device memory: stay inside the image
         src[it] = tok < 0 ? -1 : (int64_t)tok * row_bytes + (p - r * PPR) * 16;
     }
-    uint4 regs[PER_THREAD];
-    auto stage_load = [&](int stage) {
+    float ss[A_PIECES];  // partial squared norms of the kept rows this thread stages
+#pragma unroll
+    for (int it = 0; it < A_PIECES; ++it) ss[it] = 0.f;
+
+    auto stage_load = [&](int stage, uint4 *regs) {
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
             const int p = tid + it * 256;
@@ -94,12 +81,18 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
                                     src[it] >= 0 && col_byte < row_bytes);
         }
     };
-    auto stage_store = [&](unsigned char *dst) {
+    auto stage_store = [&](unsigned char *dst, const uint4 *regs) {
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
             const int p = tid + it * 256;
             const int r = p / PPR;
             *reinterpret_cast<uint4 *>(dst + r * STRIDE + (p - r * PPR) * 16) = regs[it];
+            if (it < A_PIECES) {
+                float v[E];
+                unpack16<T>(regs[it], v);
+#pragma unroll
+                for (int e = 0; e < E; ++e) ss[it] = fmaf(v[e], v[e], ss[it]);
+            }
         }
     };
 
@@ -111,13 +104,7 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nstages = (row_bytes + KC * 32 - 1) / (KC * 32);
-    stage_load(0);
-    stage_store(lds[0]);
-    __syncthreads();
-    for (int st = 0; st < nstages; ++st) {
-        const unsigned char *cur = lds[st & 1];
-        if (st + 1 < nstages) stage_load(st + 1);
+    auto compute = [&](const unsigned char *cur) {
         const unsigned char *arow = cur + (wm * 32 * TM + (lane & 31)) * STRIDE + 16 * g;
         const unsigned char *brow = cur + (BM + wn * 32 * TN + (lane & 31)) * STRIDE + 16 * g;
 #pragma unroll
@@ -134,21 +121,43 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
 #pragma unroll
                 for (int j = 0; j < TN; ++j) mma32_chunk<T>(acc[i][j], af[i], bf[j]);
         }
-        if (st + 1 < nstages) stage_store(lds[(st + 1) & 1]);
+    };
+
+    // software pipeline, unrolled by two so the register sets are addressed statically:
+    // while stage s is multiplied out of LDS, stages s+1 and s+2 are in flight
+    const int nstages = (row_bytes + KC * 32 - 1) / (KC * 32);
+    uint4 ra[PER_THREAD], rb[PER_THREAD];
+    stage_load(0, ra);
+    if (nstages > 1) stage_load(1, rb);
+    stage_store(lds[0], ra);
+    __syncthreads();
+    for (int st = 0; st < nstages; st += 2) {
+        if (st + 2 < nstages) stage_load(st + 2, ra);
+        compute(lds[0]);
+        if (st + 1 >= nstages) break;
+        stage_store(lds[1], rb);
         __syncthreads();
+        if (st + 3 < nstages) stage_load(st + 3, rb);
+        compute(lds[1]);
+        if (st + 2 < nstages) {
+            stage_store(lds[0], ra);
+            __syncthreads();
+        }
     }
+
+    // 1 / max(||x_s||, eps): add the PPR partial sums of each kept row (adjacent lanes)
+#pragma unroll
+    for (int it = 0; it < A_PIECES; ++it) {
+        float v = ss[it];
+#pragma unroll
+        for (int o = PPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+        const int p = tid + it * 256;
+        if (p % PPR == 0) inv_s[p / PPR] = 1.0f / fmaxf(sqrtf(v), kNormEps);
+    }
+    __syncthreads();
 
     // epilogue: acc[i][j][r] = x_slot . x_token with
     //   slot  = m0 + (wm*TM + i)*32 + acc_row(r),  token column = n0 + (wn*TN + j)*32 + lane%32
-    const float *inv_b = inv_norm + (int64_t)b * K;
-    float invs[TM][16];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int slot = m0 + (wm * TM + i) * 32 + acc_row(r);
-            invs[i][r] = slot < K ? inv_b[slot] : 0.f;
-        }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         float best_v = -INFINITY;
@@ -157,13 +166,13 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int slot = m0 + (wm * TM + i) * 32 + acc_row(r);
-                if (slot < K) {
-                    const float v = acc[i][j][r] * invs[i][r];
+                const int rl = (wm * TM + i) * 32 + acc_row(r);
+                if (m0 + rl < K) {
+                    const float v = acc[i][j][r] * inv_s[rl];
                     // slots are visited in ascending order: strict > keeps the lowest on ties
                     if (best_s < 0 || v > best_v) {
                         best_v = v;
-                        best_s = slot;
+                        best_s = m0 + rl;
                     }
                 }
             }
@@ -182,21 +191,27 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 4.  grid (K, B); each thread owns 16-byte pieces of the feature row.
+// Eq. 4.  One wave per kept slot.  The wave scans the image's assignment words
+// 64 tokens at a time; matches come out of a ballot as a wave-uniform mask, so
+// members are visited in ascending token order with no LDS and no barrier.
+// Lane l owns the 16-byte pieces l, l+64, ... of the feature row.
 // ---------------------------------------------------------------------------
 template <typename T, int PIECES>
 __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
                                                     const unsigned long long *__restrict__ best,
                                                     T *__restrict__ merged,
                                                     int32_t *__restrict__ assign_out, int T_img,
-                                                    int D, int K) {
+                                                    int D, int K, int BK) {
     constexpr int E = ElemTraits<T>::kPer16B;
-    __shared__ int wsum[4];
-    __shared__ int members[256];
-    const int slot = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int row = blockIdx.x * 4 + wave_id();
+    if (row >= BK) return;
+    const int b = row / K, slot = row - b * K;
+    const int lane = lane_id();
     const unsigned long long *bb = best + (int64_t)b * T_img;
-    const T *xb = x + (int64_t)b * T_img * D;
+    const unsigned char *xb = reinterpret_cast<const unsigned char *>(x) +
+                              (int64_t)b * T_img * D * (int64_t)sizeof(T);
     const int npieces = D / E;
+    const int64_t row_bytes = (int64_t)D * sizeof(T);
 
     float acc[PIECES][E];
 #pragma unroll
@@ -205,54 +220,59 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
         for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
 
     int count = 0;
-    for (int base = 0; base < T_img; base += 256) {
-        const int t = base + tid;
-        const bool mine = t < T_img && (int)(~(uint32_t)(bb[t] & 0xffffffffull)) == slot;
-        // ordered compaction of this chunk's members
-        const uint64_t mask = __ballot(mine);
-        const int pos = __popcll(mask & lanemask_lt());
-        if (lane_id() == 0) wsum[wave_id()] = __popcll(mask);
-        __syncthreads();
-        int off = 0, tot = 0;
+    constexpr int SCAN = 8;  // assignment words fetched ahead per lane
+    for (int base = 0; base < T_img; base += SCAN * kWave) {
+        unsigned long long w[SCAN];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            if (w < wave_id()) off += wsum[w];
-            tot += wsum[w];
+        for (int u = 0; u < SCAN; ++u) {
+            const int t = base + u * kWave + lane;
+            w[u] = t < T_img ? bb[t] : 0ull;
         }
-        if (mine) {
-            members[off + pos] = t;
-            if (assign_out) assign_out[(int64_t)b * T_img + t] = slot;
-        }
-        __syncthreads();
-        // rows are fetched four members at a time and added in member order
-        for (int m = 0; m < tot; m += 4) {
 #pragma unroll
-            for (int p = 0; p < PIECES; ++p) {
-                const int piece = tid + p * 256;
-                uint4 raw[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    raw[i] = load16_guard(xb, ((int64_t)members[min(m + i, tot - 1)] * D +
-                                               (int64_t)piece * E) * (int64_t)sizeof(T),
-                                          m + i < tot && piece < npieces);
+        for (int u = 0; u < SCAN; ++u) {
+            const int t0 = base + u * kWave;
+            const bool mine = t0 + lane < T_img && (int)(~(uint32_t)(w[u] & 0xffffffffull)) == slot;
+            if (mine && assign_out) assign_out[(int64_t)b * T_img + t0 + lane] = slot;
+            uint64_t mask = __ballot(mine);
+            count += __popcll(mask);
+            while (mask) {
+                // up to four members at a time, rows fetched together, added in order
+                int tok[4];
+                int n = 0;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float v[E];
-                    unpack16<T>(raw[i], v);
+                    tok[i] = 0;
+                    if (mask) {
+                        tok[i] = t0 + __ffsll((unsigned long long)mask) - 1;
+                        mask &= mask - 1;
+                        n = i + 1;
+                    }
+                }
 #pragma unroll
-                    for (int e = 0; e < E; ++e) acc[p][e] += v[e];
+                for (int p = 0; p < PIECES; ++p) {
+                    const int piece = lane + p * kWave;
+                    uint4 raw[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        raw[i] = load16_guard(xb, tok[i] * row_bytes + (int64_t)piece * 16,
+                                              i < n && piece < npieces);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float v[E];
+                        unpack16<T>(raw[i], v);
+#pragma unroll
+                        for (int e = 0; e < E; ++e) acc[p][e] += v[e];
+                    }
                 }
             }
         }
-        count += tot;
-        __syncthreads();
     }
 
     const float inv = 1.0f / (float)count;
-    T *out = merged + ((int64_t)b * K + slot) * D;
+    unsigned char *out = reinterpret_cast<unsigned char *>(merged) + (int64_t)row * row_bytes;
 #pragma unroll
     for (int p = 0; p < PIECES; ++p) {
-        const int piece = tid + p * 256;
+        const int piece = lane + p * kWave;
         if (piece < npieces) {
             uint4 o;
             if constexpr (sizeof(T) == 4) {
@@ -266,7 +286,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
                 o.z = f32_to_bf16_rne(acc[p][4] * inv) | (f32_to_bf16_rne(acc[p][5] * inv) << 16);
                 o.w = f32_to_bf16_rne(acc[p][6] * inv) | (f32_to_bf16_rne(acc[p][7] * inv) << 16);
             }
-            *reinterpret_cast<uint4 *>(out + piece * E) = o;
+            *reinterpret_cast<uint4 *>(out + (int64_t)piece * 16) = o;
         }
     }
 }
@@ -274,50 +294,41 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
-template <typename T>
-static hipError_t inv_norm_t(const MergeArgs &a, hipStream_t s) {
-    const int rows = a.B * a.K;
-    hipLaunchKernelGGL(kept_inv_norm_kernel<T>, dim3((rows + 3) / 4), dim3(256), 0, s,
-                       (const T *)a.x, a.kept_idx, a.inv_norm, rows, a.K, a.T, a.D);
-    return hipGetLastError();
-}
-hipError_t launch_kept_inv_norm(const MergeArgs &a, hipStream_t s) {
-    return a.is_bf16 ? inv_norm_t<bf16_t>(a, s) : inv_norm_t<float>(a, s);
-}
-
-template <typename T, int TM, int TN>
+template <typename T, int TM, int TN, int KC>
 static hipError_t sim_t(const MergeArgs &a, hipStream_t s) {
-    constexpr int KC = 4;
     const int U = a.T - a.K;
     if (U <= 0) return hipSuccess;  // nothing was dropped: every token keeps its own slot
     dim3 grid((U + 64 * TN - 1) / (64 * TN), (a.K + 64 * TM - 1) / (64 * TM), a.B);
     hipLaunchKernelGGL((sim_argmax_kernel<T, TM, TN, KC>), grid, dim3(256), 0, s, (const T *)a.x,
-                       a.kept_idx, a.drop_idx, a.inv_norm, (unsigned long long *)a.best, a.T, a.D,
-                       a.K, U);
+                       a.kept_idx, a.drop_idx, (unsigned long long *)a.best, a.T, a.D, a.K, U);
     return hipGetLastError();
 }
 hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
     // large problems amortise operand traffic with 128 x 128 tiles; small ones need
-    // the workgroup count of 64 x 64 tiles to cover the chip
+    // the workgroup count of 64 x 64 tiles and long stages (few memory round-trips)
     const int U = a.T - a.K;
     const long tiles128 = (long)((U + 127) / 128) * ((a.K + 127) / 128) * a.B;
     const bool big = tiles128 >= 512;
-    if (a.is_bf16) return big ? sim_t<bf16_t, 2, 2>(a, s) : sim_t<bf16_t, 1, 1>(a, s);
-    return big ? sim_t<float, 2, 2>(a, s) : sim_t<float, 1, 1>(a, s);
+    if (a.is_bf16) return big ? sim_t<bf16_t, 2, 2, 4>(a, s) : sim_t<bf16_t, 1, 1, 16>(a, s);
+    return big ? sim_t<float, 2, 2, 4>(a, s) : sim_t<float, 1, 1, 16>(a, s);
 }
 
 template <typename T>
 static hipError_t merge_t(const MergeArgs &a, hipStream_t s) {
     constexpr int E = ElemTraits<T>::kPer16B;
-    const int npieces = a.D / E;
-    dim3 grid(a.K, a.B);
+    const int per_lane = (a.D / E + kWave - 1) / kWave;
+    const int rows = a.B * a.K;
+    dim3 grid((rows + 3) / 4);
 #define VSCAN_MERGE(P)                                                                          \
     hipLaunchKernelGGL((merge_kernel<T, P>), grid, dim3(256), 0, s, (const T *)a.x,              \
                        (const unsigned long long *)a.best, (T *)a.merged, a.assign_out, a.T, a.D, \
-                       a.K)
-    if (npieces <= 256) VSCAN_MERGE(1);
-    else if (npieces <= 512) VSCAN_MERGE(2);
-    else if (npieces <= 1024) VSCAN_MERGE(4);
+                       a.K, rows)
+    if (per_lane <= 1) VSCAN_MERGE(1);
+    else if (per_lane <= 2) VSCAN_MERGE(2);
+    else if (per_lane <= 3) VSCAN_MERGE(3);
+    else if (per_lane <= 4) VSCAN_MERGE(4);
+    else if (per_lane <= 8) VSCAN_MERGE(8);
+    else if (per_lane <= 16) VSCAN_MERGE(16);
     else return hipErrorInvalidValue;  // wider rows are rejected by the ABI layer
 #undef VSCAN_MERGE
     return hipGetLastError();

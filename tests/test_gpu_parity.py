@@ -60,13 +60,22 @@ SMALL_ENCODER = {
     "bf16-mean-cls": _enc(has_cls=1, score_mode=1, grid_h=11, grid_w=12, head_dim=48),
     "f32-mean": _enc(wl.F32, has_cls=0, score_mode=1, grid_h=14, grid_w=10, head_dim=40),
     "bf16-mean-wide": _enc(has_cls=0, score_mode=1, grid_h=18, grid_w=9, head_dim=160, heads=2),
+    # more than 1024 tokens per segment: the radix-select path
+    "bf16-large-grid": _enc(grid_h=40, grid_w=37, heads=2, feat_dim=64, win_rows=5, win_cols=4,
+                            keep_global=130, keep_local=100),
+    "f32-large-grid-one-window": _enc(wl.F32, batch=1, grid_h=33, grid_w=35, heads=2, feat_dim=64,
+                                      win_rows=1, win_cols=1, keep_global=7, keep_local=300),
+    "bf16-odd-head-dim-cls": _enc(head_dim=80, heads=3, keep_global=12, keep_local=12),
 }
 
 
 @pytest.mark.parametrize("name", sorted(SMALL_ENCODER))
 def test_encoder_small(name):
     shape = SMALL_ENCODER[name]
-    inp, _, ref, info = pu.screened_encoder_case(shape, seed=1000 + len(name), logit_gain=0.25)
+    # peakier scores on the big grids: thousands of candidates leave few seeds with a clear
+    # boundary when the scores are flat
+    gain = 1.0 if "large" in name else 0.25
+    inp, _, ref, info = pu.screened_encoder_case(shape, seed=1000 + len(name), logit_gain=gain)
     out = _run_encoder(shape, inp)
     rep = pu.check_encoder(shape, inp, ref, out, name)
     print(name, info, rep)
@@ -110,6 +119,18 @@ def test_encoder_exact_ties():
     pu.check_encoder(shape, inp, ref, out, "ties")
 
 
+def test_encoder_exact_ties_large_grid():
+    """All scores tie on a segment that takes the radix-select path."""
+    shape = _enc(wl.F32, batch=1, grid_h=36, grid_w=40, win_rows=3, win_cols=4, keep_global=101,
+                 keep_local=50, feat_dim=32, heads=2)
+    inp = wl.encoder_inputs(shape, 11)
+    inp["q"][:] = 0.0
+    ref = vo.encoder_reduce(shape, inp["q"], inp["k"], inp["x"])
+    out = _run_encoder(shape, inp)
+    assert np.array_equal(pu.to_host(out["kept_idx"]), ref["kept"])
+    pu.check_encoder(shape, inp, ref, out, "ties-large")
+
+
 def test_encoder_runs_are_bit_reproducible():
     shape = SMALL_ENCODER["bf16-ragged"]
     inp = wl.encoder_inputs(shape, 3, 0.25)
@@ -142,6 +163,9 @@ SMALL_LLM = {
     "bf16-keep-all-in-place": _llm(keep=50, in_place=1),
     "bf16-keep-none": _llm(keep=0),
     "bf16-no-prefix": _llm(prefix=0, in_place=1),
+    # more than 1024 visual tokens: the radix-select path
+    "bf16-large-span": _llm(vis_len=1500, text=30, keep=700, in_place=1, hidden=128),
+    "f32-large-span": _llm(wl.F32, vis_len=1111, text=5, keep=3, hidden=72),
 }
 
 
@@ -187,6 +211,15 @@ def test_llm_exact_ties_keep_first_tokens():
     pu.check_llm(shape, inp, ref, out, "ties")
 
 
+def test_llm_exact_ties_large_span():
+    shape = _llm(wl.F32, vis_len=1300, keep=401, text=3)
+    inp = wl.llm_inputs(shape, 4)
+    inp["k"][:] = 1.0
+    ref = vo.llm_prune(shape, **inp)
+    assert ref["kept"].tolist() == [list(range(401))] * 2
+    pu.check_llm(shape, inp, ref, _run_llm(shape, inp), "ties-large")
+
+
 # ----------------------------------------------------------------------------
 # The benchmark configurations at full size
 # ----------------------------------------------------------------------------
@@ -219,3 +252,81 @@ def test_config4_llm_full():
     w = wl.config(4)
     inp, ref, info = pu.screened_llm_case(w.llm, w.seed)
     print("cfg4 llm", info, pu.check_llm(w.llm, inp, ref, _run_llm(w.llm, inp)))
+
+
+# seed offset found with the oracle alone: the first seeds of configuration 4 put two
+# candidates of some window closer than the margin (each oracle pass takes about a minute,
+# so the screen is not repeated here; the margin itself is still asserted)
+CFG4_SEED_OFFSET = 4
+
+
+def test_config4_encoder_full():
+    w = wl.config(4)
+    shape = w.encoder
+    inp = wl.encoder_inputs(shape, w.seed + CFG4_SEED_OFFSET)
+    ref = vo.encoder_reduce(shape, inp["q"], inp["k"], inp["x"])
+    sg = ref["scores"].reshape(1, 1, -1)
+    gap = pu.encoder_boundary_gap(shape, sg, sg)
+    assert gap > pu.MARGIN, gap
+    np.testing.assert_allclose(ref["scores"].sum(), 1.0, rtol=1e-9)
+    out = _run_encoder(shape, inp)
+    print("cfg4 encoder", {"gap": gap}, pu.check_encoder(shape, inp, ref, out, "cfg4"))
+
+
+def test_config5_full():
+    """Full-size stage-2 stress, all three budgets.  Every sequence is checked on the device
+    for consistency with the returned indices (a property that holds at any size); the
+    oracle checks, element by element, the first sequences whose selection boundary clears
+    the margin (decided from the oracle's own scores)."""
+    import torch
+    base = wl.config(5)
+    shape = base.llm
+    B, S, V, vs = shape.batch, shape.seq_len, shape.vis_len, shape.vis_start
+    keeps = (720, 288, 144)
+    dev = {"q": torch.empty((B, shape.q_heads, shape.n_query, shape.head_dim), dtype=torch.bfloat16,
+                            device="cuda"),
+           "k": torch.empty((B, shape.kv_heads, S, shape.head_dim), dtype=torch.bfloat16,
+                            device="cuda"),
+           "hidden": torch.empty((B, S, shape.hidden), dtype=torch.bfloat16, device="cuda")}
+    dev["v"] = torch.empty_like(dev["k"])
+    host, wanted = {}, {k: [] for k in keeps}
+    for b in range(B):
+        item = wl.llm_item(shape, base.seed, b)
+        for n in dev:
+            dev[n][b].copy_(pu.to_device(item[n], shape.dtype))
+        s_ref = vo.llm_scores(item["q"][None], item["k"][None], vs, V)
+        for k in keeps:
+            if len(wanted[k]) < 2 and pu.topk_boundary_gap(s_ref, k) > pu.MARGIN:
+                wanted[k].append(b)
+                host[b] = item
+    orig = {n: dev[n].clone() for n in ("k", "v", "hidden")}
+
+    for keep in keeps:
+        sh = dataclasses.replace(shape, keep=keep)
+        So = sh.seq_out
+        for n in orig:
+            dev[n].copy_(orig[n])
+        out = vb.llm_prune(sh, dev["q"], dev["k"], dev["v"], dev["hidden"], want_scores=True)
+        torch.cuda.synchronize()
+
+        kept = out["kept_idx"].long()
+        assert bool((kept[:, 1:] > kept[:, :-1]).all())
+        assert int(kept.min()) >= 0 and int(kept.max()) < V
+        rows = torch.cat([torch.arange(vs, device="cuda").expand(B, vs), vs + kept,
+                          torch.arange(vs + V, S, device="cuda").expand(B, S - vs - V)], dim=1)
+        assert rows.shape == (B, So)
+        want_h = torch.gather(orig["hidden"], 1, rows[:, :, None].expand(B, So, sh.hidden))
+        assert torch.equal(out["hidden"], want_h)
+        idx = rows[:, None, :, None].expand(B, sh.kv_heads, So, sh.head_dim)
+        assert torch.equal(out["k"], torch.gather(orig["k"], 2, idx))
+        assert torch.equal(out["v"], torch.gather(orig["v"], 2, idx))
+        np.testing.assert_allclose(pu.to_host(out["scores"]).sum(1), 1.0, rtol=1e-5)
+
+        assert wanted[keep], "no sequence with a clear boundary for this budget"
+        one = dataclasses.replace(sh, batch=1)
+        for b in wanted[keep]:
+            item = {n: a[None] for n, a in host[b].items()}
+            ref = vo.llm_prune(one, **item)
+            got = {n: out[n][b:b + 1] for n in ("kept_idx", "scores", "k", "v", "hidden")}
+            rep = pu.check_llm(one, item, ref, got, f"cfg5 keep {keep} sequence {b}")
+            print("cfg5 keep", keep, "sequence", b, rep)
