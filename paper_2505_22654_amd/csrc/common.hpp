@@ -94,6 +94,18 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Wave-wide integer sum through DPP row operations only (no LDS crossbar, no scalar
+// round-trip per step); every lane gets the total.
+__device__ __forceinline__ int wave_sum_dpp(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true);  // row_half_mirror
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true);  // row_mirror
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, true);  // row_bcast15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, true);  // row_bcast31 -> rows 2, 3
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
 // Block-wide reductions through a small LDS buffer (>= 16 floats); every thread
 // gets the result.  Order of combination is fixed, so results are reproducible.
 __device__ __forceinline__ float block_max(float v, float *red) {

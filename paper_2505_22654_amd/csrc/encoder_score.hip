@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256) void score_cls_generic_kernel(const T *__restr
 // size).  The key block is read as one flat, fully coalesced stream with up to 16
 // independent 16-byte loads per thread in flight: at these sizes the kernel's time
 // is the number of serialised memory round-trips, so all of them are issued at once.
-template <typename T>
+template <typename T, int LOG2_CPR>
 __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
                                                         const T *__restrict__ k,
                                                         float *__restrict__ head_scores, int H,
@@ -104,6 +104,8 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
                                                         int N, float scale_log2e) {
     constexpr int E = ElemTraits<T>::kPer16B;
     constexpr int UNR = 16;
+    constexpr int cpr = 1 << LOG2_CPR;  // 16-byte pieces per key row
+    constexpr int shift = LOG2_CPR;
     extern __shared__ __align__(16) unsigned char smem[];
     float *red = reinterpret_cast<float *>(smem);  // 16 floats
     float *qf = red + 16;                           // dh floats (dh <= 256)
@@ -116,8 +118,6 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
     const int n_keys = S - first_key;
     const int tid = threadIdx.x;
 
-    const int cpr = dh / E;  // power of two, <= 64
-    const int shift = __ffs(cpr) - 1;
     const int total = n_keys << shift;  // 16-byte pieces in the key block
     uint4 raw[UNR];
 #pragma unroll
@@ -149,6 +149,7 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
             float part = 0.f;
 #pragma unroll
             for (int e = 0; e < E; ++e) part = fmaf(kv[e], qreg[e], part);
+#pragma unroll
             for (int o = cpr >> 1; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
             if (piece == 0 && p < total) z[p >> shift] = part;
         }
@@ -393,23 +394,38 @@ static hipError_t launch_score_cls_t(const ScoreArgs &a, hipStream_t s) {
     const int n_keys = a.S - first_key;
     const size_t smem = (16 + 256 + (size_t)n_keys) * sizeof(float);
     if (smem > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_cls_kernel<T>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_cls_generic_kernel<T>),
+        hipError_t e =
+            hipFuncSetAttribute(reinterpret_cast<const void *>(score_cls_generic_kernel<T>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
     dim3 grid(a.H, a.BC);
     const int cpr = a.dh / ElemTraits<T>::kPer16B;
-    if ((cpr & (cpr - 1)) == 0)
-        hipLaunchKernelGGL(score_cls_kernel<T>, grid, dim3(256), smem, s, (const T *)a.q,
-                           (const T *)a.k, a.head_scores, a.H, a.S, a.dh, first_key,
-                           1 - first_key, a.N, a.scale * 1.4426950408889634f);
-    else
+#define VSCAN_CLS(L)                                                                          \
+    case L: {                                                                                 \
+        if (smem > 64 * 1024) {                                                               \
+            hipError_t e = hipFuncSetAttribute(                                               \
+                reinterpret_cast<const void *>(score_cls_kernel<T, L>),                       \
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                       \
+            if (e != hipSuccess) return e;                                                    \
+        }                                                                                     \
+        hipLaunchKernelGGL((score_cls_kernel<T, L>), grid, dim3(256), smem, s, (const T *)a.q, \
+                           (const T *)a.k, a.head_scores, a.H, a.S, a.dh, first_key,          \
+                           1 - first_key, a.N, a.scale * 1.4426950408889634f);                \
+        return hipGetLastError();                                                             \
+    }
+    if ((cpr & (cpr - 1)) == 0) {
+        switch (__builtin_ctz(cpr)) {
+            VSCAN_CLS(0) VSCAN_CLS(1) VSCAN_CLS(2) VSCAN_CLS(3) VSCAN_CLS(4) VSCAN_CLS(5)
+            VSCAN_CLS(6)
+        }
+    }
+#undef VSCAN_CLS
+    {
         hipLaunchKernelGGL(score_cls_generic_kernel<T>, grid, dim3(256), smem, s, (const T *)a.q,
                            (const T *)a.k, a.head_scores, a.H, a.S, a.dh, first_key,
                            1 - first_key, a.N, a.scale * 1.4426950408889634f);
+    }
     return hipGetLastError();
 }
 

@@ -10,6 +10,20 @@
 
 namespace vscan {
 
+// sum over heads of p[h * stride], added in head order; loads go out eight at a time so
+// the sum costs a couple of memory round-trips instead of one per head
+__device__ __forceinline__ float head_sum(const float *p, int heads, int stride) {
+    float s = 0.f;
+    for (int h0 = 0; h0 < heads; h0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = h0 + u < heads ? p[(int64_t)(h0 + u) * stride] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    return s;
+}
+
 struct SelectSmem {
     uint32_t hist[256];
     int wsum[16];
@@ -179,14 +193,12 @@ __global__ void encoder_select_kernel(EncSelectArgs a) {
     const int T_img = a.C * N;
 
     for (int j = tid; j < N; j += blockDim.x) {
-        float sg = 0.f;
-        for (int h = 0; h < a.H; ++h) sg += a.head_global[((int64_t)bc * a.H + h) * N + j];
+        float sg = head_sum(a.head_global + (int64_t)bc * a.H * N + j, a.H, N);
         sg *= a.norm;
         keyg[j] = float_to_key(sg);
         if (a.scores_out) a.scores_out[(int64_t)b * T_img + (int64_t)c * N + j] = sg;
         if (a.head_local) {
-            float sl = 0.f;
-            for (int h = 0; h < a.H; ++h) sl += a.head_local[((int64_t)bc * a.H + h) * N + j];
+            const float sl = head_sum(a.head_local + (int64_t)bc * a.H * N + j, a.H, N);
             keyl[j] = float_to_key(sl * a.norm);
         }
         flag[j] = 0;
@@ -239,8 +251,7 @@ __global__ void llm_select_kernel(LlmSelectArgs a) {
     uint8_t *flag = reinterpret_cast<uint8_t *>(key + a.V);
     const int b = blockIdx.x, tid = threadIdx.x, V = a.V;
     for (int j = tid; j < V; j += blockDim.x) {
-        float s = 0.f;
-        for (int g = 0; g < a.Hkv; ++g) s += a.part[((int64_t)b * a.Hkv + g) * V + j];
+        float s = head_sum(a.part + (int64_t)b * a.Hkv * V + j, a.Hkv, V);
         s *= a.norm;
         key[j] = float_to_key(s);
         flag[j] = 0;
@@ -260,40 +271,93 @@ __global__ void llm_select_kernel(LlmSelectArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// Small segments (N <= 1024): one thread per token, ranks by direct counting.
-// Every loop runs over LDS with independent (pipelined) broadcast reads and there
-// is no serial search, which is what matters when the whole call is a few
-// microseconds long.  rank(j) = #{i : (key_i, -i) > (key_j, -j)}; a token is kept
-// when its rank is below the budget, which is exactly top-k with ties to the
-// lowest index.
+// Small segments (N <= 1024).  At this size a call lasts a few microseconds, so
+// what counts is the length of the dependent instruction chain, not bandwidth:
+// a top-k is found by ONE wave that holds its candidates' keys in registers and
+// walks the 32 key bits from the top (one compare + ballot + popcount per register
+// per bit, no LDS traffic and no barrier inside the search).  Windows are spread
+// over the waves of the workgroup; the global scan is done by wave 0.
 // ---------------------------------------------------------------------------
 constexpr int kSmallSelectMax = 1024;
 
-// number of candidates that beat token j; cand[i] == 0 marks a non-candidate
-__device__ __forceinline__ int count_better(const uint32_t *cand, int n4, uint32_t kj, int j) {
-    int cnt = 0;
-    const uint4 *c4 = reinterpret_cast<const uint4 *>(cand);
-#pragma unroll 4
-    for (int q = 0; q < n4; ++q) {
-        const uint4 v = c4[q];
-        const int i = 4 * q;
-        cnt += (v.x > kj) || (v.x == kj && i < j);
-        cnt += (v.y > kj) || (v.y == kj && i + 1 < j);
-        cnt += (v.z > kj) || (v.z == kj && i + 2 < j);
-        cnt += (v.w > kj) || (v.w == kj && i + 3 < j);
+// Marks the k best of `nslots` slots; slot s -> (key, token) through `slot_fn`, which
+// returns key 0 for a slot that is no candidate.  Slots are in ascending token order,
+// so ties at the threshold go to the lowest token.  Called by a whole wave.
+template <int NREG, typename SlotFn>
+__device__ __forceinline__ void wave_topk_regs(SlotFn slot_fn, int nslots, int k, uint8_t *flag,
+                                               uint8_t mark) {
+    if (k <= 0) return;
+    const int lane = lane_id();
+    const int nreg = (nslots + kWave - 1) / kWave;  // <= NREG, wave-uniform
+    uint32_t key[NREG];
+    int idx[NREG];
+#pragma unroll
+    for (int r = 0; r < NREG; ++r) {
+        key[r] = 0u;
+        idx[r] = 0;
+        const int sl = r * kWave + lane;
+        if (r < nreg && sl < nslots) key[r] = slot_fn(sl, idx[r]);
     }
-    return cnt;
+    // Counting is done per lane with vector compares and summed over the wave with DPP:
+    // a compare whose result goes through a scalar register and a scalar popcount costs
+    // an order of magnitude more per register on this hardware.  The serial part of a
+    // step (reduce -> choose) dominates, so the threshold is built two bits at a time
+    // from three independent candidate counts, and the walk stops as soon as some
+    // candidate is reached by exactly k keys: the selected set is then already fixed.
+    uint32_t T = 0;
+    for (int shift = 30; shift >= 0; shift -= 2) {
+        const uint32_t c1 = T | (1u << shift), c2 = T | (2u << shift), c3 = T | (3u << shift);
+        int n1 = 0, n2 = 0, n3 = 0;  // registers past the last slot hold key 0 and never count
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) {
+            n1 += key[r] >= c1;
+            n2 += key[r] >= c2;
+            n3 += key[r] >= c3;
+        }
+        const int packed = wave_sum_dpp(n1 | (n2 << 16));
+        const int t3 = wave_sum_dpp(n3);
+        const int t1 = packed & 0xffff, t2 = packed >> 16;
+        if (t3 >= k) {
+            T = c3;
+            if (t3 == k) break;
+        } else if (t2 >= k) {
+            T = c2;
+            if (t2 == k) break;
+        } else if (t1 >= k) {
+            T = c1;
+            if (t1 == k) break;
+        }
+    }
+    int c_gt = 0, c_eq = 0;
+#pragma unroll
+    for (int r = 0; r < NREG; ++r) {
+        c_gt += key[r] > T;
+        c_eq += key[r] == T;
+    }
+    const int need_eq = k - wave_sum_dpp(c_gt);
+    if (wave_sum_dpp(c_eq) == need_eq) {  // no tie straddles the boundary
+#pragma unroll
+        for (int r = 0; r < NREG; ++r)
+            if (key[r] >= T) flag[idx[r]] = mark;  // T >= 1, so key 0 never passes
+        return;
+    }
+    int run = 0;
+#pragma unroll
+    for (int r = 0; r < NREG; ++r)
+        if (r < nreg) {
+            const bool eq = key[r] == T;
+            const uint64_t m = __ballot(eq);
+            const int rank = run + __popcll(m & lanemask_lt());
+            if (key[r] > T || (eq && rank < need_eq)) flag[idx[r]] = mark;
+            run += __popcll(m);
+        }
 }
 
-// slot of every kept token in thread (= token) order; two barriers
-__device__ __forceinline__ int block_slot(bool kept, int *wsum) {
-    int tot;
-    return block_excl_count(kept, wsum, tot);
-}
-
+template <int NREG_W, int NREG_G>
 __global__ __launch_bounds__(1024) void encoder_select_small_kernel(EncSelectArgs a) {
-    __shared__ __align__(16) uint32_t keyl[kSmallSelectMax];
-    __shared__ __align__(16) uint32_t cand[kSmallSelectMax];  // global-scan candidates
+    __shared__ uint32_t keyl[kSmallSelectMax];
+    __shared__ uint32_t keyg[kSmallSelectMax];
+    __shared__ uint8_t flag[kSmallSelectMax];
     __shared__ int wsum[16];
     const int N = a.gh * a.gw;
     const int bc = blockIdx.x, b = bc / a.C, c = bc - b * a.C;
@@ -301,51 +365,75 @@ __global__ __launch_bounds__(1024) void encoder_select_small_kernel(EncSelectArg
     const int T_img = a.C * N;
     const bool live = j < N;
 
-    uint32_t kg_key = 0, kl_key = 0;
     if (live) {
-        float sg = 0.f, sl = 0.f;
-        const float *hg = a.head_global + (int64_t)bc * a.H * N + j;
-        for (int h = 0; h < a.H; ++h) sg += hg[(int64_t)h * N];
-        sg *= a.norm;
-        kg_key = float_to_key(sg);
+        const float sg = head_sum(a.head_global + (int64_t)bc * a.H * N + j, a.H, N) * a.norm;
+        const uint32_t kg_key = float_to_key(sg);
+        keyg[j] = kg_key;
         if (a.scores_out) a.scores_out[(int64_t)b * T_img + (int64_t)c * N + j] = sg;
-        if (a.head_local) {
-            const float *hl = a.head_local + (int64_t)bc * a.H * N + j;
-            for (int h = 0; h < a.H; ++h) sl += hl[(int64_t)h * N];
-            kl_key = float_to_key(sl * a.norm);
-        } else {
-            kl_key = kg_key;
-        }
+        keyl[j] = a.head_local
+                      ? float_to_key(head_sum(a.head_local + (int64_t)bc * a.H * N + j, a.H, N) *
+                                     a.norm)
+                      : kg_key;
+        flag[j] = 0;
     }
-    keyl[j] = kl_key;  // 0 past the end
     __syncthreads();
 
-    // local scan: rank inside the token's own window
-    bool local = false;
-    if (live && a.kw > 0) {
-        const int r = j / a.gw, col = j - r * a.gw;
-        const int wy = r * a.wr / a.gh, wx = col * a.wc / a.gw;
-        const int r0 = ceil_div(wy * a.gh, a.wr), r1 = ceil_div((wy + 1) * a.gh, a.wr);
-        const int c0 = ceil_div(wx * a.gw, a.wc), c1 = ceil_div((wx + 1) * a.gw, a.wc);
-        int cnt = 0;
-        for (int rr = r0; rr < r1; ++rr)
-            for (int cc = c0; cc < c1; ++cc) {
-                const int i = rr * a.gw + cc;
-                const uint32_t ki = keyl[i];
-                cnt += (ki > kl_key) || (ki == kl_key && i < j);
+    // local scan.  Small windows: every token counts the tokens of its own window that
+    // beat it (a few dozen pipelined LDS reads, no serial search).  Large windows: one wave
+    // per window searches the threshold, windows round-robin over the waves.
+    if (NREG_W == 0) {
+        if (live && a.kw > 0) {
+            const int r = j / a.gw, col = j - r * a.gw;
+            const int wy = r * a.wr / a.gh, wx = col * a.wc / a.gw;
+            const int r0 = ceil_div(wy * a.gh, a.wr), r1 = ceil_div((wy + 1) * a.gh, a.wr);
+            const int c0 = ceil_div(wx * a.gw, a.wc), c1 = ceil_div((wx + 1) * a.gw, a.wc);
+            const uint32_t kj = keyl[j];
+            int cnt = 0;
+            for (int rr = r0; rr < r1; ++rr) {
+                const int row0 = rr * a.gw;
+#pragma unroll 4
+                for (int cc = c0; cc < c1; ++cc) {
+                    const int i = row0 + cc;
+                    const uint32_t ki = keyl[i];
+                    cnt += (ki > kj) || (ki == kj && i < j);
+                }
             }
-        local = cnt < a.kw;
+            if (cnt < a.kw) flag[j] = 1;
+        }
+    } else if (a.kw > 0) {
+        const int nW = a.wr * a.wc, nw = blockDim.x / kWave;
+        for (int w = wave_id(); w < nW; w += nw) {
+            const int wy = w / a.wc, wx = w - wy * a.wc;
+            const int r0 = ceil_div(wy * a.gh, a.wr), r1 = ceil_div((wy + 1) * a.gh, a.wr);
+            const int c0 = ceil_div(wx * a.gw, a.wc), c1 = ceil_div((wx + 1) * a.gw, a.wc);
+            const int wh = r1 - r0, ww = c1 - c0;
+            int shift = 0;
+            while ((1 << shift) < ww) ++shift;
+            const int gw = a.gw;
+            wave_topk_regs<(NREG_W > 0 ? NREG_W : 1)>(
+                [&](int sl, int &idx) -> uint32_t {
+                    const int rr = sl >> shift, cc = sl & ((1 << shift) - 1);
+                    idx = (r0 + rr) * gw + c0 + cc;
+                    return cc < ww ? keyl[idx] : 0u;
+                },
+                wh << shift, a.kw, flag, 1);
+        }
     }
-    cand[j] = (live && !local) ? kg_key : 0u;
     __syncthreads();
 
     // global scan over what the local scan left
-    bool global = false;
-    if (live && !local && a.kg > 0)
-        global = count_better(cand, (N + 3) >> 2, kg_key, j) < a.kg;
+    if (wave_id() == 0)
+        wave_topk_regs<NREG_G>(
+            [&](int sl, int &idx) -> uint32_t {
+                idx = sl;
+                return flag[sl] ? 0u : keyg[sl];
+            },
+            N, a.kg, flag, 2);
+    __syncthreads();
 
-    const bool kept = local || global;
-    const int slot = block_slot(kept, wsum);
+    const bool kept = live && flag[j] != 0;
+    int tot;
+    const int slot = block_excl_count(kept, wsum, tot);
     if (live) {
         const int Kseg = a.wr * a.wc * a.kw + a.kg;
         const int K = a.C * Kseg, U = T_img - K;
@@ -361,24 +449,31 @@ __global__ __launch_bounds__(1024) void encoder_select_small_kernel(EncSelectArg
     }
 }
 
+template <int NREG>
 __global__ __launch_bounds__(1024) void llm_select_small_kernel(LlmSelectArgs a) {
-    __shared__ __align__(16) uint32_t cand[kSmallSelectMax];
+    __shared__ uint32_t key[kSmallSelectMax];
+    __shared__ uint8_t flag[kSmallSelectMax];
     __shared__ int wsum[16];
     const int b = blockIdx.x, j = threadIdx.x, V = a.V;
     const bool live = j < V;
-    uint32_t key = 0;
     if (live) {
-        float s = 0.f;
-        const float *pp = a.part + (int64_t)b * a.Hkv * V + j;
-        for (int g = 0; g < a.Hkv; ++g) s += pp[(int64_t)g * V];
-        s *= a.norm;
-        key = float_to_key(s);
+        const float s = head_sum(a.part + (int64_t)b * a.Hkv * V + j, a.Hkv, V) * a.norm;
+        key[j] = float_to_key(s);
+        flag[j] = 0;
         if (a.scores_out) a.scores_out[(int64_t)b * V + j] = s;
     }
-    cand[j] = key;
     __syncthreads();
-    const bool kept = live && a.keep > 0 && count_better(cand, (V + 3) >> 2, key, j) < a.keep;
-    const int slot = block_slot(kept, wsum);
+    if (wave_id() == 0)
+        wave_topk_regs<NREG>(
+            [&](int sl, int &idx) -> uint32_t {
+                idx = sl;
+                return key[sl];
+            },
+            V, a.keep, flag, 1);
+    __syncthreads();
+    const bool kept = live && flag[j] != 0;
+    int tot;
+    const int slot = block_excl_count(kept, wsum, tot);
     if (kept) a.kept_idx[(int64_t)b * a.keep + slot] = j;
 }
 
@@ -392,8 +487,29 @@ size_t llm_select_lds_bytes(int V) { return sizeof(SelectSmem) + (size_t)V * 4 +
 hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
     const int N = a.gh * a.gw;
     if (N <= kSmallSelectMax) {
-        const int threads = ((N + 3) / 4 * 4 + kWave - 1) / kWave * kWave;
-        hipLaunchKernelGGL(encoder_select_small_kernel, dim3(a.B * a.C), dim3(threads), 0, s, a);
+        int threads = (N + kWave - 1) / kWave * kWave;
+        // registers a wave needs: the largest window (columns padded to a power of two)
+        // and the whole segment for the global scan
+        int wcols = 1;
+        while (wcols < (a.gw + a.wc - 1) / a.wc) wcols <<= 1;
+        const int win_slots = a.kw > 0 ? ((a.gh + a.wr - 1) / a.wr) * wcols : 0;
+        const bool count_windows = win_slots <= 256;  // rank by counting inside small windows
+        if (!count_windows) {  // one wave per window where that fits
+            const int want = a.wr * a.wc * kWave;
+            if (want > threads) threads = want < 1024 ? want : 1024;
+        }
+        const int nreg_g = (N + kWave - 1) / kWave;
+        const dim3 grid(a.B * a.C), block(threads);
+#define VSCAN_SEL(W, G) hipLaunchKernelGGL((encoder_select_small_kernel<W, G>), grid, block, 0, s, a)
+        if (count_windows) {
+            if (nreg_g <= 4) VSCAN_SEL(0, 4);
+            else if (nreg_g <= 10) VSCAN_SEL(0, 10);
+            else VSCAN_SEL(0, 16);
+        } else {
+            if (nreg_g <= 10) VSCAN_SEL(32, 10);
+            else VSCAN_SEL(32, 16);
+        }
+#undef VSCAN_SEL
         return hipGetLastError();
     }
     const size_t smem = encoder_select_lds_bytes(N, a.head_local != nullptr);
@@ -409,8 +525,11 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
 
 hipError_t launch_llm_select(const LlmSelectArgs &a, hipStream_t s) {
     if (a.V <= kSmallSelectMax) {
-        const int threads = ((a.V + 3) / 4 * 4 + kWave - 1) / kWave * kWave;
-        hipLaunchKernelGGL(llm_select_small_kernel, dim3(a.B), dim3(threads), 0, s, a);
+        const int threads = (a.V + kWave - 1) / kWave * kWave;
+        if (threads <= 4 * kWave)
+            hipLaunchKernelGGL(llm_select_small_kernel<4>, dim3(a.B), dim3(threads), 0, s, a);
+        else
+            hipLaunchKernelGGL(llm_select_small_kernel<16>, dim3(a.B), dim3(threads), 0, s, a);
         return hipGetLastError();
     }
     const size_t smem = llm_select_lds_bytes(a.V);

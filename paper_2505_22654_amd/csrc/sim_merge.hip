@@ -192,10 +192,15 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
 
 // ---------------------------------------------------------------------------
 // Eq. 4.  One wave per kept slot.  The wave scans the image's assignment words
-// 64 tokens at a time; matches come out of a ballot as a wave-uniform mask, so
-// members are visited in ascending token order with no LDS and no barrier.
+// 64 tokens at a time; matches come out of a ballot in ascending token order and
+// are appended to a small per-wave list, which is then drained eight members at
+// a time so that many row loads are in flight together (members are still added
+// in ascending order).  No barrier: only lanes of one wave touch a list.
 // Lane l owns the 16-byte pieces l, l+64, ... of the feature row.
 // ---------------------------------------------------------------------------
+constexpr int kMergeListCap = 128;
+constexpr int kMergeBatch = 8;
+
 template <typename T, int PIECES>
 __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
                                                     const unsigned long long *__restrict__ best,
@@ -203,8 +208,10 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
                                                     int32_t *__restrict__ assign_out, int T_img,
                                                     int D, int K, int BK) {
     constexpr int E = ElemTraits<T>::kPer16B;
+    __shared__ int lists[4][kMergeListCap];
     const int row = blockIdx.x * 4 + wave_id();
     if (row >= BK) return;
+    int *list = lists[wave_id()];
     const int b = row / K, slot = row - b * K;
     const int lane = lane_id();
     const unsigned long long *bb = best + (int64_t)b * T_img;
@@ -219,7 +226,32 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
 #pragma unroll
         for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
 
-    int count = 0;
+    int count = 0, nlist = 0;
+    auto drain = [&]() {
+        for (int m = 0; m < nlist; m += kMergeBatch) {
+            int tok[kMergeBatch];
+#pragma unroll
+            for (int i = 0; i < kMergeBatch; ++i) tok[i] = list[min(m + i, nlist - 1)];
+#pragma unroll
+            for (int p = 0; p < PIECES; ++p) {
+                const int piece = lane + p * kWave;
+                uint4 raw[kMergeBatch];
+#pragma unroll
+                for (int i = 0; i < kMergeBatch; ++i)
+                    raw[i] = load16_guard(xb, tok[i] * row_bytes + (int64_t)piece * 16,
+                                          m + i < nlist && piece < npieces);
+#pragma unroll
+                for (int i = 0; i < kMergeBatch; ++i) {
+                    float v[E];
+                    unpack16<T>(raw[i], v);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[p][e] += v[e];
+                }
+            }
+        }
+        nlist = 0;
+    };
+
     constexpr int SCAN = 8;  // assignment words fetched ahead per lane
     for (int base = 0; base < T_img; base += SCAN * kWave) {
         unsigned long long w[SCAN];
@@ -230,43 +262,20 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
         }
 #pragma unroll
         for (int u = 0; u < SCAN; ++u) {
-            const int t0 = base + u * kWave;
-            const bool mine = t0 + lane < T_img && (int)(~(uint32_t)(w[u] & 0xffffffffull)) == slot;
-            if (mine && assign_out) assign_out[(int64_t)b * T_img + t0 + lane] = slot;
-            uint64_t mask = __ballot(mine);
-            count += __popcll(mask);
-            while (mask) {
-                // up to four members at a time, rows fetched together, added in order
-                int tok[4];
-                int n = 0;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    tok[i] = 0;
-                    if (mask) {
-                        tok[i] = t0 + __ffsll((unsigned long long)mask) - 1;
-                        mask &= mask - 1;
-                        n = i + 1;
-                    }
-                }
-#pragma unroll
-                for (int p = 0; p < PIECES; ++p) {
-                    const int piece = lane + p * kWave;
-                    uint4 raw[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        raw[i] = load16_guard(xb, tok[i] * row_bytes + (int64_t)piece * 16,
-                                              i < n && piece < npieces);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float v[E];
-                        unpack16<T>(raw[i], v);
-#pragma unroll
-                        for (int e = 0; e < E; ++e) acc[p][e] += v[e];
-                    }
-                }
+            const int t = base + u * kWave + lane;
+            const bool mine = t < T_img && (int)(~(uint32_t)(w[u] & 0xffffffffull)) == slot;
+            const uint64_t mask = __ballot(mine);
+            if (mine) {
+                list[nlist + __popcll(mask & lanemask_lt())] = t;
+                if (assign_out) assign_out[(int64_t)b * T_img + t] = slot;
             }
+            const int n = __popcll(mask);
+            nlist += n;
+            count += n;
+            if (nlist > kMergeListCap - kWave) drain();
         }
     }
+    drain();
 
     const float inv = 1.0f / (float)count;
     unsigned char *out = reinterpret_cast<unsigned char *>(merged) + (int64_t)row * row_bytes;
@@ -309,8 +318,8 @@ hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
     const int U = a.T - a.K;
     const long tiles128 = (long)((U + 127) / 128) * ((a.K + 127) / 128) * a.B;
     const bool big = tiles128 >= 512;
-    if (a.is_bf16) return big ? sim_t<bf16_t, 2, 2, 4>(a, s) : sim_t<bf16_t, 1, 1, 16>(a, s);
-    return big ? sim_t<float, 2, 2, 4>(a, s) : sim_t<float, 1, 1, 16>(a, s);
+    if (a.is_bf16) return big ? sim_t<bf16_t, 2, 2, 4>(a, s) : sim_t<bf16_t, 1, 1, 8>(a, s);
+    return big ? sim_t<float, 2, 2, 4>(a, s) : sim_t<float, 1, 1, 8>(a, s);
 }
 
 template <typename T>
