@@ -126,14 +126,20 @@ class DeviceCase:
                 for n, t in self.pristine.items():
                     s[n].copy_(t)
 
-    def run(self, i: int):
+    def run_encoder(self):
         if self.enc_in is not None:
             self.vb.encoder_reduce(self.w.encoder, self.enc_in["q"], self.enc_in["k"],
                                    self.enc_in["x"], workspace=self.enc_ws, out=self.enc_out)
+
+    def run_llm(self, i: int):
         if self.llm_in:
             s = self.llm_in[i % len(self.llm_in)]
             self.vb.llm_prune(self.w.llm, s["q"], s["k"], s["v"], s["hidden"],
                               workspace=self.llm_ws, out=self.llm_out)
+
+    def run(self, i: int):
+        self.run_encoder()
+        self.run_llm(i)
 
 
 def _to_device(a, dtype):
@@ -212,6 +218,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
+                    help="also run N plain device copies of 256 MiB (a kernel of known traffic "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
+                    help="2: issue the encoder calls and the LLM calls of a step on two streams "
+                         "(they are independent in this benchmark); default 1 = strictly serial")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path shards by image / "
@@ -223,6 +235,14 @@ def main():
         sys.exit("bench.py: no GPU visible")
     vb.lib()
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.calibrate_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     index = int(args.workload[3:])
     points = sweep_points(index)
     hosts = host_inputs(points)
@@ -233,9 +253,23 @@ def main():
     ring = steps if in_place else 1
     cases = [DeviceCase(w, h, ring) for w, h in zip(points, hosts)]
 
+    side = torch.cuda.Stream() if args.streams == 2 else None
+
     def step(i):
+        if side is None:
+            for c in cases:
+                c.run(i)
+            return
+        # encoder calls on the current stream, LLM calls on a second one; both sides are
+        # joined again before the step ends
+        main_stream = torch.cuda.current_stream()
+        side.wait_stream(main_stream)
         for c in cases:
-            c.run(i)
+            c.run_encoder()
+        with torch.cuda.stream(side):
+            for c in cases:
+                c.run_llm(i)
+        main_stream.wait_stream(side)
 
     for i in range(warmup):
         step(i)
@@ -298,6 +332,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": args.workload + ": " + ", ".join(w.name for w in points),
+                   "streams": args.streams,
                    "tokens_reduced_per_step": reduced,
                    "step": "encoder_reduce + llm_prune for every keep budget of the sweep"},
         "roofline": roof,

@@ -204,6 +204,32 @@ __device__ __forceinline__ void mma16_chunk<float>(f32x4_t &acc, const uint4 &a,
                                                0, 0);
 }
 
+// ---------------------------------------------------------------------------
+// Workgroup -> (image, item) mapping that keeps every image on one XCD.
+// Workgroups are handed to the 8 XCDs round-robin by linear index, and each XCD
+// has its own L2.  With `affine` set, image b is served only by XCD (b mod 8), so
+// rows of its feature matrix that one kernel pulled into that L2 are still there
+// for the next workgroup - and for the next kernel that maps images the same way.
+// Grid size: image_affine_grid().  Returns false for a padding workgroup.
+// ---------------------------------------------------------------------------
+constexpr int kXcds = 8;
+__host__ __device__ inline int image_affine_grid(int images, int per_image, bool affine) {
+    return affine ? kXcds * ((images + kXcds - 1) / kXcds) * per_image : images * per_image;
+}
+__device__ __forceinline__ bool image_affine_decode(int images, int per_image, bool affine,
+                                                    int &image, int &item) {
+    const int id = blockIdx.x;
+    if (affine) {
+        const int j = id / kXcds;
+        image = (id % kXcds) + kXcds * (j / per_image);
+        item = j % per_image;
+        return image < images;
+    }
+    image = id / per_image;
+    item = id % per_image;
+    return true;
+}
+
 __device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
 
 // 16-byte global load, zero when `valid` is false (never touches memory then).

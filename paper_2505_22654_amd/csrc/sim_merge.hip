@@ -32,7 +32,8 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
                                                          const int32_t *__restrict__ kept_idx,
                                                          const int32_t *__restrict__ drop_idx,
                                                          unsigned long long *__restrict__ best,
-                                                         int T_img, int D, int K, int U) {
+                                                         int T_img, int D, int K, int U, int B,
+                                                         int affine) {
     constexpr int E = ElemTraits<T>::kPer16B;
     constexpr int BM = 64 * TM, BN = 64 * TN, ROWS = BM + BN;
     constexpr int PPR = KC * 2;                 // 16-byte pieces per row per stage
@@ -44,8 +45,10 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
     __shared__ __align__(16) unsigned char lds[2][ROWS * STRIDE];
     __shared__ float inv_s[BM];
 
-    const int b = blockIdx.z;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int tiles_n = (U + BN - 1) / BN, tiles_m = (K + BM - 1) / BM;
+    int b, tile;
+    if (!image_affine_decode(B, tiles_m * tiles_n, affine != 0, b, tile)) return;
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
     const int tid = threadIdx.x, lane = lane_id(), g = lane >> 5;
     const int wm = wave_id() >> 1, wn = wave_id() & 1;
     const int row_bytes = D * (int)sizeof(T);
@@ -206,13 +209,15 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
                                                     const unsigned long long *__restrict__ best,
                                                     T *__restrict__ merged,
                                                     int32_t *__restrict__ assign_out, int T_img,
-                                                    int D, int K, int BK) {
+                                                    int D, int K, int B, int affine) {
     constexpr int E = ElemTraits<T>::kPer16B;
     __shared__ int lists[4][kMergeListCap];
-    const int row = blockIdx.x * 4 + wave_id();
-    if (row >= BK) return;
+    int b, group;
+    if (!image_affine_decode(B, (K + 3) / 4, affine != 0, b, group)) return;
+    const int slot = group * 4 + wave_id();
+    if (slot >= K) return;
+    const int row = b * K + slot;
     int *list = lists[wave_id()];
-    const int b = row / K, slot = row - b * K;
     const int lane = lane_id();
     const unsigned long long *bb = best + (int64_t)b * T_img;
     const unsigned char *xb = reinterpret_cast<const unsigned char *>(x) +
@@ -303,13 +308,24 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
+// Images are pinned to XCDs when there are enough of them to keep all eight busy and one
+// XCD's share of the feature matrix has a chance to stay in its 4 MiB L2.
+static bool image_affinity(const MergeArgs &a) {
+    const int64_t image_bytes = (int64_t)a.T * a.D * (a.is_bf16 ? 2 : 4);
+    const int per_xcd = (a.B + kXcds - 1) / kXcds;
+    return a.B >= kXcds && per_xcd * image_bytes <= (int64_t)8 << 20;
+}
+
 template <typename T, int TM, int TN, int KC>
 static hipError_t sim_t(const MergeArgs &a, hipStream_t s) {
     const int U = a.T - a.K;
     if (U <= 0) return hipSuccess;  // nothing was dropped: every token keeps its own slot
-    dim3 grid((U + 64 * TN - 1) / (64 * TN), (a.K + 64 * TM - 1) / (64 * TM), a.B);
+    const int tiles = ((U + 64 * TN - 1) / (64 * TN)) * ((a.K + 64 * TM - 1) / (64 * TM));
+    const bool affine = image_affinity(a);
+    dim3 grid(image_affine_grid(a.B, tiles, affine));
     hipLaunchKernelGGL((sim_argmax_kernel<T, TM, TN, KC>), grid, dim3(256), 0, s, (const T *)a.x,
-                       a.kept_idx, a.drop_idx, (unsigned long long *)a.best, a.T, a.D, a.K, U);
+                       a.kept_idx, a.drop_idx, (unsigned long long *)a.best, a.T, a.D, a.K, U, a.B,
+                       (int)affine);
     return hipGetLastError();
 }
 hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
@@ -326,12 +342,12 @@ template <typename T>
 static hipError_t merge_t(const MergeArgs &a, hipStream_t s) {
     constexpr int E = ElemTraits<T>::kPer16B;
     const int per_lane = (a.D / E + kWave - 1) / kWave;
-    const int rows = a.B * a.K;
-    dim3 grid((rows + 3) / 4);
+    const bool affine = image_affinity(a);
+    dim3 grid(image_affine_grid(a.B, (a.K + 3) / 4, affine));
 #define VSCAN_MERGE(P)                                                                          \
     hipLaunchKernelGGL((merge_kernel<T, P>), grid, dim3(256), 0, s, (const T *)a.x,              \
                        (const unsigned long long *)a.best, (T *)a.merged, a.assign_out, a.T, a.D, \
-                       a.K, rows)
+                       a.K, a.B, (int)affine)
     if (per_lane <= 1) VSCAN_MERGE(1);
     else if (per_lane <= 2) VSCAN_MERGE(2);
     else if (per_lane <= 3) VSCAN_MERGE(3);
