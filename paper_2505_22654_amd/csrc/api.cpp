@@ -64,6 +64,7 @@ int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
     p->U = p->T - p->K;
     // limits of the kernels
     if (d->feat_dim * es > 16 * 1024) return VSCAN_ERR_UNSUPPORTED;
+    if ((int64_t)p->T * d->feat_dim * es >= ((int64_t)1 << 31)) return VSCAN_ERR_UNSUPPORTED;
     if (d->score_mode == VSCAN_SCORE_MEAN_RECEIVED && d->head_dim * es > 512)
         return VSCAN_ERR_UNSUPPORTED;
     if (encoder_select_lds_bytes(p->N, with_local) > kLdsBudget) return VSCAN_ERR_UNSUPPORTED;

@@ -251,6 +251,7 @@ __global__ __launch_bounds__(256, 2) void mean_lse_kernel(const T *__restrict__ 
                                 qrow < N && 32 * c + 16 * g < row_bytes);
 
     float m_run = -INFINITY, l_run = 0.f;
+    bool have_ref = false;
     Stage st;
     const int ntiles = (n_keys + kMeanTile - 1) / kMeanTile;
     st.load(kbase, 0, n_keys, row_bytes);
@@ -272,22 +273,43 @@ __global__ __launch_bounds__(256, 2) void mean_lse_kernel(const T *__restrict__ 
             }
             // acc[r] = q_row(lane%32) . k_(key0 + acc_row(r)); mask the ragged tail
             const int key0 = t * kMeanTile + sub * 32;
-            float mx = -INFINITY;
             if (key0 + 32 > n_keys) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (key0 + acc_row(r) >= n_keys) acc[r] = -INFINITY;
             }
+            // Lazy reference: exponentials are taken against a per-lane reference m_run that
+            // is an actual logit of the row (so the sum is >= 1 and small terms may underflow
+            // harmlessly) and is only raised when the partial sum threatens to overflow.  That
+            // removes the per-element running max; the rescue path is rare.
+            if (!have_ref) {
+                float mx = -INFINITY;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[r]);
-            const float m_new = fmaxf(m_run, mx * sl2);
-            if (m_new > -INFINITY) {
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+                if (mx > -INFINITY) {
+                    m_run = mx * sl2;
+                    have_ref = true;
+                }
+            }
+            if (have_ref) {
                 float add = 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    add += __builtin_amdgcn_exp2f(fmaf(acc[r], sl2, -m_new));
-                l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + add;
-                m_run = m_new;
+                    add += __builtin_amdgcn_exp2f(fmaf(acc[r], sl2, -m_run));
+                if (add < 0x1p100f) {
+                    l_run += add;
+                } else {  // a logit far above the reference: re-base on this tile's maximum
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+                    const float m_new = fmaxf(m_run, mx * sl2);
+                    add = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        add += __builtin_amdgcn_exp2f(fmaf(acc[r], sl2, -m_new));
+                    l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + add;
+                    m_run = m_new;
+                }
             }
         }
         if (t + 1 < ntiles) st.store(lds[(t + 1) & 1]);

@@ -14,9 +14,12 @@ namespace vscan {
 //   part[b][g][j] = sum_r softmax(row r)_j          (j over the visual span).
 // ---------------------------------------------------------------------------
 constexpr int kScoreDepth = 4;  // 16-key tiles a wave keeps in flight
+constexpr int kScoreWaves = 8;  // waves per workgroup: the logits of a long span leave LDS
+                                // room for one workgroup per CU, so it carries all the
+                                // memory-level parallelism of that CU
 
 template <typename T, int NC, int NRB>
-__global__ __launch_bounds__(256) void llm_score_kernel(const T *__restrict__ q,
+__global__ __launch_bounds__(kScoreWaves * kWave) void llm_score_kernel(const T *__restrict__ q,
                                                         const T *__restrict__ k,
                                                         float *__restrict__ part, int Hq, int Hkv,
                                                         int Tq, int S, int dh, int vis_start, int V,
@@ -47,10 +50,11 @@ __global__ __launch_bounds__(256) void llm_score_kernel(const T *__restrict__ q,
         }
 
     const int ntiles = nk16 >> 4;
-    const int my_tiles = ntiles > w ? (ntiles - w + 3) >> 2 : 0;  // tiles w, w+4, ...
+    // this wave's tiles: w, w + kScoreWaves, ...
+    const int my_tiles = ntiles > w ? (ntiles - w + kScoreWaves - 1) / kScoreWaves : 0;
     uint4 ring[kScoreDepth][NC];
     auto fetch = [&](int n, uint4 *dst) {
-        const int key = (w + 4 * n) * 16 + l16;
+        const int key = (w + kScoreWaves * n) * 16 + l16;
         const bool ok = n < my_tiles && key < nk;
 #pragma unroll
         for (int c = 0; c < NC; ++c)
@@ -65,7 +69,7 @@ __global__ __launch_bounds__(256) void llm_score_kernel(const T *__restrict__ q,
         for (int d = 0; d < kScoreDepth; ++d) {
             const int n = n0 + d;
             if (n < my_tiles) {
-                const int key0 = (w + 4 * n) * 16;
+                const int key0 = (w + kScoreWaves * n) * 16;
 #pragma unroll
                 for (int rb = 0; rb < NRB; ++rb) {
                     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(256) void llm_score_kernel(const T *__restrict__ q,
     }
     __syncthreads();
 
-    for (int row = w; row < R; row += 4) {
+    for (int row = w; row < R; row += kScoreWaves) {
         const float *zr = z + (int64_t)row * nk16;
         float m = -INFINITY;
         for (int j = lane; j < nk16; j += kWave) m = fmaxf(m, zr[j]);
@@ -138,7 +142,8 @@ static hipError_t llm_score_launch(const LlmScoreArgs &a, hipStream_t s) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((llm_score_kernel<T, NC, NRB>), dim3(a.Hkv, a.B), dim3(256), smem, s,
+    hipLaunchKernelGGL((llm_score_kernel<T, NC, NRB>), dim3(a.Hkv, a.B), dim3(kScoreWaves * kWave),
+                       smem, s,
                        (const T *)a.q, (const T *)a.k, a.part, a.Hq, a.Hkv, a.Tq, a.S, a.dh,
                        a.vis_start, a.V, k0, nk, a.scale * 1.4426950408889634f);
     return hipGetLastError();

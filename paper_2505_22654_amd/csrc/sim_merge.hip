@@ -27,7 +27,7 @@ constexpr float kNormEps = 1e-12f;
 // are a handful of stages long, so their time is set by how many memory
 // round-trips are serialised, not by bandwidth.
 // ---------------------------------------------------------------------------
-template <typename T, int TM, int TN, int KC>
+template <typename T, int TM, int TN, int KC, bool DEEP>
 __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x,
                                                          const int32_t *__restrict__ kept_idx,
                                                          const int32_t *__restrict__ drop_idx,
@@ -55,8 +55,9 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
     const unsigned char *xb =
         reinterpret_cast<const unsigned char *>(x) + (int64_t)b * T_img * row_bytes;
 
-    // source byte offset of each piece this thread stages (-1: row outside the problem)
-    int64_t src[PER_THREAD];
+    // source byte offset of each piece this thread stages (-1: row outside the problem);
+    // 32 bits are enough: the ABI layer rejects images of 2 GiB or more
+    int src[PER_THREAD];
 #pragma unroll
     for (int it = 0; it < PER_THREAD; ++it) {
         const int p = tid + it * 256;
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
             if (n0 + r - BM < U) tok = drop_idx[(int64_t)b * U + n0 + r - BM];
         }
         tok = min(tok, T_img - 1);  // indices come from device memory: stay inside the image
-        src[it] = tok < 0 ? -1 : (int64_t)tok * row_bytes + (p - r * PPR) * 16;
+        src[it] = tok < 0 ? -1 : tok * row_bytes + (p - r * PPR) * 16;
     }
     float ss[A_PIECES];  // partial squared norms of the kept rows this thread stages
 #pragma unroll
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
             const int p = tid + it * 256;
             const int piece = p % PPR;
             const int col_byte = stage * KC * 32 + piece * 16;
-            regs[it] = load16_guard(xb, src[it] + (int64_t)stage * KC * 32,
+            regs[it] = load16_guard(xb, (int64_t)src[it] + (int64_t)stage * KC * 32,
                                     src[it] >= 0 && col_byte < row_bytes);
         }
     };
@@ -126,25 +127,41 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
         }
     };
 
-    // software pipeline, unrolled by two so the register sets are addressed statically:
-    // while stage s is multiplied out of LDS, stages s+1 and s+2 are in flight
     const int nstages = (row_bytes + KC * 32 - 1) / (KC * 32);
-    uint4 ra[PER_THREAD], rb[PER_THREAD];
-    stage_load(0, ra);
-    if (nstages > 1) stage_load(1, rb);
-    stage_store(lds[0], ra);
-    __syncthreads();
-    for (int st = 0; st < nstages; st += 2) {
-        if (st + 2 < nstages) stage_load(st + 2, ra);
-        compute(lds[0]);
-        if (st + 1 >= nstages) break;
-        stage_store(lds[1], rb);
+    if constexpr (DEEP) {
+        // short problems: while stage s is multiplied out of LDS, stages s+1 and s+2 are in
+        // flight (two register sets, loop unrolled by two so they are addressed statically)
+        uint4 ra[PER_THREAD], rb[PER_THREAD];
+        stage_load(0, ra);
+        if (nstages > 1) stage_load(1, rb);
+        stage_store(lds[0], ra);
         __syncthreads();
-        if (st + 3 < nstages) stage_load(st + 3, rb);
-        compute(lds[1]);
-        if (st + 2 < nstages) {
-            stage_store(lds[0], ra);
+        for (int st = 0; st < nstages; st += 2) {
+            if (st + 2 < nstages) stage_load(st + 2, ra);
+            compute(lds[0]);
+            if (st + 1 >= nstages) break;
+            stage_store(lds[1], rb);
             __syncthreads();
+            if (st + 3 < nstages) stage_load(st + 3, rb);
+            compute(lds[1]);
+            if (st + 2 < nstages) {
+                stage_store(lds[0], ra);
+                __syncthreads();
+            }
+        }
+    } else {
+        // long problems: one register set, so two workgroups fit a CU and hide each other
+        uint4 ra[PER_THREAD];
+        stage_load(0, ra);
+        stage_store(lds[0], ra);
+        __syncthreads();
+        for (int st = 0; st < nstages; ++st) {
+            if (st + 1 < nstages) stage_load(st + 1, ra);
+            compute(lds[st & 1]);
+            if (st + 1 < nstages) {
+                stage_store(lds[(st + 1) & 1], ra);
+                __syncthreads();
+            }
         }
     }
 
@@ -316,14 +333,14 @@ static bool image_affinity(const MergeArgs &a) {
     return a.B >= kXcds && per_xcd * image_bytes <= (int64_t)8 << 20;
 }
 
-template <typename T, int TM, int TN, int KC>
+template <typename T, int TM, int TN, int KC, bool DEEP>
 static hipError_t sim_t(const MergeArgs &a, hipStream_t s) {
     const int U = a.T - a.K;
     if (U <= 0) return hipSuccess;  // nothing was dropped: every token keeps its own slot
     const int tiles = ((U + 64 * TN - 1) / (64 * TN)) * ((a.K + 64 * TM - 1) / (64 * TM));
     const bool affine = image_affinity(a);
     dim3 grid(image_affine_grid(a.B, tiles, affine));
-    hipLaunchKernelGGL((sim_argmax_kernel<T, TM, TN, KC>), grid, dim3(256), 0, s, (const T *)a.x,
+    hipLaunchKernelGGL((sim_argmax_kernel<T, TM, TN, KC, DEEP>), grid, dim3(256), 0, s, (const T *)a.x,
                        a.kept_idx, a.drop_idx, (unsigned long long *)a.best, a.T, a.D, a.K, U, a.B,
                        (int)affine);
     return hipGetLastError();
@@ -334,8 +351,9 @@ hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
     const int U = a.T - a.K;
     const long tiles128 = (long)((U + 127) / 128) * ((a.K + 127) / 128) * a.B;
     const bool big = tiles128 >= 512;
-    if (a.is_bf16) return big ? sim_t<bf16_t, 2, 2, 4>(a, s) : sim_t<bf16_t, 1, 1, 8>(a, s);
-    return big ? sim_t<float, 2, 2, 4>(a, s) : sim_t<float, 1, 1, 8>(a, s);
+    if (a.is_bf16)
+        return big ? sim_t<bf16_t, 2, 2, 4, false>(a, s) : sim_t<bf16_t, 1, 1, 8, true>(a, s);
+    return big ? sim_t<float, 2, 2, 4, false>(a, s) : sim_t<float, 1, 1, 8, true>(a, s);
 }
 
 template <typename T>
