@@ -176,6 +176,42 @@ int vscan_profile_enable(int on);
 int vscan_profile_read(vscan_kernel_time *out, int capacity, int *count);
 
 /* ---------------------------------------------------------------------------
+ * Host-side budget arithmetic.  Pure functions of their arguments: no GPU, no
+ * state; all pointers are HOST pointers.
+ * ------------------------------------------------------------------------- */
+
+/* Token counts of the two stages for retention rates r1 (encoder stage) and r2
+ * (LLM stage), and the resulting average number of visual tokens over the LLM's
+ * layers (Sec. 5.1 "Implementation Details"; App. "Remarks on Ensuring Fair
+ * Comparisons": the first `prune_layer` of `n_layers` decoder layers see the
+ * stage-1 count, the rest the stage-2 count).
+ *   keep_encoder = nearest integer to r1 * n_visual   (halves round up)
+ *   keep_llm     = nearest integer to r2 * keep_encoder
+ *   avg_tokens   = (prune_layer * keep_encoder + (n_layers - prune_layer) * keep_llm) / n_layers
+ * n_visual is the unit the budget applies to (one image, or one crop of a
+ * multi-crop image).  Any output pointer may be NULL.
+ * Errors: VSCAN_ERR_SHAPE (n_visual < 0, n_layers <= 0, prune_layer outside
+ * [0, n_layers]), VSCAN_ERR_BUDGET (a rate outside [0, 1] or not finite). */
+int vscan_budget(int32_t n_visual, int32_t n_layers, int32_t prune_layer, double r1, double r2,
+                 int32_t *keep_encoder, int32_t *keep_llm, double *avg_tokens);
+
+/* Inverse of the above for a fixed r2 (the paper fixes r2 = 33.3 % and adjusts
+ * r1): the r1 whose layer-averaged retention equals avg_rate,
+ *   r1 = avg_rate * n_layers / (prune_layer + (n_layers - prune_layer) * r2).
+ * Errors as above, plus VSCAN_ERR_BUDGET when the answer would exceed 1 or the
+ * denominator is zero. */
+int vscan_budget_solve_r1(int32_t n_layers, int32_t prune_layer, double avg_rate, double r2,
+                          double *r1);
+
+/* Theoretical prefill FLOPs spent on visual tokens (Eq. 6, App. "Computational
+ * Complexity"): sum over layers of 4 n d^2 + 2 n^2 d + 3 n d m, with
+ * n = n_per_layer[layer] (host array of n_layers counts), d the hidden size and
+ * m the FFN intermediate size.  Errors: VSCAN_ERR_NULL, VSCAN_ERR_SHAPE
+ * (n_layers <= 0, d or m <= 0, a negative count). */
+int vscan_flops(const int32_t *n_per_layer, int32_t n_layers, int64_t d, int64_t m,
+                double *flops);
+
+/* ---------------------------------------------------------------------------
  * Misc
  * ------------------------------------------------------------------------- */
 const char *vscan_status_string(int status);

@@ -23,7 +23,7 @@ VSCAN_KEYS_VISUAL_ONLY, VSCAN_KEYS_ALL = 0, 1
 
 EXPORTS = ("vscan_encoder_workspace_size", "vscan_encoder_reduce", "vscan_llm_workspace_size",
            "vscan_llm_prune", "vscan_profile_enable", "vscan_profile_read", "vscan_status_string",
-           "vscan_version")
+           "vscan_version", "vscan_budget", "vscan_budget_solve_r1", "vscan_flops")
 
 
 class EncoderDesc(ctypes.Structure):
@@ -89,6 +89,15 @@ def lib():
         L.vscan_status_string.argtypes = [ctypes.c_int]
         L.vscan_status_string.restype = ctypes.c_char_p
         L.vscan_version.restype = ctypes.c_uint32
+        dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+        L.vscan_budget.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
+                                   ctypes.c_double, ip, ip, dp]
+        L.vscan_budget.restype = ctypes.c_int
+        L.vscan_budget_solve_r1.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
+                                            ctypes.c_double, dp]
+        L.vscan_budget_solve_r1.restype = ctypes.c_int
+        L.vscan_flops.argtypes = [ip, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, dp]
+        L.vscan_flops.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -115,6 +124,35 @@ def profile_read() -> Dict[str, Dict[str, float]]:
         raise VscanError(rc, "vscan_profile_read")
     return {buf[i].name.decode(): {"launches": int(buf[i].launches),
                                    "total_ms": float(buf[i].total_ms)} for i in range(n.value)}
+
+
+def budget(n_visual: int, n_layers: int, prune_layer: int, r1: float, r2: float):
+    """(keep_encoder, keep_llm, average tokens over the LLM layers) for retention rates r1, r2."""
+    n1, n2, avg = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_double(0.0)
+    rc = lib().vscan_budget(n_visual, n_layers, prune_layer, r1, r2, ctypes.byref(n1),
+                            ctypes.byref(n2), ctypes.byref(avg))
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_budget")
+    return int(n1.value), int(n2.value), float(avg.value)
+
+
+def budget_solve_r1(n_layers: int, prune_layer: int, avg_rate: float, r2: float) -> float:
+    """Stage-1 retention rate that gives the layer-averaged retention `avg_rate` at fixed r2."""
+    r1 = ctypes.c_double(0.0)
+    rc = lib().vscan_budget_solve_r1(n_layers, prune_layer, avg_rate, r2, ctypes.byref(r1))
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_budget_solve_r1")
+    return float(r1.value)
+
+
+def flops(n_per_layer, d: int, m: int) -> float:
+    """Eq. 6 for a per-layer list of visual token counts."""
+    arr = (ctypes.c_int32 * max(len(n_per_layer), 1))(*[int(n) for n in n_per_layer])
+    out = ctypes.c_double(0.0)
+    rc = lib().vscan_flops(arr, len(n_per_layer), d, m, ctypes.byref(out))
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_flops")
+    return float(out.value)
 
 
 def _dtype_code(dtype: str) -> int:

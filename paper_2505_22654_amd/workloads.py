@@ -135,9 +135,9 @@ class Workload:
     note: str = ""
 
 
-def _enc_llava(dtype, batch, crops, keep_total_per_seg, win):
+def _enc_llava(dtype, batch, crops, keep_total_per_seg, win, grid=24):
     half = keep_total_per_seg // 2
-    return EncoderShape(dtype=dtype, batch=batch, n_segments=crops, grid_h=24, grid_w=24,
+    return EncoderShape(dtype=dtype, batch=batch, n_segments=crops, grid_h=grid, grid_w=grid,
                         has_cls=1, score_mode=0, heads=16, head_dim=64, feat_dim=1024,
                         win_rows=win, win_cols=win, keep_global=keep_total_per_seg - half,
                         keep_local=half)
@@ -150,7 +150,8 @@ def _llm_llama(dtype, batch, prefix, vis, text, keep, n_query=1, in_place=0):
 
 
 def config(index: int, sweep: Optional[int] = None, batch: Optional[int] = None) -> Workload:
-    """The five benchmark configurations (1-based index).
+    """The benchmark configurations (1-based index; 6 is a video shape: 8 frames of 16x16
+    patches, 2048 visual tokens, at the 25 % average budget of the paper's video table).
 
     `sweep` picks the keep budget where a configuration sweeps one: the encoder
     keep {192,128,64} for 2 and the LLM keep {720,288,144} for 5."""
@@ -181,8 +182,14 @@ def config(index: int, sweep: Optional[int] = None, batch: Optional[int] = None)
         assert k in (720, 288, 144)
         llm = _llm_llama(BF16, 32, 35, 2880, 512, k, n_query=8, in_place=1)
         w = Workload(f"cfg5-llm-stress-keep{k}", seed, None, llm)
+    elif index == 6:
+        # 25 % average retention at R2 = 33.3 %, middle-layer pruning: R1 = 37.5 %, i.e. 96 of
+        # 256 tokens per frame (768 per video) before the LLM and 256 after (average 512 of 2048)
+        enc = _enc_llava(BF16, 4, 8, 96, 4, grid=16)
+        llm = _llm_llama(BF16, 4, 35, 768, 64, 256)
+        w = Workload("cfg6-video-8frames-b4", seed, enc, llm)
     else:
-        raise ValueError("config index must be 1..5")
+        raise ValueError("config index must be 1..6")
     if batch is not None:
         w = replace(w, encoder=None if w.encoder is None else replace(w.encoder, batch=batch),
                     llm=None if w.llm is None else replace(w.llm, batch=batch))

@@ -248,6 +248,14 @@ def test_config3_full():
     print("cfg3 llm", info, pu.check_llm(w.llm, inp, ref, _run_llm(w.llm, inp)))
 
 
+def test_config6_video_full():
+    w = wl.config(6)
+    inp, _, ref, info = pu.screened_encoder_case(w.encoder, w.seed)
+    print("cfg6 encoder", info, pu.check_encoder(w.encoder, inp, ref, _run_encoder(w.encoder, inp)))
+    inp, ref, info = pu.screened_llm_case(w.llm, w.seed)
+    print("cfg6 llm", info, pu.check_llm(w.llm, inp, ref, _run_llm(w.llm, inp)))
+
+
 def test_config4_llm_full():
     w = wl.config(4)
     inp, ref, info = pu.screened_llm_case(w.llm, w.seed)
