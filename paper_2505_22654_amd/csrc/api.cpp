@@ -330,7 +330,10 @@ int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, vo
     ca.k_out = k_out;
     ca.v_out = v_out;
     ca.hidden_out = hidden_out;
-    ca.kept_idx = kept_idx;
+    // The compaction kernels fetch an index for every row from a clamped position, so the
+    // table must be readable even when nothing is kept: the (never used) value then comes
+    // from the start of the workspace.
+    ca.kept_idx = d->keep > 0 ? kept_idx : reinterpret_cast<const int32_t *>(ws + p.off_part);
     ca.B = d->batch;
     ca.Hkv = d->kv_heads;
     ca.S = d->seq_len;

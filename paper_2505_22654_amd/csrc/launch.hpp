@@ -76,7 +76,7 @@ size_t llm_select_lds_bytes(int V);
 struct CompactArgs {
     void *k, *v, *hidden;              // sources (and destinations when in_place)
     void *k_out, *v_out, *hidden_out;  // NULL when in_place
-    const int32_t *kept_idx;           // [B, keep]
+    const int32_t *kept_idx;           // [B, keep]; at least one readable int when keep == 0
     int B, Hkv, S, dh, Dh, vis_start, V, keep, elem_bytes, in_place;
 };
 hipError_t launch_compact(const CompactArgs &a, hipStream_t s);

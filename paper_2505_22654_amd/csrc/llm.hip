@@ -214,11 +214,27 @@ __device__ __forceinline__ Strip decode_strip(const CompactArgs &a, int id, int 
     return s;
 }
 
-__device__ __forceinline__ int src_row(const CompactArgs &a, const int32_t *kept_b, int p) {
-    if (p < a.vis_start) return p;
-    if (p < a.vis_start + a.keep)  // clamped: the index comes from device memory
-        return a.vis_start + min(max(kept_b[p - a.vis_start], 0), a.V - 1);
-    return p + (a.V - a.keep);
+// Source rows of N output rows p[i].  The kept indices are fetched for every p from a clamped
+// position (never predicated, and pinned ahead of the selects by an empty asm so the compiler
+// cannot sink them into branches): the index loads of a tile are independent of each other and
+// all in flight together; a value is used only inside the kept span.  With keep == 0 the
+// table still holds one readable int.
+template <int N>
+__device__ __forceinline__ void src_rows(const CompactArgs &a, const int32_t *kept_b,
+                                         const int *p, int *sr) {
+    int kv[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        kv[i] = kept_b[min(max(p[i] - a.vis_start, 0), max(a.keep, 1) - 1)];
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(kv[i]));
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        // clamped: the index comes from device memory
+        const int kept_row = a.vis_start + min(max(kv[i], 0), a.V - 1);
+        sr[i] = p[i] < a.vis_start ? p[i]
+                                   : (p[i] < a.vis_start + a.keep ? kept_row : p[i] + (a.V - a.keep));
+    }
 }
 
 constexpr int kCompactRpt = 8;                   // rows per thread per tile
@@ -264,12 +280,15 @@ __global__ __launch_bounds__(256) void compact_inplace_kernel(CompactArgs a) {
     const int piece = tid & 15, rloc = tid >> 4;
     const bool col_ok = piece * 16 < s.width;
     auto load_tile = [&](int tile, uint4 *dst) {
+        int pr[kCompactRpt], sr[kCompactRpt];  // all index fetches first, then all row fetches
+#pragma unroll
+        for (int i = 0; i < kCompactRpt; ++i) pr[i] = p0 + tile * kCompactTile + i * 16 + rloc;
+        src_rows<kCompactRpt>(a, kept_b, pr, sr);
 #pragma unroll
         for (int i = 0; i < kCompactRpt; ++i) {
             const int p = p0 + tile * kCompactTile + i * 16 + rloc;
             const bool ok = col_ok && p < S_out;
-            const int sr = ok ? src_row(a, kept_b, p) : 0;
-            dst[i] = load16_guard(s.src, (int64_t)sr * s.src_stride + piece * 16, ok);
+            dst[i] = load16_guard(s.src, (int64_t)sr[i] * s.src_stride + piece * 16, ok);
         }
     };
     auto store_tile = [&](int tile, const uint4 *v) {
@@ -305,12 +324,15 @@ __global__ __launch_bounds__(256) void compact_gather_kernel(CompactArgs a) {
     const int piece = threadIdx.x & 15, rloc = threadIdx.x >> 4;
     if (piece * 16 >= s.width) return;
     uint4 v[kCompactRpt];
+    int pr[kCompactRpt], sr[kCompactRpt];  // all index fetches first, then all row fetches
+#pragma unroll
+    for (int i = 0; i < kCompactRpt; ++i) pr[i] = blockIdx.y * kCompactTile + i * 16 + rloc;
+    src_rows<kCompactRpt>(a, kept_b, pr, sr);
 #pragma unroll
     for (int i = 0; i < kCompactRpt; ++i) {
         const int p = blockIdx.y * kCompactTile + i * 16 + rloc;
         const bool ok = p < S_out;
-        const int sr = ok ? src_row(a, kept_b, p) : 0;
-        v[i] = load16_guard(s.src, (int64_t)sr * s.src_stride + piece * 16, ok);
+        v[i] = load16_guard(s.src, (int64_t)sr[i] * s.src_stride + piece * 16, ok);
     }
 #pragma unroll
     for (int i = 0; i < kCompactRpt; ++i) {

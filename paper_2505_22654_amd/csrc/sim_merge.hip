@@ -58,18 +58,34 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
     // source byte offset of each piece this thread stages (-1: row outside the problem);
     // 32 bits are enough: the ABI layer rejects images of 2 GiB or more
     int src[PER_THREAD];
+    {
+        // token of every row this thread stages.  Positions are clamped, not predicated: the
+        // index loads stay independent of each other and are all in flight together.  A thread's
+        // first A_PIECES pieces belong to kept rows, the rest to dropped rows.
+        int tok[PER_THREAD];
 #pragma unroll
-    for (int it = 0; it < PER_THREAD; ++it) {
-        const int p = tid + it * 256;
-        const int r = p / PPR;
-        int tok = -1;
-        if (r < BM) {
-            if (m0 + r < K) tok = kept_idx[(int64_t)b * K + m0 + r];
-        } else {
-            if (n0 + r - BM < U) tok = drop_idx[(int64_t)b * U + n0 + r - BM];
+        for (int it = 0; it < PER_THREAD; ++it) {
+            const int r = (tid + it * 256) / PPR;
+            tok[it] = it < A_PIECES ? kept_idx[(int64_t)b * K + min(m0 + r, K - 1)]
+                                    : drop_idx[(int64_t)b * U + min(n0 + r - BM, U - 1)];
         }
-        tok = min(tok, T_img - 1);  // indices come from device memory: stay inside the image
-        src[it] = tok < 0 ? -1 : tok * row_bytes + (p - r * PPR) * 16;
+#pragma unroll
+        for (int it = 0; it < PER_THREAD; ++it) {
+            const int p = tid + it * 256;
+            const int r = p / PPR;
+            const bool inside = it < A_PIECES ? m0 + r < K : n0 + r - BM < U;
+            // indices come from device memory: stay inside the image
+            const int t = min(max(tok[it], 0), T_img - 1);
+            src[it] = inside ? t * row_bytes + (p - r * PPR) * 16 : -1;
+        }
+    }
+    // dropped token of each result column this lane reports in the epilogue (fetched here so
+    // that the latency is long gone by then)
+    int col_tok[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+        col_tok[j] = drop_idx[(int64_t)b * U + min(col, U - 1)];
     }
     float ss[A_PIECES];  // partial squared norms of the kept rows this thread stages
 #pragma unroll
@@ -204,120 +220,209 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
         if (other > packed) packed = other;
         const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
         if (g == 0 && col < U && packed != 0ull) {
-            const int tok = min(max(drop_idx[(int64_t)b * U + col], 0), T_img - 1);
+            const int tok = min(max(col_tok[j], 0), T_img - 1);
             atomicMax(best + (int64_t)b * T_img + tok, packed);
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 4.  One wave per kept slot.  The wave scans the image's assignment words
-// 64 tokens at a time; matches come out of a ballot in ascending token order and
-// are appended to a small per-wave list, which is then drained eight members at
-// a time so that many row loads are in flight together (members are still added
-// in ascending order).  No barrier: only lanes of one wave touch a list.
+// Eq. 4.  A workgroup (4 waves) owns 4 * spw consecutive kept slots of one image.
+//
+// Phase 1 (whole workgroup): one pass over the image's assignment words; a token whose slot
+// belongs to the workgroup is appended to that slot's member list in LDS (position from an LDS
+// counter, so the order inside a list is arbitrary at this point).
+// Phase 2 (one wave per slot, spw slots one after the other): groups of up to kMergeSortCap
+// members.  The list is sorted by token index (rank by counting, one member per lane) and
+// drained a batch of rows at a time, so that many row loads are in flight together; members are
+// added in ascending token order.
+// Phase 3 (whole workgroup, one large group after the other): group sizes are heavy-tailed (many
+// dropped tokens look like the same kept token), and one wave adding hundreds of rows would set
+// the kernel's time.  Wave w gathers the members inside the w-th quarter of the token range
+// with an ordered ballot scan and adds them in ascending order; the four partial sums are
+// combined in wave order through LDS.
+// Every sum has a fixed order of additions, so results do not depend on scheduling.
 // Lane l owns the 16-byte pieces l, l+64, ... of the feature row.
 // ---------------------------------------------------------------------------
-constexpr int kMergeListCap = 128;
-constexpr int kMergeBatch = 8;
+constexpr int kMergeListCap = 128;  // ints of LDS per list
+constexpr int kMergeSortCap = 64;   // longest group that one wave sorts and adds
+constexpr int kMergeMaxSpw = 4;     // slots a wave handles one after the other, at most
 
 template <typename T, int PIECES>
 __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
                                                     const unsigned long long *__restrict__ best,
                                                     T *__restrict__ merged,
                                                     int32_t *__restrict__ assign_out, int T_img,
-                                                    int D, int K, int B, int affine) {
+                                                    int D, int K, int B, int affine, int spw) {
     constexpr int E = ElemTraits<T>::kPer16B;
-    __shared__ int lists[4][kMergeListCap];
+    constexpr int BATCH = PIECES <= 2 ? 16 : 8;  // rows fetched together (register budget)
+    __shared__ int cnt[4 * kMergeMaxSpw];
+    __shared__ int lists[4 * kMergeMaxSpw][kMergeListCap];
+    extern __shared__ float part[];  // D floats: partial sums of a large group
+    const int ns = 4 * spw;  // slots of this workgroup
     int b, group;
-    if (!image_affine_decode(B, (K + 3) / 4, affine != 0, b, group)) return;
-    const int slot = group * 4 + wave_id();
-    if (slot >= K) return;
-    const int row = b * K + slot;
-    int *list = lists[wave_id()];
-    const int lane = lane_id();
-    const unsigned long long *bb = best + (int64_t)b * T_img;
+    if (!image_affine_decode(B, (K + ns - 1) / ns, affine != 0, b, group)) return;
+    const int slot0 = group * ns;
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    // low halves of the assignment words: the complemented slot of every token
+    const uint32_t *slot_word = reinterpret_cast<const uint32_t *>(best + (int64_t)b * T_img);
     const unsigned char *xb = reinterpret_cast<const unsigned char *>(x) +
                               (int64_t)b * T_img * D * (int64_t)sizeof(T);
     const int npieces = D / E;
     const int64_t row_bytes = (int64_t)D * sizeof(T);
 
-    float acc[PIECES][E];
-#pragma unroll
-    for (int p = 0; p < PIECES; ++p)
-#pragma unroll
-        for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
+    if (tid < 4 * kMergeMaxSpw) cnt[tid] = 0;
+    __syncthreads();
 
-    int count = 0, nlist = 0;
-    auto drain = [&]() {
-        for (int m = 0; m < nlist; m += kMergeBatch) {
-            int tok[kMergeBatch];
+    constexpr int SCAN = 8;  // assignment words fetched ahead per thread
+    for (int base = 0; base < T_img; base += SCAN * 256) {
+        // The index is clamped, not predicated: the loads stay independent of each other and
+        // in flight together.
+        uint32_t w[SCAN];
 #pragma unroll
-            for (int i = 0; i < kMergeBatch; ++i) tok[i] = list[min(m + i, nlist - 1)];
+        for (int u = 0; u < SCAN; ++u) w[u] = slot_word[2 * min(base + u * 256 + tid, T_img - 1)];
+#pragma unroll
+        for (int u = 0; u < SCAN; ++u) {
+            const int t = base + u * 256 + tid;
+            const int s = (int)(~w[u]);
+            const unsigned rel = (unsigned)(s - slot0);
+            if (t < T_img && rel < (unsigned)ns && s < K) {
+                const int pos = atomicAdd(&cnt[rel], 1);
+                if (pos < kMergeListCap) lists[rel][pos] = t;
+                if (assign_out) assign_out[(int64_t)b * T_img + t] = s;
+            }
+        }
+    }
+    __syncthreads();
+
+    float acc[PIECES][E];
+    auto clear = [&]() {
+#pragma unroll
+        for (int p = 0; p < PIECES; ++p)
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
+    };
+    // adds rows list[0 .. n) to acc, in list order
+    auto drain = [&](const int *list, int n) {
+        for (int m = 0; m < n; m += BATCH) {
+            int tok[BATCH];
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) tok[j] = list[min(m + j, n - 1)];
 #pragma unroll
             for (int p = 0; p < PIECES; ++p) {
                 const int piece = lane + p * kWave;
-                uint4 raw[kMergeBatch];
+                uint4 raw[BATCH];
 #pragma unroll
-                for (int i = 0; i < kMergeBatch; ++i)
-                    raw[i] = load16_guard(xb, tok[i] * row_bytes + (int64_t)piece * 16,
-                                          m + i < nlist && piece < npieces);
+                for (int j = 0; j < BATCH; ++j)
+                    raw[j] = load16_guard(xb, tok[j] * row_bytes + (int64_t)piece * 16,
+                                          m + j < n && piece < npieces);
 #pragma unroll
-                for (int i = 0; i < kMergeBatch; ++i) {
+                for (int j = 0; j < BATCH; ++j) {
                     float v[E];
-                    unpack16<T>(raw[i], v);
+                    unpack16<T>(raw[j], v);
 #pragma unroll
                     for (int e = 0; e < E; ++e) acc[p][e] += v[e];
                 }
             }
         }
-        nlist = 0;
+    };
+    auto write_row = [&](int slot, int count) {
+        const float inv = 1.0f / (float)count;
+        unsigned char *out = reinterpret_cast<unsigned char *>(merged) +
+                             ((int64_t)b * K + slot) * row_bytes;
+#pragma unroll
+        for (int p = 0; p < PIECES; ++p) {
+            const int piece = lane + p * kWave;
+            if (piece < npieces) {
+                uint4 o;
+                if constexpr (sizeof(T) == 4) {
+                    o.x = __float_as_uint(acc[p][0] * inv);
+                    o.y = __float_as_uint(acc[p][1] * inv);
+                    o.z = __float_as_uint(acc[p][2] * inv);
+                    o.w = __float_as_uint(acc[p][3] * inv);
+                } else {
+                    o.x = f32_to_bf16_rne(acc[p][0] * inv) | (f32_to_bf16_rne(acc[p][1] * inv) << 16);
+                    o.y = f32_to_bf16_rne(acc[p][2] * inv) | (f32_to_bf16_rne(acc[p][3] * inv) << 16);
+                    o.z = f32_to_bf16_rne(acc[p][4] * inv) | (f32_to_bf16_rne(acc[p][5] * inv) << 16);
+                    o.w = f32_to_bf16_rne(acc[p][6] * inv) | (f32_to_bf16_rne(acc[p][7] * inv) << 16);
+                }
+                *reinterpret_cast<uint4 *>(out + (int64_t)piece * 16) = o;
+            }
+        }
     };
 
-    constexpr int SCAN = 8;  // assignment words fetched ahead per lane
-    for (int base = 0; base < T_img; base += SCAN * kWave) {
-        unsigned long long w[SCAN];
-#pragma unroll
-        for (int u = 0; u < SCAN; ++u) {
-            const int t = base + u * kWave + lane;
-            w[u] = t < T_img ? bb[t] : 0ull;
-        }
-#pragma unroll
-        for (int u = 0; u < SCAN; ++u) {
-            const int t = base + u * kWave + lane;
-            const bool mine = t < T_img && (int)(~(uint32_t)(w[u] & 0xffffffffull)) == slot;
-            const uint64_t mask = __ballot(mine);
-            if (mine) {
-                list[nlist + __popcll(mask & lanemask_lt())] = t;
-                if (assign_out) assign_out[(int64_t)b * T_img + t] = slot;
-            }
-            const int n = __popcll(mask);
-            nlist += n;
-            count += n;
-            if (nlist > kMergeListCap - kWave) drain();
-        }
+    // ---- phase 2: groups one wave handles alone
+    bool any_large = false;
+    for (int i = 0; i < spw; ++i) {
+        const int rel = wave + 4 * i;
+        const int slot = slot0 + rel;
+        if (slot >= K) break;
+        const int count = __builtin_amdgcn_readfirstlane(cnt[rel]);
+        if (count > kMergeSortCap) continue;
+        int *list = lists[rel];
+        // only this wave touches the list from here on; LDS operations of one wave complete
+        // in order, so the reads below are done before the sorted write-back
+        const int v = lane < count ? list[lane] : 0x7fffffff;
+        int rank = 0;
+        for (int j = 0; j < count; ++j) rank += (__builtin_amdgcn_readlane(v, j) < v) ? 1 : 0;
+        if (lane < count) list[rank] = v;
+        clear();
+        drain(list, count);
+        write_row(slot, count);
     }
-    drain();
+    for (int rel = 0; rel < ns; ++rel) any_large |= cnt[rel] > kMergeSortCap;
+    if (!any_large) return;  // the same decision in every wave: cnt is final since the barrier
+    __syncthreads();         // the lists are free from here on
 
-    const float inv = 1.0f / (float)count;
-    unsigned char *out = reinterpret_cast<unsigned char *>(merged) + (int64_t)row * row_bytes;
+    // ---- phase 3: large groups, all four waves on one group at a time
+    const int quarter = ((T_img + 4 * kWave - 1) / (4 * kWave)) * kWave;
+    const int t_begin = wave * quarter, t_end = min(T_img, t_begin + quarter);
+    int *list = lists[wave];
+    for (int rel = 0; rel < ns; ++rel) {
+        const int slot = slot0 + rel;
+        const int count = cnt[rel];
+        if (slot >= K || count <= kMergeSortCap) continue;  // uniform over the workgroup
+        clear();
+        int nlist = 0;
+        for (int base = t_begin; base < t_end; base += SCAN * kWave) {
+            uint32_t w[SCAN];
 #pragma unroll
-    for (int p = 0; p < PIECES; ++p) {
-        const int piece = lane + p * kWave;
-        if (piece < npieces) {
-            uint4 o;
-            if constexpr (sizeof(T) == 4) {
-                o.x = __float_as_uint(acc[p][0] * inv);
-                o.y = __float_as_uint(acc[p][1] * inv);
-                o.z = __float_as_uint(acc[p][2] * inv);
-                o.w = __float_as_uint(acc[p][3] * inv);
-            } else {
-                o.x = f32_to_bf16_rne(acc[p][0] * inv) | (f32_to_bf16_rne(acc[p][1] * inv) << 16);
-                o.y = f32_to_bf16_rne(acc[p][2] * inv) | (f32_to_bf16_rne(acc[p][3] * inv) << 16);
-                o.z = f32_to_bf16_rne(acc[p][4] * inv) | (f32_to_bf16_rne(acc[p][5] * inv) << 16);
-                o.w = f32_to_bf16_rne(acc[p][6] * inv) | (f32_to_bf16_rne(acc[p][7] * inv) << 16);
+            for (int u = 0; u < SCAN; ++u)
+                w[u] = slot_word[2 * min(base + u * kWave + lane, T_img - 1)];
+#pragma unroll
+            for (int u = 0; u < SCAN; ++u) {
+                const int t = base + u * kWave + lane;
+                const bool mine = t < t_end && (int)(~w[u]) == slot;
+                const uint64_t mask = __ballot(mine);
+                if (mine) list[nlist + __popcll(mask & lanemask_lt())] = t;
+                nlist += __popcll(mask);
+                if (nlist > kMergeListCap - kWave) {
+                    drain(list, nlist);
+                    nlist = 0;
+                }
             }
-            *reinterpret_cast<uint4 *>(out + (int64_t)piece * 16) = o;
+        }
+        drain(list, nlist);
+        // partial sums combined in wave order: part = acc0; part += acc1; part += acc2;
+        // wave 3 adds its own on top and writes the row
+        for (int w = 0; w < 4; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int p = 0; p < PIECES; ++p) {
+                    const int piece = lane + p * kWave;
+                    if (piece < npieces) {
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            float &slot_sum = part[piece * E + e];
+                            if (w == 0) slot_sum = acc[p][e];
+                            else if (w < 3) slot_sum += acc[p][e];
+                            else acc[p][e] = slot_sum + acc[p][e];
+                        }
+                    }
+                }
+                if (w == 3) write_row(slot, count);
+            }
+            __syncthreads();
         }
     }
 }
@@ -361,11 +466,17 @@ static hipError_t merge_t(const MergeArgs &a, hipStream_t s) {
     constexpr int E = ElemTraits<T>::kPer16B;
     const int per_lane = (a.D / E + kWave - 1) / kWave;
     const bool affine = image_affinity(a);
-    dim3 grid(image_affine_grid(a.B, (a.K + 3) / 4, affine));
+    // slots per wave: one while that still gives every CU two workgroups; more for very many
+    // slots, where the shared scan of the assignment words is what has to be amortised
+    int spw = 1;
+    while (spw < kMergeMaxSpw && (int64_t)a.B * a.K >= (int64_t)4 * 512 * 2 * spw) spw *= 2;
+    const int ns = 4 * spw;
+    dim3 grid(image_affine_grid(a.B, (a.K + ns - 1) / ns, affine));
+    const size_t part_bytes = (size_t)a.D * sizeof(float);  // at most 32 KiB (row <= 16 KiB)
 #define VSCAN_MERGE(P)                                                                          \
-    hipLaunchKernelGGL((merge_kernel<T, P>), grid, dim3(256), 0, s, (const T *)a.x,              \
+    hipLaunchKernelGGL((merge_kernel<T, P>), grid, dim3(256), part_bytes, s, (const T *)a.x,     \
                        (const unsigned long long *)a.best, (T *)a.merged, a.assign_out, a.T, a.D, \
-                       a.K, a.B, (int)affine)
+                       a.K, a.B, (int)affine, spw)
     if (per_lane <= 1) VSCAN_MERGE(1);
     else if (per_lane <= 2) VSCAN_MERGE(2);
     else if (per_lane <= 3) VSCAN_MERGE(3);

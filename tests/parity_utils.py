@@ -99,6 +99,31 @@ def screened_encoder_case(shape, seed, logit_gain=1.0, with_local=False, max_tri
     raise AssertionError(f"no seed in {max_tries} tries clears the boundary margin")
 
 
+def screened_encoder_batch(shape, seed, logit_gain=1.0, max_items=None):
+    """Like screened_encoder_case, but screens image by image: the batch is assembled from the
+    first `shape.batch` images of the seed's item streams whose boundaries clear MARGIN.  For
+    batches with so many boundaries that no whole-batch seed would pass."""
+    from dataclasses import replace
+    one = replace(shape, batch=1)
+    proj = wl.encoder_projections(shape, seed)
+    items, refs, tried = [], [], 0
+    max_items = max_items or 8 * shape.batch
+    N = shape.n_tokens
+    while len(items) < shape.batch:
+        assert tried < max_items, "too few images clear the boundary margin"
+        it = wl.encoder_item(shape, seed, tried, logit_gain, proj)
+        tried += 1
+        it = {key: it[key][None] for key in ("q", "k", "x")}
+        ref = vo.encoder_reduce(one, it["q"], it["k"], it["x"])
+        sg = ref["scores"].reshape(1, shape.n_segments, N)
+        if encoder_boundary_gap(one, sg, sg) > MARGIN:
+            items.append(it)
+            refs.append(ref)
+    inp = {key: np.concatenate([it[key] for it in items]) for key in ("q", "k", "x")}
+    ref = {key: np.concatenate([r[key] for r in refs]) for key in refs[0]}
+    return inp, None, ref, {"seed": seed, "images_tried": tried}
+
+
 def screened_llm_case(shape, seed, max_tries=16):
     for attempt in range(max_tries):
         inp = wl.llm_inputs(shape, seed + attempt)

@@ -222,6 +222,15 @@ def test_llm_exact_ties_large_span():
 
 # ----------------------------------------------------------------------------
 # The benchmark configurations at full size
+def test_encoder_many_slots():
+    """Enough kept slots in the batch that the merge gives every wave four slots in turn."""
+    shape = _enc(batch=32, grid_h=24, grid_w=24, heads=2, feat_dim=72, win_rows=4, win_cols=4,
+                 keep_global=128, keep_local=128)
+    inp, _, ref, info = pu.screened_encoder_batch(shape, seed=4242, logit_gain=1.0)
+    out = _run_encoder(shape, inp)
+    print("many-slots", info, pu.check_encoder(shape, inp, ref, out, "many-slots"))
+
+
 # ----------------------------------------------------------------------------
 def test_config1_full():
     w = wl.config(1)
