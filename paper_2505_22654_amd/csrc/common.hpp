@@ -232,6 +232,13 @@ __device__ __forceinline__ bool image_affine_decode(int images, int per_image, b
 
 __device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
 
+// 16-byte global load, unconditional: the caller guarantees the address is readable (typically
+// by clamping an index).  Loads that are not wrapped in a branch stay independent of each other,
+// so the compiler can keep several in flight and wait only for the one it needs.
+__device__ __forceinline__ uint4 load16(const void *base, int64_t byte_off) {
+    return *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(base) + byte_off);
+}
+
 // 16-byte global load, zero when `valid` is false (never touches memory then).
 __device__ __forceinline__ uint4 load16_guard(const void *base, int64_t byte_off, bool valid) {
     if (!valid) return zero16();

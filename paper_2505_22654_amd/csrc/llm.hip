@@ -7,37 +7,61 @@ namespace vscan {
 
 // ---------------------------------------------------------------------------
 // Scoring.  One workgroup per (sequence, kv head) streams that head's keys once
-// from HBM straight into matrix-core operands and multiplies them with all the
-// query rows sharing the kv head (R = (Hq/Hkv) * Tq rows, padded to 16 per
-// block).  Logits stay in LDS until the row maxima / sums are known, then the
-// normalised rows are summed in a fixed order into
+// from HBM and multiplies them on the matrix cores with all the query rows
+// sharing the kv head (R = (Hq/Hkv) * Tq rows, padded to 16 per block).  Logits
+// stay in LDS until the row maxima / sums are known, then the normalised rows
+// are summed in a fixed order into
 //   part[b][g][j] = sum_r softmax(row r)_j          (j over the visual span).
+//
+// How the keys reach the matrix cores (STAGED): a 16x16 operand wants lane l to
+// hold 16 bytes of key (l % 16), so loading operands straight from memory makes
+// every quarter-wave touch 16 different rows - 16 B per cache-line lookup, which
+// caps the CU's load path far below HBM speed.  Instead a wave fetches a tile
+// (16 consecutive keys = 16 * row_bytes contiguous bytes) fully coalesced, 1 KiB
+// per instruction, drops it into a private LDS staging area with padded rows and
+// reads it back in operand layout.  Only this wave touches its staging area and
+// the LDS operations of one wave complete in order, so no barrier is involved.
+// All global addresses are clamped into the key range (never predicated), which
+// keeps the loads independent: the compiler waits only for the tile it is about
+// to use while kScoreDepth - 1 later tiles stay in flight.
+// When the staging areas do not fit in LDS beside the logits, the operands are
+// loaded directly (!STAGED).
 // ---------------------------------------------------------------------------
 constexpr int kScoreDepth = 4;  // 16-key tiles a wave keeps in flight
 constexpr int kScoreWaves = 8;  // waves per workgroup: the logits of a long span leave LDS
                                 // room for one workgroup per CU, so it carries all the
                                 // memory-level parallelism of that CU
 
-template <typename T, int NC, int NRB>
+__host__ __device__ inline int score_logit_stride(int nk) {
+    // floats per logit row: >= nk rounded up to 16, and = 16 mod 64 so that the 16 query rows
+    // a wave writes at once start in different LDS banks
+    const int nk16 = (nk + 15) & ~15;
+    return nk16 + ((16 - nk16 % 64) + 64) % 64;
+}
+
+template <typename T, int NC, int NRB, bool STAGED>
 __global__ __launch_bounds__(kScoreWaves * kWave) void llm_score_kernel(const T *__restrict__ q,
                                                         const T *__restrict__ k,
                                                         float *__restrict__ part, int Hq, int Hkv,
                                                         int Tq, int S, int dh, int vis_start, int V,
                                                         int k0, int nk, float sl2) {
+    constexpr int STR = NC * 64 + 16;  // bytes per key in a staging area
     extern __shared__ __align__(16) unsigned char smem[];
     float *rowM = reinterpret_cast<float *>(smem);  // 64
     float *rowInvL = rowM + 64;                      // 64
-    float *z = rowInvL + 64;                         // [R][nk16]
+    float *z = rowInvL + 64;                         // [R][zs]
 
     const int g_kv = blockIdx.x, b = blockIdx.y;
     const int group = Hq / Hkv, R = group * Tq;
     const int nk16 = (nk + 15) & ~15;
+    const int zs = score_logit_stride(nk);
     const int row_bytes = dh * (int)sizeof(T);
     const unsigned char *qbase = reinterpret_cast<const unsigned char *>(q) +
                                  ((int64_t)b * Hq + (int64_t)g_kv * group) * Tq * row_bytes;
     const unsigned char *kbase = reinterpret_cast<const unsigned char *>(k) +
                                  (((int64_t)b * Hkv + g_kv) * S + k0) * row_bytes;
     const int lane = lane_id(), l16 = lane & 15, g = lane >> 4, w = wave_id();
+    unsigned char *stage = reinterpret_cast<unsigned char *>(z + (int64_t)R * zs) + w * 16 * STR;
 
     uint4 qfrag[NRB][NC];
 #pragma unroll
@@ -49,55 +73,105 @@ __global__ __launch_bounds__(kScoreWaves * kWave) void llm_score_kernel(const T 
                                         row < R && 64 * c + 16 * g < row_bytes);
         }
 
+    // STAGED: piece m of a tile that this lane fetches: byte 1024 m + 16 lane of the tile's
+    // 16 * row_bytes contiguous bytes = key tile_r[m], column tile_col[m] (lanes past the end of
+    // the tile fetch its first piece again and do not store it)
+    int tile_r[NC], tile_col[NC], tile_lds[NC];
+    if constexpr (STAGED) {
+#pragma unroll
+        for (int m = 0; m < NC; ++m) {
+            const int o = 1024 * m + 16 * lane;
+            const bool ok = o < 16 * row_bytes;
+            tile_r[m] = ok ? o / row_bytes : 0;
+            tile_col[m] = ok ? o - tile_r[m] * row_bytes : 0;
+            // where the piece goes in the staging area; a lane past the end of the tile drops
+            // its (repeated) piece into the padding of key 0, which nothing reads
+            tile_lds[m] = ok ? tile_r[m] * STR + tile_col[m] : NC * 64;
+        }
+        // columns past the end of a key are never written again and must not hold NaN patterns
+        for (int i = lane * 16; i < 16 * STR; i += kWave * 16)
+            *reinterpret_cast<uint4 *>(stage + i) = zero16();
+    }
+
     const int ntiles = nk16 >> 4;
     // this wave's tiles: w, w + kScoreWaves, ...
     const int my_tiles = ntiles > w ? (ntiles - w + kScoreWaves - 1) / kScoreWaves : 0;
     uint4 ring[kScoreDepth][NC];
-    auto fetch = [&](int n, uint4 *dst) {
-        const int key = (w + kScoreWaves * n) * 16 + l16;
-        const bool ok = n < my_tiles && key < nk;
+    auto fetch = [&](int n, uint4(&dst)[NC]) {
+        const int key0 = (w + kScoreWaves * n) * 16;
+        if constexpr (STAGED) {
 #pragma unroll
-        for (int c = 0; c < NC; ++c)
-            dst[c] = load16_guard(kbase, (int64_t)key * row_bytes + 64 * c + 16 * g,
-                                  ok && 64 * c + 16 * g < row_bytes);
+            for (int m = 0; m < NC; ++m) {
+                const int key = min(key0 + tile_r[m], nk - 1);  // inside the key range, always
+                dst[m] = load16(kbase, (int64_t)key * row_bytes + tile_col[m]);
+            }
+        } else {
+            const int key = key0 + l16;
+            const bool ok = n < my_tiles && key < nk;
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                dst[c] = load16_guard(kbase, (int64_t)key * row_bytes + 64 * c + 16 * g,
+                                      ok && 64 * c + 16 * g < row_bytes);
+        }
     };
 #pragma unroll
     for (int d = 0; d < kScoreDepth; ++d) fetch(d, ring[d]);
 
-    for (int n0 = 0; n0 < my_tiles; n0 += kScoreDepth) {
+    // multiplies tile n (held in `tile`) with the query rows and files the logits
+    auto process = [&](int n, const uint4(&tile)[NC]) {
+        const int key0 = (w + kScoreWaves * n) * 16;
+        uint4 kf[NC];  // operand layout: key l16, bytes 64 c + 16 g
+        if constexpr (STAGED) {
+#pragma unroll
+            for (int m = 0; m < NC; ++m)
+                *reinterpret_cast<uint4 *>(stage + tile_lds[m]) = tile[m];
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                kf[c] = *reinterpret_cast<const uint4 *>(stage + l16 * STR + 64 * c + 16 * g);
+        } else {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) kf[c] = tile[c];
+        }
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < NC; ++c) mma16_chunk<T>(acc, kf[c], qfrag[rb][c]);
+            // acc[r]: key key0 + 4g + r, query row rb*16 + l16
+            const int row = rb * 16 + l16;
+            if (row < R) {
+                const int t = row % Tq;
+                const int last_pos = S - Tq + t;  // causal limit of this query
+                float4 o;
+                float *op = &o.x;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int kk = key0 + 4 * g + r;
+                    op[r] = (kk < nk && k0 + kk <= last_pos) ? acc[r] * sl2 : -INFINITY;
+                }
+                *reinterpret_cast<float4 *>(z + (int64_t)row * zs + key0 + 4 * g) = o;
+            }
+        }
+    };
+
+    // full rounds of kScoreDepth tiles: no condition around the loads, so each tile is awaited
+    // on its own while the later ones stay in flight (fetches past the last tile are clamped
+    // into the key range and ignored)
+    int n0 = 0;
+    for (; n0 + kScoreDepth <= my_tiles; n0 += kScoreDepth) {
 #pragma unroll
         for (int d = 0; d < kScoreDepth; ++d) {
-            const int n = n0 + d;
-            if (n < my_tiles) {
-                const int key0 = (w + kScoreWaves * n) * 16;
-#pragma unroll
-                for (int rb = 0; rb < NRB; ++rb) {
-                    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int c = 0; c < NC; ++c) mma16_chunk<T>(acc, ring[d][c], qfrag[rb][c]);
-                    // acc[r]: key key0 + 4g + r, query row rb*16 + l16
-                    const int row = rb * 16 + l16;
-                    if (row < R) {
-                        const int t = row % Tq;
-                        const int last_pos = S - Tq + t;  // causal limit of this query
-                        float4 o;
-                        float *op = &o.x;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int kk = key0 + 4 * g + r;
-                            op[r] = (kk < nk && k0 + kk <= last_pos) ? acc[r] * sl2 : -INFINITY;
-                        }
-                        *reinterpret_cast<float4 *>(z + (int64_t)row * nk16 + key0 + 4 * g) = o;
-                    }
-                }
-            }
-            fetch(n + kScoreDepth, ring[d]);
+            process(n0 + d, ring[d]);
+            fetch(n0 + d + kScoreDepth, ring[d]);
         }
     }
+#pragma unroll
+    for (int d = 0; d < kScoreDepth; ++d)  // the last, partial round
+        if (n0 + d < my_tiles) process(n0 + d, ring[d]);
     __syncthreads();
 
     for (int row = w; row < R; row += kScoreWaves) {
-        const float *zr = z + (int64_t)row * nk16;
+        const float *zr = z + (int64_t)row * zs;
         float m = -INFINITY;
         for (int j = lane; j < nk16; j += kWave) m = fmaxf(m, zr[j]);
         m = wave_max(m);
@@ -116,37 +190,48 @@ __global__ __launch_bounds__(kScoreWaves * kWave) void llm_score_kernel(const T 
     for (int j = threadIdx.x; j < V; j += blockDim.x) {
         float s = 0.f;
         for (int row = 0; row < R; ++row)
-            s += __builtin_amdgcn_exp2f(z[(int64_t)row * nk16 + col0 + j] - rowM[row]) *
+            s += __builtin_amdgcn_exp2f(z[(int64_t)row * zs + col0 + j] - rowM[row]) *
                  rowInvL[row];
         out[j] = s;
     }
 }
 
-static size_t llm_score_lds(int rows, int nk) {
-    return (size_t)(128 + (int64_t)rows * ((nk + 15) & ~15)) * sizeof(float);
+// LDS bytes: row maxima / sums, logits, and (staged) one tile per wave
+static size_t llm_score_lds(int rows, int nk, int nc, bool staged) {
+    return (size_t)(128 + (int64_t)rows * score_logit_stride(nk)) * sizeof(float) +
+           (staged ? (size_t)kScoreWaves * 16 * (nc * 64 + 16) : 0);
 }
+constexpr size_t kScoreLdsMax = 160 * 1024;
 
 bool llm_score_supported(int rows, int nk, int row_bytes) {
-    return rows <= 64 && row_bytes <= 512 && llm_score_lds(rows, nk) <= 160 * 1024;
+    return rows <= 64 && row_bytes <= 512 &&
+           llm_score_lds(rows, nk, (row_bytes + 63) / 64, false) <= kScoreLdsMax;
+}
+
+template <typename T, int NC, int NRB, bool STAGED>
+static hipError_t llm_score_launch2(const LlmScoreArgs &a, hipStream_t s, size_t smem) {
+    const int k0 = a.domain_all ? 0 : a.vis_start;
+    const int nk = a.domain_all ? a.S : a.V;
+    if (smem > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(llm_score_kernel<T, NC, NRB, STAGED>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((llm_score_kernel<T, NC, NRB, STAGED>), dim3(a.Hkv, a.B),
+                       dim3(kScoreWaves * kWave), smem, s, (const T *)a.q, (const T *)a.k, a.part,
+                       a.Hq, a.Hkv, a.Tq, a.S, a.dh, a.vis_start, a.V, k0, nk,
+                       a.scale * 1.4426950408889634f);
+    return hipGetLastError();
 }
 
 template <typename T, int NC, int NRB>
 static hipError_t llm_score_launch(const LlmScoreArgs &a, hipStream_t s) {
     const int rows = (a.Hq / a.Hkv) * a.Tq;
-    const int k0 = a.domain_all ? 0 : a.vis_start;
     const int nk = a.domain_all ? a.S : a.V;
-    const size_t smem = llm_score_lds(rows, nk);
-    if (smem > 64 * 1024) {
-        hipError_t e =
-            hipFuncSetAttribute(reinterpret_cast<const void *>(llm_score_kernel<T, NC, NRB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((llm_score_kernel<T, NC, NRB>), dim3(a.Hkv, a.B), dim3(kScoreWaves * kWave),
-                       smem, s,
-                       (const T *)a.q, (const T *)a.k, a.part, a.Hq, a.Hkv, a.Tq, a.S, a.dh,
-                       a.vis_start, a.V, k0, nk, a.scale * 1.4426950408889634f);
-    return hipGetLastError();
+    const size_t staged = llm_score_lds(rows, nk, NC, true);
+    if (staged <= kScoreLdsMax) return llm_score_launch2<T, NC, NRB, true>(a, s, staged);
+    return llm_score_launch2<T, NC, NRB, false>(a, s, llm_score_lds(rows, nk, NC, false));
 }
 
 template <typename T>
