@@ -1,36 +1,45 @@
 // Stage 2 (Sec. 4.2): text-to-visual attention scoring (Eq. 5) and the
 // order-preserving compaction of hidden states and K/V ("Remarks on KV Cache").
+#include <algorithm>
+
 #include "common.hpp"
 #include "launch.hpp"
 
 namespace vscan {
 
 // ---------------------------------------------------------------------------
-// Scoring.  One workgroup per (sequence, kv head) streams that head's keys once
-// from HBM and multiplies them on the matrix cores with all the query rows
-// sharing the kv head (R = (Hq/Hkv) * Tq rows, padded to 16 per block).  Logits
-// stay in LDS until the row maxima / sums are known, then the normalised rows
-// are summed in a fixed order into
+// Scoring.  An item is one (sequence, kv head): its keys are streamed once from
+// HBM and multiplied on the matrix cores with all the query rows sharing the kv
+// head (R = (Hq/Hkv) * Tq rows, padded to 16 per block).  Logits stay in LDS until
+// the row maxima / sums are known, then the normalised rows are summed in a fixed
+// order into
 //   part[b][g][j] = sum_r softmax(row r)_j          (j over the visual span).
 //
 // How the keys reach the matrix cores (STAGED): a 16x16 operand wants lane l to
 // hold 16 bytes of key (l % 16), so loading operands straight from memory makes
-// every quarter-wave touch 16 different rows - 16 B per cache-line lookup, which
-// caps the CU's load path far below HBM speed.  Instead a wave fetches a tile
-// (16 consecutive keys = 16 * row_bytes contiguous bytes) fully coalesced, 1 KiB
-// per instruction, drops it into a private LDS staging area with padded rows and
-// reads it back in operand layout.  Only this wave touches its staging area and
-// the LDS operations of one wave complete in order, so no barrier is involved.
-// All global addresses are clamped into the key range (never predicated), which
-// keeps the loads independent: the compiler waits only for the tile it is about
-// to use while kScoreDepth - 1 later tiles stay in flight.
-// When the staging areas do not fit in LDS beside the logits, the operands are
-// loaded directly (!STAGED).
+// every quarter-wave touch 16 different rows.  Instead a wave fetches a tile (16
+// consecutive keys = 16 * row_bytes contiguous bytes) fully coalesced, 1 KiB per
+// instruction, drops it into a private LDS staging area with padded rows and reads
+// it back in operand layout.  Only this wave touches its staging area and the LDS
+// operations of one wave complete in order, so no barrier is involved.  All global
+// addresses are clamped into the key range (never predicated), which keeps the
+// loads independent: the compiler waits only for the tile it is about to use while
+// the later tiles stay in flight.  When the staging areas do not fit in
+// LDS beside the logits, the operands are loaded directly (!STAGED).
+//
+// The logits of a long span leave LDS room for one workgroup per CU, so nothing
+// else would keep that CU's memory pipe busy while the workgroup normalises.  The
+// grid is therefore persistent (a workgroup takes items blockIdx.x, + gridDim.x,
+// ...) and the tile stream runs across items: during the last round of an item the
+// first tiles of the next item are already being fetched (and its queries right
+// after), and they arrive while the softmax epilogue runs.
 // ---------------------------------------------------------------------------
-constexpr int kScoreDepth = 4;  // 16-key tiles a wave keeps in flight
-constexpr int kScoreWaves = 8;  // waves per workgroup: the logits of a long span leave LDS
-                                // room for one workgroup per CU, so it carries all the
-                                // memory-level parallelism of that CU
+// DEPTH = 16-key tiles a wave keeps in flight: four for long spans, two for the widest rows
+// (register budget) and for short spans, where a wave has no more than two tiles per item and
+// the smaller register footprint lets a second workgroup share the CU.
+constexpr int kScoreWaves = 8;  // waves per workgroup
+constexpr int kScoreHeader = 128 + kScoreWaves * 64;  // floats of LDS before the logits
+constexpr int kCus = 256;       // compute units of the MI355X
 
 __host__ __device__ inline int score_logit_stride(int nk) {
     // floats per logit row: >= nk rounded up to 16, and = 16 mod 64 so that the 16 query rows
@@ -39,54 +48,56 @@ __host__ __device__ inline int score_logit_stride(int nk) {
     return nk16 + ((16 - nk16 % 64) + 64) % 64;
 }
 
-template <typename T, int NC, int NRB, bool STAGED>
-__global__ __launch_bounds__(kScoreWaves * kWave) void llm_score_kernel(const T *__restrict__ q,
+template <typename T, int NC, int NRB, bool STAGED, int DEPTH>
+__global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB == 1) ? 4 : 2) void llm_score_kernel(const T *__restrict__ q,
                                                         const T *__restrict__ k,
-                                                        float *__restrict__ part, int Hq, int Hkv,
-                                                        int Tq, int S, int dh, int vis_start, int V,
-                                                        int k0, int nk, float sl2) {
-    constexpr int STR = NC * 64 + 16;  // bytes per key in a staging area
+                                                        float *__restrict__ part, int B, int Hq,
+                                                        int Hkv, int Tq, int S, int dh,
+                                                        int vis_start, int V, int k0, int nk,
+                                                        float sl2) {
+    constexpr int STR = NC * 64 + 16;          // bytes per key in a staging area
     extern __shared__ __align__(16) unsigned char smem[];
-    float *rowM = reinterpret_cast<float *>(smem);  // 64
-    float *rowInvL = rowM + 64;                      // 64
-    float *z = rowInvL + 64;                         // [R][zs]
+    float *rowM = reinterpret_cast<float *>(smem);  // 64: row maxima
+    float *rowInvL = rowM + 64;                      // 64: 1 / row sums
+    float *waveM = rowInvL + 64;                     // [waves][64]: per-wave row maxima
+    float *z = rowM + kScoreHeader;                  // [R][zs]
 
-    const int g_kv = blockIdx.x, b = blockIdx.y;
     const int group = Hq / Hkv, R = group * Tq;
     const int nk16 = (nk + 15) & ~15;
     const int zs = score_logit_stride(nk);
     const int row_bytes = dh * (int)sizeof(T);
-    const unsigned char *qbase = reinterpret_cast<const unsigned char *>(q) +
-                                 ((int64_t)b * Hq + (int64_t)g_kv * group) * Tq * row_bytes;
-    const unsigned char *kbase = reinterpret_cast<const unsigned char *>(k) +
-                                 (((int64_t)b * Hkv + g_kv) * S + k0) * row_bytes;
     const int lane = lane_id(), l16 = lane & 15, g = lane >> 4, w = wave_id();
     unsigned char *stage = reinterpret_cast<unsigned char *>(z + (int64_t)R * zs) + w * 16 * STR;
+    const int items = B * Hkv;
 
-    uint4 qfrag[NRB][NC];
+    auto q_of = [&](int item) {  // item = b * Hkv + kv head; its query rows are contiguous
+        return reinterpret_cast<const unsigned char *>(q) + (int64_t)item * group * Tq * row_bytes;
+    };
+    auto k_of = [&](int item) {
+        return reinterpret_cast<const unsigned char *>(k) + ((int64_t)item * S + k0) * row_bytes;
+    };
+    auto load_q = [&](const unsigned char *qbase, uint4(&dst)[NRB][NC]) {
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
+        for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int row = rb * 16 + l16;
-            qfrag[rb][c] = load16_guard(qbase, (int64_t)row * row_bytes + 64 * c + 16 * g,
-                                        row < R && 64 * c + 16 * g < row_bytes);
-        }
+            for (int c = 0; c < NC; ++c) {
+                const int row = rb * 16 + l16;
+                dst[rb][c] = load16_guard(qbase, (int64_t)row * row_bytes + 64 * c + 16 * g,
+                                          row < R && 64 * c + 16 * g < row_bytes);
+            }
+    };
 
-    // STAGED: piece m of a tile that this lane fetches: byte 1024 m + 16 lane of the tile's
-    // 16 * row_bytes contiguous bytes = key tile_r[m], column tile_col[m] (lanes past the end of
-    // the tile fetch its first piece again and do not store it)
-    int tile_r[NC], tile_col[NC], tile_lds[NC];
+    // STAGED: piece m of a tile that this lane fetches is byte 1024 m + 16 lane of the tile's
+    // 16 * row_bytes contiguous bytes.  tile_lds[m]: where it goes in the staging area (key
+    // o / row_bytes, column o % row_bytes); a lane past the end of the tile drops what it
+    // fetched into the padding of key 0, which nothing reads.
+    int tile_lds[NC];
     if constexpr (STAGED) {
 #pragma unroll
         for (int m = 0; m < NC; ++m) {
             const int o = 1024 * m + 16 * lane;
-            const bool ok = o < 16 * row_bytes;
-            tile_r[m] = ok ? o / row_bytes : 0;
-            tile_col[m] = ok ? o - tile_r[m] * row_bytes : 0;
-            // where the piece goes in the staging area; a lane past the end of the tile drops
-            // its (repeated) piece into the padding of key 0, which nothing reads
-            tile_lds[m] = ok ? tile_r[m] * STR + tile_col[m] : NC * 64;
+            const int r = o / row_bytes;
+            tile_lds[m] = o < 16 * row_bytes ? r * STR + (o - r * row_bytes) : NC * 64;
         }
         // columns past the end of a key are never written again and must not hold NaN patterns
         for (int i = lane * 16; i < 16 * STR; i += kWave * 16)
@@ -94,29 +105,33 @@ __global__ __launch_bounds__(kScoreWaves * kWave) void llm_score_kernel(const T 
     }
 
     const int ntiles = nk16 >> 4;
-    // this wave's tiles: w, w + kScoreWaves, ...
+    // this wave's tiles of an item: w, w + kScoreWaves, ...; every wave runs the same number of
+    // rounds of DEPTH tiles, the surplus tiles are fetched (clamped) and ignored
     const int my_tiles = ntiles > w ? (ntiles - w + kScoreWaves - 1) / kScoreWaves : 0;
-    uint4 ring[kScoreDepth][NC];
-    auto fetch = [&](int n, uint4(&dst)[NC]) {
+    const int rounds = ((ntiles + kScoreWaves - 1) / kScoreWaves + DEPTH - 1) / DEPTH;
+    const int full_rounds = my_tiles / DEPTH;
+
+    uint4 ring[DEPTH][NC];
+    auto fetch = [&](const unsigned char *kbase, int n, uint4(&dst)[NC]) {
         const int key0 = (w + kScoreWaves * n) * 16;
         if constexpr (STAGED) {
+            // byte offsets are clamped to the last piece of the key range: always readable
+            const int last_piece = nk * row_bytes - 16;
 #pragma unroll
-            for (int m = 0; m < NC; ++m) {
-                const int key = min(key0 + tile_r[m], nk - 1);  // inside the key range, always
-                dst[m] = load16(kbase, (int64_t)key * row_bytes + tile_col[m]);
-            }
+            for (int m = 0; m < NC; ++m)
+                dst[m] = load16(kbase, min(key0 * row_bytes + 1024 * m + 16 * lane, last_piece));
         } else {
             const int key = key0 + l16;
-            const bool ok = n < my_tiles && key < nk;
+            const bool ok = key < nk;
 #pragma unroll
             for (int c = 0; c < NC; ++c)
                 dst[c] = load16_guard(kbase, (int64_t)key * row_bytes + 64 * c + 16 * g,
                                       ok && 64 * c + 16 * g < row_bytes);
         }
     };
-#pragma unroll
-    for (int d = 0; d < kScoreDepth; ++d) fetch(d, ring[d]);
 
+    uint4 qfrag[NRB][NC];
+    float mx[NRB];  // running maximum of the logits this lane has filed, per row block
     // multiplies tile n (held in `tile`) with the query rows and files the logits
     auto process = [&](int n, const uint4(&tile)[NC]) {
         const int key0 = (w + kScoreWaves * n) * 16;
@@ -149,56 +164,110 @@ __global__ __launch_bounds__(kScoreWaves * kWave) void llm_score_kernel(const T 
                     const int kk = key0 + 4 * g + r;
                     op[r] = (kk < nk && k0 + kk <= last_pos) ? acc[r] * sl2 : -INFINITY;
                 }
+                mx[rb] = fmaxf(fmaxf(mx[rb], fmaxf(o.x, o.y)), fmaxf(o.z, o.w));
                 *reinterpret_cast<float4 *>(z + (int64_t)row * zs + key0 + 4 * g) = o;
             }
         }
     };
 
-    // full rounds of kScoreDepth tiles: no condition around the loads, so each tile is awaited
-    // on its own while the later ones stay in flight (fetches past the last tile are clamped
-    // into the key range and ignored)
-    int n0 = 0;
-    for (; n0 + kScoreDepth <= my_tiles; n0 += kScoreDepth) {
+    int item = blockIdx.x;
+    if (item >= items) return;
+    const unsigned char *kbase = k_of(item);
+    load_q(q_of(item), qfrag);
 #pragma unroll
-        for (int d = 0; d < kScoreDepth; ++d) {
-            process(n0 + d, ring[d]);
-            fetch(n0 + d + kScoreDepth, ring[d]);
-        }
-    }
+    for (int d = 0; d < DEPTH; ++d) fetch(kbase, d, ring[d]);
+
+    for (; item < items; item += gridDim.x) {
+        const bool has_next = item + (int)gridDim.x < items;
+        const int next = has_next ? item + (int)gridDim.x : item;
+        const unsigned char *kbase_next = k_of(next);
 #pragma unroll
-    for (int d = 0; d < kScoreDepth; ++d)  // the last, partial round
-        if (n0 + d < my_tiles) process(n0 + d, ring[d]);
-    __syncthreads();
+        for (int rb = 0; rb < NRB; ++rb) mx[rb] = -INFINITY;
 
-    for (int row = w; row < R; row += kScoreWaves) {
-        const float *zr = z + (int64_t)row * zs;
-        float m = -INFINITY;
-        for (int j = lane; j < nk16; j += kWave) m = fmaxf(m, zr[j]);
-        m = wave_max(m);
-        float sum = 0.f;
-        for (int j = lane; j < nk16; j += kWave) sum += __builtin_amdgcn_exp2f(zr[j] - m);
-        sum = wave_sum(sum);
-        if (lane == 0) {
-            rowM[row] = m;
-            rowInvL[row] = 1.0f / sum;
+        // Round r works on tiles 4r .. 4r+3 and refills each ring slot with the tile of the next
+        // round - in the last round, with the first tiles of the next item.  Full rounds carry
+        // no condition, so each tile is awaited on its own while the later ones stay in flight.
+        int r = 0;
+        if (full_rounds > 0 && rounds > 1) {
+            // The first round is kept out of the loop below: here the stores of the previous
+            // item's scores may still be pending next to the prefetched tiles, and the wait
+            // that sorts that out should not be paid in every round.
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                process(d, ring[d]);
+                fetch(kbase, DEPTH + d, ring[d]);
+            }
+            r = 1;
         }
-    }
-    __syncthreads();
+        for (; r < full_rounds && r + 1 < rounds; ++r) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                process(DEPTH * r + d, ring[d]);
+                fetch(kbase, DEPTH * (r + 1) + d, ring[d]);
+            }
+        }
+        for (; r < rounds; ++r) {  // the last round, and a partial one before it if there is one
+            const bool last = r + 1 == rounds;
+            const unsigned char *fbase = last ? kbase_next : kbase;
+            const int fn = last ? 0 : DEPTH * (r + 1);
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                if (DEPTH * r + d < my_tiles) process(DEPTH * r + d, ring[d]);
+                if (!last || has_next) fetch(fbase, fn + d, ring[d]);
+            }
+        }
+        if (has_next) load_q(q_of(next), qfrag);  // this item's queries are no longer needed
 
-    float *out = part + ((int64_t)b * Hkv + g_kv) * V;
-    const int col0 = vis_start - k0;
-    for (int j = threadIdx.x; j < V; j += blockDim.x) {
-        float s = 0.f;
-        for (int row = 0; row < R; ++row)
-            s += __builtin_amdgcn_exp2f(z[(int64_t)row * zs + col0 + j] - rowM[row]) *
-                 rowInvL[row];
-        out[j] = s;
+        // row maxima: over this lane's logits, the four key groups of the wave, the waves
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            float m = mx[rb];
+            m = fmaxf(m, __shfl_xor(m, 16, kWave));
+            m = fmaxf(m, __shfl_xor(m, 32, kWave));
+            if (g == 0) waveM[w * 64 + rb * 16 + l16] = m;
+        }
+        __syncthreads();
+
+        // one wave per row: exponentials against the row maximum, written back over the
+        // logits, and their sum
+        for (int row = w; row < R; row += kScoreWaves) {
+            float m = waveM[row];
+#pragma unroll
+            for (int ww = 1; ww < kScoreWaves; ++ww) m = fmaxf(m, waveM[ww * 64 + row]);
+            float4 *zr = reinterpret_cast<float4 *>(z + (int64_t)row * zs);
+            float sum = 0.f;
+            for (int j = lane; j < (nk16 >> 2); j += kWave) {
+                float4 v = zr[j];
+                v.x = __builtin_amdgcn_exp2f(v.x - m);
+                v.y = __builtin_amdgcn_exp2f(v.y - m);
+                v.z = __builtin_amdgcn_exp2f(v.z - m);
+                v.w = __builtin_amdgcn_exp2f(v.w - m);
+                zr[j] = v;
+                sum += (v.x + v.y) + (v.z + v.w);
+            }
+            sum = wave_sum(sum);
+            if (lane == 0) rowInvL[row] = 1.0f / sum;
+        }
+        __syncthreads();
+
+        // columns: sum over the rows in a fixed order
+        float *out = part + (int64_t)item * V;
+        const int col0 = vis_start - k0;
+        for (int j = threadIdx.x; j < V; j += blockDim.x) {
+            float s = 0.f;
+            for (int row = 0; row < R; ++row) s += z[(int64_t)row * zs + col0 + j] * rowInvL[row];
+            out[j] = s;
+        }
+        if (!has_next) break;
+        __syncthreads();  // the logits are free for the next item
+
+        kbase = kbase_next;
     }
 }
 
-// LDS bytes: row maxima / sums, logits, and (staged) one tile per wave
+// LDS bytes: header, logits, and (staged) one tile per wave
 static size_t llm_score_lds(int rows, int nk, int nc, bool staged) {
-    return (size_t)(128 + (int64_t)rows * score_logit_stride(nk)) * sizeof(float) +
+    return (size_t)(kScoreHeader + (int64_t)rows * score_logit_stride(nk)) * sizeof(float) +
            (staged ? (size_t)kScoreWaves * 16 * (nc * 64 + 16) : 0);
 }
 constexpr size_t kScoreLdsMax = 160 * 1024;
@@ -208,21 +277,34 @@ bool llm_score_supported(int rows, int nk, int row_bytes) {
            llm_score_lds(rows, nk, (row_bytes + 63) / 64, false) <= kScoreLdsMax;
 }
 
-template <typename T, int NC, int NRB, bool STAGED>
-static hipError_t llm_score_launch2(const LlmScoreArgs &a, hipStream_t s, size_t smem) {
+template <typename T, int NC, int NRB, bool STAGED, int DEPTH>
+static hipError_t llm_score_launch3(const LlmScoreArgs &a, hipStream_t s, size_t smem) {
     const int k0 = a.domain_all ? 0 : a.vis_start;
     const int nk = a.domain_all ? a.S : a.V;
     if (smem > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(llm_score_kernel<T, NC, NRB, STAGED>),
+            reinterpret_cast<const void *>(llm_score_kernel<T, NC, NRB, STAGED, DEPTH>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((llm_score_kernel<T, NC, NRB, STAGED>), dim3(a.Hkv, a.B),
+    // persistent grid: as many workgroups as the CUs hold at once (LDS decides, at most four
+    // per CU), each taking every gridDim.x-th item
+    const int64_t items = (int64_t)a.B * a.Hkv;
+    const int per_cu = (int)std::min<size_t>(4, std::max<size_t>(1, kScoreLdsMax / smem));
+    const int grid = (int)std::min<int64_t>(items, (int64_t)kCus * per_cu);
+    hipLaunchKernelGGL((llm_score_kernel<T, NC, NRB, STAGED, DEPTH>), dim3(grid),
                        dim3(kScoreWaves * kWave), smem, s, (const T *)a.q, (const T *)a.k, a.part,
-                       a.Hq, a.Hkv, a.Tq, a.S, a.dh, a.vis_start, a.V, k0, nk,
+                       a.B, a.Hq, a.Hkv, a.Tq, a.S, a.dh, a.vis_start, a.V, k0, nk,
                        a.scale * 1.4426950408889634f);
     return hipGetLastError();
+}
+
+template <typename T, int NC, int NRB, bool STAGED>
+static hipError_t llm_score_launch2(const LlmScoreArgs &a, hipStream_t s, size_t smem) {
+    const int nk = a.domain_all ? a.S : a.V;
+    const int tiles_per_wave = ((nk + 15) / 16 + kScoreWaves - 1) / kScoreWaves;
+    if (NC >= 8 || tiles_per_wave <= 2) return llm_score_launch3<T, NC, NRB, STAGED, 2>(a, s, smem);
+    return llm_score_launch3<T, NC, NRB, STAGED, 4>(a, s, smem);
 }
 
 template <typename T, int NC, int NRB>
@@ -230,7 +312,9 @@ static hipError_t llm_score_launch(const LlmScoreArgs &a, hipStream_t s) {
     const int rows = (a.Hq / a.Hkv) * a.Tq;
     const int nk = a.domain_all ? a.S : a.V;
     const size_t staged = llm_score_lds(rows, nk, NC, true);
-    if (staged <= kScoreLdsMax) return llm_score_launch2<T, NC, NRB, true>(a, s, staged);
+    // (the widest rows with many query rows would spill registers in the staged form)
+    if (staged <= kScoreLdsMax && !(NC >= 8 && NRB >= 4))
+        return llm_score_launch2<T, NC, NRB, true>(a, s, staged);
     return llm_score_launch2<T, NC, NRB, false>(a, s, llm_score_lds(rows, nk, NC, false));
 }
 
