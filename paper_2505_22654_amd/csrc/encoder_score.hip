@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void score_cls_generic_kernel(const T *__restr
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             const int row = base + u * nw * rpw + row_in_wave;
-            raw[u] = load16_guard(kbase, row * row_bytes + piece * 16, active && row < n_keys);
+            raw[u] = load16_stream_guard(kbase, row * row_bytes + piece * 16, active && row < n_keys);
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
         const int p = u * 256 + tid;
-        raw[u] = load16_guard(kbase, (int64_t)p * 16, p < total);
+        raw[u] = load16_stream_guard(kbase, (int64_t)p * 16, p < total);
     }
     for (int e = tid; e < dh; e += 256) qf[e] = load_elem<T>(qrow + e) * scale_log2e;
     __syncthreads();
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
                 const int p = base + 256 * UNR + u * 256 + tid;
-                nxt[u] = load16_guard(kbase, (int64_t)p * 16, p < total);
+                nxt[u] = load16_stream_guard(kbase, (int64_t)p * 16, p < total);
             }
         }
 #pragma unroll

@@ -119,14 +119,15 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
             const int last_piece = nk * row_bytes - 16;
 #pragma unroll
             for (int m = 0; m < NC; ++m)
-                dst[m] = load16(kbase, min(key0 * row_bytes + 1024 * m + 16 * lane, last_piece));
+                dst[m] = load16_stream(kbase,
+                                       min(key0 * row_bytes + 1024 * m + 16 * lane, last_piece));
         } else {
             const int key = key0 + l16;
             const bool ok = key < nk;
 #pragma unroll
             for (int c = 0; c < NC; ++c)
-                dst[c] = load16_guard(kbase, (int64_t)key * row_bytes + 64 * c + 16 * g,
-                                      ok && 64 * c + 16 * g < row_bytes);
+                dst[c] = load16_stream_guard(kbase, (int64_t)key * row_bytes + 64 * c + 16 * g,
+                                             ok && 64 * c + 16 * g < row_bytes);
         }
     };
 
