@@ -20,27 +20,30 @@ constexpr float kNormEps = 1e-12f;
 
 // ---------------------------------------------------------------------------
 // kept x dropped similarity with fused norm and argmax.
-// Workgroup tile: (64*TM) kept slots x (64*TN) dropped tokens, 4 waves as 2 x 2,
-// each wave TM x TN blocks of 32 x 32.  The feature axis is streamed through LDS
-// in stages of KC 32-byte chunks, rows gathered by index.  Two stages are kept
-// in flight in registers on top of the one being multiplied: the small problems
-// are a handful of stages long, so their time is set by how many memory
-// round-trips are serialised, not by bandwidth.
+// Workgroup tile: (64*TM) kept slots x (64*TN) dropped tokens, multiplied by 4 waves as 2 x 2,
+// each wave TM x TN blocks of 32 x 32.  The feature axis is streamed through LDS in stages of
+// KC 32-byte chunks, rows gathered by index.  NSETS stages are kept in flight in registers on
+// top of the one being multiplied.  The small problems are a handful of stages long and give
+// a CU one workgroup at most, so their time is set by how many memory round-trips are
+// serialised, not by bandwidth: they run with 8 waves (the upper four only fetch), which halves
+// the registers a stage costs per thread and lets four stages fly.  Large problems use one
+// register set, so that two workgroups fit a CU and hide each other.
 // ---------------------------------------------------------------------------
-template <typename T, int TM, int TN, int KC, bool DEEP>
-__global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x,
-                                                         const int32_t *__restrict__ kept_idx,
-                                                         const int32_t *__restrict__ drop_idx,
-                                                         unsigned long long *__restrict__ best,
-                                                         int T_img, int D, int K, int U, int B,
-                                                         int affine) {
+template <typename T, int TM, int TN, int KC, int NSETS, int THREADS>
+__global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict__ x,
+                                                             const int32_t *__restrict__ kept_idx,
+                                                             const int32_t *__restrict__ drop_idx,
+                                                             unsigned long long *__restrict__ best,
+                                                             int T_img, int D, int K, int U, int B,
+                                                             int affine) {
     constexpr int E = ElemTraits<T>::kPer16B;
     constexpr int BM = 64 * TM, BN = 64 * TN, ROWS = BM + BN;
     constexpr int PPR = KC * 2;                 // 16-byte pieces per row per stage
     constexpr int STRIDE = KC * 32 + 16;        // LDS row stride in bytes
-    constexpr int PER_THREAD = ROWS * PPR / 256;
-    constexpr int A_PIECES = BM * PPR / 256;    // the first A_PIECES pieces of a thread are kept rows
-    static_assert(ROWS * PPR % 256 == 0 && BM * PPR % 256 == 0, "tile must split evenly");
+    constexpr int PER_THREAD = ROWS * PPR / THREADS;
+    constexpr int A_PIECES = BM * PPR / THREADS;  // the first A_PIECES pieces of a thread are kept rows
+    static_assert(ROWS * PPR % THREADS == 0 && BM * PPR % THREADS == 0, "tile must split evenly");
+    static_assert(NSETS == 1 || NSETS == 2 || NSETS == 4, "register sets");
     static_assert(PPR <= 64 && (PPR & (PPR - 1)) == 0, "a row's pieces must sit in one wave");
     __shared__ __align__(16) unsigned char lds[2][ROWS * STRIDE];
     __shared__ float inv_s[BM];
@@ -50,7 +53,8 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
     if (!image_affine_decode(B, tiles_m * tiles_n, affine != 0, b, tile)) return;
     const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
     const int tid = threadIdx.x, lane = lane_id(), g = lane >> 5;
-    const int wm = wave_id() >> 1, wn = wave_id() & 1;
+    const bool computes = THREADS == 256 || wave_id() < 4;  // waves 4.. (if any) only fetch
+    const int wm = (wave_id() & 3) >> 1, wn = wave_id() & 1;
     const int row_bytes = D * (int)sizeof(T);
     const unsigned char *xb =
         reinterpret_cast<const unsigned char *>(x) + (int64_t)b * T_img * row_bytes;
@@ -65,13 +69,13 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
         int tok[PER_THREAD];
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
-            const int r = (tid + it * 256) / PPR;
+            const int r = (tid + it * THREADS) / PPR;
             tok[it] = it < A_PIECES ? kept_idx[(int64_t)b * K + min(m0 + r, K - 1)]
                                     : drop_idx[(int64_t)b * U + min(n0 + r - BM, U - 1)];
         }
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
-            const int p = tid + it * 256;
+            const int p = tid + it * THREADS;
             const int r = p / PPR;
             const bool inside = it < A_PIECES ? m0 + r < K : n0 + r - BM < U;
             // indices come from device memory: stay inside the image
@@ -94,7 +98,7 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
     auto stage_load = [&](int stage, uint4 *regs) {
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
-            const int p = tid + it * 256;
+            const int p = tid + it * THREADS;
             const int piece = p % PPR;
             const int col_byte = stage * KC * 32 + piece * 16;
             regs[it] = load16_guard(xb, (int64_t)src[it] + (int64_t)stage * KC * 32,
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
     auto stage_store = [&](unsigned char *dst, const uint4 *regs) {
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
-            const int p = tid + it * 256;
+            const int p = tid + it * THREADS;
             const int r = p / PPR;
             *reinterpret_cast<uint4 *>(dst + r * STRIDE + (p - r * PPR) * 16) = regs[it];
             if (it < A_PIECES) {
@@ -143,40 +147,42 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
         }
     };
 
+    // Stage s sits in register set s % NSETS until it is written to LDS buffer s % 2, one
+    // iteration before it is multiplied; the set is then refilled with stage s + NSETS.  (The
+    // loop is unrolled by NSETS so that the sets are addressed statically.)
     const int nstages = (row_bytes + KC * 32 - 1) / (KC * 32);
-    if constexpr (DEEP) {
-        // short problems: while stage s is multiplied out of LDS, stages s+1 and s+2 are in
-        // flight (two register sets, loop unrolled by two so they are addressed statically)
-        uint4 ra[PER_THREAD], rb[PER_THREAD];
-        stage_load(0, ra);
-        if (nstages > 1) stage_load(1, rb);
-        stage_store(lds[0], ra);
-        __syncthreads();
-        for (int st = 0; st < nstages; st += 2) {
-            if (st + 2 < nstages) stage_load(st + 2, ra);
-            compute(lds[0]);
-            if (st + 1 >= nstages) break;
-            stage_store(lds[1], rb);
-            __syncthreads();
-            if (st + 3 < nstages) stage_load(st + 3, rb);
-            compute(lds[1]);
-            if (st + 2 < nstages) {
-                stage_store(lds[0], ra);
-                __syncthreads();
-            }
-        }
-    } else {
-        // long problems: one register set, so two workgroups fit a CU and hide each other
+    if constexpr (NSETS == 1) {
         uint4 ra[PER_THREAD];
         stage_load(0, ra);
         stage_store(lds[0], ra);
         __syncthreads();
         for (int st = 0; st < nstages; ++st) {
             if (st + 1 < nstages) stage_load(st + 1, ra);
-            compute(lds[st & 1]);
+            if (computes) compute(lds[st & 1]);
             if (st + 1 < nstages) {
                 stage_store(lds[(st + 1) & 1], ra);
                 __syncthreads();
+            }
+        }
+    } else {
+        uint4 regs[NSETS][PER_THREAD];
+#pragma unroll
+        for (int j = 0; j < NSETS; ++j)
+            if (j < nstages) stage_load(j, regs[j]);
+        stage_store(lds[0], regs[0]);
+        __syncthreads();
+        for (int st = 0; st < nstages; st += NSETS) {
+#pragma unroll
+            for (int j = 0; j < NSETS; ++j) {
+                const int cur = st + j;
+                if (cur < nstages) {
+                    if (cur + NSETS < nstages) stage_load(cur + NSETS, regs[j]);
+                    if (computes) compute(lds[cur & 1]);
+                    if (cur + 1 < nstages) {
+                        stage_store(lds[(cur + 1) & 1], regs[(j + 1) % NSETS]);
+                        __syncthreads();
+                    }
+                }
             }
         }
     }
@@ -187,11 +193,12 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
         float v = ss[it];
 #pragma unroll
         for (int o = PPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-        const int p = tid + it * 256;
+        const int p = tid + it * THREADS;
         if (p % PPR == 0) inv_s[p / PPR] = 1.0f / fmaxf(sqrtf(v), kNormEps);
     }
     __syncthreads();
 
+    if (!computes) return;  // no barrier below
     // epilogue: acc[i][j][r] = x_slot . x_token with
     //   slot  = m0 + (wm*TM + i)*32 + acc_row(r),  token column = n0 + (wn*TN + j)*32 + lane%32
 #pragma unroll
@@ -232,20 +239,20 @@ __global__ __launch_bounds__(256) void sim_argmax_kernel(const T *__restrict__ x
 // Phase 1 (whole workgroup): one pass over the image's assignment words; a token whose slot
 // belongs to the workgroup is appended to that slot's member list in LDS (position from an LDS
 // counter, so the order inside a list is arbitrary at this point).
-// Phase 2 (one wave per slot, spw slots one after the other): groups of up to kMergeSortCap
-// members.  The list is sorted by token index (rank by counting, one member per lane) and
-// drained a batch of rows at a time, so that many row loads are in flight together; members are
-// added in ascending token order.
-// Phase 3 (whole workgroup, one large group after the other): group sizes are heavy-tailed (many
-// dropped tokens look like the same kept token), and one wave adding hundreds of rows would set
-// the kernel's time.  Wave w gathers the members inside the w-th quarter of the token range
-// with an ordered ballot scan and adds them in ascending order; the four partial sums are
+// Phase 2 (one wave per slot, spw slots one after the other): the list is sorted by token index
+// (rank by counting); a group of up to kMergeAloneCap members is added up by that wave right
+// away, one batch of row loads in flight together.
+// Phase 3 (whole workgroup, one larger group after the other): group sizes are heavy-tailed
+// (many dropped tokens look like the same kept token), and one wave adding dozens or hundreds
+// of rows would set the kernel's time.  The four waves share such a group: each takes a quarter
+// of the sorted list - or, when the group is longer than the list, gathers the members inside
+// its quarter of the token range with an ordered ballot scan - and the four partial sums are
 // combined in wave order through LDS.
 // Every sum has a fixed order of additions, so results do not depend on scheduling.
 // Lane l owns the 16-byte pieces l, l+64, ... of the feature row.
 // ---------------------------------------------------------------------------
 constexpr int kMergeListCap = 128;  // ints of LDS per list
-constexpr int kMergeSortCap = 64;   // longest group that one wave sorts and adds
+constexpr int kMergeAloneCap = 16;  // longest group that one wave adds alone (one batch of rows)
 constexpr int kMergeMaxSpw = 4;     // slots a wave handles one after the other, at most
 
 template <typename T, int PIECES>
@@ -258,7 +265,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
     constexpr int BATCH = PIECES <= 2 ? 16 : 8;  // rows fetched together (register budget)
     __shared__ int cnt[4 * kMergeMaxSpw];
     __shared__ int lists[4 * kMergeMaxSpw][kMergeListCap];
-    extern __shared__ float part[];  // D floats: partial sums of a large group
+    __shared__ int scratch_lists[4][kMergeListCap];  // per wave, for the scans of phase 3
+    extern __shared__ float part[];  // D floats: partial sums of a shared group
     const int ns = 4 * spw;  // slots of this workgroup
     int b, group;
     if (!image_affine_decode(B, (K + ns - 1) / ns, affine != 0, b, group)) return;
@@ -351,58 +359,85 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
         }
     };
 
-    // ---- phase 2: groups one wave handles alone
-    bool any_large = false;
+    // sorts list[0 .. count) ascending, count <= kMergeListCap: rank by counting, up to two
+    // members per lane.  Only the calling wave touches the list; LDS operations of one wave
+    // complete in order, so the reads are done before the write-back.
+    auto sort_list = [&](int *list, int count) {
+        const int v0 = lane < count ? list[lane] : 0x7fffffff;
+        const int v1 = kWave + lane < count ? list[kWave + lane] : 0x7fffffff;
+        int r0 = 0, r1 = 0;
+        const int n0 = min(count, kWave);
+        for (int j = 0; j < n0; ++j) {
+            const int o = __builtin_amdgcn_readlane(v0, j);
+            r0 += o < v0 ? 1 : 0;
+            r1 += o < v1 ? 1 : 0;
+        }
+        for (int j = kWave; j < count; ++j) {
+            const int o = __builtin_amdgcn_readlane(v1, j - kWave);
+            r0 += o < v0 ? 1 : 0;
+            r1 += o < v1 ? 1 : 0;
+        }
+        if (lane < count) list[r0] = v0;
+        if (kWave + lane < count) list[r1] = v1;
+    };
+
+    // ---- phase 2: every wave sorts the lists of its slots and finishes the small groups
+    bool any_shared = false;
     for (int i = 0; i < spw; ++i) {
         const int rel = wave + 4 * i;
         const int slot = slot0 + rel;
         if (slot >= K) break;
         const int count = __builtin_amdgcn_readfirstlane(cnt[rel]);
-        if (count > kMergeSortCap) continue;
+        if (count > kMergeListCap) continue;  // list incomplete: gathered by a scan in phase 3
         int *list = lists[rel];
-        // only this wave touches the list from here on; LDS operations of one wave complete
-        // in order, so the reads below are done before the sorted write-back
-        const int v = lane < count ? list[lane] : 0x7fffffff;
-        int rank = 0;
-        for (int j = 0; j < count; ++j) rank += (__builtin_amdgcn_readlane(v, j) < v) ? 1 : 0;
-        if (lane < count) list[rank] = v;
+        sort_list(list, count);
+        if (count > kMergeAloneCap) continue;
         clear();
         drain(list, count);
         write_row(slot, count);
     }
-    for (int rel = 0; rel < ns; ++rel) any_large |= cnt[rel] > kMergeSortCap;
-    if (!any_large) return;  // the same decision in every wave: cnt is final since the barrier
-    __syncthreads();         // the lists are free from here on
+    for (int rel = 0; rel < ns; ++rel) any_shared |= slot0 + rel < K && cnt[rel] > kMergeAloneCap;
+    if (!any_shared) return;  // the same decision in every wave: cnt is final since the barrier
+    __syncthreads();          // sorted lists visible to all waves
 
-    // ---- phase 3: large groups, all four waves on one group at a time
+    // ---- phase 3: larger groups, all four waves on one group at a time
     const int quarter = ((T_img + 4 * kWave - 1) / (4 * kWave)) * kWave;
     const int t_begin = wave * quarter, t_end = min(T_img, t_begin + quarter);
-    int *list = lists[wave];
+    int *scan_list = scratch_lists[wave];
     for (int rel = 0; rel < ns; ++rel) {
         const int slot = slot0 + rel;
         const int count = cnt[rel];
-        if (slot >= K || count <= kMergeSortCap) continue;  // uniform over the workgroup
+        if (slot >= K || count <= kMergeAloneCap) continue;  // uniform over the workgroup
         clear();
-        int nlist = 0;
-        for (int base = t_begin; base < t_end; base += SCAN * kWave) {
-            uint32_t w[SCAN];
+        if (count <= kMergeListCap) {
+            // the sorted list is complete: wave w takes its w-th quarter
+            const int per = (count + 3) >> 2;
+            const int lo = min(wave * per, count), hi = min(lo + per, count);
+            drain(lists[rel] + lo, hi - lo);
+        } else {
+            // too long for the list: wave w gathers the members inside the w-th quarter of the
+            // token range with an ordered ballot scan
+            int nlist = 0;
+            for (int base = t_begin; base < t_end; base += SCAN * kWave) {
+                uint32_t w[SCAN];
 #pragma unroll
-            for (int u = 0; u < SCAN; ++u)
-                w[u] = slot_word[2 * min(base + u * kWave + lane, T_img - 1)];
+                for (int u = 0; u < SCAN; ++u)
+                    w[u] = slot_word[2 * min(base + u * kWave + lane, T_img - 1)];
 #pragma unroll
-            for (int u = 0; u < SCAN; ++u) {
-                const int t = base + u * kWave + lane;
-                const bool mine = t < t_end && (int)(~w[u]) == slot;
-                const uint64_t mask = __ballot(mine);
-                if (mine) list[nlist + __popcll(mask & lanemask_lt())] = t;
-                nlist += __popcll(mask);
-                if (nlist > kMergeListCap - kWave) {
-                    drain(list, nlist);
-                    nlist = 0;
+                for (int u = 0; u < SCAN; ++u) {
+                    const int t = base + u * kWave + lane;
+                    const bool mine = t < t_end && (int)(~w[u]) == slot;
+                    const uint64_t mask = __ballot(mine);
+                    if (mine) scan_list[nlist + __popcll(mask & lanemask_lt())] = t;
+                    nlist += __popcll(mask);
+                    if (nlist > kMergeListCap - kWave) {
+                        drain(scan_list, nlist);
+                        nlist = 0;
+                    }
                 }
             }
+            drain(scan_list, nlist);
         }
-        drain(list, nlist);
         // partial sums combined in wave order: part = acc0; part += acc1; part += acc2;
         // wave 3 adds its own on top and writes the row
         for (int w = 0; w < 4; ++w) {
@@ -438,16 +473,16 @@ static bool image_affinity(const MergeArgs &a) {
     return a.B >= kXcds && per_xcd * image_bytes <= (int64_t)8 << 20;
 }
 
-template <typename T, int TM, int TN, int KC, bool DEEP>
+template <typename T, int TM, int TN, int KC, int NSETS, int THREADS>
 static hipError_t sim_t(const MergeArgs &a, hipStream_t s) {
     const int U = a.T - a.K;
     if (U <= 0) return hipSuccess;  // nothing was dropped: every token keeps its own slot
     const int tiles = ((U + 64 * TN - 1) / (64 * TN)) * ((a.K + 64 * TM - 1) / (64 * TM));
     const bool affine = image_affinity(a);
     dim3 grid(image_affine_grid(a.B, tiles, affine));
-    hipLaunchKernelGGL((sim_argmax_kernel<T, TM, TN, KC, DEEP>), grid, dim3(256), 0, s, (const T *)a.x,
-                       a.kept_idx, a.drop_idx, (unsigned long long *)a.best, a.T, a.D, a.K, U, a.B,
-                       (int)affine);
+    hipLaunchKernelGGL((sim_argmax_kernel<T, TM, TN, KC, NSETS, THREADS>), grid, dim3(THREADS), 0, s,
+                       (const T *)a.x, a.kept_idx, a.drop_idx, (unsigned long long *)a.best, a.T,
+                       a.D, a.K, U, a.B, (int)affine);
     return hipGetLastError();
 }
 hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
@@ -457,8 +492,8 @@ hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
     const long tiles128 = (long)((U + 127) / 128) * ((a.K + 127) / 128) * a.B;
     const bool big = tiles128 >= 512;
     if (a.is_bf16)
-        return big ? sim_t<bf16_t, 2, 2, 4, false>(a, s) : sim_t<bf16_t, 1, 1, 8, true>(a, s);
-    return big ? sim_t<float, 2, 2, 4, false>(a, s) : sim_t<float, 1, 1, 8, true>(a, s);
+        return big ? sim_t<bf16_t, 2, 2, 4, 1, 256>(a, s) : sim_t<bf16_t, 1, 1, 8, 4, 512>(a, s);
+    return big ? sim_t<float, 2, 2, 4, 1, 256>(a, s) : sim_t<float, 1, 1, 8, 4, 512>(a, s);
 }
 
 template <typename T>
