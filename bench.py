@@ -194,6 +194,15 @@ def cpu_baseline(points, hosts, budget_s=12.0):
                                         f"{dt * 1e3:.1f} ms per step"}
 
 
+def kernel_source_digest(kernel: str) -> str:
+    """sha256 over the kernel's source file and the headers every kernel includes."""
+    h = hashlib.sha256()
+    for name in (KERNEL_SOURCE[kernel], "common.hpp", "launch.hpp"):
+        with open(os.path.join(ROOT, "paper_2505_22654_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def stored_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed counter runs, or None when absent or when the
     kernel's source changed after the counters were taken."""
@@ -202,9 +211,7 @@ def stored_traffic(kernel: str, workload: str):
         return None
     try:
         rec = json.load(open(path)).get(f"{workload}:{kernel}")
-        src = os.path.join(ROOT, "paper_2505_22654_amd", "csrc", KERNEL_SOURCE[kernel])
-        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
-        if rec and rec.get("source_sha256") == digest:
+        if rec and rec.get("source_sha256") == kernel_source_digest(kernel):
             return rec["bytes_per_launch"]
     except (OSError, ValueError, KeyError):
         pass
