@@ -176,6 +176,44 @@ int vscan_profile_enable(int on);
 int vscan_profile_read(vscan_kernel_time *out, int capacity, int *count);
 
 /* ---------------------------------------------------------------------------
+ * Ragged stage-2 batches: every sequence has its own length, visual span and
+ * budget (dynamic-resolution encoders emit between 4 and 16384 visual tokens per
+ * image, Sec. 5.1 "Models"; re-selection for a later question in a multi-turn
+ * dialogue, App. "Remarks on Multi-Turn Conversations", is the out-of-place call
+ * again on the same pool).
+ *
+ * The descriptor gives what the sequences share (dtype, batch, heads, head_dim,
+ * hidden, n_query, softmax_domain, scale, in_place) and the CAPACITIES:
+ *   desc->seq_len  rows per sequence of k, v, hidden AND of the out-of-place
+ *                  outputs (k_out, v_out [B,Hkv,seq_len,dh], hidden_out
+ *                  [B,seq_len,hidden]: shaped like the inputs)
+ *   desc->vis_len  row length of scores_out [B, vis_len] and of the workspace
+ *                  (vscan_llm_workspace_size with this descriptor)
+ *   desc->keep     row length of kept_idx [B, keep]
+ *   desc->vis_start is ignored.
+ * meta_host and meta_device hold the same `batch` entries, on the host (read and
+ * validated by the call) and on the device (read by the kernels, so it must stay
+ * valid and unchanged until the enqueued work has run).
+ * Sequence b: scores_out[b, 0 .. vis_len_b), kept_idx[b, 0 .. keep_b) ascending and
+ * -1 in the entries after them; its result occupies rows [0, seq_len_b - vis_len_b
+ * + keep_b) of the destinations, later rows are left as they were.
+ * Errors as vscan_llm_prune; a sequence that does not fit the capacities or its
+ * own length gives VSCAN_ERR_SHAPE / VSCAN_ERR_BUDGET.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t seq_len;   /* tokens of this sequence */
+    int32_t vis_start; /* first visual position */
+    int32_t vis_len;   /* visual tokens, >= 1 */
+    int32_t keep;      /* visual tokens to keep, 0 .. vis_len */
+} vscan_seq_meta;
+
+int vscan_llm_prune_ragged(const vscan_llm_desc *desc, const vscan_seq_meta *meta_host,
+                           const vscan_seq_meta *meta_device, const void *q, void *k, void *v,
+                           void *hidden, int32_t *kept_idx, void *k_out, void *v_out,
+                           void *hidden_out, float *scores_out, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * Host-side budget arithmetic.  Pure functions of their arguments: no GPU, no
  * state; all pointers are HOST pointers.
  * ------------------------------------------------------------------------- */

@@ -23,7 +23,8 @@ VSCAN_KEYS_VISUAL_ONLY, VSCAN_KEYS_ALL = 0, 1
 
 EXPORTS = ("vscan_encoder_workspace_size", "vscan_encoder_reduce", "vscan_llm_workspace_size",
            "vscan_llm_prune", "vscan_profile_enable", "vscan_profile_read", "vscan_status_string",
-           "vscan_version", "vscan_budget", "vscan_budget_solve_r1", "vscan_flops")
+           "vscan_version", "vscan_budget", "vscan_budget_solve_r1", "vscan_flops",
+           "vscan_llm_prune_ragged")
 
 
 class EncoderDesc(ctypes.Structure):
@@ -81,6 +82,9 @@ def lib():
         L.vscan_llm_prune.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, vp, i32p, vp, vp, vp,
                                       f32p, vp, ctypes.c_size_t, vp]
         L.vscan_llm_prune.restype = ctypes.c_int
+        L.vscan_llm_prune_ragged.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, vp, vp, vp, i32p,
+                                             vp, vp, vp, f32p, vp, ctypes.c_size_t, vp]
+        L.vscan_llm_prune_ragged.restype = ctypes.c_int
         L.vscan_profile_enable.argtypes = [ctypes.c_int]
         L.vscan_profile_enable.restype = ctypes.c_int
         L.vscan_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int,
@@ -153,6 +157,41 @@ def flops(n_per_layer, d: int, m: int) -> float:
     if rc != VSCAN_OK:
         raise VscanError(rc, "vscan_flops")
     return float(out.value)
+
+
+def llm_prune_ragged(shape, meta, q, k, v, hidden, want_scores: bool = False) -> Dict[str, object]:
+    """vscan_llm_prune_ragged.  `shape` carries the shared fields and the capacities (seq_len,
+    vis_len, keep); `meta` is a list of (seq_len, vis_start, vis_len, keep) per sequence.
+    Out-of-place results are tensors shaped like the inputs (rows past a sequence's result are
+    zero-filled here so that they are defined); `out_len` lists the result lengths."""
+    import torch
+    desc = llm_desc(shape)
+    need = llm_workspace_size(desc)
+    dev = q.device
+    B = shape.batch
+    assert len(meta) == B
+    host = (ctypes.c_int32 * (4 * max(B, 1)))(*[int(x) for m in meta for x in m])
+    meta_dev = torch.tensor([list(map(int, m)) for m in meta], dtype=torch.int32,
+                            device=dev).reshape(B, 4).contiguous()
+    workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = {"kept_idx": torch.empty((B, shape.keep), dtype=torch.int32, device=dev)}
+    if want_scores:
+        out["scores"] = torch.zeros((B, shape.vis_len), dtype=torch.float32, device=dev)
+    if shape.in_place:
+        ko = vo = ho = None
+    else:
+        ko, vo, ho = torch.zeros_like(k), torch.zeros_like(v), torch.zeros_like(hidden)
+    rc = lib().vscan_llm_prune_ragged(ctypes.byref(desc), ctypes.cast(host, ctypes.c_void_p),
+                                      _ptr(meta_dev), _ptr(q), _ptr(k), _ptr(v), _ptr(hidden),
+                                      _ptr(out["kept_idx"]), _ptr(ko), _ptr(vo), _ptr(ho),
+                                      _ptr(out.get("scores")), _ptr(workspace),
+                                      workspace.numel(), _stream_handle())
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_llm_prune_ragged")
+    out["k"], out["v"], out["hidden"] = (k, v, hidden) if shape.in_place else (ko, vo, ho)
+    out["out_len"] = [m[0] - m[2] + m[3] for m in meta]
+    out["meta_device"], out["workspace"] = meta_dev, workspace  # alive until the work has run
+    return out
 
 
 def _dtype_code(dtype: str) -> int:

@@ -273,12 +273,12 @@ int vscan_llm_workspace_size(const vscan_llm_desc *desc, size_t *bytes) {
     return VSCAN_OK;
 }
 
-int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, void *hidden,
-                    int32_t *kept_idx, void *k_out, void *v_out, void *hidden_out,
-                    float *scores_out, void *workspace, size_t workspace_bytes, void *stream) {
-    LlmPlan p;
-    const int rc = plan_llm(d, &p);
-    if (rc != VSCAN_OK) return rc;
+// Shared by the uniform and the ragged entry point.  `meta` (device) is NULL for a uniform
+// batch; `max_out_rows` is the longest result, `out_rows` the row stride of the destinations.
+static int run_llm(const vscan_llm_desc *d, const LlmPlan &p, const SeqMeta *meta, int max_out_rows,
+                   int out_rows, const void *q, void *k, void *v, void *hidden, int32_t *kept_idx,
+                   void *k_out, void *v_out, void *hidden_out, float *scores_out, void *workspace,
+                   size_t workspace_bytes, void *stream) {
     if (!q || !k || !v || !hidden || (!kept_idx && d->keep > 0)) return VSCAN_ERR_NULL;
     const bool outs_null = !k_out && !v_out && !hidden_out;
     const bool outs_all = k_out && v_out && hidden_out;
@@ -310,6 +310,7 @@ int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, vo
     sa.domain_all = d->softmax_domain == VSCAN_KEYS_ALL;
     sa.is_bf16 = d->dtype == VSCAN_BF16;
     sa.scale = resolve_scale(d->scale, d->head_dim);
+    sa.meta = meta;
     VSCAN_LAUNCH("llm_score", launch_llm_score(sa, s));
 
     LlmSelectArgs se;
@@ -321,6 +322,7 @@ int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, vo
     se.norm = 1.0f / ((float)d->n_query * (float)d->q_heads);
     se.kept_idx = kept_idx;
     se.scores_out = scores_out;
+    se.meta = meta;
     VSCAN_LAUNCH("llm_select", launch_llm_select(se, s));
 
     CompactArgs ca;
@@ -344,8 +346,53 @@ int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, vo
     ca.keep = d->keep;
     ca.elem_bytes = elem_bytes(d->dtype);
     ca.in_place = d->in_place;
+    ca.out_rows = out_rows;
+    ca.max_out_rows = max_out_rows;
+    ca.meta = meta;
     VSCAN_LAUNCH("compact", launch_compact(ca, s));
     return VSCAN_OK;
+}
+
+int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, void *hidden,
+                    int32_t *kept_idx, void *k_out, void *v_out, void *hidden_out,
+                    float *scores_out, void *workspace, size_t workspace_bytes, void *stream) {
+    LlmPlan p;
+    const int rc = plan_llm(d, &p);
+    if (rc != VSCAN_OK) return rc;
+    return run_llm(d, p, nullptr, p.S_out, d->in_place ? d->seq_len : p.S_out, q, k, v, hidden,
+                   kept_idx, k_out, v_out, hidden_out, scores_out, workspace, workspace_bytes,
+                   stream);
+}
+
+int vscan_llm_prune_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
+                           const vscan_seq_meta *meta_device, const void *q, void *k, void *v,
+                           void *hidden, int32_t *kept_idx, void *k_out, void *v_out,
+                           void *hidden_out, float *scores_out, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+    if (!d) return VSCAN_ERR_NULL;
+    if (d->struct_size != sizeof(vscan_llm_desc)) return VSCAN_ERR_VERSION;
+    // the descriptor's lengths are capacities here; its vis_start has no meaning
+    vscan_llm_desc caps = *d;
+    caps.vis_start = 0;
+    LlmPlan p;
+    const int rc = plan_llm(&caps, &p);
+    if (rc != VSCAN_OK) return rc;
+    if (d->batch > 0 && (!meta_host || !meta_device)) return VSCAN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(meta_device) & 3u) return VSCAN_ERR_ALIGN;
+    int max_out_rows = 0;
+    for (int b = 0; b < d->batch; ++b) {
+        const vscan_seq_meta &m = meta_host[b];
+        if (m.seq_len < 1 || m.seq_len > d->seq_len || m.vis_start < 0 || m.vis_len < 1 ||
+            m.vis_len > d->vis_len)
+            return VSCAN_ERR_SHAPE;
+        if ((int64_t)m.vis_start + m.vis_len + d->n_query > m.seq_len) return VSCAN_ERR_SHAPE;
+        if (m.keep < 0 || m.keep > m.vis_len || m.keep > d->keep) return VSCAN_ERR_BUDGET;
+        max_out_rows = std::max(max_out_rows, m.seq_len - m.vis_len + m.keep);
+    }
+    static_assert(sizeof(SeqMeta) == sizeof(vscan_seq_meta), "same layout");
+    return run_llm(&caps, p, reinterpret_cast<const SeqMeta *>(meta_device), max_out_rows,
+                   d->seq_len, q, k, v, hidden, kept_idx, k_out, v_out, hidden_out, scores_out,
+                   workspace, workspace_bytes, stream);
 }
 
 int vscan_profile_enable(int on) {

@@ -49,6 +49,14 @@ struct MergeArgs {
 hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s);
 hipError_t launch_merge(const MergeArgs &a, hipStream_t s);
 
+// Per-sequence lengths of a ragged stage-2 batch (same layout as vscan_seq_meta).  Where an
+// args struct carries a non-NULL `meta` (a DEVICE array of B entries), the kernels take
+// seq_len / vis_start / vis_len / keep of sequence b from meta[b]; the struct's own S, V, keep
+// then are capacities: tensor strides and LDS sizes.
+struct SeqMeta {
+    int32_t seq_len, vis_start, vis_len, keep;
+};
+
 // stage 2 scoring (Eq. 5)
 struct LlmScoreArgs {
     const void *q;             // [B, Hq, Tq, dh]
@@ -57,6 +65,7 @@ struct LlmScoreArgs {
     int B, Hq, Hkv, Tq, S, dh, vis_start, V;
     int domain_all, is_bf16;
     float scale;
+    const SeqMeta *meta = nullptr;
 };
 hipError_t launch_llm_score(const LlmScoreArgs &a, hipStream_t s);
 // rows = (Hq/Hkv)*Tq query rows per kv head, nk = keys in the softmax domain
@@ -66,8 +75,9 @@ struct LlmSelectArgs {
     const float *part;         // [B, Hkv, V]
     int B, Hkv, V, keep;
     float norm;                // 1/(Tq*Hq)
-    int32_t *kept_idx;         // [B, keep]
+    int32_t *kept_idx;         // [B, keep]; ragged: entries past a sequence's own keep are -1
     float *scores_out;         // optional [B, V]
+    const SeqMeta *meta = nullptr;
 };
 hipError_t launch_llm_select(const LlmSelectArgs &a, hipStream_t s);
 size_t llm_select_lds_bytes(int V);
@@ -78,6 +88,11 @@ struct CompactArgs {
     void *k_out, *v_out, *hidden_out;  // NULL when in_place
     const int32_t *kept_idx;           // [B, keep]; at least one readable int when keep == 0
     int B, Hkv, S, dh, Dh, vis_start, V, keep, elem_bytes, in_place;
+    // rows between consecutive slabs of the destinations: S - V + keep for the dense
+    // out-of-place result, S when compacting in place or into tensors shaped like the inputs
+    int out_rows;
+    int max_out_rows;  // rows of the longest result (S - V + keep when every sequence is alike)
+    const SeqMeta *meta = nullptr;
 };
 hipError_t launch_compact(const CompactArgs &a, hipStream_t s);
 

@@ -52,9 +52,14 @@ template <typename T, int NC, int NRB, bool STAGED, int DEPTH>
 __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB == 1) ? 4 : 2) void llm_score_kernel(const T *__restrict__ q,
                                                         const T *__restrict__ k,
                                                         float *__restrict__ part, int B, int Hq,
-                                                        int Hkv, int Tq, int S, int dh,
-                                                        int vis_start, int V, int k0, int nk,
+                                                        int Hkv, int Tq, int S_cap, int dh,
+                                                        int vis_start_u, int V_cap, int k0_u,
+                                                        int nk_u, int domain_all,
+                                                        const SeqMeta *__restrict__ meta,
                                                         float sl2) {
+    // S_cap, V_cap: rows per sequence of k and of part (tensor strides).  Without `meta` every
+    // sequence has the lengths (S_cap, vis_start_u, V_cap) and the key domain [k0_u, k0_u + nk_u);
+    // with it, sequence b has those of meta[b], and nk_u is the longest domain (LDS layout).
     constexpr int STR = NC * 64 + 16;          // bytes per key in a staging area
     extern __shared__ __align__(16) unsigned char smem[];
     float *rowM = reinterpret_cast<float *>(smem);  // 64: row maxima
@@ -63,8 +68,7 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
     float *z = rowM + kScoreHeader;                  // [R][zs]
 
     const int group = Hq / Hkv, R = group * Tq;
-    const int nk16 = (nk + 15) & ~15;
-    const int zs = score_logit_stride(nk);
+    const int zs = score_logit_stride(nk_u);
     const int row_bytes = dh * (int)sizeof(T);
     const int lane = lane_id(), l16 = lane & 15, g = lane >> 4, w = wave_id();
     unsigned char *stage = reinterpret_cast<unsigned char *>(z + (int64_t)R * zs) + w * 16 * STR;
@@ -73,8 +77,24 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
     auto q_of = [&](int item) {  // item = b * Hkv + kv head; its query rows are contiguous
         return reinterpret_cast<const unsigned char *>(q) + (int64_t)item * group * Tq * row_bytes;
     };
-    auto k_of = [&](int item) {
-        return reinterpret_cast<const unsigned char *>(k) + ((int64_t)item * S + k0) * row_bytes;
+    struct Geom {
+        int S, vs, V, k0, nk;  // sequence length, visual span, key domain of an item
+    };
+    auto geom_of = [&](int item) {
+        Geom gm = {S_cap, vis_start_u, V_cap, k0_u, nk_u};
+        if (meta) {
+            const SeqMeta m = meta[item / Hkv];
+            gm.S = m.seq_len;
+            gm.vs = m.vis_start;
+            gm.V = m.vis_len;
+            gm.k0 = domain_all ? 0 : m.vis_start;
+            gm.nk = domain_all ? m.seq_len : m.vis_len;
+        }
+        return gm;
+    };
+    auto k_of = [&](int item, int k0) {
+        return reinterpret_cast<const unsigned char *>(k) +
+               ((int64_t)item * S_cap + k0) * row_bytes;
     };
     auto load_q = [&](const unsigned char *qbase, uint4(&dst)[NRB][NC]) {
 #pragma unroll
@@ -104,15 +124,10 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
             *reinterpret_cast<uint4 *>(stage + i) = zero16();
     }
 
-    const int ntiles = nk16 >> 4;
-    // this wave's tiles of an item: w, w + kScoreWaves, ...; every wave runs the same number of
-    // rounds of DEPTH tiles, the surplus tiles are fetched (clamped) and ignored
-    const int my_tiles = ntiles > w ? (ntiles - w + kScoreWaves - 1) / kScoreWaves : 0;
-    const int rounds = ((ntiles + kScoreWaves - 1) / kScoreWaves + DEPTH - 1) / DEPTH;
-    const int full_rounds = my_tiles / DEPTH;
-
+    Geom gc;  // the item being multiplied; set at the top of every item
     uint4 ring[DEPTH][NC];
-    auto fetch = [&](const unsigned char *kbase, int n, uint4(&dst)[NC]) {
+    // tile n of the item whose keys start at kbase and whose key domain is nk keys long
+    auto fetch = [&](const unsigned char *kbase, int nk, int n, uint4(&dst)[NC]) {
         const int key0 = (w + kScoreWaves * n) * 16;
         if constexpr (STAGED) {
             // byte offsets are clamped to the last piece of the key range: always readable
@@ -157,13 +172,13 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
             const int row = rb * 16 + l16;
             if (row < R) {
                 const int t = row % Tq;
-                const int last_pos = S - Tq + t;  // causal limit of this query
+                const int last_pos = gc.S - Tq + t;  // causal limit of this query
                 float4 o;
                 float *op = &o.x;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int kk = key0 + 4 * g + r;
-                    op[r] = (kk < nk && k0 + kk <= last_pos) ? acc[r] * sl2 : -INFINITY;
+                    op[r] = (kk < gc.nk && gc.k0 + kk <= last_pos) ? acc[r] * sl2 : -INFINITY;
                 }
                 mx[rb] = fmaxf(fmaxf(mx[rb], fmaxf(o.x, o.y)), fmaxf(o.z, o.w));
                 *reinterpret_cast<float4 *>(z + (int64_t)row * zs + key0 + 4 * g) = o;
@@ -173,21 +188,30 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
 
     int item = blockIdx.x;
     if (item >= items) return;
-    const unsigned char *kbase = k_of(item);
+    gc = geom_of(item);
+    const unsigned char *kbase = k_of(item, gc.k0);
     load_q(q_of(item), qfrag);
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) fetch(kbase, d, ring[d]);
+    for (int d = 0; d < DEPTH; ++d) fetch(kbase, gc.nk, d, ring[d]);
 
     for (; item < items; item += gridDim.x) {
         const bool has_next = item + (int)gridDim.x < items;
         const int next = has_next ? item + (int)gridDim.x : item;
-        const unsigned char *kbase_next = k_of(next);
+        const Geom gn = has_next ? geom_of(next) : gc;
+        const unsigned char *kbase_next = k_of(next, gn.k0);
+        const int nk16 = (gc.nk + 15) & ~15, ntiles = nk16 >> 4;
+        // this wave's tiles of the item: w, w + kScoreWaves, ...; every wave runs the same
+        // number of rounds of DEPTH tiles, the surplus tiles are fetched (clamped) and ignored
+        const int my_tiles = ntiles > w ? (ntiles - w + kScoreWaves - 1) / kScoreWaves : 0;
+        const int rounds = ((ntiles + kScoreWaves - 1) / kScoreWaves + DEPTH - 1) / DEPTH;
+        const int full_rounds = my_tiles / DEPTH;
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) mx[rb] = -INFINITY;
 
-        // Round r works on tiles 4r .. 4r+3 and refills each ring slot with the tile of the next
-        // round - in the last round, with the first tiles of the next item.  Full rounds carry
-        // no condition, so each tile is awaited on its own while the later ones stay in flight.
+        // Round r works on tiles DEPTH r .. DEPTH r + DEPTH - 1 and refills each ring slot with
+        // the tile of the next round - in the last round, with the first tiles of the next item.
+        // Full rounds carry no condition, so each tile is awaited on its own while the later
+        // ones stay in flight.
         int r = 0;
         if (full_rounds > 0 && rounds > 1) {
             // The first round is kept out of the loop below: here the stores of the previous
@@ -196,7 +220,7 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
                 process(d, ring[d]);
-                fetch(kbase, DEPTH + d, ring[d]);
+                fetch(kbase, gc.nk, DEPTH + d, ring[d]);
             }
             r = 1;
         }
@@ -204,17 +228,18 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
                 process(DEPTH * r + d, ring[d]);
-                fetch(kbase, DEPTH * (r + 1) + d, ring[d]);
+                fetch(kbase, gc.nk, DEPTH * (r + 1) + d, ring[d]);
             }
         }
         for (; r < rounds; ++r) {  // the last round, and a partial one before it if there is one
             const bool last = r + 1 == rounds;
             const unsigned char *fbase = last ? kbase_next : kbase;
+            const int fnk = last ? gn.nk : gc.nk;
             const int fn = last ? 0 : DEPTH * (r + 1);
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
                 if (DEPTH * r + d < my_tiles) process(DEPTH * r + d, ring[d]);
-                if (!last || has_next) fetch(fbase, fn + d, ring[d]);
+                if (!last || has_next) fetch(fbase, fnk, fn + d, ring[d]);
             }
         }
         if (has_next) load_q(q_of(next), qfrag);  // this item's queries are no longer needed
@@ -252,9 +277,9 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
         __syncthreads();
 
         // columns: sum over the rows in a fixed order
-        float *out = part + (int64_t)item * V;
-        const int col0 = vis_start - k0;
-        for (int j = threadIdx.x; j < V; j += blockDim.x) {
+        float *out = part + (int64_t)item * V_cap;
+        const int col0 = gc.vs - gc.k0;
+        for (int j = threadIdx.x; j < gc.V; j += blockDim.x) {
             float s = 0.f;
             for (int row = 0; row < R; ++row) s += z[(int64_t)row * zs + col0 + j] * rowInvL[row];
             out[j] = s;
@@ -263,6 +288,7 @@ __global__ __launch_bounds__(kScoreWaves * kWave, (DEPTH == 2 && NC <= 4 && NRB 
         __syncthreads();  // the logits are free for the next item
 
         kbase = kbase_next;
+        gc = gn;
     }
 }
 
@@ -295,8 +321,8 @@ static hipError_t llm_score_launch3(const LlmScoreArgs &a, hipStream_t s, size_t
     const int grid = (int)std::min<int64_t>(items, (int64_t)kCus * per_cu);
     hipLaunchKernelGGL((llm_score_kernel<T, NC, NRB, STAGED, DEPTH>), dim3(grid),
                        dim3(kScoreWaves * kWave), smem, s, (const T *)a.q, (const T *)a.k, a.part,
-                       a.B, a.Hq, a.Hkv, a.Tq, a.S, a.dh, a.vis_start, a.V, k0, nk,
-                       a.scale * 1.4426950408889634f);
+                       a.B, a.Hq, a.Hkv, a.Tq, a.S, a.dh, a.vis_start, a.V, k0, nk, a.domain_all,
+                       a.meta, a.scale * 1.4426950408889634f);
     return hipGetLastError();
 }
 
@@ -352,7 +378,8 @@ struct Strip {
     int b;
 };
 
-__device__ __forceinline__ Strip decode_strip(const CompactArgs &a, int id, int S_out) {
+// slab bases only: valid before the per-sequence lengths of a ragged batch are known
+__device__ __forceinline__ Strip decode_strip(const CompactArgs &a, int id) {
     const int kv_w = a.dh * a.elem_bytes, hid_w = a.Dh * a.elem_bytes;
     const int kv_strips = (kv_w + 255) / 256, hid_strips = (hid_w + 255) / 256;
     const int n_kv = a.B * a.Hkv * kv_strips;
@@ -367,7 +394,7 @@ __device__ __forceinline__ Strip decode_strip(const CompactArgs &a, int id, int 
         s.src_stride = kv_w;
         s.dst_stride = kv_w;
         s.src = in + (int64_t)slab * a.S * kv_w + strip * 256;
-        s.dst = a.in_place ? s.src : out + (int64_t)slab * S_out * kv_w + strip * 256;
+        s.dst = a.in_place ? s.src : out + (int64_t)slab * a.out_rows * kv_w + strip * 256;
         s.width = min(256, kv_w - strip * 256);
     } else {
         const int r = id - 2 * n_kv;
@@ -378,10 +405,24 @@ __device__ __forceinline__ Strip decode_strip(const CompactArgs &a, int id, int 
         s.src_stride = hid_w;
         s.dst_stride = hid_w;
         s.src = in + (int64_t)b * a.S * hid_w + strip * 256;
-        s.dst = a.in_place ? s.src : out + (int64_t)b * S_out * hid_w + strip * 256;
+        s.dst = a.in_place ? s.src : out + (int64_t)b * a.out_rows * hid_w + strip * 256;
         s.width = min(256, hid_w - strip * 256);
     }
     return s;
+}
+
+// Ragged batch: replace the lengths in the (by-value) argument block by those of sequence b.
+// Returns the kept-index row of the sequence.
+__device__ __forceinline__ const int32_t *sequence_view(CompactArgs &a, int b) {
+    const int32_t *kept_b = a.kept_idx + (int64_t)b * a.keep;  // a.keep is still the stride here
+    if (a.meta) {
+        const SeqMeta m = a.meta[b];
+        a.S = m.seq_len;
+        a.vis_start = m.vis_start;
+        a.V = m.vis_len;
+        a.keep = m.keep;
+    }
+    return kept_b;
 }
 
 // Source rows of N output rows p[i].  The kept indices are fetched for every p from a clamped
@@ -427,10 +468,10 @@ __device__ __forceinline__ void wait_for_loads(const uint4 *regs, int n) {
 // every later tile's sources (source row >= destination row, both ascending).
 __global__ __launch_bounds__(256) void compact_inplace_kernel(CompactArgs a) {
     __shared__ int red[4];
+    const Strip s = decode_strip(a, blockIdx.x);
+    const int32_t *kept_b = sequence_view(a, s.b);
     if (a.keep == a.V) return;  // nothing was pruned
     const int S_out = a.S - a.V + a.keep;
-    const Strip s = decode_strip(a, blockIdx.x, S_out);
-    const int32_t *kept_b = a.kept_idx + (int64_t)s.b * a.keep;
     const int tid = threadIdx.x;
 
     // first destination row whose source differs
@@ -488,9 +529,9 @@ __global__ __launch_bounds__(256) void compact_inplace_kernel(CompactArgs a) {
 
 // Out of place: a plain row gather; grid (strips, row tiles).
 __global__ __launch_bounds__(256) void compact_gather_kernel(CompactArgs a) {
+    const Strip s = decode_strip(a, blockIdx.x);
+    const int32_t *kept_b = sequence_view(a, s.b);
     const int S_out = a.S - a.V + a.keep;
-    const Strip s = decode_strip(a, blockIdx.x, S_out);
-    const int32_t *kept_b = a.kept_idx + (int64_t)s.b * a.keep;
     const int piece = threadIdx.x & 15, rloc = threadIdx.x >> 4;
     if (piece * 16 >= s.width) return;
     uint4 v[kCompactRpt];
@@ -519,8 +560,7 @@ hipError_t launch_compact(const CompactArgs &a, hipStream_t s) {
     if (a.in_place) {
         hipLaunchKernelGGL(compact_inplace_kernel, dim3(strips), dim3(256), 0, s, a);
     } else {
-        const int S_out = a.S - a.V + a.keep;
-        dim3 grid(strips, (S_out + kCompactTile - 1) / kCompactTile);
+        dim3 grid(strips, (a.max_out_rows + kCompactTile - 1) / kCompactTile);
         hipLaunchKernelGGL(compact_gather_kernel, grid, dim3(256), 0, s, a);
     }
     return hipGetLastError();

@@ -357,23 +357,28 @@ __global__ __launch_bounds__(1024) void llm_select_kernel(LlmSelectArgs a) {
     SelectSmem &sm = *reinterpret_cast<SelectSmem *>(smem);
     uint32_t *key = reinterpret_cast<uint32_t *>(smem + sizeof(SelectSmem));
     uint8_t *flag = reinterpret_cast<uint8_t *>(key + a.V);
-    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, V = a.V;
+    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
+    // ragged batch: this sequence's own span and budget; a.V and a.keep stay the strides
+    const int V = a.meta ? a.meta[b].vis_len : a.V;
+    const int keep = a.meta ? a.meta[b].keep : a.keep;
     for (int j = tid; j < V; j += nt) {
-        const float s = head_sum(a.part + (int64_t)b * a.Hkv * V + j, a.Hkv, V) * a.norm;
+        const float s = head_sum(a.part + (int64_t)b * a.Hkv * a.V + j, a.Hkv, a.V) * a.norm;
         key[j] = float_to_key(s);
         flag[j] = 0;
-        if (a.scores_out) a.scores_out[(int64_t)b * V + j] = s;
+        if (a.scores_out) a.scores_out[(int64_t)b * a.V + j] = s;
     }
+    if (a.meta)
+        for (int i = keep + tid; i < a.keep; i += nt) a.kept_idx[(int64_t)b * a.keep + i] = -1;
     __syncthreads();
     auto slot = [&](int sl, int &idx) -> uint32_t {
         idx = sl;
         return key[sl];
     };
     if (GLOBAL_WAVE) {
-        if (wave_id() == 0) wave_topk_regs<NREG>(slot, V, a.keep, flag, 1);
+        if (wave_id() == 0) wave_topk_regs<NREG>(slot, V, keep, flag, 1);
         __syncthreads();
     } else {
-        block_topk_regs<NREG>(slot, V, a.keep, flag, 1, sm);
+        block_topk_regs<NREG>(slot, V, keep, flag, 1, sm);
     }
     int run = 0;
     for (int base = 0; base < V; base += nt) {

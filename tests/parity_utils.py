@@ -188,3 +188,66 @@ def check_llm(shape, inp, ref, out, what=""):
         assert got.shape == ref[name].shape, f"{what}: {name} shape"
         assert np.array_equal(got, ref[name]), f"{what}: compacted {name} differs"
     return report
+
+
+def ragged_llm_case(base, seqs, seed):
+    """A ragged stage-2 batch.  `base`: an LlmShape giving the shared fields; `seqs`: list of
+    (prefix, vis_len, text, keep).  Every sequence is generated and screened on its own (batch-1
+    shapes) and padded with noise to the common capacity.  Returns the capacity shape, the meta
+    rows (seq_len, vis_start, vis_len, keep), the padded inputs and the per-sequence oracle
+    results."""
+    from dataclasses import replace
+    cap_S = max(p + v + t for p, v, t, _ in seqs)
+    cap_V = max(v for _, v, _, _ in seqs)
+    cap_keep = max(kp for *_, kp in seqs)
+    caps = replace(base, batch=len(seqs), prefix=0, vis_len=cap_V, text=cap_S - cap_V,
+                   keep=cap_keep)
+    rng = np.random.default_rng(seed)
+    H, Hq, dh, Dh, Tq = base.kv_heads, base.q_heads, base.head_dim, base.hidden, base.n_query
+    pad = lambda *shape: wl._finish(rng.standard_normal(shape).astype(np.float32), base.dtype)
+    inp = {"q": np.empty((len(seqs), Hq, Tq, dh), np.float32), "k": pad(len(seqs), H, cap_S, dh),
+           "v": pad(len(seqs), H, cap_S, dh), "hidden": pad(len(seqs), cap_S, Dh)}
+    meta, refs = [], []
+    for b, (p, v, t, kp) in enumerate(seqs):
+        one = replace(base, batch=1, prefix=p, vis_len=v, text=t, keep=kp)
+        for attempt in range(32):
+            item = wl.llm_inputs(one, seed + 100 * b + attempt)
+            ref = vo.llm_prune(one, **item)
+            if topk_boundary_gap(ref["scores"], kp) > MARGIN:
+                break
+        else:
+            raise AssertionError("no seed clears the boundary margin")
+        S = one.seq_len
+        inp["q"][b] = item["q"][0]
+        inp["k"][b, :, :S] = item["k"][0]
+        inp["v"][b, :, :S] = item["v"][0]
+        inp["hidden"][b, :S] = item["hidden"][0]
+        meta.append((S, p, v, kp))
+        refs.append(ref)
+    return caps, meta, inp, refs
+
+
+def check_llm_ragged(caps, meta, inp, refs, out, in_place, what=""):
+    """Per sequence against the oracle; entries and rows outside a sequence's result must be
+    the padding value (-1 for indices) or untouched."""
+    kept = to_host(out["kept_idx"])
+    scores = to_host(out["scores"]) if "scores" in out else None
+    got = {n: to_host(out[n]) for n in ("k", "v", "hidden")}
+    worst = 0.0
+    for b, (S, vs, V, kp) in enumerate(meta):
+        ref = refs[b]
+        assert np.array_equal(kept[b, :kp], ref["kept"][0]), f"{what}[{b}]: kept indices differ"
+        assert np.all(kept[b, kp:] == -1), f"{what}[{b}]: index padding"
+        if scores is not None:
+            worst = max(worst, check_scores(scores[b:b + 1, :V], ref["scores"], f"{what}[{b}]"))
+        So = S - V + kp
+        assert np.array_equal(got["k"][b, :, :So], ref["k"][0]), f"{what}[{b}]: k"
+        assert np.array_equal(got["v"][b, :, :So], ref["v"][0]), f"{what}[{b}]: v"
+        assert np.array_equal(got["hidden"][b, :So], ref["hidden"][0]), f"{what}[{b}]: hidden"
+        if in_place:  # rows past the sequence's own length are never touched
+            assert np.array_equal(got["k"][b, :, S:], inp["k"][b, :, S:]), f"{what}[{b}]: k padding"
+            assert np.array_equal(got["hidden"][b, S:], inp["hidden"][b, S:]), f"{what}[{b}]: hidden padding"
+        else:         # the binding zero-fills the destinations; rows past the result stay zero
+            assert not got["k"][b, :, So:].any() and not got["hidden"][b, So:].any(), \
+                f"{what}[{b}]: rows past the result were written"
+    return {"score_rel_err": worst}

@@ -169,6 +169,47 @@ def test_llm_rejects_bad_pointers_and_workspace():
     assert _llm_call(inplace, ko=None, vo=None, ho=None, ws=None) == vb.VSCAN_ERR_WORKSPACE
 
 
+def _ragged_call(desc, rows, meta_dev=FAKE, **kw):
+    host = (ctypes.c_int32 * (4 * max(len(rows), 1)))(*[x for r in rows for x in r])
+    a = dict(q=FAKE, k=FAKE, v=FAKE, hidden=FAKE, kept=FAKE, ko=FAKE, vo=FAKE, ho=FAKE, ws=FAKE)
+    a.update(kw)
+    return vb.lib().vscan_llm_prune_ragged(
+        ctypes.byref(desc), ctypes.cast(host, ctypes.c_void_p) if rows is not None else None,
+        meta_dev, a["q"], a["k"], a["v"], a["hidden"], a["kept"], a["ko"], a["vo"], a["ho"], None,
+        a["ws"], 1 << 40, None)
+
+
+@pytest.mark.parametrize("row,status", [
+    ((140, 35, 64, 32), vb.VSCAN_ERR_SHAPE),    # longer than the capacity (139 rows)
+    ((0, 0, 1, 0), vb.VSCAN_ERR_SHAPE),
+    ((139, -1, 64, 32), vb.VSCAN_ERR_SHAPE),
+    ((139, 35, 0, 0), vb.VSCAN_ERR_SHAPE),      # no visual token
+    ((139, 35, 65, 32), vb.VSCAN_ERR_SHAPE),    # span longer than the capacity (64)
+    ((100, 40, 60, 10), vb.VSCAN_ERR_SHAPE),    # no room for the query position after the span
+    ((139, 35, 64, 33), vb.VSCAN_ERR_BUDGET),   # above the index capacity (32)
+    ((139, 35, 20, 21), vb.VSCAN_ERR_BUDGET),   # more than the sequence has
+    ((139, 35, 64, -1), vb.VSCAN_ERR_BUDGET),
+])
+def test_ragged_rejects_bad_sequences(row, status):
+    desc = vb.llm_desc(_llm_shape(batch=2))
+    good = (139, 35, 64, 32)
+    assert _ragged_call(desc, [good, row]) == status
+
+
+def test_ragged_pointer_checks_and_empty_batch():
+    desc = vb.llm_desc(_llm_shape(batch=1))
+    good = [(139, 35, 64, 32)]
+    assert _ragged_call(desc, good, meta_dev=None) == vb.VSCAN_ERR_NULL
+    assert _ragged_call(desc, good, meta_dev=FAKE + 2) == vb.VSCAN_ERR_ALIGN
+    assert _ragged_call(desc, good, hidden=None) == vb.VSCAN_ERR_NULL
+    assert _ragged_call(desc, good, ko=None) == vb.VSCAN_ERR_NULL
+    assert _ragged_call(desc, good, ws=None) == vb.VSCAN_ERR_WORKSPACE
+    empty = vb.llm_desc(_llm_shape(batch=0))
+    assert _ragged_call(empty, [], meta_dev=None) == vb.VSCAN_OK      # nothing to enqueue
+    # the capacities themselves go through the same checks as a uniform descriptor
+    assert _ragged_call(vb.llm_desc(_llm_shape(head_dim=100)), good) == vb.VSCAN_ERR_SHAPE
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(vb, "_lib", None)
     monkeypatch.setattr(vb, "LIB_PATH", "/nonexistent/libvscan.so")

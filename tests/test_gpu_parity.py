@@ -178,6 +178,76 @@ def test_llm_small(name):
     print(name, info, rep)
 
 
+def test_llm_multi_turn_reselection():
+    """A second question re-scores the same unpruned pool (App. "Remarks on Multi-Turn
+    Conversations"): out-of-place pruning leaves hidden states and K/V untouched, and each turn's result
+    matches the oracle for that turn's queries."""
+    import torch
+    shape = _llm(batch=3, prefix=5, vis_len=333, text=40, keep=77, n_query=2)
+    inp1, ref1, info1 = pu.screened_llm_case(shape, seed=4100)
+    inp2, ref2, info2 = pu.screened_llm_case(shape, seed=4200)
+    # turn 2 = turn 1's pool with turn 2's queries
+    turn2 = dict(inp1, q=inp2["q"])
+    ref_t2 = vo.llm_prune(shape, **turn2)
+    if pu.topk_boundary_gap(ref_t2["scores"], shape.keep) <= pu.MARGIN:
+        pytest.skip("second-turn boundary too close for this seed")
+    q1, k, v, h = (pu.to_device(inp1[n], shape.dtype) for n in ("q", "k", "v", "hidden"))
+    q2 = pu.to_device(inp2["q"], shape.dtype)
+    pool = [t.clone() for t in (k, v, h)]
+    out1 = vb.llm_prune(shape, q1, k, v, h, want_scores=True)
+    out2 = vb.llm_prune(shape, q2, k, v, h, want_scores=True)
+    torch.cuda.synchronize()
+    for before, after in zip(pool, (k, v, h)):
+        assert torch.equal(before, after), "out-of-place pruning modified the pool"
+    print("turn 1", info1, pu.check_llm(shape, inp1, ref1, out1, "turn1"))
+    print("turn 2", pu.check_llm(shape, turn2, ref_t2, out2, "turn2"))
+    assert not np.array_equal(pu.to_host(out1["kept_idx"]), pu.to_host(out2["kept_idx"]))
+
+
+RAGGED_SEQS = [
+    # (prefix, vis_len, text, keep): long and short spans, nothing kept, everything kept,
+    # a span shorter than one tile, the longest sequence not the one with the longest span
+    (35, 900, 70, 300), (3, 5, 9, 2), (0, 333, 41, 0), (12, 257, 300, 257), (7, 1100, 13, 1),
+    (20, 64, 20, 63),
+]
+
+
+@pytest.mark.parametrize("variant", ["bf16", "bf16-inplace", "f32-all-keys", "bf16-gqa-inplace"])
+def test_llm_ragged(variant):
+    """Per-sequence lengths, spans and budgets in one call (dynamic-resolution inputs,
+    Sec. 5.1 "Models"), each sequence against the oracle run on that sequence alone."""
+    import torch
+    base = {
+        "bf16": _llm(n_query=1),
+        "bf16-inplace": _llm(in_place=1, n_query=2),
+        "f32-all-keys": _llm(wl.F32, softmax_domain=1, head_dim=64, n_query=1),
+        "bf16-gqa-inplace": _llm(in_place=1, q_heads=8, kv_heads=2, head_dim=128, n_query=3),
+    }[variant]
+    caps, meta, inp, refs = pu.ragged_llm_case(base, RAGGED_SEQS, seed=7000 + len(variant))
+    q, k, v, h = (pu.to_device(inp[n], caps.dtype) for n in ("q", "k", "v", "hidden"))
+    out = vb.llm_prune_ragged(caps, meta, q, k, v, h, want_scores=True)
+    torch.cuda.synchronize()
+    print(variant, pu.check_llm_ragged(caps, meta, inp, refs, out, caps.in_place, variant))
+
+
+def test_llm_ragged_matches_uniform():
+    """A ragged call whose sequences all have the descriptor's own lengths gives exactly what
+    the uniform entry point gives."""
+    import torch
+    shape = _llm(batch=4, prefix=9, vis_len=400, text=33, keep=100, n_query=2)
+    inp, ref, info = pu.screened_llm_case(shape, seed=7300)
+    q, k, v, h = (pu.to_device(inp[n], shape.dtype) for n in ("q", "k", "v", "hidden"))
+    uni = vb.llm_prune(shape, q, k, v, h, want_scores=True)
+    meta = [(shape.seq_len, shape.vis_start, shape.vis_len, shape.keep)] * shape.batch
+    rag = vb.llm_prune_ragged(shape, meta, q, k, v, h, want_scores=True)
+    torch.cuda.synchronize()
+    So = shape.seq_out
+    assert torch.equal(uni["kept_idx"], rag["kept_idx"]) and torch.equal(uni["scores"], rag["scores"])
+    assert torch.equal(uni["k"], rag["k"][:, :, :So]) and torch.equal(uni["v"], rag["v"][:, :, :So])
+    assert torch.equal(uni["hidden"], rag["hidden"][:, :So])
+    print("ragged == uniform", info, pu.check_llm(shape, inp, ref, uni, "uniform"))
+
+
 @pytest.mark.parametrize("pattern", ["last", "first", "alternate"])
 def test_in_place_compaction_hazards(pattern):
     """Steer the selection (by planting large keys) to the patterns that stress the
