@@ -20,16 +20,17 @@
 
 namespace vscan {
 
-// sum over heads of p[h * stride], added in head order; loads go out eight at a time so
-// the sum costs a couple of memory round-trips instead of one per head
+// sum over heads of p[h * stride], added in head order
 __device__ __forceinline__ float head_sum(const float *p, int heads, int stride) {
+    // sixteen heads at a time; the head index is clamped, not predicated, so that the loads of a
+    // batch are independent of each other and in flight together
     float s = 0.f;
-    for (int h0 = 0; h0 < heads; h0 += 8) {
-        float v[8];
+    for (int h0 = 0; h0 < heads; h0 += 16) {
+        float v[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = h0 + u < heads ? p[(int64_t)(h0 + u) * stride] : 0.f;
+        for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)min(h0 + u, heads - 1) * stride];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += v[u];
+        for (int u = 0; u < 16; ++u) s += h0 + u < heads ? v[u] : 0.f;
     }
     return s;
 }
