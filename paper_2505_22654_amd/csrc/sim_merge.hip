@@ -59,8 +59,10 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
     const unsigned char *xb =
         reinterpret_cast<const unsigned char *>(x) + (int64_t)b * T_img * row_bytes;
 
-    // source byte offset of each piece this thread stages (-1: row outside the problem);
-    // 32 bits are enough: the ABI layer rejects images of 2 GiB or more
+    // byte offset of the row behind each piece this thread stages; 32 bits are enough: the ABI
+    // layer rejects images of 2 GiB or more.  Rows outside the problem (slots >= K, columns
+    // >= U) stage some other row of the image: their results are masked in the epilogue, and
+    // a real row keeps every load unconditional and inside the image.
     int src[PER_THREAD];
     {
         // token of every row this thread stages.  Positions are clamped, not predicated: the
@@ -74,14 +76,8 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
                                     : drop_idx[(int64_t)b * U + min(n0 + r - BM, U - 1)];
         }
 #pragma unroll
-        for (int it = 0; it < PER_THREAD; ++it) {
-            const int p = tid + it * THREADS;
-            const int r = p / PPR;
-            const bool inside = it < A_PIECES ? m0 + r < K : n0 + r - BM < U;
-            // indices come from device memory: stay inside the image
-            const int t = min(max(tok[it], 0), T_img - 1);
-            src[it] = inside ? t * row_bytes + (p - r * PPR) * 16 : -1;
-        }
+        for (int it = 0; it < PER_THREAD; ++it)  // indices come from device memory: stay inside
+            src[it] = min(max(tok[it], 0), T_img - 1) * row_bytes;
     }
     // dropped token of each result column this lane reports in the epilogue (fetched here so
     // that the latency is long gone by then)
@@ -95,25 +91,27 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
 #pragma unroll
     for (int it = 0; it < A_PIECES; ++it) ss[it] = 0.f;
 
-    auto stage_load = [&](int stage, uint4 *regs) {
+    // Loads carry no condition (a piece past the end of the row re-reads the row's last piece
+    // and is cleared when it is written to LDS), so the compiler can leave the loads of later
+    // stages in flight while it waits for the stage it needs.
+    auto stage_load = [&](int stage, uint4(&regs)[PER_THREAD]) {
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
-            const int p = tid + it * THREADS;
-            const int piece = p % PPR;
-            const int col_byte = stage * KC * 32 + piece * 16;
-            regs[it] = load16_guard(xb, (int64_t)src[it] + (int64_t)stage * KC * 32,
-                                    src[it] >= 0 && col_byte < row_bytes);
+            const int piece = (tid + it * THREADS) % PPR;
+            const int col_byte = min(stage * KC * 32 + piece * 16, row_bytes - 16);
+            regs[it] = load16(xb, (int64_t)src[it] + col_byte);
         }
     };
-    auto stage_store = [&](unsigned char *dst, const uint4 *regs) {
+    auto stage_store = [&](unsigned char *dst, const uint4(&regs)[PER_THREAD], int stage) {
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
             const int p = tid + it * THREADS;
-            const int r = p / PPR;
-            *reinterpret_cast<uint4 *>(dst + r * STRIDE + (p - r * PPR) * 16) = regs[it];
+            const int r = p / PPR, piece = p - r * PPR;
+            const uint4 val = stage * KC * 32 + piece * 16 < row_bytes ? regs[it] : zero16();
+            *reinterpret_cast<uint4 *>(dst + r * STRIDE + piece * 16) = val;
             if (it < A_PIECES) {
                 float v[E];
-                unpack16<T>(regs[it], v);
+                unpack16<T>(val, v);
 #pragma unroll
                 for (int e = 0; e < E; ++e) ss[it] = fmaf(v[e], v[e], ss[it]);
             }
@@ -154,13 +152,13 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
     if constexpr (NSETS == 1) {
         uint4 ra[PER_THREAD];
         stage_load(0, ra);
-        stage_store(lds[0], ra);
+        stage_store(lds[0], ra, 0);
         __syncthreads();
         for (int st = 0; st < nstages; ++st) {
             if (st + 1 < nstages) stage_load(st + 1, ra);
             if (computes) compute(lds[st & 1]);
             if (st + 1 < nstages) {
-                stage_store(lds[(st + 1) & 1], ra);
+                stage_store(lds[(st + 1) & 1], ra, st + 1);
                 __syncthreads();
             }
         }
@@ -169,9 +167,22 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
 #pragma unroll
         for (int j = 0; j < NSETS; ++j)
             if (j < nstages) stage_load(j, regs[j]);
-        stage_store(lds[0], regs[0]);
+        stage_store(lds[0], regs[0], 0);
         __syncthreads();
-        for (int st = 0; st < nstages; st += NSETS) {
+        int st = 0;
+        // groups in which every stage refills its register set: no condition around the loads,
+        // so the wait before a stage is written to LDS leaves the later stages in flight
+        for (; st + 2 * NSETS <= nstages; st += NSETS) {
+#pragma unroll
+            for (int j = 0; j < NSETS; ++j) {
+                const int cur = st + j;
+                stage_load(cur + NSETS, regs[j]);
+                if (computes) compute(lds[cur & 1]);
+                stage_store(lds[(cur + 1) & 1], regs[(j + 1) % NSETS], cur + 1);
+                __syncthreads();
+            }
+        }
+        for (; st < nstages; st += NSETS) {  // the last groups
 #pragma unroll
             for (int j = 0; j < NSETS; ++j) {
                 const int cur = st + j;
@@ -179,7 +190,7 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
                     if (cur + NSETS < nstages) stage_load(cur + NSETS, regs[j]);
                     if (computes) compute(lds[cur & 1]);
                     if (cur + 1 < nstages) {
-                        stage_store(lds[(cur + 1) & 1], regs[(j + 1) % NSETS]);
+                        stage_store(lds[(cur + 1) & 1], regs[(j + 1) % NSETS], cur + 1);
                         __syncthreads();
                     }
                 }
@@ -490,10 +501,10 @@ hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
     // the workgroup count of 64 x 64 tiles and long stages (few memory round-trips)
     const int U = a.T - a.K;
     const long tiles128 = (long)((U + 127) / 128) * ((a.K + 127) / 128) * a.B;
-    const bool big = tiles128 >= 512;
+    const bool big = tiles128 >= 400;
     if (a.is_bf16)
-        return big ? sim_t<bf16_t, 2, 2, 4, 1, 256>(a, s) : sim_t<bf16_t, 1, 1, 8, 4, 512>(a, s);
-    return big ? sim_t<float, 2, 2, 4, 1, 256>(a, s) : sim_t<float, 1, 1, 8, 4, 512>(a, s);
+        return big ? sim_t<bf16_t, 2, 2, 4, 1, 256>(a, s) : sim_t<bf16_t, 1, 1, 8, 2, 512>(a, s);
+    return big ? sim_t<float, 2, 2, 4, 1, 256>(a, s) : sim_t<float, 1, 1, 8, 2, 512>(a, s);
 }
 
 template <typename T>
