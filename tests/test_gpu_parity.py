@@ -52,6 +52,11 @@ SMALL_ENCODER = {
     "bf16-global-only": _enc(keep_local=0, keep_global=21),
     "bf16-many-kept": _enc(grid_h=20, grid_w=20, keep_global=150, keep_local=100, feat_dim=264),
     "bf16-wide-rows": _enc(head_dim=256, feat_dim=1032, heads=2),
+    # feature rows near the 16 KiB limit: every lane of the merge owns up to 16 pieces
+    "bf16-widest-rows": _enc(feat_dim=8192, heads=2, grid_h=10, grid_w=9, keep_global=7,
+                             keep_local=8),
+    "f32-widest-rows": _enc(wl.F32, feat_dim=4088, heads=2, grid_h=9, grid_w=10, keep_global=6,
+                            keep_local=4),
     "f32-keep-one": _enc(wl.F32, keep_global=1, keep_local=0),
     "bf16-mean": _enc(has_cls=0, score_mode=1, grid_h=15, grid_w=13, head_dim=80, heads=3,
                       win_rows=3, win_cols=3, keep_global=20, keep_local=18),
