@@ -444,7 +444,8 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
     const int nreg = (N + threads - 1) / threads;
     if (win_slots * nreg <= 128) {
         if (nreg <= 4) VSCAN_SEL(0, 1, false, 4);
-        VSCAN_SEL(0, 1, false, 16);
+        if (nreg <= 16) VSCAN_SEL(0, 1, false, 16);
+        VSCAN_SEL(0, 1, false, 32);
     }
     if (win_slots <= 256) {
         if (nreg <= 4) VSCAN_SEL(1, 4, false, 4);
@@ -456,11 +457,13 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
         if (nreg <= 16) VSCAN_SEL(1, 32, false, 16);
         VSCAN_SEL(1, 32, false, 32);
     }
-    // a window padded to a power of two may hold up to twice the segment's tokens
+    // one register count serves the window searches and the global one; a window padded to a
+    // power of two may hold up to twice the segment's tokens
     const int nreg_w = (win_slots + threads - 1) / threads;
-    if (nreg_w <= 4) VSCAN_SEL(2, 1, false, 4);
-    if (nreg_w <= 16) VSCAN_SEL(2, 1, false, 16);
-    if (nreg_w <= 32) VSCAN_SEL(2, 1, false, 32);
+    const int nreg_both = nreg_w > nreg ? nreg_w : nreg;
+    if (nreg_both <= 4) VSCAN_SEL(2, 1, false, 4);
+    if (nreg_both <= 16) VSCAN_SEL(2, 1, false, 16);
+    if (nreg_both <= 32) VSCAN_SEL(2, 1, false, 32);
     VSCAN_SEL(2, 1, false, 64);
 #undef VSCAN_SEL
 }

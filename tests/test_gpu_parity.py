@@ -183,6 +183,18 @@ def test_llm_small(name):
     print(name, info, rep)
 
 
+def test_llm_max_span():
+    """A visual span close to the largest the stage-2 select takes (keys and flags of one
+    sequence fill LDS), in place; the next size up is refused."""
+    shape = _llm(batch=2, prefix=3, vis_len=32500, text=5, q_heads=1, kv_heads=1, head_dim=16,
+                 hidden=16, keep=150, n_query=1, in_place=1)
+    inp, ref, info = pu.screened_llm_case(shape, seed=9100)
+    print("max-span", info, pu.check_llm(shape, inp, ref, _run_llm(shape, inp), "max-span"))
+    with pytest.raises(vb.VscanError) as e:
+        vb.llm_workspace_size(vb.llm_desc(dataclasses.replace(shape, vis_len=32700)))
+    assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
+
+
 def test_llm_multi_turn_reselection():
     """A second question re-scores the same unpruned pool (App. "Remarks on Multi-Turn
     Conversations"): out-of-place pruning leaves hidden states and K/V untouched, and each turn's result
@@ -297,6 +309,23 @@ def test_llm_exact_ties_large_span():
 
 # ----------------------------------------------------------------------------
 # The benchmark configurations at full size
+@pytest.mark.parametrize("win,keep_local,keep_global", [(2, 12, 20), (1, 0, 32), (6, 36, 20)])
+def test_encoder_max_segment(win, keep_local, keep_global):
+    """The largest segment the select kernel takes (its candidate keys and flags fill LDS):
+    180 x 180 patches = 32 candidates per thread in the global search; windows searched by
+    the whole workgroup, no windows at all, windows searched by one wave each."""
+    shape = _enc(wl.F32, batch=1, grid_h=180, grid_w=180, heads=2, head_dim=32, feat_dim=64,
+                 win_rows=win, win_cols=win, keep_global=keep_global, keep_local=keep_local)
+    inp, _, ref, info = pu.screened_encoder_case(shape, seed=9000, logit_gain=1.0)
+    out = _run_encoder(shape, inp)
+    print("max-segment", info, pu.check_encoder(shape, inp, ref, out, "max-segment"))
+    # one more row of patches does not fit any more and is refused, not mis-computed
+    too_big = dataclasses.replace(shape, grid_h=182)
+    with pytest.raises(vb.VscanError) as e:
+        vb.encoder_workspace_size(vb.encoder_desc(too_big))
+    assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
+
+
 def test_encoder_many_slots():
     """Enough kept slots in the batch that the merge gives every wave four slots in turn."""
     shape = _enc(batch=32, grid_h=24, grid_w=24, heads=2, feat_dim=72, win_rows=4, win_cols=4,
