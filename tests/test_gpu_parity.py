@@ -326,6 +326,81 @@ def test_encoder_max_segment(win, keep_local, keep_global):
     assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
 
 
+# Shapes chosen so that, together with the cases above, every branch of the kernels' launch
+# heuristics (register counts of the searches, window modes, tile forms, row widths) runs at
+# least once.  Feature and head dimensions are kept small: the oracle stays cheap.
+DISPATCH_ENCODER = {
+    # select: one thread per token, 16 candidates per lane in the global wave
+    "sel-900": _enc(grid_h=30, grid_w=30, heads=2, head_dim=16, feat_dim=32, win_rows=3,
+                    win_cols=3, keep_global=20, keep_local=18),
+    # select: one big window on a small segment (one wave searches up to 2048 window slots)
+    "sel-one-window-400": _enc(grid_h=20, grid_w=20, heads=2, head_dim=16, feat_dim=32,
+                               win_rows=1, win_cols=1, keep_global=0, keep_local=25),
+    # select: large segment without windows, 4 and 16 candidates per thread
+    "sel-global-1480": _enc(grid_h=40, grid_w=37, heads=2, head_dim=16, feat_dim=32,
+                            win_rows=1, win_cols=1, keep_global=40, keep_local=0),
+    "sel-global-5000": _enc(batch=1, grid_h=50, grid_w=100, heads=2, head_dim=16, feat_dim=32,
+                            win_rows=1, win_cols=1, keep_global=40, keep_local=0),
+    # select: mid-size windows searched by one wave each on a 4096-token segment
+    "sel-wave-windows-4096": _enc(batch=1, grid_h=64, grid_w=64, heads=2, head_dim=16,
+                                  feat_dim=32, win_rows=2, win_cols=4, keep_global=30,
+                                  keep_local=24),
+    # select: one window of 8100 tokens searched by the workgroup, 16 candidates per thread
+    "sel-block-window-8100": _enc(batch=1, grid_h=90, grid_w=90, heads=2, head_dim=16,
+                                  feat_dim=32, win_rows=1, win_cols=1, keep_global=20,
+                                  keep_local=30),
+    # select: small windows on the largest segment (32 candidates per thread, wave per window)
+    "sel-small-windows-32400": _enc(wl.F32, batch=1, grid_h=180, grid_w=180, heads=2, head_dim=32,
+                                    feat_dim=64, win_rows=12, win_cols=12, keep_global=20,
+                                    keep_local=144),
+    # select: one window over the largest segment (64 window slots per thread)
+    "sel-one-window-32400": _enc(wl.F32, batch=1, grid_h=180, grid_w=180, heads=2, head_dim=32,
+                                 feat_dim=64, win_rows=1, win_cols=1, keep_global=0,
+                                 keep_local=32),
+    # merge: 4 and 8 pieces of a feature row per lane
+    "merge-feat-2048": _enc(feat_dim=2048, heads=2),
+    "merge-feat-4096": _enc(feat_dim=4096, heads=2),
+    # mean-attention scoring: 256- and 512-byte head rows
+    "mean-head-128": _enc(has_cls=0, score_mode=1, grid_h=12, grid_w=13, head_dim=128, heads=2),
+    "mean-head-256": _enc(has_cls=0, score_mode=1, grid_h=11, grid_w=12, head_dim=256, heads=2),
+    # similarity: the large-tile form in fp32
+    "sim-large-tiles-f32": _enc(wl.F32, batch=8, grid_h=64, grid_w=64, heads=2, head_dim=16,
+                                feat_dim=32, win_rows=1, win_cols=1, keep_global=512,
+                                keep_local=0),
+}
+
+
+@pytest.mark.parametrize("name", sorted(DISPATCH_ENCODER))
+def test_encoder_dispatch_coverage(name):
+    shape = DISPATCH_ENCODER[name]
+    # 144 window boundaries on flat scores never all clear the margin: peakier logits there
+    gain = 2.0 if name == "sel-small-windows-32400" else 1.0
+    inp, _, ref, info = pu.screened_encoder_batch(shape, seed=8000 + len(name), logit_gain=gain,
+                                                  max_items=64 * shape.batch)
+    out = _run_encoder(shape, inp)
+    print(name, info, pu.check_encoder(shape, inp, ref, out, name))
+
+
+DISPATCH_LLM = {
+    # select: 16 candidates per thread
+    "span-8000": _llm(batch=2, vis_len=8000, text=6, q_heads=1, kv_heads=1, head_dim=16,
+                      hidden=16, keep=90),
+    # scoring: logits of 8 rows x 4500 keys leave no LDS for the staging areas
+    "unstaged-8x4500": _llm(batch=2, vis_len=4500, text=4, q_heads=8, kv_heads=1, head_dim=128,
+                            hidden=16, keep=50),
+    # scoring: 512-byte key rows with more than 16 query rows
+    "f32-wide-many-rows": _llm(wl.F32, batch=2, vis_len=300, text=8, q_heads=8, kv_heads=2,
+                               head_dim=128, hidden=16, keep=40, n_query=5),
+}
+
+
+@pytest.mark.parametrize("name", sorted(DISPATCH_LLM))
+def test_llm_dispatch_coverage(name):
+    shape = DISPATCH_LLM[name]
+    inp, ref, info = pu.screened_llm_case(shape, seed=8500 + len(name), max_tries=48)
+    print(name, info, pu.check_llm(shape, inp, ref, _run_llm(shape, inp), name))
+
+
 def test_encoder_many_slots():
     """Enough kept slots in the batch that the merge gives every wave four slots in turn."""
     shape = _enc(batch=32, grid_h=24, grid_w=24, heads=2, feat_dim=72, win_rows=4, win_cols=4,
