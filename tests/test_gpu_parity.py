@@ -357,6 +357,9 @@ DISPATCH_ENCODER = {
     "sel-one-window-32400": _enc(wl.F32, batch=1, grid_h=180, grid_w=180, heads=2, head_dim=32,
                                  feat_dim=64, win_rows=1, win_cols=1, keep_global=0,
                                  keep_local=32),
+    # images pinned to XCDs with a batch that is not a multiple of eight (padding workgroups)
+    "affine-batch-10": _enc(batch=10, grid_h=14, grid_w=14, heads=2, head_dim=16, feat_dim=96,
+                            keep_global=12, keep_local=8),
     # merge: 4 and 8 pieces of a feature row per lane
     "merge-feat-2048": _enc(feat_dim=2048, heads=2),
     "merge-feat-4096": _enc(feat_dim=4096, heads=2),
