@@ -233,7 +233,7 @@ def main():
                          "(they are independent in this benchmark); default 1 = strictly serial")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build measures one GPU only (the path shards by image / "
+        sys.exit("bench.py: one GPU only (the path shards by image / "
                  "sequence with no exchange); run with --gpus 1")
 
     import torch
