@@ -190,16 +190,19 @@ struct TileStage {
     static constexpr int kBytes = ROWS * kStride;
     uint4 regs[kPerThread];
 
-    // rows [row0, row0+ROWS) of a [*, row_bytes] matrix at `base`; rows >= row_end
-    // and bytes >= row_bytes read as zero
+    // rows [row0, row0+ROWS) of a [*, row_bytes] matrix at `base`.  The loads carry no
+    // condition: a row >= row_end re-reads row row_end - 1 and a piece past the end of a row
+    // re-reads the row's last piece.  What lands in LDS for them is finite data that the
+    // consumers neutralise (rows past the end are masked or carry an infinite log-sum-exp; the
+    // register-resident operand is zero in the bytes past the row).
     __device__ __forceinline__ void load(const void *base, int row0, int row_end, int row_bytes) {
 #pragma unroll
         for (int it = 0; it < kPerThread; ++it) {
-            const int p = threadIdx.x + it * 256;
+            const int p = min((int)threadIdx.x + it * 256, kPieces - 1);
             const int r = p / kPiecesPerRow;
             const int piece = p - r * kPiecesPerRow;
-            const bool ok = p < kPieces && row0 + r < row_end && piece * 16 < row_bytes;
-            regs[it] = load16_guard(base, (int64_t)(row0 + r) * row_bytes + piece * 16, ok);
+            const int row = min(row0 + r, row_end - 1);
+            regs[it] = load16(base, (int64_t)row * row_bytes + min(piece * 16, row_bytes - 16));
         }
     }
     __device__ __forceinline__ void store(unsigned char *lds) const {
