@@ -96,14 +96,13 @@ __global__ __launch_bounds__(256) void score_cls_generic_kernel(const T *__restr
 // size).  The key block is read as one flat, fully coalesced stream with up to 16
 // independent 16-byte loads per thread in flight: at these sizes the kernel's time
 // is the number of serialised memory round-trips, so all of them are issued at once.
-template <typename T, int LOG2_CPR>
+template <typename T, int LOG2_CPR, int UNR>
 __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
                                                         const T *__restrict__ k,
                                                         float *__restrict__ head_scores, int H,
                                                         int S, int dh, int first_key, int col0,
                                                         int N, float scale_log2e) {
     constexpr int E = ElemTraits<T>::kPer16B;
-    constexpr int UNR = 16;
     constexpr int cpr = 1 << LOG2_CPR;  // 16-byte pieces per key row
     constexpr int shift = LOG2_CPR;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -122,8 +121,10 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
     uint4 raw[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-        const int p = u * 256 + tid;
-        raw[u] = load16_stream_guard(kbase, (int64_t)p * 16, p < total);
+        // clamped, not predicated: the loads of a batch stay independent of each other; what a
+        // thread past the end fetched is dropped where the logits are filed
+        const int p = min(u * 256 + tid, total - 1);
+        raw[u] = load16_stream(kbase, (int64_t)p * 16);
     }
     for (int e = tid; e < dh; e += 256) qf[e] = load_elem<T>(qrow + e) * scale_log2e;
     __syncthreads();
@@ -137,8 +138,8 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
         if (base + 256 * UNR < total) {
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
-                const int p = base + 256 * UNR + u * 256 + tid;
-                nxt[u] = load16_stream_guard(kbase, (int64_t)p * 16, p < total);
+                const int p = min(base + 256 * UNR + u * 256 + tid, total - 1);
+                nxt[u] = load16_stream(kbase, (int64_t)p * 16);
             }
         }
 #pragma unroll
@@ -426,19 +427,28 @@ static hipError_t launch_score_cls_t(const ScoreArgs &a, hipStream_t s) {
     }
     dim3 grid(a.H, a.BC);
     const int cpr = a.dh / ElemTraits<T>::kPer16B;
-#define VSCAN_CLS(L)                                                                          \
-    case L: {                                                                                 \
+    // 16 pieces per thread and batch; 20 when that takes the whole key block in one batch (the
+    // 577-row blocks of a 24 x 24 encoder with 128-byte heads: one memory round-trip less)
+    const int64_t total = (int64_t)n_keys * cpr;
+    // (only while every workgroup gets a CU to itself: the larger register set halves occupancy)
+    const bool one_shot = total > 256 * 16 && total <= 256 * 20 && (int64_t)a.H * a.BC <= 256;
+#define VSCAN_CLS_U(L, U)                                                                     \
+    {                                                                                         \
         if (smem > 64 * 1024) {                                                               \
             hipError_t e = hipFuncSetAttribute(                                               \
-                reinterpret_cast<const void *>(score_cls_kernel<T, L>),                       \
+                reinterpret_cast<const void *>(score_cls_kernel<T, L, U>),                    \
                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                       \
             if (e != hipSuccess) return e;                                                    \
         }                                                                                     \
-        hipLaunchKernelGGL((score_cls_kernel<T, L>), grid, dim3(256), smem, s, (const T *)a.q, \
-                           (const T *)a.k, a.head_scores, a.H, a.S, a.dh, first_key,          \
-                           1 - first_key, a.N, a.scale * 1.4426950408889634f);                \
+        hipLaunchKernelGGL((score_cls_kernel<T, L, U>), grid, dim3(256), smem, s,             \
+                           (const T *)a.q, (const T *)a.k, a.head_scores, a.H, a.S, a.dh,     \
+                           first_key, 1 - first_key, a.N, a.scale * 1.4426950408889634f);     \
         return hipGetLastError();                                                             \
     }
+#define VSCAN_CLS(L)                                                                          \
+    case L:                                                                                   \
+        if (one_shot) VSCAN_CLS_U(L, 20)                                                      \
+        VSCAN_CLS_U(L, 16)
     if ((cpr & (cpr - 1)) == 0) {
         switch (__builtin_ctz(cpr)) {
             VSCAN_CLS(0) VSCAN_CLS(1) VSCAN_CLS(2) VSCAN_CLS(3) VSCAN_CLS(4) VSCAN_CLS(5)
@@ -446,6 +456,7 @@ static hipError_t launch_score_cls_t(const ScoreArgs &a, hipStream_t s) {
         }
     }
 #undef VSCAN_CLS
+#undef VSCAN_CLS_U
     {
         hipLaunchKernelGGL(score_cls_generic_kernel<T>, grid, dim3(256), smem, s, (const T *)a.q,
                            (const T *)a.k, a.head_scores, a.H, a.S, a.dh, first_key,
