@@ -287,6 +287,17 @@ def llm_item(shape: LlmShape, seed: int, b: int) -> Dict[str, np.ndarray]:
             "v": _finish(v, shape.dtype), "hidden": _finish(hidden, shape.dtype)}
 
 
+def llm_weights(shape: LlmShape, seed: int) -> Dict[str, np.ndarray]:
+    """Projection weights of the pruning layer for the fused form of stage 2: w_q [Hq*dh, Dh],
+    w_k [Hkv*dh, Dh], rows = output features, entries N(0, 1/Dh) so that projected queries and
+    keys of N(0,1) hidden states have unit-variance components."""
+    r = _rng(seed, 2_000_003)
+    sd = 1.0 / np.sqrt(shape.hidden)
+    wq = r.normal(0.0, sd, size=(shape.q_heads * shape.head_dim, shape.hidden)).astype(np.float32)
+    wk = r.normal(0.0, sd, size=(shape.kv_heads * shape.head_dim, shape.hidden)).astype(np.float32)
+    return {"w_q": _finish(wq, shape.dtype), "w_k": _finish(wk, shape.dtype)}
+
+
 def llm_inputs(shape: LlmShape, seed: int) -> Dict[str, np.ndarray]:
     """Whole batch: q [B,Hq,Tq,dh], k, v [B,Hkv,S,dh], hidden [B,S,Dh]."""
     items = [llm_item(shape, seed, b) for b in range(shape.batch)]

@@ -420,3 +420,60 @@ def test_llm_end_to_end_invariants():
     inp["k"][:] = 1.0
     r = vo.llm_prune(shape, **inp)
     assert r["kept"].tolist() == [list(range(7))] * 2
+
+
+# ---- Eq. 5 written out from the hidden states -------------------------------------------------
+
+def test_scores_from_hidden_agree_with_projected_form():
+    """Projecting first (in fp64, handed to the C oracle as fp32) and scoring from the hidden
+    states directly are the same definition; they agree to fp32 rounding of the projections."""
+    from paper_2505_22654_amd import workloads as wl
+    shape = wl.LlmShape(dtype=wl.BF16, batch=2, prefix=3, vis_len=40, text=6, n_query=2,
+                        q_heads=4, kv_heads=2, head_dim=16, hidden=48, keep=10)
+    x = wl.llm_inputs(shape, 77)["hidden"]
+    w = wl.llm_weights(shape, 77)
+    got = vo.llm_scores_from_hidden(x, w["w_q"], w["w_k"], shape.vis_start, shape.vis_len,
+                                    shape.n_query, shape.q_heads, shape.kv_heads, shape.head_dim)
+    x64 = x.astype(np.float64)
+    B, S, _ = x.shape
+    q = (x64[:, S - 2:] @ w["w_q"].astype(np.float64).T).reshape(B, 2, 4, 16).transpose(0, 2, 1, 3)
+    k = (x64 @ w["w_k"].astype(np.float64).T).reshape(B, S, 2, 16).transpose(0, 2, 1, 3)
+    want = vo.llm_scores(q.astype(np.float32), k.astype(np.float32), shape.vis_start,
+                         shape.vis_len)
+    np.testing.assert_allclose(got, want, rtol=5e-6)
+    np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-12)
+
+
+def test_scores_from_hidden_closed_form():
+    """Identity projections on one head: the score of token j is softmax_j(x_last . x_j * scale);
+    with x_j = a_j * e_0 and x_last = e_0 that is softmax(a * scale)."""
+    V, Dh = 7, 4
+    a = np.log(np.arange(1, V + 1))           # softmax(a) = (j+1) / sum
+    x = np.zeros((1, V + 1, Dh))
+    x[0, :V, 0] = a
+    x[0, V, 0] = 1.0                            # the last token
+    eye = np.eye(Dh)
+    got = vo.llm_scores_from_hidden(x, eye, eye, 0, V, 1, 1, 1, Dh, scale=1.0)
+    np.testing.assert_allclose(got[0], np.arange(1, V + 1) / np.arange(1, V + 1).sum(), rtol=1e-12)
+    # a transposed weight would contract the wrong axis: a non-symmetric W_K catches it
+    wk = np.zeros((Dh, Dh)); wk[0, 1] = 1.0    # key feature 0 reads hidden feature 1
+    x2 = np.zeros((1, V + 1, Dh)); x2[0, :V, 1] = a; x2[0, V, 0] = 1.0
+    got2 = vo.llm_scores_from_hidden(x2, eye, wk, 0, V, 1, 1, 1, Dh, scale=1.0)
+    np.testing.assert_allclose(got2[0], np.arange(1, V + 1) / np.arange(1, V + 1).sum(), rtol=1e-12)
+
+
+def test_scores_from_hidden_gqa_and_queries():
+    """Grouped heads read the kv head floor(h * Hkv / Hq); several query positions are averaged."""
+    rng = np.random.default_rng(5)
+    B, S, Dh, Hq, Hkv, dh, V, Tq = 1, 9, 6, 4, 2, 3, 5, 2
+    x = rng.standard_normal((B, S, Dh)); wq = rng.standard_normal((Hq * dh, Dh)); wk = rng.standard_normal((Hkv * dh, Dh))
+    got = vo.llm_scores_from_hidden(x, wq, wk, 1, V, Tq, Hq, Hkv, dh)
+    want = np.zeros(V)
+    for h in range(Hq):
+        for t in range(Tq):
+            qv = wq[h * dh:(h + 1) * dh] @ x[0, S - Tq + t]
+            g = h // (Hq // Hkv)
+            kv = x[0, 1:1 + V] @ wk[g * dh:(g + 1) * dh].T
+            l = kv @ qv / np.sqrt(dh)
+            e = np.exp(l - l.max()); want += e / e.sum()
+    np.testing.assert_allclose(got[0], want / (Hq * Tq), rtol=1e-12)
