@@ -214,6 +214,38 @@ int vscan_llm_prune_ragged(const vscan_llm_desc *desc, const vscan_seq_meta *met
                            size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * Stage 2 for a caller that does not hold the layer's queries and keys: the
+ * scores of Eq. 5 computed as the equation is written, from the hidden states
+ * and the layer's projection weights (Sec. 4.2: Q = x_last W_Q^h,
+ * K_V = x_V W_K^h per head h, softmax over the key domain, mean over heads),
+ * then the same top-`keep` selection, and the compaction applied to the hidden
+ * states only (K and V of this layer do not exist yet; the caller computes them
+ * for the tokens that are left).  No positional rotation is applied to Q or K,
+ * as in the equation.  bf16 only (VSCAN_ERR_UNSUPPORTED for fp32).
+ *
+ * desc        HOST; as for vscan_llm_prune.  `hidden` and `head_dim` must be
+ *             multiples of 8.
+ * hidden      DEVICE [B, S, hidden]; in/out when in_place, else read only
+ * w_q         DEVICE [Hq*dh, hidden], read only: row n holds the weights of
+ *             output feature n (head n / dh), i.e. q = w_q x
+ * w_k_t       DEVICE [hidden, Hkv*dh], read only: row c holds the weights that
+ *             input feature c contributes to every output feature, i.e. the
+ *             matrix W_K of the paper with the heads side by side (the
+ *             transpose of the w_q convention; k = w_k_t^T x)
+ * kept_idx    out [B, keep] int32 ascending
+ * hidden_out  out [B, S_out, hidden], NULL when in_place
+ * scores_out  out optional [B, V] fp32
+ * workspace   vscan_llm_fused_workspace_size bytes, caller-owned, 16-byte aligned
+ * Errors as vscan_llm_prune; sizes whose byte offsets inside one tensor do not
+ * fit 32 bits give VSCAN_ERR_UNSUPPORTED.  Asynchronous on `stream`.
+ * ------------------------------------------------------------------------- */
+int vscan_llm_fused_workspace_size(const vscan_llm_desc *desc, size_t *bytes);
+int vscan_llm_prune_fused(const vscan_llm_desc *desc, void *hidden, const void *w_q,
+                          const void *w_k_t, int32_t *kept_idx, void *hidden_out,
+                          float *scores_out, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/* ---------------------------------------------------------------------------
  * Host-side budget arithmetic.  Pure functions of their arguments: no GPU, no
  * state; all pointers are HOST pointers.
  * ------------------------------------------------------------------------- */

@@ -202,29 +202,32 @@ def llm_prune(shape, q, k, v, hidden) -> Dict[str, np.ndarray]:
 
 
 def llm_scores_from_hidden(hidden, w_q, w_k, vis_start, V, n_query, q_heads, kv_heads, head_dim,
-                           scale: float = 0.0):
+                           domain: int = 0, scale: float = 0.0):
     """Eq. 5 written out from the hidden states (Sec. 4.2): with the layer's projection weights
     w_q [Hq*dh, Dh], w_k [Hkv*dh, Dh] (rows = output features),
-        Q = x_last W_Q^h,  K_V = x_V W_K^h,  S^h = softmax(Q K_V^T * scale)   per head h,
+        Q = x_last W_Q^h,  K = x W_K^h,  S^h = softmax(Q K^T * scale)   per head h,
     then the mean over query heads (and over the last n_query positions, an extension of the
-    paper's single last token).  hidden [B,S,Dh] -> scores [B,V] fp64.  Plain numpy in fp64;
-    the softmax is over the visual keys only, as the equation is written."""
+    paper's single last token).  hidden [B,S,Dh] -> scores [B,V] fp64.  Plain numpy in fp64.
+    domain 0: the softmax runs over the visual keys only, as the equation is written;
+    domain 1: over all S keys, and the visual columns are taken (same two readings as
+    llm_scores)."""
     x = np.asarray(hidden, dtype=np.float64)
     wq = np.asarray(w_q, dtype=np.float64)
     wk = np.asarray(w_k, dtype=np.float64)
     B, S, Dh = x.shape
     sc = default_scale(head_dim, scale)
     group = q_heads // kv_heads
+    k0, nk = (0, S) if domain else (vis_start, V)
     q = (x[:, S - n_query:, :] @ wq.T).reshape(B, n_query, q_heads, head_dim)
-    k = (x[:, vis_start:vis_start + V, :] @ wk.T).reshape(B, V, kv_heads, head_dim)
+    k = (x[:, k0:k0 + nk, :] @ wk.T).reshape(B, nk, kv_heads, head_dim)
     out = np.zeros((B, V), dtype=np.float64)
     for b in range(B):
         for h in range(q_heads):
-            kh = k[b, :, h // group, :]                      # [V, dh]
+            kh = k[b, :, h // group, :]                      # [nk, dh]
             for t in range(n_query):
-                logit = kh @ q[b, t, h] * sc                 # [V]
+                logit = kh @ q[b, t, h] * sc                 # [nk]
                 e = np.exp(logit - logit.max())
-                out[b] += e / e.sum()
+                out[b] += (e / e.sum())[vis_start - k0:vis_start - k0 + V]
     return out / (q_heads * n_query)
 
 
@@ -232,7 +235,8 @@ def llm_prune_fused(shape, hidden, w_q, w_k) -> Dict[str, np.ndarray]:
     """Stage 2 from the hidden states alone: Eq. 5 scores, top-keep, compaction of the hidden
     states (K and V of the layer do not exist yet and are computed on what is left)."""
     s = llm_scores_from_hidden(hidden, w_q, w_k, shape.vis_start, shape.vis_len, shape.n_query,
-                               shape.q_heads, shape.kv_heads, shape.head_dim, shape.scale)
+                               shape.q_heads, shape.kv_heads, shape.head_dim,
+                               shape.softmax_domain, shape.scale)
     kept = topk(s, shape.keep)
     return {"scores": s, "kept": kept,
             "hidden": compact(hidden, kept, shape.vis_start, shape.vis_len)}

@@ -24,7 +24,7 @@ VSCAN_KEYS_VISUAL_ONLY, VSCAN_KEYS_ALL = 0, 1
 EXPORTS = ("vscan_encoder_workspace_size", "vscan_encoder_reduce", "vscan_llm_workspace_size",
            "vscan_llm_prune", "vscan_profile_enable", "vscan_profile_read", "vscan_status_string",
            "vscan_version", "vscan_budget", "vscan_budget_solve_r1", "vscan_flops",
-           "vscan_llm_prune_ragged")
+           "vscan_llm_prune_ragged", "vscan_llm_fused_workspace_size", "vscan_llm_prune_fused")
 
 
 class EncoderDesc(ctypes.Structure):
@@ -85,6 +85,12 @@ def lib():
         L.vscan_llm_prune_ragged.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, vp, vp, vp, i32p,
                                              vp, vp, vp, f32p, vp, ctypes.c_size_t, vp]
         L.vscan_llm_prune_ragged.restype = ctypes.c_int
+        L.vscan_llm_fused_workspace_size.argtypes = [ctypes.POINTER(LlmDesc),
+                                                     ctypes.POINTER(ctypes.c_size_t)]
+        L.vscan_llm_fused_workspace_size.restype = ctypes.c_int
+        L.vscan_llm_prune_fused.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, i32p, vp, f32p, vp,
+                                            ctypes.c_size_t, vp]
+        L.vscan_llm_prune_fused.restype = ctypes.c_int
         L.vscan_profile_enable.argtypes = [ctypes.c_int]
         L.vscan_profile_enable.restype = ctypes.c_int
         L.vscan_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int,
@@ -232,6 +238,14 @@ def llm_workspace_size(desc: LlmDesc) -> int:
     return int(n.value)
 
 
+def llm_fused_workspace_size(desc: LlmDesc) -> int:
+    n = ctypes.c_size_t(0)
+    rc = lib().vscan_llm_fused_workspace_size(ctypes.byref(desc), ctypes.byref(n))
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_llm_fused_workspace_size")
+    return int(n.value)
+
+
 def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
@@ -328,5 +342,42 @@ def llm_prune(shape, q, k, v, hidden, want_scores: bool = False, workspace=None,
         out["k"], out["v"], out["hidden"] = k[:, :, :So], v[:, :, :So], hidden[:, :So]
     else:
         out["k"], out["v"], out["hidden"] = ko, vo, ho
+    out["workspace"] = workspace
+    return out
+
+
+def llm_prune_fused(shape, hidden, w_q, w_k_t, want_scores: bool = False, workspace=None,
+                    out=None) -> Dict[str, object]:
+    """vscan_llm_prune_fused on CUDA bf16 tensors hidden [B,S,Dh], w_q [Hq*dh, Dh] (rows =
+    output features), w_k_t [Dh, Hkv*dh] (rows = input features).  Returns kept_idx, optional
+    scores and the compacted hidden states (a view of `hidden` when shape.in_place)."""
+    import torch
+    desc = llm_desc(shape)
+    need = llm_fused_workspace_size(desc)
+    dev = hidden.device
+    for t in (hidden, w_q, w_k_t):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16
+    B, S, So = shape.batch, shape.seq_len, shape.seq_out
+    assert tuple(hidden.shape) == (B, S, shape.hidden)
+    assert tuple(w_q.shape) == (shape.q_heads * shape.head_dim, shape.hidden)
+    assert tuple(w_k_t.shape) == (shape.hidden, shape.kv_heads * shape.head_dim)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = dict(out) if out else {}
+    if "kept_idx" not in out:
+        out["kept_idx"] = torch.empty((B, shape.keep), dtype=torch.int32, device=dev)
+    if want_scores and "scores" not in out:
+        out["scores"] = torch.empty((B, shape.vis_len), dtype=torch.float32, device=dev)
+    ho = None
+    if not shape.in_place:
+        ho = out.get("hidden")
+        if ho is None:
+            ho = torch.empty((B, So, shape.hidden), dtype=hidden.dtype, device=dev)
+    rc = lib().vscan_llm_prune_fused(ctypes.byref(desc), _ptr(hidden), _ptr(w_q), _ptr(w_k_t),
+                                     _ptr(out["kept_idx"]), _ptr(ho), _ptr(out.get("scores")),
+                                     _ptr(workspace), workspace.numel(), _stream_handle())
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_llm_prune_fused")
+    out["hidden"] = hidden[:, :So] if shape.in_place else ho
     out["workspace"] = workspace
     return out

@@ -119,6 +119,60 @@ int plan_llm(const vscan_llm_desc *d, LlmPlan *p) {
     return VSCAN_OK;
 }
 
+struct FusedPlan {
+    int k0, nk, S_out, ks_q, ks_l, R;
+    size_t off_cq, off_qpl, off_cqt, off_qtpl, off_cl, off_stats, off_part, bytes;
+};
+
+int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
+    if (!d) return VSCAN_ERR_NULL;
+    if (d->struct_size != sizeof(vscan_llm_desc)) return VSCAN_ERR_VERSION;
+    if (d->dtype != VSCAN_F32 && d->dtype != VSCAN_BF16) return VSCAN_ERR_DTYPE;
+    if (d->softmax_domain != VSCAN_KEYS_VISUAL_ONLY && d->softmax_domain != VSCAN_KEYS_ALL)
+        return VSCAN_ERR_DTYPE;
+    if (d->batch < 0 || d->seq_len < 1 || d->vis_start < 0 || d->vis_len < 1 || d->n_query < 1)
+        return VSCAN_ERR_SHAPE;
+    if ((int64_t)d->vis_start + d->vis_len + d->n_query > d->seq_len) return VSCAN_ERR_SHAPE;
+    if (d->q_heads < 1 || d->kv_heads < 1 || d->q_heads % d->kv_heads) return VSCAN_ERR_SHAPE;
+    if (d->head_dim < 8 || d->head_dim % 8 || d->head_dim > 256) return VSCAN_ERR_SHAPE;
+    if (d->hidden < 8 || d->hidden % 8) return VSCAN_ERR_SHAPE;
+    if (d->in_place != 0 && d->in_place != 1) return VSCAN_ERR_SHAPE;
+    if (d->keep < 0 || d->keep > d->vis_len) return VSCAN_ERR_BUDGET;
+    if (d->dtype != VSCAN_BF16) return VSCAN_ERR_UNSUPPORTED;
+    p->k0 = d->softmax_domain == VSCAN_KEYS_ALL ? 0 : d->vis_start;
+    p->nk = d->softmax_domain == VSCAN_KEYS_ALL ? d->seq_len : d->vis_len;
+    p->S_out = d->seq_len - d->vis_len + d->keep;
+    p->R = d->q_heads * d->n_query;
+    // 32-bit row offsets inside the kernels
+    const int64_t lim = (int64_t)1 << 32;
+    const int64_t B = d->batch, Dh = d->hidden, N = (int64_t)d->q_heads * d->head_dim;
+    if (B * d->seq_len * Dh * 2 >= lim || N * Dh * 2 >= lim ||
+        Dh * d->kv_heads * d->head_dim * 2 >= lim || B * d->n_query * N * 2 >= lim ||
+        B * p->R * Dh * 2 >= lim || B * p->R > (1 << 24) || (int64_t)p->R > 65535)
+        return VSCAN_ERR_UNSUPPORTED;
+    if (llm_select_lds_bytes(d->vis_len) > kLdsBudget) return VSCAN_ERR_UNSUPPORTED;
+    const int M = d->batch * d->n_query;
+    p->ks_q = fused_ksplit((int)N, M, 1, d->hidden);
+    p->ks_l = fused_ksplit(p->nk, p->R, d->batch, d->hidden);
+    size_t off = 0;
+    p->off_cq = off;
+    off += align_up((size_t)p->ks_q * M * N * sizeof(float));
+    p->off_qpl = off;
+    off += align_up((size_t)3 * M * N * 2);
+    p->off_cqt = off;
+    off += align_up((size_t)B * p->R * Dh * sizeof(float));
+    p->off_qtpl = off;
+    off += align_up((size_t)kFusedQtPlanes * B * p->R * Dh * 2);
+    p->off_cl = off;
+    off += align_up((size_t)p->ks_l * B * p->R * p->nk * sizeof(float));
+    p->off_stats = off;
+    off += align_up((size_t)B * p->R * 2 * sizeof(float));
+    p->off_part = off;
+    off += align_up((size_t)B * d->vis_len * sizeof(float));
+    p->bytes = off ? off : kAlign;
+    return VSCAN_OK;
+}
+
 inline float resolve_scale(float scale, int head_dim) {
     return scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
 }
@@ -393,6 +447,100 @@ int vscan_llm_prune_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_h
     return run_llm(&caps, p, reinterpret_cast<const SeqMeta *>(meta_device), max_out_rows,
                    d->seq_len, q, k, v, hidden, kept_idx, k_out, v_out, hidden_out, scores_out,
                    workspace, workspace_bytes, stream);
+}
+
+int vscan_llm_fused_workspace_size(const vscan_llm_desc *desc, size_t *bytes) {
+    if (!bytes) return VSCAN_ERR_NULL;
+    FusedPlan p;
+    const int rc = plan_fused(desc, &p);
+    if (rc != VSCAN_OK) return rc;
+    *bytes = p.bytes;
+    return VSCAN_OK;
+}
+
+int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q,
+                          const void *w_k_t, int32_t *kept_idx, void *hidden_out,
+                          float *scores_out, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+    FusedPlan p;
+    const int rc = plan_fused(d, &p);
+    if (rc != VSCAN_OK) return rc;
+    if (!hidden || !w_q || !w_k_t || (!kept_idx && d->keep > 0)) return VSCAN_ERR_NULL;
+    if (d->in_place ? hidden_out != nullptr : hidden_out == nullptr) return VSCAN_ERR_NULL;
+    if (!aligned16(hidden) || !aligned16(w_q) || !aligned16(w_k_t) || !aligned16(hidden_out))
+        return VSCAN_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(kept_idx) & 3u) || (reinterpret_cast<uintptr_t>(scores_out) & 3u))
+        return VSCAN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < p.bytes) return VSCAN_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return VSCAN_ERR_ALIGN;
+    if (d->batch == 0) return VSCAN_OK;
+
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+
+    FusedArgs fa;
+    fa.hidden = hidden;
+    fa.w_q = w_q;
+    fa.w_k_t = w_k_t;
+    fa.c_q = reinterpret_cast<float *>(ws + p.off_cq);
+    fa.q_planes = reinterpret_cast<uint16_t *>(ws + p.off_qpl);
+    fa.c_qt = reinterpret_cast<float *>(ws + p.off_cqt);
+    fa.qt_planes = reinterpret_cast<uint16_t *>(ws + p.off_qtpl);
+    fa.c_l = reinterpret_cast<float *>(ws + p.off_cl);
+    fa.stats = reinterpret_cast<float2 *>(ws + p.off_stats);
+    fa.part = reinterpret_cast<float *>(ws + p.off_part);
+    fa.B = d->batch;
+    fa.S = d->seq_len;
+    fa.Dh = d->hidden;
+    fa.Hq = d->q_heads;
+    fa.Hkv = d->kv_heads;
+    fa.dh = d->head_dim;
+    fa.Tq = d->n_query;
+    fa.vis_start = d->vis_start;
+    fa.V = d->vis_len;
+    fa.k0 = p.k0;
+    fa.nk = p.nk;
+    fa.ks_q = p.ks_q;
+    fa.ks_l = p.ks_l;
+    fa.scale = resolve_scale(d->scale, d->head_dim);
+    VSCAN_LAUNCH("fused_q", launch_fused_q(fa, s));
+    VSCAN_LAUNCH("fused_split_q", launch_fused_split_q(fa, s));
+    VSCAN_LAUNCH("fused_qt", launch_fused_qt(fa, s));
+    VSCAN_LAUNCH("fused_split_qt", launch_fused_split_qt(fa, s));
+    VSCAN_LAUNCH("fused_logits", launch_fused_logits(fa, s));
+    VSCAN_LAUNCH("fused_stats", launch_fused_stats(fa, s));
+    VSCAN_LAUNCH("fused_colsum", launch_fused_colsum(fa, s));
+
+    LlmSelectArgs se;
+    se.part = fa.part;
+    se.B = d->batch;
+    se.Hkv = 1;
+    se.V = d->vis_len;
+    se.keep = d->keep;
+    se.norm = 1.0f / (float)p.R;
+    se.kept_idx = kept_idx;
+    se.scores_out = scores_out;
+    VSCAN_LAUNCH("llm_select", launch_llm_select(se, s));
+
+    CompactArgs ca;
+    ca.k = ca.v = ca.k_out = ca.v_out = nullptr;
+    ca.hidden = hidden;
+    ca.hidden_out = hidden_out;
+    ca.kept_idx = d->keep > 0 ? kept_idx : reinterpret_cast<const int32_t *>(ws + p.off_part);
+    ca.B = d->batch;
+    ca.Hkv = 0;  // no K / V strips
+    ca.S = d->seq_len;
+    ca.dh = d->head_dim;
+    ca.Dh = d->hidden;
+    ca.vis_start = d->vis_start;
+    ca.V = d->vis_len;
+    ca.keep = d->keep;
+    ca.elem_bytes = 2;
+    ca.in_place = d->in_place;
+    ca.out_rows = d->in_place ? d->seq_len : p.S_out;
+    ca.max_out_rows = p.S_out;
+    VSCAN_LAUNCH("compact", launch_compact(ca, s));
+    return VSCAN_OK;
 }
 
 int vscan_profile_enable(int on) {

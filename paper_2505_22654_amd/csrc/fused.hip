@@ -1,0 +1,376 @@
+// Stage-2 scores computed from the hidden states and the layer's projection weights
+// (Eq. 5 as written: Q = x_last W_Q^h, K_V = x_V W_K^h), for a caller that has no Q and K yet.
+//
+// The keys are never projected.  For one query row q of head h,
+//     q . (W_K^h x_j) = (W_K^hT q) . x_j ,
+// so the query is carried into hidden space once (qt = W_K^hT q, one vector of `hidden`
+// entries per head and query position) and the logits are a single contraction of qt
+// with the visual span of the hidden states: B*V*hidden*Hq*Tq multiply-adds instead of the
+// B*V*hidden*Hkv*dh of a key projection (a factor dh*Hkv/(Hq*Tq), 128 for an MHA layer of
+// head size 128 and one query position).
+//
+// Precision.  Inputs are bf16.  All three contractions run on the matrix cores with bf16
+// operands and fp32 accumulation; q and qt are fp32 results that become operands again, so
+// each is split into a sum of bf16 planes (value = hi + mid + lo, every plane the bf16
+// rounding of what the previous ones left over: three planes carry 24 mantissa bits, i.e. the
+// whole fp32 value) and the planes are contracted one after the other into the same
+// accumulators.  The other operand (weights, hidden states) is bf16 already, so every product
+// is exact and the only rounding is that of the fp32 accumulation.
+//
+// Steps (every contraction is C[p][s] = sum_k P[p][k] * S[s][k], both operands with the
+// contraction axis contiguous; S is the large, streamed operand):
+//   1. q   [B*Tq, Hq*dh]        P = last Tq hidden rows of every sequence, S = W_Q rows
+//   2. qt  [Hkv][B*g*Tq, Dh]    P = q planes of the group's heads,         S = W_K^T rows
+//   3. l   [B][Hq*Tq, nk]       P = qt planes,                             S = hidden rows
+//   4. per (sequence, query row) softmax statistics, 5. per key the sum over rows.
+// Contractions with few output tiles split the contraction axis over `ksplit` workgroups;
+// partial results are stored side by side and summed, in fixed order, by whichever kernel reads
+// them next.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace vscan {
+namespace {
+
+constexpr int kGemmThreads = 256;
+constexpr int kTileS = 128;                   // streamed rows per workgroup, 32 per wave
+constexpr int kChunkBytes = 128;              // contraction bytes staged per step (64 bf16)
+constexpr int kRowPitch = kChunkBytes + 16;   // LDS row pitch: 36 words, conflict-free b128 reads
+constexpr int kTargetWorkgroups = 512;        // two per compute unit before the axis is split
+
+struct GemmDims {
+    int rows_s, rows_p;   // valid rows of the two operands
+    int k_bytes;          // contraction length in bytes (multiple of 16)
+    int ksplit;
+    float *c;             // [ksplit][Z][rows_p][rows_s]
+};
+
+// ---- operand addressing of the three contractions -------------------------------------------
+// s_base/p_base: wave-uniform base of batch entry z (and plane pl); s_off/p_off: byte offset of a
+// row's first contraction element from that base.
+
+struct ProbQ {
+    static constexpr int PL = 1;
+    GemmDims d;
+    const char *hidden, *w_q;
+    int Tq, S, row_bytes;  // row_bytes = Dh * 2
+    __device__ const char *s_base(int) const { return w_q; }
+    __device__ uint32_t s_off(int n) const { return (uint32_t)n * (uint32_t)row_bytes; }
+    __device__ const char *p_base(int, int) const { return hidden; }
+    __device__ uint32_t p_off(int m) const {
+        const int b = m / Tq, t = m - b * Tq;
+        return (uint32_t)(b * S + S - Tq + t) * (uint32_t)row_bytes;
+    }
+};
+
+struct ProbQt {
+    static constexpr int PL = 3;
+    GemmDims d;
+    const char *q_planes, *w_k_t;
+    int Tq, group, dh, Hq, Hkv;
+    int64_t plane_bytes;  // B*Tq*Hq*dh*2
+    __device__ const char *s_base(int g) const { return w_k_t + (int64_t)g * dh * 2; }
+    __device__ uint32_t s_off(int c) const { return (uint32_t)c * (uint32_t)(Hkv * dh * 2); }
+    __device__ const char *p_base(int g, int pl) const {
+        return q_planes + pl * plane_bytes + (int64_t)g * group * dh * 2;
+    }
+    __device__ uint32_t p_off(int m) const {  // m = (b*group + hh)*Tq + t
+        const int t = m % Tq, bh = m / Tq;
+        const int hh = bh % group, b = bh / group;
+        return (uint32_t)((b * Tq + t) * Hq * dh + hh * dh) * 2u;
+    }
+};
+
+template <int PLANES>
+struct ProbLogit {
+    static constexpr int PL = PLANES;
+    GemmDims d;
+    const char *hidden, *qt_planes;
+    int Tq, group, S, k0, row_bytes, Mg;  // Mg = B*group*Tq rows of qt per kv head
+    int64_t plane_bytes;                  // Hkv*Mg*Dh*2
+    __device__ const char *s_base(int b) const {
+        return hidden + ((int64_t)b * S + k0) * row_bytes;
+    }
+    __device__ uint32_t s_off(int j) const { return (uint32_t)j * (uint32_t)row_bytes; }
+    __device__ const char *p_base(int b, int pl) const {
+        return qt_planes + pl * plane_bytes + (int64_t)b * group * Tq * row_bytes;
+    }
+    __device__ uint32_t p_off(int r) const {  // r = h*Tq + t
+        const int t = r % Tq, h = r / Tq;
+        const int g = h / group, hh = h - g * group;
+        return (uint32_t)(g * Mg + hh * Tq + t) * (uint32_t)row_bytes;
+    }
+};
+
+// One workgroup: 128 streamed rows x 32*NP plane-operand rows, one share of the contraction
+// axis.  Both operands pass through LDS in 128-byte row chunks: the next chunk is fetched into
+// registers (coalesced, 8 lanes per row) while the matrix cores work on the current one.  Row
+// indices past the operand's end are clamped (the rows are computed and not stored); chunk
+// pieces past the contraction length are fetched from a clamped offset and zeroed on their way
+// into LDS.
+template <class Prob, int NP>
+__global__ __launch_bounds__(kGemmThreads) void nt_gemm_kernel(Prob pr) {
+    constexpr int PL = Prob::PL;
+    constexpr int TP = 32 * NP;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_s[kTileS * kRowPitch];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_p[PL * TP * kRowPitch];
+
+    const GemmDims d = pr.d;
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    const int z = blockIdx.z;
+    const int s0 = blockIdx.x * kTileS;
+    const int ptile = blockIdx.y / d.ksplit, ks = blockIdx.y - ptile * d.ksplit;
+    const int p0 = ptile * TP;
+    const int nchunks = (d.k_bytes + kChunkBytes - 1) / kChunkBytes;
+    const int cps = (nchunks + d.ksplit - 1) / d.ksplit;
+    const int c_begin = ks * cps, c_end = min(nchunks, c_begin + cps);
+
+    const int piece = tid & 7, srow = tid >> 3;
+    const char *sb = pr.s_base(z);
+    const char *pb[PL];
+#pragma unroll
+    for (int pl = 0; pl < PL; ++pl) pb[pl] = pr.p_base(z, pl);
+    uint32_t s_off[4], p_off[NP];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s_off[i] = pr.s_off(min(s0 + srow + 32 * i, d.rows_s - 1));
+#pragma unroll
+    for (int i = 0; i < NP; ++i) p_off[i] = pr.p_off(min(p0 + srow + 32 * i, d.rows_p - 1));
+
+    f32x16_t acc[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+    uint4 rs[4], rp[PL * NP];
+    auto fetch = [&](int c) {
+        const uint32_t col = (uint32_t)min(c * kChunkBytes + piece * 16, d.k_bytes - 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rs[i] = load16(sb, (int64_t)s_off[i] + col);
+#pragma unroll
+        for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+            for (int i = 0; i < NP; ++i) rp[pl * NP + i] = load16(pb[pl], (int64_t)p_off[i] + col);
+    };
+
+    if (c_begin < c_end) fetch(c_begin);
+    for (int c = c_begin; c < c_end; ++c) {
+        const bool valid = c * kChunkBytes + piece * 16 < d.k_bytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<uint4 *>(lds_s + (srow + 32 * i) * kRowPitch + piece * 16) =
+                valid ? rs[i] : zero16();
+#pragma unroll
+        for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+            for (int i = 0; i < NP; ++i)
+                *reinterpret_cast<uint4 *>(lds_p + (pl * TP + srow + 32 * i) * kRowPitch +
+                                           piece * 16) = valid ? rp[pl * NP + i] : zero16();
+        __syncthreads();
+        fetch(min(c + 1, c_end - 1));  // unconditional; the last round re-reads its own chunk
+#pragma unroll
+        for (int sub = 0; sub < kChunkBytes / 32; ++sub) {
+            const int colb = sub * 32 + 16 * (lane >> 5);
+            const uint4 b = *reinterpret_cast<const uint4 *>(
+                lds_s + (w * 32 + (lane & 31)) * kRowPitch + colb);
+#pragma unroll
+            for (int i = 0; i < NP; ++i)
+#pragma unroll
+                for (int pl = 0; pl < PL; ++pl) {
+                    const uint4 a = *reinterpret_cast<const uint4 *>(
+                        lds_p + (pl * TP + i * 32 + (lane & 31)) * kRowPitch + colb);
+                    mma32_chunk<bf16_t>(acc[i], a, b);
+                }
+        }
+        __syncthreads();
+    }
+
+    // acc[i][r] = C[p0 + 32 i + acc_row(r)][s0 + 32 w + lane % 32]: lanes run along the
+    // streamed rows, which are contiguous in C
+    const int s_out = s0 + w * 32 + (lane & 31);
+    if (s_out < d.rows_s) {
+        float *c_z = d.c + ((int64_t)ks * gridDim.z + z) * d.rows_p * d.rows_s;
+#pragma unroll
+        for (int i = 0; i < NP; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int p_out = p0 + i * 32 + acc_row(r);
+                if (p_out < d.rows_p) c_z[(int64_t)p_out * d.rows_s + s_out] = acc[i][r];
+            }
+    }
+}
+
+template <class Prob>
+hipError_t launch_gemm(const Prob &pr, int Z, hipStream_t s) {
+    const GemmDims &d = pr.d;
+    const int np = d.rows_p <= 32 ? 1 : (d.rows_p <= 64 ? 2 : 4);
+    const int ptiles = (d.rows_p + 32 * np - 1) / (32 * np);
+    dim3 grid((d.rows_s + kTileS - 1) / kTileS, ptiles * d.ksplit, Z);
+    if (np == 1)
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 1>), grid, dim3(kGemmThreads), 0, s, pr);
+    else if (np == 2)
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2>), grid, dim3(kGemmThreads), 0, s, pr);
+    else
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4>), grid, dim3(kGemmThreads), 0, s, pr);
+    return hipGetLastError();
+}
+
+// value = sum of PL bf16 planes: plane p is the bf16 rounding of what planes < p left over
+// (the remainders are exact in fp32).  Input: `ksplit` partial sums per element.
+template <int PL>
+__global__ __launch_bounds__(256) void split_planes_kernel(const float *__restrict__ c, int ksplit,
+                                                           int64_t n, uint16_t *__restrict__ planes) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float v = 0.f;
+    for (int ks = 0; ks < ksplit; ++ks) v += c[ks * n + i];
+#pragma unroll
+    for (int pl = 0; pl < PL; ++pl) {
+        const uint32_t bits = f32_to_bf16_rne(v);
+        planes[pl * n + i] = (uint16_t)bits;
+        v -= __uint_as_float(bits << 16);
+    }
+}
+
+// Softmax statistics of one (sequence, query row): maximum and reciprocal of the sum of
+// exponentials of the scaled logits over the key domain.
+__global__ __launch_bounds__(256) void fused_stats_kernel(const float *__restrict__ c, int ksplit,
+                                                          int64_t ks_stride, int nk, float scale,
+                                                          float2 *__restrict__ stats) {
+    __shared__ float red[16];
+    const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const float *l = c + row * nk;
+    float m = -INFINITY;
+    for (int j = threadIdx.x; j < nk; j += 256) {
+        float v = 0.f;
+        for (int ks = 0; ks < ksplit; ++ks) v += l[ks * ks_stride + j];
+        m = fmaxf(m, v * scale);
+    }
+    m = block_max(m, red);
+    float sum = 0.f;
+    for (int j = threadIdx.x; j < nk; j += 256) {
+        float v = 0.f;
+        for (int ks = 0; ks < ksplit; ++ks) v += l[ks * ks_stride + j];
+        sum += __expf(v * scale - m);
+    }
+    sum = block_sum(sum, red);
+    if (threadIdx.x == 0) stats[row] = make_float2(m, 1.0f / sum);
+}
+
+// part[b][j] = sum over the query rows of the softmax weight of visual token j (Eq. 5 before
+// the division by the number of rows).  A thread owns one key of the domain.
+__global__ __launch_bounds__(256) void fused_colsum_kernel(const float *__restrict__ c, int ksplit,
+                                                           int64_t ks_stride, int R, int nk,
+                                                           int vis_off, int V, float scale,
+                                                           const float2 *__restrict__ stats,
+                                                           float *__restrict__ part) {
+    const int b = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int jc = min(j, nk - 1);
+    const float *l = c + (int64_t)b * R * nk + jc;
+    const float2 *st = stats + (int64_t)b * R;
+    float acc = 0.f;
+    for (int r = 0; r < R; ++r) {
+        float v = 0.f;
+        for (int ks = 0; ks < ksplit; ++ks) v += l[ks * ks_stride + (int64_t)r * nk];
+        const float2 s2 = st[r];
+        acc += __expf(v * scale - s2.x) * s2.y;
+    }
+    const int t = j - vis_off;
+    if (j < nk && t >= 0 && t < V) part[(int64_t)b * V + t] = acc;
+}
+
+GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
+    GemmDims d;
+    d.rows_s = rows_s;
+    d.rows_p = rows_p;
+    d.k_bytes = k_elems * 2;
+    d.ksplit = ksplit;
+    d.c = c;
+    return d;
+}
+
+}  // namespace
+
+int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems) {
+    const int np = rows_p <= 32 ? 1 : (rows_p <= 64 ? 2 : 4);
+    const int64_t tiles =
+        (int64_t)((rows_s + kTileS - 1) / kTileS) * ((rows_p + 32 * np - 1) / (32 * np)) * Z;
+    const int nchunks = (k_elems * 2 + kChunkBytes - 1) / kChunkBytes;
+    int ks = (int)((kTargetWorkgroups + tiles - 1) / tiles);
+    ks = max(1, min(ks, min(16, nchunks / 2)));
+    return ks;
+}
+
+hipError_t launch_fused_q(const FusedArgs &a, hipStream_t s) {
+    ProbQ pr;
+    pr.d = dims(a.Hq * a.dh, a.B * a.Tq, a.Dh, a.ks_q, a.c_q);
+    pr.hidden = reinterpret_cast<const char *>(a.hidden);
+    pr.w_q = reinterpret_cast<const char *>(a.w_q);
+    pr.Tq = a.Tq;
+    pr.S = a.S;
+    pr.row_bytes = a.Dh * 2;
+    return launch_gemm(pr, 1, s);
+}
+
+hipError_t launch_fused_split_q(const FusedArgs &a, hipStream_t s) {
+    const int64_t n = (int64_t)a.B * a.Tq * a.Hq * a.dh;
+    hipLaunchKernelGGL(split_planes_kernel<3>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                       a.c_q, a.ks_q, n, a.q_planes);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s) {
+    const int group = a.Hq / a.Hkv;
+    ProbQt pr;
+    pr.d = dims(a.Dh, a.B * group * a.Tq, a.dh, 1, a.c_qt);
+    pr.q_planes = reinterpret_cast<const char *>(a.q_planes);
+    pr.w_k_t = reinterpret_cast<const char *>(a.w_k_t);
+    pr.Tq = a.Tq;
+    pr.group = group;
+    pr.dh = a.dh;
+    pr.Hq = a.Hq;
+    pr.Hkv = a.Hkv;
+    pr.plane_bytes = (int64_t)a.B * a.Tq * a.Hq * a.dh * 2;
+    return launch_gemm(pr, a.Hkv, s);
+}
+
+hipError_t launch_fused_split_qt(const FusedArgs &a, hipStream_t s) {
+    const int64_t n = (int64_t)a.B * a.Hq * a.Tq * a.Dh;
+    hipLaunchKernelGGL(split_planes_kernel<kFusedQtPlanes>, dim3((unsigned)((n + 255) / 256)),
+                       dim3(256), 0, s, a.c_qt, 1, n, a.qt_planes);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s) {
+    const int group = a.Hq / a.Hkv;
+    ProbLogit<kFusedQtPlanes> pr;
+    pr.d = dims(a.nk, a.Hq * a.Tq, a.Dh, a.ks_l, a.c_l);
+    pr.hidden = reinterpret_cast<const char *>(a.hidden);
+    pr.qt_planes = reinterpret_cast<const char *>(a.qt_planes);
+    pr.Tq = a.Tq;
+    pr.group = group;
+    pr.S = a.S;
+    pr.k0 = a.k0;
+    pr.row_bytes = a.Dh * 2;
+    pr.Mg = a.B * group * a.Tq;
+    pr.plane_bytes = (int64_t)a.Hkv * pr.Mg * a.Dh * 2;
+    return launch_gemm(pr, a.B, s);
+}
+
+hipError_t launch_fused_stats(const FusedArgs &a, hipStream_t s) {
+    const int R = a.Hq * a.Tq;
+    hipLaunchKernelGGL(fused_stats_kernel, dim3(R, a.B), dim3(256), 0, s, a.c_l, a.ks_l,
+                       (int64_t)a.B * R * a.nk, a.nk, a.scale, a.stats);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s) {
+    const int R = a.Hq * a.Tq;
+    hipLaunchKernelGGL(fused_colsum_kernel, dim3((a.nk + 255) / 256, a.B), dim3(256), 0, s, a.c_l,
+                       a.ks_l, (int64_t)a.B * R * a.nk, R, a.nk, a.vis_start - a.k0, a.V, a.scale,
+                       a.stats, a.part);
+    return hipGetLastError();
+}
+
+}  // namespace vscan

@@ -251,3 +251,32 @@ def check_llm_ragged(caps, meta, inp, refs, out, in_place, what=""):
             assert not got["k"][b, :, So:].any() and not got["hidden"][b, So:].any(), \
                 f"{what}[{b}]: rows past the result were written"
     return {"score_rel_err": worst}
+
+
+def fused_reference(shape, hidden, w_q, w_k):
+    return vo.llm_prune_fused(shape, hidden, w_q, w_k)
+
+
+def screened_fused_case(shape, seed, max_tries=16):
+    """Hidden states and projection weights whose oracle selection clears the margin."""
+    for attempt in range(max_tries):
+        hidden = wl.llm_inputs(shape, seed + attempt)["hidden"]
+        w = wl.llm_weights(shape, seed + attempt)
+        ref = fused_reference(shape, hidden, w["w_q"], w["w_k"])
+        gap = topk_boundary_gap(ref["scores"], shape.keep)
+        if gap > MARGIN:
+            inp = {"hidden": hidden, "w_q": w["w_q"], "w_k": w["w_k"]}
+            return inp, ref, {"seed": seed + attempt, "attempts": attempt + 1, "gap": gap}
+    raise AssertionError(f"no seed in {max_tries} tries clears the boundary margin")
+
+
+def check_fused(shape, ref, out, what=""):
+    kept = to_host(out["kept_idx"])
+    assert np.array_equal(kept, ref["kept"]), f"{what}: kept indices differ"
+    report = {}
+    if "scores" in out:
+        report["score_rel_err"] = check_scores(to_host(out["scores"]), ref["scores"], what)
+    got = to_host(out["hidden"])
+    assert got.shape == ref["hidden"].shape, f"{what}: hidden shape"
+    assert np.array_equal(got, ref["hidden"]), f"{what}: compacted hidden differs"
+    return report

@@ -1,0 +1,109 @@
+"""GPU parity of stage 2 scored from hidden states and projection weights (Eq. 5 as written)
+against the CPU oracle's plain definition.  Rules and tolerances: tests/parity_utils.py."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import vscan_oracle as vo
+from paper_2505_22654_amd import binding as vb
+from paper_2505_22654_amd import workloads as wl
+from tests import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(shape, inp):
+    import torch
+    h = pu.to_device(inp["hidden"], wl.BF16)
+    wq = pu.to_device(inp["w_q"], wl.BF16)
+    wkt = pu.to_device(np.ascontiguousarray(inp["w_k"].T), wl.BF16)
+    out = vb.llm_prune_fused(shape, h, wq, wkt, want_scores=True)
+    torch.cuda.synchronize()
+    return out
+
+
+def _shape(**kw):
+    base = dict(dtype=wl.BF16, batch=2, prefix=5, vis_len=150, text=9, n_query=1, q_heads=8,
+                kv_heads=8, head_dim=64, hidden=512, keep=40)
+    base.update(kw)
+    return wl.LlmShape(**base)
+
+
+SMALL_FUSED = {
+    # several 128-row tiles with a ragged tail; hidden size not a multiple of the 64-element chunk
+    "ragged-tiles": _shape(batch=3, vis_len=300, hidden=520, keep=100),
+    "in-place": _shape(in_place=1),
+    "all-keys": _shape(softmax_domain=1, prefix=37, text=21),
+    # grouped heads and several query positions: 24 query rows
+    "gqa-queries": _shape(q_heads=8, kv_heads=2, n_query=3, head_dim=32, hidden=256),
+    # more query rows than one 128-row tile of the plane operand
+    "many-rows": _shape(q_heads=16, kv_heads=4, n_query=9, head_dim=40, hidden=320, vis_len=200,
+                        text=12, keep=60),
+    # 33..64 query rows (two 32-row tiles per workgroup)
+    "two-row-tiles": _shape(q_heads=12, kv_heads=12, n_query=4, head_dim=24, hidden=264),
+    # long rows and few output tiles: the contraction axis is split over workgroups
+    "split-axis": _shape(batch=1, hidden=4096, q_heads=4, kv_heads=2, head_dim=128, vis_len=70,
+                         keep=11),
+    "one-visual-token": _shape(vis_len=1, keep=1),
+    "keep-nothing": _shape(keep=0),
+    "keep-everything": _shape(keep=150),
+    "head-dim-8": _shape(head_dim=8, hidden=64, q_heads=3, kv_heads=1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SMALL_FUSED))
+def test_fused_small(name):
+    shape = SMALL_FUSED[name]
+    inp, ref, info = pu.screened_fused_case(shape, 9100 + sorted(SMALL_FUSED).index(name) * 31)
+    print("case", name, info, flush=True)
+    out = _run(shape, inp)
+    print(name, pu.check_fused(shape, ref, out, name))
+
+
+def test_fused_fp32_is_rejected():
+    import torch
+    shape = _shape(dtype=wl.F32)
+    with pytest.raises(vb.VscanError) as e:
+        vb.llm_fused_workspace_size(vb.llm_desc(shape))
+    assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
+
+
+def test_fused_agrees_with_projected_path():
+    """The same selection as vscan_llm_prune fed with q and k projected on the host (fp64, rounded
+    to fp32): two routes to Eq. 5 through different kernels."""
+    import torch
+    shape = _shape(dtype=wl.F32, batch=2, vis_len=260, keep=77, hidden=384)
+    bshape = dataclasses.replace(shape, dtype=wl.BF16)
+    inp, ref, info = pu.screened_fused_case(bshape, 9900)
+    print("case", info, flush=True)
+    out = _run(bshape, inp)
+    x = inp["hidden"].astype(np.float64)
+    B, S, _ = x.shape
+    q = (x[:, S - 1:] @ inp["w_q"].astype(np.float64).T).reshape(B, 1, 8, 64).transpose(0, 2, 1, 3)
+    k = (x @ inp["w_k"].astype(np.float64).T).reshape(B, S, 8, 64).transpose(0, 2, 1, 3)
+    dev = [pu.to_device(np.ascontiguousarray(a, dtype=np.float32), wl.F32)
+           for a in (q, k, k, inp["hidden"])]
+    proj = vb.llm_prune(shape, *dev, want_scores=True)
+    torch.cuda.synchronize()
+    assert torch.equal(proj["kept_idx"], out["kept_idx"])
+    np.testing.assert_allclose(pu.to_host(out["scores"]), pu.to_host(proj["scores"]), rtol=4e-5)
+
+
+def test_fused_runs_are_bit_reproducible():
+    import torch
+    shape = SMALL_FUSED["split-axis"]
+    inp, _, _ = pu.screened_fused_case(shape, 9300)
+    a, b = _run(shape, inp), _run(shape, inp)
+    assert torch.equal(a["kept_idx"], b["kept_idx"])
+    assert torch.equal(a["scores"], b["scores"])
+
+
+def test_fused_config2_shape():
+    """The stage-2 shape of the headline configuration (16 sequences, 192 visual tokens, 32 heads
+    of 128, hidden 4096), every sequence checked against the oracle."""
+    shape = wl.config(2).llm
+    inp, ref, info = pu.screened_fused_case(shape, 9500, max_tries=4)
+    print("case", info, flush=True)
+    out = _run(shape, inp)
+    print("cfg2 stage-2 shape", pu.check_fused(shape, ref, out, "cfg2 fused"))

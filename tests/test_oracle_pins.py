@@ -454,6 +454,10 @@ def test_scores_from_hidden_closed_form():
     x[0, V, 0] = 1.0                            # the last token
     eye = np.eye(Dh)
     got = vo.llm_scores_from_hidden(x, eye, eye, 0, V, 1, 1, 1, Dh, scale=1.0)
+    # all-keys domain: the last token's own key (logit 1) joins the denominator
+    got_all = vo.llm_scores_from_hidden(x, eye, eye, 0, V, 1, 1, 1, Dh, domain=1, scale=1.0)
+    np.testing.assert_allclose(got_all[0], np.arange(1, V + 1) / (np.arange(1, V + 1).sum() + np.e),
+                               rtol=1e-12)
     np.testing.assert_allclose(got[0], np.arange(1, V + 1) / np.arange(1, V + 1).sum(), rtol=1e-12)
     # a transposed weight would contract the wrong axis: a non-symmetric W_K catches it
     wk = np.zeros((Dh, Dh)); wk[0, 1] = 1.0    # key feature 0 reads hidden feature 1
