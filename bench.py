@@ -33,6 +33,9 @@ KERNEL_SOURCE = {
     "score_mean_colsum": "encoder_score.hip", "encoder_select": "select.hip",
     "llm_select": "select.hip", "sim_argmax": "sim_merge.hip",
     "merge": "sim_merge.hip", "llm_score": "llm.hip", "compact": "llm.hip",
+    "fused_q": "fused.hip", "fused_split_q": "fused.hip", "fused_qt": "fused.hip",
+    "fused_split_qt": "fused.hip", "fused_logits": "fused.hip", "fused_softmax": "fused.hip",
+    "fused_colsum": "fused.hip",
 }
 
 
@@ -44,7 +47,7 @@ def sweep_points(index: int):
     return [wl.config(index)]
 
 
-def algorithmic_work(w: wl.Workload):
+def algorithmic_work(w: wl.Workload, stage2: str = "qk"):
     """Per-kernel algorithmic work of ONE call pair on this workload:
     {kernel: (bound, amount)} with bytes for "hbm" and flops for "mfma"."""
     out = {}
@@ -66,10 +69,26 @@ def algorithmic_work(w: wl.Workload):
     if l is not None:
         es = 2 if l.dtype == wl.BF16 else 4
         row = (l.hidden + 2 * l.kv_heads * l.head_dim) * es
-        out["llm_score"] = ("hbm", l.batch * l.kv_heads * l.vis_len * l.head_dim * es)
         out["llm_select"] = ("hbm", l.batch * l.vis_len * 4 + l.batch * l.keep * 4)
         moved = (l.keep + l.text) if l.in_place else l.seq_out
-        out["compact"] = ("hbm", l.batch * moved * row * 2)
+        if stage2 == "qk":
+            out["llm_score"] = ("hbm", l.batch * l.kv_heads * l.vis_len * l.head_dim * es)
+            out["compact"] = ("hbm", l.batch * moved * row * 2)
+        else:
+            # scored from hidden states and weights: each operand read once, each result
+            # written once; the logit contraction counts as matrix-core work once its flops
+            # per byte exceed the chip's ridge (2.5 PFLOP/s over 8 TB/s)
+            B, Dh, R, V = l.batch, l.hidden, l.q_heads * l.n_query, l.vis_len
+            nq, nkv = l.q_heads * l.head_dim, l.kv_heads * l.head_dim
+            out["fused_q"] = ("hbm", nq * Dh * 2 + B * l.n_query * (Dh * 2 + nq * 4))
+            out["fused_split_q"] = ("hbm", B * l.n_query * nq * (4 + 6))
+            out["fused_qt"] = ("hbm", nkv * Dh * 2 + B * l.n_query * nq * 6 + B * R * Dh * 4)
+            out["fused_split_qt"] = ("hbm", B * R * Dh * (4 + 4))
+            flops, byts = 2.0 * B * V * Dh * R, B * V * (Dh * 2 + R * 4) + B * R * Dh * 4
+            out["fused_logits"] = ("mfma", flops) if flops / byts > 312 else ("hbm", byts)
+            out["fused_softmax"] = ("hbm", B * R * V * 8)
+            out["fused_colsum"] = ("hbm", B * R * V * 4 + B * V * 4)
+            out["compact"] = ("hbm", l.batch * moved * l.hidden * es * 2)
     return out
 
 
@@ -85,10 +104,10 @@ def tokens_reduced(w: wl.Workload) -> int:
 class DeviceCase:
     """Device-resident inputs, outputs and workspaces of one sweep point."""
 
-    def __init__(self, w: wl.Workload, host, ring: int):
+    def __init__(self, w: wl.Workload, host, ring: int, stage2: str = "qk"):
         import torch
         from paper_2505_22654_amd import binding as vb
-        self.w, self.vb, self.torch = w, vb, torch
+        self.w, self.vb, self.torch, self.stage2 = w, vb, torch, stage2
         self.enc_in = self.enc_out = self.enc_ws = None
         if w.encoder is not None:
             e = w.encoder
@@ -107,6 +126,11 @@ class DeviceCase:
             self.llm_in = [base] + [{n: (t if n == "q" else t.clone()) for n, t in base.items()}
                                     for _ in range(sets - 1)]
             need = vb.llm_workspace_size(vb.llm_desc(l))
+            if stage2 == "hidden":
+                import numpy as np
+                need = vb.llm_fused_workspace_size(vb.llm_desc(l))
+                self.w_q = _to_device(host["weights"]["w_q"], l.dtype)
+                self.w_k_t = _to_device(np.ascontiguousarray(host["weights"]["w_k"].T), l.dtype)
             self.llm_ws = torch.empty(need, dtype=torch.uint8, device="cuda")
             self.llm_out = {"kept_idx": torch.empty((l.batch, l.keep), dtype=torch.int32,
                                                     device="cuda")}
@@ -134,6 +158,10 @@ class DeviceCase:
     def run_llm(self, i: int):
         if self.llm_in:
             s = self.llm_in[i % len(self.llm_in)]
+            if self.stage2 == "hidden":
+                self.vb.llm_prune_fused(self.w.llm, s["hidden"], self.w_q, self.w_k_t,
+                                        workspace=self.llm_ws, out=self.llm_out)
+                return
             self.vb.llm_prune(self.w.llm, s["q"], s["k"], s["v"], s["hidden"],
                               workspace=self.llm_ws, out=self.llm_out)
 
@@ -150,7 +178,7 @@ def _to_device(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-def host_inputs(points):
+def host_inputs(points, stage2: str = "qk"):
     """Seeded inputs per sweep point; tensors that do not depend on the budget are shared."""
     cache, hosts = {}, []
     for w in points:
@@ -165,11 +193,15 @@ def host_inputs(points):
             if key not in cache:
                 cache[key] = wl.llm_inputs(w.llm, w.seed)
             h["llm"] = cache[key]
+            if stage2 == "hidden":
+                if ("weights", key) not in cache:
+                    cache[("weights", key)] = wl.llm_weights(w.llm, w.seed)
+                h["weights"] = cache[("weights", key)]
         hosts.append(h)
     return hosts
 
 
-def cpu_baseline(points, hosts, budget_s=12.0):
+def cpu_baseline(points, hosts, budget_s=12.0, stage2: str = "qk"):
     """The CPU oracle on this host's cores over whole steps of the same inputs."""
     from oracle import vscan_oracle as vo
 
@@ -177,7 +209,10 @@ def cpu_baseline(points, hosts, budget_s=12.0):
         for w, h in zip(points, hosts):
             if w.encoder is not None:
                 vo.encoder_reduce(w.encoder, h["enc"]["q"], h["enc"]["k"], h["enc"]["x"])
-            if w.llm is not None:
+            if w.llm is not None and stage2 == "hidden":
+                vo.llm_prune_fused(w.llm, h["llm"]["hidden"], h["weights"]["w_q"],
+                                   h["weights"]["w_k"])
+            elif w.llm is not None:
                 vo.llm_prune(w.llm, **h["llm"])
 
     t0 = time.perf_counter()
@@ -228,6 +263,9 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
                     help="also run N plain device copies of 256 MiB (a kernel of known traffic "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--stage2", default="qk", choices=["qk", "hidden"],
+                    help="qk: vscan_llm_prune on the layer's Q and K (the default step); "
+                         "hidden: vscan_llm_prune_fused on hidden states and projection weights")
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="2: issue the encoder calls and the LLM calls of a step on two streams "
                          "(they are independent in this benchmark); default 1 = strictly serial")
@@ -252,13 +290,13 @@ def main():
 
     index = int(args.workload[3:])
     points = sweep_points(index)
-    hosts = host_inputs(points)
+    hosts = host_inputs(points, args.stage2)
     in_place = any(w.llm is not None and w.llm.in_place for w in points)
     steps, warmup = args.steps, args.warmup
     if index in (4, 5):
         steps, warmup = min(steps, 20), min(warmup, 3)
     ring = steps if in_place else 1
-    cases = [DeviceCase(w, h, ring) for w, h in zip(points, hosts)]
+    cases = [DeviceCase(w, h, ring, args.stage2) for w, h in zip(points, hosts)]
 
     side = torch.cuda.Stream() if args.streams == 2 else None
 
@@ -303,7 +341,7 @@ def main():
 
     work = {}
     for w in points:
-        for name, (bound, amount) in algorithmic_work(w).items():
+        for name, (bound, amount) in algorithmic_work(w, args.stage2).items():
             b, a = work.get(name, (bound, 0.0))
             work[name] = (bound, a + amount)
     dtype = (points[0].encoder or points[0].llm).dtype
@@ -341,12 +379,14 @@ def main():
         "config": {"workload": args.workload + ": " + ", ".join(w.name for w in points),
                    "streams": args.streams,
                    "tokens_reduced_per_step": reduced,
-                   "step": "encoder_reduce + llm_prune for every keep budget of the sweep"},
+                   "step": "encoder_reduce + " + ("llm_prune" if args.stage2 == "qk" else
+                                                  "llm_prune_fused")
+                           + " for every keep budget of the sweep"},
         "roofline": roof,
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(points, hosts)
+        result["cpu_baseline"] = cpu_baseline(points, hosts, stage2=args.stage2)
     print(json.dumps(result))
 
 

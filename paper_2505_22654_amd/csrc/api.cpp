@@ -121,7 +121,7 @@ int plan_llm(const vscan_llm_desc *d, LlmPlan *p) {
 
 struct FusedPlan {
     int k0, nk, S_out, ks_q, ks_l, R;
-    size_t off_cq, off_qpl, off_cqt, off_qtpl, off_cl, off_stats, off_part, bytes;
+    size_t off_cq, off_qpl, off_cqt, off_qtpl, off_cl, off_part, bytes;
 };
 
 int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
@@ -165,8 +165,6 @@ int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
     off += align_up((size_t)kFusedQtPlanes * B * p->R * Dh * 2);
     p->off_cl = off;
     off += align_up((size_t)p->ks_l * B * p->R * p->nk * sizeof(float));
-    p->off_stats = off;
-    off += align_up((size_t)B * p->R * 2 * sizeof(float));
     p->off_part = off;
     off += align_up((size_t)B * d->vis_len * sizeof(float));
     p->bytes = off ? off : kAlign;
@@ -487,7 +485,6 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     fa.c_qt = reinterpret_cast<float *>(ws + p.off_cqt);
     fa.qt_planes = reinterpret_cast<uint16_t *>(ws + p.off_qtpl);
     fa.c_l = reinterpret_cast<float *>(ws + p.off_cl);
-    fa.stats = reinterpret_cast<float2 *>(ws + p.off_stats);
     fa.part = reinterpret_cast<float *>(ws + p.off_part);
     fa.B = d->batch;
     fa.S = d->seq_len;
@@ -508,7 +505,7 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     VSCAN_LAUNCH("fused_qt", launch_fused_qt(fa, s));
     VSCAN_LAUNCH("fused_split_qt", launch_fused_split_qt(fa, s));
     VSCAN_LAUNCH("fused_logits", launch_fused_logits(fa, s));
-    VSCAN_LAUNCH("fused_stats", launch_fused_stats(fa, s));
+    VSCAN_LAUNCH("fused_softmax", launch_fused_softmax(fa, s));
     VSCAN_LAUNCH("fused_colsum", launch_fused_colsum(fa, s));
 
     LlmSelectArgs se;

@@ -22,7 +22,7 @@
 //   1. q   [B*Tq, Hq*dh]        P = last Tq hidden rows of every sequence, S = W_Q rows
 //   2. qt  [Hkv][B*g*Tq, Dh]    P = q planes of the group's heads,         S = W_K^T rows
 //   3. l   [B][Hq*Tq, nk]       P = qt planes,                             S = hidden rows
-//   4. per (sequence, query row) softmax statistics, 5. per key the sum over rows.
+//   4. softmax of every (sequence, query row), in place; 5. per key the sum over rows.
 // Contractions with few output tiles split the contraction axis over `ksplit` workgroups;
 // partial results are stored side by side and summed, in fixed order, by whichever kernel reads
 // them next.
@@ -232,52 +232,92 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
     }
 }
 
-// Softmax statistics of one (sequence, query row): maximum and reciprocal of the sum of
-// exponentials of the scaled logits over the key domain.
-__global__ __launch_bounds__(256) void fused_stats_kernel(const float *__restrict__ c, int ksplit,
-                                                          int64_t ks_stride, int nk, float scale,
-                                                          float2 *__restrict__ stats) {
+// Softmax of one (sequence, query row) over the key domain.  The scaled logits of the row
+// (partial sums added in fixed order) stay in registers between the maximum, the sum of
+// exponentials and the normalised weights, which overwrite the row's first partial slot.
+// NREG * 256 >= nk.
+template <int NREG>
+__global__ __launch_bounds__(256) void fused_softmax_kernel(float *__restrict__ c, int ksplit,
+                                                            int64_t ks_stride, int nk, float scale) {
     __shared__ float red[16];
     const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-    const float *l = c + row * nk;
+    float *l = c + row * nk;
+    float v[NREG];
+#pragma unroll
+    for (int i = 0; i < NREG; ++i) v[i] = 0.f;
+    for (int ks = 0; ks < ksplit; ++ks)
+#pragma unroll
+        for (int i = 0; i < NREG; ++i)
+            v[i] += l[ks * ks_stride + min((int)threadIdx.x + 256 * i, nk - 1)];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NREG; ++i) {
+        v[i] *= scale;
+        if ((int)threadIdx.x + 256 * i < nk) m = fmaxf(m, v[i]);
+    }
+    m = block_max(m, red);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NREG; ++i) {
+        v[i] = __expf(v[i] - m);
+        if ((int)threadIdx.x + 256 * i < nk) sum += v[i];
+    }
+    sum = block_sum(sum, red);
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int i = 0; i < NREG; ++i)
+        if ((int)threadIdx.x + 256 * i < nk) l[threadIdx.x + 256 * i] = v[i] * inv;
+}
+
+// Rows too long for the register form: three passes over the row.
+__global__ __launch_bounds__(256) void fused_softmax_long_kernel(float *__restrict__ c, int ksplit,
+                                                                 int64_t ks_stride, int nk,
+                                                                 float scale) {
+    __shared__ float red[16];
+    const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    float *l = c + row * nk;
     float m = -INFINITY;
     for (int j = threadIdx.x; j < nk; j += 256) {
         float v = 0.f;
         for (int ks = 0; ks < ksplit; ++ks) v += l[ks * ks_stride + j];
-        m = fmaxf(m, v * scale);
+        v *= scale;
+        l[j] = v;  // only this thread reads element j again
+        m = fmaxf(m, v);
     }
     m = block_max(m, red);
     float sum = 0.f;
-    for (int j = threadIdx.x; j < nk; j += 256) {
-        float v = 0.f;
-        for (int ks = 0; ks < ksplit; ++ks) v += l[ks * ks_stride + j];
-        sum += __expf(v * scale - m);
-    }
+    for (int j = threadIdx.x; j < nk; j += 256) sum += __expf(l[j] - m);
     sum = block_sum(sum, red);
-    if (threadIdx.x == 0) stats[row] = make_float2(m, 1.0f / sum);
+    const float inv = 1.0f / sum;
+    for (int j = threadIdx.x; j < nk; j += 256) l[j] = __expf(l[j] - m) * inv;
 }
 
 // part[b][j] = sum over the query rows of the softmax weight of visual token j (Eq. 5 before
-// the division by the number of rows).  A thread owns one key of the domain.
-__global__ __launch_bounds__(256) void fused_colsum_kernel(const float *__restrict__ c, int ksplit,
-                                                           int64_t ks_stride, int R, int nk,
-                                                           int vis_off, int V, float scale,
-                                                           const float2 *__restrict__ stats,
+// the division by the number of rows).  A workgroup owns 64 keys; its four waves take every
+// fourth row and their sums are added in wave order.
+__global__ __launch_bounds__(256) void fused_colsum_kernel(const float *__restrict__ p, int R, int nk,
+                                                           int vis_off, int V,
                                                            float *__restrict__ part) {
+    __shared__ float red[4][64];
     const int b = blockIdx.y;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    const int jc = min(j, nk - 1);
-    const float *l = c + (int64_t)b * R * nk + jc;
-    const float2 *st = stats + (int64_t)b * R;
+    const int j = blockIdx.x * 64 + lane_id();
+    const float *col = p + (int64_t)b * R * nk + min(j, nk - 1);
     float acc = 0.f;
-    for (int r = 0; r < R; ++r) {
-        float v = 0.f;
-        for (int ks = 0; ks < ksplit; ++ks) v += l[ks * ks_stride + (int64_t)r * nk];
-        const float2 s2 = st[r];
-        acc += __expf(v * scale - s2.x) * s2.y;
+    int r = wave_id();
+    for (; r + 28 < R; r += 32) {
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = col[(int64_t)(r + 4 * u) * nk];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += t[u];
     }
+    for (; r < R; r += 4) acc += col[(int64_t)r * nk];
+    red[wave_id()][lane_id()] = acc;
+    __syncthreads();
     const int t = j - vis_off;
-    if (j < nk && t >= 0 && t < V) part[(int64_t)b * V + t] = acc;
+    if (wave_id() == 0 && j < nk && t >= 0 && t < V)
+        part[(int64_t)b * V + t] =
+            ((red[0][lane_id()] + red[1][lane_id()]) + red[2][lane_id()]) + red[3][lane_id()];
 }
 
 GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
@@ -358,18 +398,24 @@ hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s) {
     return launch_gemm(pr, a.B, s);
 }
 
-hipError_t launch_fused_stats(const FusedArgs &a, hipStream_t s) {
+hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
     const int R = a.Hq * a.Tq;
-    hipLaunchKernelGGL(fused_stats_kernel, dim3(R, a.B), dim3(256), 0, s, a.c_l, a.ks_l,
-                       (int64_t)a.B * R * a.nk, a.nk, a.scale, a.stats);
+    const int64_t ks_stride = (int64_t)a.B * R * a.nk;
+    const dim3 grid(R, a.B), block(256);
+    if (a.nk <= 256)
+        hipLaunchKernelGGL(fused_softmax_kernel<1>, grid, block, 0, s, a.c_l, a.ks_l, ks_stride, a.nk, a.scale);
+    else if (a.nk <= 1024)
+        hipLaunchKernelGGL(fused_softmax_kernel<4>, grid, block, 0, s, a.c_l, a.ks_l, ks_stride, a.nk, a.scale);
+    else if (a.nk <= 4096)
+        hipLaunchKernelGGL(fused_softmax_kernel<16>, grid, block, 0, s, a.c_l, a.ks_l, ks_stride, a.nk, a.scale);
+    else
+        hipLaunchKernelGGL(fused_softmax_long_kernel, grid, block, 0, s, a.c_l, a.ks_l, ks_stride, a.nk, a.scale);
     return hipGetLastError();
 }
 
 hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s) {
-    const int R = a.Hq * a.Tq;
-    hipLaunchKernelGGL(fused_colsum_kernel, dim3((a.nk + 255) / 256, a.B), dim3(256), 0, s, a.c_l,
-                       a.ks_l, (int64_t)a.B * R * a.nk, R, a.nk, a.vis_start - a.k0, a.V, a.scale,
-                       a.stats, a.part);
+    hipLaunchKernelGGL(fused_colsum_kernel, dim3((a.nk + 63) / 64, a.B), dim3(256), 0, s, a.c_l,
+                       a.Hq * a.Tq, a.nk, a.vis_start - a.k0, a.V, a.part);
     return hipGetLastError();
 }
 

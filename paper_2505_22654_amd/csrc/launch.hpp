@@ -106,8 +106,8 @@ struct FusedArgs {
     uint16_t *q_planes;        // [3][B*Tq][Hq*dh] bf16
     float *c_qt;               // [Hkv][B*(Hq/Hkv)*Tq][Dh]
     uint16_t *qt_planes;       // [kFusedQtPlanes][Hkv][B*(Hq/Hkv)*Tq][Dh] bf16
-    float *c_l;                // [ks_l][B][Hq*Tq][nk] partial sums of the unscaled logits
-    float2 *stats;             // [B][Hq*Tq] (max, 1/sum) of the scaled logits
+    float *c_l;                // [ks_l][B][Hq*Tq][nk] partial sums of the unscaled logits; the
+                               // first slot becomes the softmax weights
     float *part;               // [B][V] sums over the query rows
     int B, S, Dh, Hq, Hkv, dh, Tq, vis_start, V, k0, nk;
     int ks_q, ks_l;            // shares of the contraction axis (fused_ksplit)
@@ -120,7 +120,7 @@ hipError_t launch_fused_split_q(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_split_qt(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s);
-hipError_t launch_fused_stats(const FusedArgs &a, hipStream_t s);
+hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s);
 
 }  // namespace vscan

@@ -45,6 +45,11 @@ SMALL_FUSED = {
     # long rows and few output tiles: the contraction axis is split over workgroups
     "split-axis": _shape(batch=1, hidden=4096, q_heads=4, kv_heads=2, head_dim=128, vis_len=70,
                          keep=11),
+    # key domains of every softmax form: up to 1024, up to 4096, longer
+    "domain-1k": _shape(batch=1, vis_len=700, keep=200, hidden=128, q_heads=4, kv_heads=4, head_dim=32),
+    "domain-4k": _shape(batch=1, vis_len=2500, keep=700, hidden=64, q_heads=2, kv_heads=1, head_dim=32),
+    "domain-long": _shape(batch=1, vis_len=4300, keep=1000, hidden=64, q_heads=2, kv_heads=2,
+                          head_dim=32, n_query=2),
     "one-visual-token": _shape(vis_len=1, keep=1),
     "keep-nothing": _shape(keep=0),
     "keep-everything": _shape(keep=150),
