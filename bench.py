@@ -34,7 +34,7 @@ KERNEL_SOURCE = {
     "llm_select": "select.hip", "sim_argmax": "sim_merge.hip",
     "merge": "sim_merge.hip", "llm_score": "llm.hip", "compact": "llm.hip",
     "fused_q": "fused.hip", "fused_split_q": "fused.hip", "fused_qt": "fused.hip",
-    "fused_split_qt": "fused.hip", "fused_logits": "fused.hip", "fused_softmax": "fused.hip",
+    "fused_logits": "fused.hip", "fused_softmax": "fused.hip",
     "fused_colsum": "fused.hip",
 }
 
@@ -83,7 +83,6 @@ def algorithmic_work(w: wl.Workload, stage2: str = "qk"):
             out["fused_q"] = ("hbm", nq * Dh * 2 + B * l.n_query * (Dh * 2 + nq * 4))
             out["fused_split_q"] = ("hbm", B * l.n_query * nq * (4 + 6))
             out["fused_qt"] = ("hbm", nkv * Dh * 2 + B * l.n_query * nq * 6 + B * R * Dh * 4)
-            out["fused_split_qt"] = ("hbm", B * R * Dh * (4 + 4))
             flops, byts = 2.0 * B * V * Dh * R, B * V * (Dh * 2 + R * 4) + B * R * Dh * 4
             out["fused_logits"] = ("mfma", flops) if flops / byts > 312 else ("hbm", byts)
             out["fused_softmax"] = ("hbm", B * R * V * 8)

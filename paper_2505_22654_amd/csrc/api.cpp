@@ -121,7 +121,7 @@ int plan_llm(const vscan_llm_desc *d, LlmPlan *p) {
 
 struct FusedPlan {
     int k0, nk, S_out, ks_q, ks_l, R;
-    size_t off_cq, off_qpl, off_cqt, off_qtpl, off_cl, off_part, bytes;
+    size_t off_cq, off_qpl, off_qtpl, off_cl, off_part, bytes;
 };
 
 int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
@@ -159,8 +159,6 @@ int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
     off += align_up((size_t)p->ks_q * M * N * sizeof(float));
     p->off_qpl = off;
     off += align_up((size_t)3 * M * N * 2);
-    p->off_cqt = off;
-    off += align_up((size_t)B * p->R * Dh * sizeof(float));
     p->off_qtpl = off;
     off += align_up((size_t)kFusedQtPlanes * B * p->R * Dh * 2);
     p->off_cl = off;
@@ -482,7 +480,6 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     fa.w_k_t = w_k_t;
     fa.c_q = reinterpret_cast<float *>(ws + p.off_cq);
     fa.q_planes = reinterpret_cast<uint16_t *>(ws + p.off_qpl);
-    fa.c_qt = reinterpret_cast<float *>(ws + p.off_cqt);
     fa.qt_planes = reinterpret_cast<uint16_t *>(ws + p.off_qtpl);
     fa.c_l = reinterpret_cast<float *>(ws + p.off_cl);
     fa.part = reinterpret_cast<float *>(ws + p.off_part);
@@ -503,7 +500,6 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     VSCAN_LAUNCH("fused_q", launch_fused_q(fa, s));
     VSCAN_LAUNCH("fused_split_q", launch_fused_split_q(fa, s));
     VSCAN_LAUNCH("fused_qt", launch_fused_qt(fa, s));
-    VSCAN_LAUNCH("fused_split_qt", launch_fused_split_qt(fa, s));
     VSCAN_LAUNCH("fused_logits", launch_fused_logits(fa, s));
     VSCAN_LAUNCH("fused_softmax", launch_fused_softmax(fa, s));
     VSCAN_LAUNCH("fused_colsum", launch_fused_colsum(fa, s));

@@ -21,6 +21,7 @@
 // contraction axis contiguous; S is the large, streamed operand):
 //   1. q   [B*Tq, Hq*dh]        P = last Tq hidden rows of every sequence, S = W_Q rows
 //   2. qt  [Hkv][B*g*Tq, Dh]    P = q planes of the group's heads,         S = W_K^T rows
+//      (stored as bf16 planes straight from the accumulators)
 //   3. l   [B][Hq*Tq, nk]       P = qt planes,                             S = hidden rows
 //   4. softmax of every (sequence, query row), in place; 5. per key the sum over rows.
 // Contractions with few output tiles split the contraction axis over `ksplit` workgroups;
@@ -32,8 +33,6 @@
 namespace vscan {
 namespace {
 
-constexpr int kGemmThreads = 256;
-constexpr int kTileS = 128;                   // streamed rows per workgroup, 32 per wave
 constexpr int kChunkBytes = 128;              // contraction bytes staged per step (64 bf16)
 constexpr int kRowPitch = kChunkBytes + 16;   // LDS row pitch: 36 words, conflict-free b128 reads
 constexpr int kTargetWorkgroups = 512;        // two per compute unit before the axis is split
@@ -42,8 +41,16 @@ struct GemmDims {
     int rows_s, rows_p;   // valid rows of the two operands
     int k_bytes;          // contraction length in bytes (multiple of 16)
     int ksplit;
+    int Z, s_tiles, p_tiles;  // batch entries and tiles per entry (set by the launcher)
+    int affine;           // keep a batch entry's workgroups on one XCD (and its L2)
     float *c;             // [ksplit][Z][rows_p][rows_s]
 };
+
+// fp32 partial result of share ks
+__device__ __forceinline__ void emit_partial(const GemmDims &d, int ks, int z, int p, int s_row,
+                                             float v) {
+    d.c[(((int64_t)ks * d.Z + z) * d.rows_p + p) * d.rows_s + s_row] = v;
+}
 
 // ---- operand addressing of the three contractions -------------------------------------------
 // s_base/p_base: wave-uniform base of batch entry z (and plane pl); s_off/p_off: byte offset of a
@@ -60,6 +67,9 @@ struct ProbQ {
     __device__ uint32_t p_off(int m) const {
         const int b = m / Tq, t = m - b * Tq;
         return (uint32_t)(b * S + S - Tq + t) * (uint32_t)row_bytes;
+    }
+    __device__ void emit(int ks, int z, int p, int s_row, float v) const {
+        emit_partial(d, ks, z, p, s_row, v);
     }
 };
 
@@ -78,6 +88,18 @@ struct ProbQt {
         const int t = m % Tq, bh = m / Tq;
         const int hh = bh % group, b = bh / group;
         return (uint32_t)((b * Tq + t) * Hq * dh + hh * dh) * 2u;
+    }
+    // the result goes out as bf16 planes right away (this contraction is never split)
+    uint16_t *qt_planes;      // [kFusedQtPlanes][Hkv][rows_p][rows_s]
+    int64_t qt_plane_elems;   // Hkv*rows_p*rows_s
+    __device__ void emit(int, int g, int p, int s_row, float v) const {
+        uint16_t *o = qt_planes + ((int64_t)g * d.rows_p + p) * d.rows_s + s_row;
+#pragma unroll
+        for (int pl = 0; pl < kFusedQtPlanes; ++pl) {
+            const uint32_t bits = f32_to_bf16_rne(v);
+            o[pl * qt_plane_elems] = (uint16_t)bits;
+            v -= __uint_as_float(bits << 16);
+        }
     }
 };
 
@@ -100,27 +122,36 @@ struct ProbLogit {
         const int g = h / group, hh = h - g * group;
         return (uint32_t)(g * Mg + hh * Tq + t) * (uint32_t)row_bytes;
     }
+    __device__ void emit(int ks, int z, int p, int s_row, float v) const {
+        emit_partial(d, ks, z, p, s_row, v);
+    }
 };
 
-// One workgroup: 128 streamed rows x 32*NP plane-operand rows, one share of the contraction
-// axis.  Both operands pass through LDS in 128-byte row chunks: the next chunk is fetched into
-// registers (coalesced, 8 lanes per row) while the matrix cores work on the current one.  Row
-// indices past the operand's end are clamped (the rows are computed and not stored); chunk
-// pieces past the contraction length are fetched from a clamped offset and zeroed on their way
-// into LDS.
-template <class Prob, int NP>
-__global__ __launch_bounds__(kGemmThreads) void nt_gemm_kernel(Prob pr) {
+// One workgroup of WS x WP waves: 32*FS*WS streamed rows x 32*FP*WP plane-operand rows, one
+// share of the contraction axis; a wave owns FS x FP tiles of 32 x 32.  Both operands pass
+// through LDS in 128-byte row chunks: the next chunk is fetched into registers (coalesced, 8
+// lanes per row) while the matrix cores work on the current one.  Row indices past the
+// operand's end are clamped (the rows are computed and not stored); chunk pieces past the
+// contraction length are fetched from a clamped offset and zeroed on their way into LDS.
+template <class Prob, int WS, int WP, int FS, int FP>
+__global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
     constexpr int PL = Prob::PL;
-    constexpr int TP = 32 * NP;
-    __shared__ __attribute__((aligned(16))) unsigned char lds_s[kTileS * kRowPitch];
+    constexpr int THREADS = 64 * WS * WP;
+    constexpr int TS = 32 * FS * WS, TP = 32 * FP * WP;
+    constexpr int ROWS_PER_PASS = THREADS / 8;           // rows one staging pass covers
+    constexpr int NS = TS / ROWS_PER_PASS, NP = TP / ROWS_PER_PASS;
+    static_assert(TS % ROWS_PER_PASS == 0 && TP % ROWS_PER_PASS == 0, "staging covers whole tiles");
+    __shared__ __attribute__((aligned(16))) unsigned char lds_s[TS * kRowPitch];
     __shared__ __attribute__((aligned(16))) unsigned char lds_p[PL * TP * kRowPitch];
 
     const GemmDims d = pr.d;
-    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
-    const int z = blockIdx.z;
-    const int s0 = blockIdx.x * kTileS;
-    const int ptile = blockIdx.y / d.ksplit, ks = blockIdx.y - ptile * d.ksplit;
-    const int p0 = ptile * TP;
+    const int tid = threadIdx.x, lane = lane_id();
+    const int ws = wave_id() % WS, wp = wave_id() / WS;
+    int z, item;
+    if (!image_affine_decode(d.Z, d.s_tiles * d.p_tiles * d.ksplit, d.affine != 0, z, item)) return;
+    const int s_tile = item % d.s_tiles, rest = item / d.s_tiles;
+    const int ptile = rest / d.ksplit, ks = rest - ptile * d.ksplit;
+    const int s0 = s_tile * TS, p0 = ptile * TP;
     const int nchunks = (d.k_bytes + kChunkBytes - 1) / kChunkBytes;
     const int cps = (nchunks + d.ksplit - 1) / d.ksplit;
     const int c_begin = ks * cps, c_end = min(nchunks, c_begin + cps);
@@ -130,23 +161,27 @@ __global__ __launch_bounds__(kGemmThreads) void nt_gemm_kernel(Prob pr) {
     const char *pb[PL];
 #pragma unroll
     for (int pl = 0; pl < PL; ++pl) pb[pl] = pr.p_base(z, pl);
-    uint32_t s_off[4], p_off[NP];
+    uint32_t s_off[NS], p_off[NP];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) s_off[i] = pr.s_off(min(s0 + srow + 32 * i, d.rows_s - 1));
-#pragma unroll
-    for (int i = 0; i < NP; ++i) p_off[i] = pr.p_off(min(p0 + srow + 32 * i, d.rows_p - 1));
-
-    f32x16_t acc[NP];
+    for (int i = 0; i < NS; ++i)
+        s_off[i] = pr.s_off(min(s0 + srow + ROWS_PER_PASS * i, d.rows_s - 1));
 #pragma unroll
     for (int i = 0; i < NP; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        p_off[i] = pr.p_off(min(p0 + srow + ROWS_PER_PASS * i, d.rows_p - 1));
 
-    uint4 rs[4], rp[PL * NP];
+    f32x16_t acc[FP][FS];
+#pragma unroll
+    for (int i = 0; i < FP; ++i)
+#pragma unroll
+        for (int j = 0; j < FS; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    uint4 rs[NS], rp[PL * NP];
     auto fetch = [&](int c) {
         const uint32_t col = (uint32_t)min(c * kChunkBytes + piece * 16, d.k_bytes - 16);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rs[i] = load16(sb, (int64_t)s_off[i] + col);
+        for (int i = 0; i < NS; ++i) rs[i] = load16(sb, (int64_t)s_off[i] + col);
 #pragma unroll
         for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
@@ -157,61 +192,84 @@ __global__ __launch_bounds__(kGemmThreads) void nt_gemm_kernel(Prob pr) {
     for (int c = c_begin; c < c_end; ++c) {
         const bool valid = c * kChunkBytes + piece * 16 < d.k_bytes;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<uint4 *>(lds_s + (srow + 32 * i) * kRowPitch + piece * 16) =
+        for (int i = 0; i < NS; ++i)
+            *reinterpret_cast<uint4 *>(lds_s + (srow + ROWS_PER_PASS * i) * kRowPitch + piece * 16) =
                 valid ? rs[i] : zero16();
 #pragma unroll
         for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
             for (int i = 0; i < NP; ++i)
-                *reinterpret_cast<uint4 *>(lds_p + (pl * TP + srow + 32 * i) * kRowPitch +
+                *reinterpret_cast<uint4 *>(lds_p + (pl * TP + srow + ROWS_PER_PASS * i) * kRowPitch +
                                            piece * 16) = valid ? rp[pl * NP + i] : zero16();
         __syncthreads();
         fetch(min(c + 1, c_end - 1));  // unconditional; the last round re-reads its own chunk
 #pragma unroll
         for (int sub = 0; sub < kChunkBytes / 32; ++sub) {
             const int colb = sub * 32 + 16 * (lane >> 5);
-            const uint4 b = *reinterpret_cast<const uint4 *>(
-                lds_s + (w * 32 + (lane & 31)) * kRowPitch + colb);
+            uint4 b[FS];
 #pragma unroll
-            for (int i = 0; i < NP; ++i)
+            for (int j = 0; j < FS; ++j)
+                b[j] = *reinterpret_cast<const uint4 *>(
+                    lds_s + ((ws * FS + j) * 32 + (lane & 31)) * kRowPitch + colb);
+#pragma unroll
+            for (int i = 0; i < FP; ++i)
 #pragma unroll
                 for (int pl = 0; pl < PL; ++pl) {
                     const uint4 a = *reinterpret_cast<const uint4 *>(
-                        lds_p + (pl * TP + i * 32 + (lane & 31)) * kRowPitch + colb);
-                    mma32_chunk<bf16_t>(acc[i], a, b);
+                        lds_p + (pl * TP + (wp * FP + i) * 32 + (lane & 31)) * kRowPitch + colb);
+#pragma unroll
+                    for (int j = 0; j < FS; ++j) mma32_chunk<bf16_t>(acc[i][j], a, b[j]);
                 }
         }
         __syncthreads();
     }
 
-    // acc[i][r] = C[p0 + 32 i + acc_row(r)][s0 + 32 w + lane % 32]: lanes run along the
-    // streamed rows, which are contiguous in C
-    const int s_out = s0 + w * 32 + (lane & 31);
-    if (s_out < d.rows_s) {
-        float *c_z = d.c + ((int64_t)ks * gridDim.z + z) * d.rows_p * d.rows_s;
+    // acc[i][j][r] = C[p0 + 32 (wp FP + i) + acc_row(r)][s0 + 32 (ws FS + j) + lane % 32]: lanes
+    // run along the streamed rows, which are contiguous in the result
 #pragma unroll
-        for (int i = 0; i < NP; ++i)
+    for (int j = 0; j < FS; ++j) {
+        const int s_out = s0 + (ws * FS + j) * 32 + (lane & 31);
+        if (s_out >= d.rows_s) continue;
+#pragma unroll
+        for (int i = 0; i < FP; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int p_out = p0 + i * 32 + acc_row(r);
-                if (p_out < d.rows_p) c_z[(int64_t)p_out * d.rows_s + s_out] = acc[i][r];
+                const int p_out = p0 + (wp * FP + i) * 32 + acc_row(r);
+                if (p_out < d.rows_p) pr.emit(ks, z, p_out, s_out, acc[i][j][r]);
             }
     }
 }
 
+// Tile shapes by the number of plane-operand rows: <= 32, <= 64, <= 128, more.
+struct TileShape {
+    int ts, tp;
+};
+TileShape tile_shape(int rows_p) {
+    if (rows_p <= 32) return {128, 32};
+    if (rows_p <= 64) return {128, 64};
+    if (rows_p <= 128) return {256, 128};
+    return {256, 256};
+}
+
 template <class Prob>
-hipError_t launch_gemm(const Prob &pr, int Z, hipStream_t s) {
-    const GemmDims &d = pr.d;
-    const int np = d.rows_p <= 32 ? 1 : (d.rows_p <= 64 ? 2 : 4);
-    const int ptiles = (d.rows_p + 32 * np - 1) / (32 * np);
-    dim3 grid((d.rows_s + kTileS - 1) / kTileS, ptiles * d.ksplit, Z);
-    if (np == 1)
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 1>), grid, dim3(kGemmThreads), 0, s, pr);
-    else if (np == 2)
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2>), grid, dim3(kGemmThreads), 0, s, pr);
+hipError_t launch_gemm(Prob pr, int Z, hipStream_t s) {
+    GemmDims &d = pr.d;
+    const TileShape t = tile_shape(d.rows_p);
+    d.Z = Z;
+    d.s_tiles = (d.rows_s + t.ts - 1) / t.ts;
+    d.p_tiles = (d.rows_p + t.tp - 1) / t.tp;
+    // with at least one batch entry per XCD, an entry's workgroups share the plane operand
+    // through that XCD's L2
+    d.affine = Z >= kXcds;
+    const dim3 grid(image_affine_grid(Z, d.s_tiles * d.p_tiles * d.ksplit, d.affine != 0));
+    if (t.tp == 32)
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4, 1, 1, 1>), grid, dim3(256), 0, s, pr);
+    else if (t.tp == 64)
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4, 1, 1, 2>), grid, dim3(256), 0, s, pr);
+    else if (t.tp == 128)
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2, 2, 4, 2>), grid, dim3(256), 0, s, pr);
     else
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4>), grid, dim3(kGemmThreads), 0, s, pr);
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2, 4, 4, 2>), grid, dim3(512), 0, s, pr);
     return hipGetLastError();
 }
 
@@ -235,49 +293,50 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
 // Softmax of one (sequence, query row) over the key domain.  The scaled logits of the row
 // (partial sums added in fixed order) stay in registers between the maximum, the sum of
 // exponentials and the normalised weights, which overwrite the row's first partial slot.
-// NREG * 256 >= nk.
-template <int NREG>
-__global__ __launch_bounds__(256) void fused_softmax_kernel(float *__restrict__ c, int ksplit,
-                                                            int64_t ks_stride, int nk, float scale) {
+// NREG * THREADS >= nk.
+template <int THREADS, int NREG>
+__global__ __launch_bounds__(THREADS) void fused_softmax_kernel(float *__restrict__ c, int ksplit,
+                                                                int64_t ks_stride, int nk,
+                                                                float scale) {
     __shared__ float red[16];
     const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
     float *l = c + row * nk;
+    const int tid = threadIdx.x;
     float v[NREG];
 #pragma unroll
     for (int i = 0; i < NREG; ++i) v[i] = 0.f;
     for (int ks = 0; ks < ksplit; ++ks)
 #pragma unroll
-        for (int i = 0; i < NREG; ++i)
-            v[i] += l[ks * ks_stride + min((int)threadIdx.x + 256 * i, nk - 1)];
+        for (int i = 0; i < NREG; ++i) v[i] += l[ks * ks_stride + min(tid + THREADS * i, nk - 1)];
     float m = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NREG; ++i) {
         v[i] *= scale;
-        if ((int)threadIdx.x + 256 * i < nk) m = fmaxf(m, v[i]);
+        if (tid + THREADS * i < nk) m = fmaxf(m, v[i]);
     }
     m = block_max(m, red);
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < NREG; ++i) {
         v[i] = __expf(v[i] - m);
-        if ((int)threadIdx.x + 256 * i < nk) sum += v[i];
+        if (tid + THREADS * i < nk) sum += v[i];
     }
     sum = block_sum(sum, red);
     const float inv = 1.0f / sum;
 #pragma unroll
     for (int i = 0; i < NREG; ++i)
-        if ((int)threadIdx.x + 256 * i < nk) l[threadIdx.x + 256 * i] = v[i] * inv;
+        if (tid + THREADS * i < nk) l[tid + THREADS * i] = v[i] * inv;
 }
 
 // Rows too long for the register form: three passes over the row.
-__global__ __launch_bounds__(256) void fused_softmax_long_kernel(float *__restrict__ c, int ksplit,
-                                                                 int64_t ks_stride, int nk,
-                                                                 float scale) {
+__global__ __launch_bounds__(1024) void fused_softmax_long_kernel(float *__restrict__ c, int ksplit,
+                                                                  int64_t ks_stride, int nk,
+                                                                  float scale) {
     __shared__ float red[16];
     const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
     float *l = c + row * nk;
     float m = -INFINITY;
-    for (int j = threadIdx.x; j < nk; j += 256) {
+    for (int j = threadIdx.x; j < nk; j += 1024) {
         float v = 0.f;
         for (int ks = 0; ks < ksplit; ++ks) v += l[ks * ks_stride + j];
         v *= scale;
@@ -286,10 +345,10 @@ __global__ __launch_bounds__(256) void fused_softmax_long_kernel(float *__restri
     }
     m = block_max(m, red);
     float sum = 0.f;
-    for (int j = threadIdx.x; j < nk; j += 256) sum += __expf(l[j] - m);
+    for (int j = threadIdx.x; j < nk; j += 1024) sum += __expf(l[j] - m);
     sum = block_sum(sum, red);
     const float inv = 1.0f / sum;
-    for (int j = threadIdx.x; j < nk; j += 256) l[j] = __expf(l[j] - m) * inv;
+    for (int j = threadIdx.x; j < nk; j += 1024) l[j] = __expf(l[j] - m) * inv;
 }
 
 // part[b][j] = sum over the query rows of the softmax weight of visual token j (Eq. 5 before
@@ -326,6 +385,8 @@ GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
     d.rows_p = rows_p;
     d.k_bytes = k_elems * 2;
     d.ksplit = ksplit;
+    d.Z = d.s_tiles = d.p_tiles = 1;
+    d.affine = 0;
     d.c = c;
     return d;
 }
@@ -333,9 +394,8 @@ GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
 }  // namespace
 
 int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems) {
-    const int np = rows_p <= 32 ? 1 : (rows_p <= 64 ? 2 : 4);
-    const int64_t tiles =
-        (int64_t)((rows_s + kTileS - 1) / kTileS) * ((rows_p + 32 * np - 1) / (32 * np)) * Z;
+    const TileShape t = tile_shape(rows_p);
+    const int64_t tiles = (int64_t)((rows_s + t.ts - 1) / t.ts) * ((rows_p + t.tp - 1) / t.tp) * Z;
     const int nchunks = (k_elems * 2 + kChunkBytes - 1) / kChunkBytes;
     int ks = (int)((kTargetWorkgroups + tiles - 1) / tiles);
     ks = max(1, min(ks, min(16, nchunks / 2)));
@@ -363,7 +423,7 @@ hipError_t launch_fused_split_q(const FusedArgs &a, hipStream_t s) {
 hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s) {
     const int group = a.Hq / a.Hkv;
     ProbQt pr;
-    pr.d = dims(a.Dh, a.B * group * a.Tq, a.dh, 1, a.c_qt);
+    pr.d = dims(a.Dh, a.B * group * a.Tq, a.dh, 1, nullptr);
     pr.q_planes = reinterpret_cast<const char *>(a.q_planes);
     pr.w_k_t = reinterpret_cast<const char *>(a.w_k_t);
     pr.Tq = a.Tq;
@@ -372,14 +432,9 @@ hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s) {
     pr.Hq = a.Hq;
     pr.Hkv = a.Hkv;
     pr.plane_bytes = (int64_t)a.B * a.Tq * a.Hq * a.dh * 2;
+    pr.qt_planes = a.qt_planes;
+    pr.qt_plane_elems = (int64_t)a.B * a.Hq * a.Tq * a.Dh;
     return launch_gemm(pr, a.Hkv, s);
-}
-
-hipError_t launch_fused_split_qt(const FusedArgs &a, hipStream_t s) {
-    const int64_t n = (int64_t)a.B * a.Hq * a.Tq * a.Dh;
-    hipLaunchKernelGGL(split_planes_kernel<kFusedQtPlanes>, dim3((unsigned)((n + 255) / 256)),
-                       dim3(256), 0, s, a.c_qt, 1, n, a.qt_planes);
-    return hipGetLastError();
 }
 
 hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s) {
@@ -401,15 +456,22 @@ hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s) {
 hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
     const int R = a.Hq * a.Tq;
     const int64_t ks_stride = (int64_t)a.B * R * a.nk;
-    const dim3 grid(R, a.B), block(256);
+    const dim3 grid(R, a.B);
+#define VSCAN_SOFTMAX(T, N)                                                                      \
+    hipLaunchKernelGGL((fused_softmax_kernel<T, N>), grid, dim3(T), 0, s, a.c_l, a.ks_l, ks_stride, \
+                       a.nk, a.scale)
     if (a.nk <= 256)
-        hipLaunchKernelGGL(fused_softmax_kernel<1>, grid, block, 0, s, a.c_l, a.ks_l, ks_stride, a.nk, a.scale);
+        VSCAN_SOFTMAX(256, 1);
     else if (a.nk <= 1024)
-        hipLaunchKernelGGL(fused_softmax_kernel<4>, grid, block, 0, s, a.c_l, a.ks_l, ks_stride, a.nk, a.scale);
+        VSCAN_SOFTMAX(256, 4);
     else if (a.nk <= 4096)
-        hipLaunchKernelGGL(fused_softmax_kernel<16>, grid, block, 0, s, a.c_l, a.ks_l, ks_stride, a.nk, a.scale);
+        VSCAN_SOFTMAX(1024, 4);
+    else if (a.nk <= 16384)
+        VSCAN_SOFTMAX(1024, 16);
     else
-        hipLaunchKernelGGL(fused_softmax_long_kernel, grid, block, 0, s, a.c_l, a.ks_l, ks_stride, a.nk, a.scale);
+        hipLaunchKernelGGL(fused_softmax_long_kernel, grid, dim3(1024), 0, s, a.c_l, a.ks_l,
+                           ks_stride, a.nk, a.scale);
+#undef VSCAN_SOFTMAX
     return hipGetLastError();
 }
 

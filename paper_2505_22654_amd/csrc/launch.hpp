@@ -104,7 +104,6 @@ struct FusedArgs {
     const void *w_k_t;         // [Dh, Hkv*dh]  rows = input features
     float *c_q;                // [ks_q][B*Tq][Hq*dh] partial sums of q
     uint16_t *q_planes;        // [3][B*Tq][Hq*dh] bf16
-    float *c_qt;               // [Hkv][B*(Hq/Hkv)*Tq][Dh]
     uint16_t *qt_planes;       // [kFusedQtPlanes][Hkv][B*(Hq/Hkv)*Tq][Dh] bf16
     float *c_l;                // [ks_l][B][Hq*Tq][nk] partial sums of the unscaled logits; the
                                // first slot becomes the softmax weights
@@ -118,7 +117,6 @@ int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems);
 hipError_t launch_fused_q(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_split_q(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s);
-hipError_t launch_fused_split_qt(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s);

@@ -50,6 +50,11 @@ SMALL_FUSED = {
     "domain-4k": _shape(batch=1, vis_len=2500, keep=700, hidden=64, q_heads=2, kv_heads=1, head_dim=32),
     "domain-long": _shape(batch=1, vis_len=4300, keep=1000, hidden=64, q_heads=2, kv_heads=2,
                           head_dim=32, n_query=2),
+    "domain-longest": _shape(batch=1, vis_len=17000, keep=3000, hidden=64, q_heads=1, kv_heads=1,
+                             head_dim=32),
+    # eight or more sequences: a sequence's workgroups stay on one XCD
+    "nine-sequences": _shape(batch=9, vis_len=140, keep=30, hidden=128, q_heads=4, kv_heads=2,
+                             head_dim=32),
     "one-visual-token": _shape(vis_len=1, keep=1),
     "keep-nothing": _shape(keep=0),
     "keep-everything": _shape(keep=150),
