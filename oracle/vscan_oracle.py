@@ -240,3 +240,49 @@ def llm_prune_fused(shape, hidden, w_q, w_k) -> Dict[str, np.ndarray]:
     kept = topk(s, shape.keep)
     return {"scores": s, "kept": kept,
             "hidden": compact(hidden, kept, shape.vis_start, shape.vis_len)}
+
+
+def encoder_scores_from_hidden(hidden, w_q, w_k, heads, head_dim, domain: int = 0,
+                               scale: float = 0.0):
+    """Eq. 1-2 written out from the rows the attention layer sees (Sec. 4.1 "Global Scan"):
+    hidden [B,C,S,D] with the [CLS] row first, w_q, w_k [H*dh, D] (rows = output features),
+        Q = x_CLS W_Q^h,  K = x W_K^h,  S^h = softmax(Q K^T * scale),  S_avg = mean over heads.
+    Returns the [CLS] row's attention to the N = S-1 patch tokens, [B,C,N] fp64.  domain 0: the
+    softmax runs over the patch keys only; domain 1: over all S keys ([CLS] included) and the
+    patch columns are taken (the two readings of `encoder_scores`).  Plain numpy in fp64."""
+    x = np.asarray(hidden, dtype=np.float64)
+    wq = np.asarray(w_q, dtype=np.float64)
+    wk = np.asarray(w_k, dtype=np.float64)
+    B, C, S, D = x.shape
+    sc = default_scale(head_dim, scale)
+    k0 = 0 if domain else 1
+    q = (x[:, :, 0, :] @ wq.T).reshape(B, C, heads, head_dim)
+    k = (x[:, :, k0:, :] @ wk.T).reshape(B, C, S - k0, heads, head_dim)
+    out = np.zeros((B, C, S - 1), dtype=np.float64)
+    for b in range(B):
+        for c in range(C):
+            for h in range(heads):
+                logit = k[b, c, :, h, :] @ q[b, c, h] * sc
+                e = np.exp(logit - logit.max())
+                out[b, c] += (e / e.sum())[1 - k0:]
+    return out / heads
+
+
+def encoder_reduce_fused(shape, hidden, w_q, w_k, x, hidden_local=None, w_q_local=None,
+                         w_k_local=None) -> Dict[str, np.ndarray]:
+    """Sec. 4.1 end to end with the scores taken from hidden states and projection weights
+    ([CLS] scoring only); the optional second triple is the shallow layer of the local scan."""
+    s_global = encoder_scores_from_hidden(hidden, w_q, w_k, shape.heads, shape.head_dim,
+                                          shape.softmax_domain, shape.scale)
+    if hidden_local is not None:
+        s_local = encoder_scores_from_hidden(hidden_local, w_q_local, w_k_local, shape.heads,
+                                             shape.head_dim, shape.softmax_domain, shape.scale)
+    else:
+        s_local = s_global
+    kept = select(s_local, s_global, shape.grid_h, shape.grid_w, shape.win_rows, shape.win_cols,
+                  shape.keep_local, shape.keep_global)
+    a = assign(x, kept)
+    merged, counts = merge(x, kept, a)
+    return {"scores": s_global.reshape(s_global.shape[0], -1),
+            "scores_local": s_local.reshape(s_local.shape[0], -1),
+            "kept": kept, "assign": a, "merged": merged, "counts": counts}

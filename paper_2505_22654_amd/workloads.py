@@ -218,15 +218,10 @@ def encoder_projections(shape: EncoderShape, seed: int):
     return wq, wk
 
 
-def encoder_item(shape: EncoderShape, seed: int, b: int, logit_gain: float = 1.0,
-                 proj=None, stream: int = 0) -> Dict[str, np.ndarray]:
-    """Inputs of image `b`: q, k [C,H,S,dh] and x [C*N,D] as fp32 arrays.
-
-    `stream` selects an independent draw of the features behind q/k only (used
-    for the shallow-layer pair of the local scan); x always comes from stream 0."""
-    C, N, S = shape.n_segments, shape.n_tokens, shape.rows
-    H, dh, D = shape.heads, shape.head_dim, shape.feat_dim
-    wq, wk = proj if proj is not None else encoder_projections(shape, seed)
+def _encoder_rows(shape: EncoderShape, seed: int, b: int, stream: int):
+    """Features of image `b` in fp64: x [C,N,D] (patch tokens) and rows [C,S,D] (the rows the
+    attention layer sees: [CLS] first where there is one)."""
+    C, N, S, D = shape.n_segments, shape.n_tokens, shape.rows, shape.feat_dim
     r = _rng(seed, b, 0)
     centres = r.normal(0.0, 1.0, size=(N_CENTRES, D))
     x = np.empty((C, N, D))
@@ -247,6 +242,19 @@ def encoder_item(shape: EncoderShape, seed: int, b: int, logit_gain: float = 1.0
         # the same features perturbed, so local and global rankings differ
         r2 = _rng(seed, b, stream)
         rows = rows + r2.normal(0.0, 0.5, size=rows.shape)
+    return x, rows
+
+
+def encoder_item(shape: EncoderShape, seed: int, b: int, logit_gain: float = 1.0,
+                 proj=None, stream: int = 0) -> Dict[str, np.ndarray]:
+    """Inputs of image `b`: q, k [C,H,S,dh] and x [C*N,D] as fp32 arrays.
+
+    `stream` selects an independent draw of the features behind q/k only (used
+    for the shallow-layer pair of the local scan); x always comes from stream 0."""
+    C, N, S = shape.n_segments, shape.n_tokens, shape.rows
+    H, dh, D = shape.heads, shape.head_dim, shape.feat_dim
+    wq, wk = proj if proj is not None else encoder_projections(shape, seed)
+    x, rows = _encoder_rows(shape, seed, b, stream)
     q = (rows.reshape(C * S, D) @ wq) * logit_gain
     k = rows.reshape(C * S, D) @ wk
     q = q.reshape(C, S, H, dh).transpose(0, 2, 1, 3)
@@ -256,6 +264,22 @@ def encoder_item(shape: EncoderShape, seed: int, b: int, logit_gain: float = 1.0
         "k": _finish(k, shape.dtype),
         "x": _finish(x.reshape(C * N, D), shape.dtype),
     }
+
+
+def encoder_hidden_inputs(shape: EncoderShape, seed: int, logit_gain: float = 1.0,
+                          stream: int = 0) -> Dict[str, np.ndarray]:
+    """Whole batch for the form of stage 1 that scores from the layer's input rows and its
+    projection weights: hidden [B,C,S,D] (the rows behind q and k of `encoder_inputs`, rounded
+    to the workload's dtype), x [B,C*N,D], w_q and w_k [H*dh, D] (rows = output features; the
+    logit gain is folded into w_q)."""
+    wq, wk = encoder_projections(shape, seed)
+    hidden, xs = [], []
+    for b in range(shape.batch):
+        x, rows = _encoder_rows(shape, seed, b, stream)
+        hidden.append(rows)
+        xs.append(x.reshape(shape.n_segments * shape.n_tokens, shape.feat_dim))
+    return {"hidden": _finish(np.stack(hidden), shape.dtype), "x": _finish(np.stack(xs), shape.dtype),
+            "w_q": _finish((wq * logit_gain).T, shape.dtype), "w_k": _finish(wk.T, shape.dtype)}
 
 
 def encoder_inputs(shape: EncoderShape, seed: int, logit_gain: float = 1.0,

@@ -481,3 +481,43 @@ def test_scores_from_hidden_gqa_and_queries():
             l = kv @ qv / np.sqrt(dh)
             e = np.exp(l - l.max()); want += e / e.sum()
     np.testing.assert_allclose(got[0], want / (Hq * Tq), rtol=1e-12)
+
+
+# ---- Eq. 1-2 written out from the encoder's hidden states ------------------------------------
+
+def test_encoder_scores_from_hidden_agree_with_projected_form():
+    from paper_2505_22654_amd import workloads as wl
+    shape = wl.EncoderShape(dtype=wl.BF16, batch=2, n_segments=2, grid_h=5, grid_w=4, has_cls=1,
+                            score_mode=0, heads=3, head_dim=8, feat_dim=24, win_rows=1,
+                            win_cols=1, keep_global=4, keep_local=0)
+    inp = wl.encoder_hidden_inputs(shape, 31)
+    x = inp["hidden"].astype(np.float64)
+    B, C, S, D = x.shape
+    q = (x @ inp["w_q"].astype(np.float64).T).reshape(B, C, S, 3, 8).transpose(0, 1, 3, 2, 4)
+    k = (x @ inp["w_k"].astype(np.float64).T).reshape(B, C, S, 3, 8).transpose(0, 1, 3, 2, 4)
+    for domain in (0, 1):
+        got = vo.encoder_scores_from_hidden(inp["hidden"], inp["w_q"], inp["w_k"], 3, 8, domain)
+        want = vo.encoder_scores(q.astype(np.float32), k.astype(np.float32), 1, 0, domain)
+        np.testing.assert_allclose(got, want, rtol=5e-6)
+    np.testing.assert_allclose(
+        vo.encoder_scores_from_hidden(inp["hidden"], inp["w_q"], inp["w_k"], 3, 8, 0).sum(axis=2),
+        1.0, rtol=1e-12)
+
+
+def test_encoder_scores_from_hidden_closed_form():
+    """One head, identity-like weights: the [CLS] row e_0 against patch rows a_j e_1 with a key
+    weight that reads hidden feature 1 into key feature 0 (a transposed weight would give a
+    uniform score instead)."""
+    N, D = 6, 4
+    a = np.log(np.arange(1, N + 1))
+    x = np.zeros((1, 1, N + 1, D))
+    x[0, 0, 0, 0] = 1.0
+    x[0, 0, 1:, 1] = a
+    wq = np.eye(D)
+    wk = np.zeros((D, D)); wk[0, 1] = 1.0
+    got = vo.encoder_scores_from_hidden(x, wq, wk, 1, D, 0, scale=1.0)
+    np.testing.assert_allclose(got[0, 0], np.arange(1, N + 1) / np.arange(1, N + 1).sum(), rtol=1e-12)
+    # all keys: the [CLS] key has logit 0 and adds exp(0) = 1 to the denominator
+    got = vo.encoder_scores_from_hidden(x, wq, wk, 1, D, 1, scale=1.0)
+    np.testing.assert_allclose(got[0, 0], np.arange(1, N + 1) / (np.arange(1, N + 1).sum() + 1.0),
+                               rtol=1e-12)
