@@ -246,6 +246,38 @@ int vscan_llm_prune_fused(const vscan_llm_desc *desc, void *hidden, const void *
                           void *stream);
 
 /* ---------------------------------------------------------------------------
+ * Stage 1 for a caller that does not hold the attention layer's queries and
+ * keys: the [CLS] scores of Eq. 1-2 computed as written, from the rows the
+ * layer sees and its projection weights (Sec. 4.1 "Global Scan": Q = X W_Q^h,
+ * K = X W_K^h, the [CLS] row of softmax(Q K^T * scale), mean over heads), then
+ * the same local scan, global scan, assignment and merge as
+ * vscan_encoder_reduce.  VSCAN_SCORE_CLS_ROW and bf16 only
+ * (VSCAN_ERR_UNSUPPORTED otherwise); projection biases are not part of the
+ * equations and not applied.
+ *
+ * desc          HOST; as for vscan_encoder_reduce; the hidden size of the layer
+ *               is desc->feat_dim
+ * hidden        DEVICE [B*C, S, feat_dim], S = 1 + grid_h*grid_w, the [CLS] row
+ *               first; read only
+ * w_q           DEVICE [H*dh, feat_dim]  (row n: weights of output feature n)
+ * w_k_t         DEVICE [feat_dim, H*dh]  (row c: what input feature c
+ *               contributes; the paper's W_K with the heads side by side)
+ * hidden_local, w_q_local, w_k_t_local
+ *               optional (all three or none): the same of the shallow layer
+ *               whose scores drive the local scan (Sec. 4.1 "Local Scan")
+ * x, kept_idx, merged, assign_out, scores_out, stream: as vscan_encoder_reduce
+ * workspace     vscan_encoder_fused_workspace_size bytes
+ * ------------------------------------------------------------------------- */
+int vscan_encoder_fused_workspace_size(const vscan_encoder_desc *desc, int with_local_triple,
+                                       size_t *bytes);
+int vscan_encoder_reduce_fused(const vscan_encoder_desc *desc, const void *hidden, const void *w_q,
+                               const void *w_k_t, const void *hidden_local,
+                               const void *w_q_local, const void *w_k_t_local, const void *x,
+                               int32_t *kept_idx, void *merged, int32_t *assign_out,
+                               float *scores_out, void *workspace, size_t workspace_bytes,
+                               void *stream);
+
+/* ---------------------------------------------------------------------------
  * Host-side budget arithmetic.  Pure functions of their arguments: no GPU, no
  * state; all pointers are HOST pointers.
  * ------------------------------------------------------------------------- */

@@ -24,7 +24,8 @@ VSCAN_KEYS_VISUAL_ONLY, VSCAN_KEYS_ALL = 0, 1
 EXPORTS = ("vscan_encoder_workspace_size", "vscan_encoder_reduce", "vscan_llm_workspace_size",
            "vscan_llm_prune", "vscan_profile_enable", "vscan_profile_read", "vscan_status_string",
            "vscan_version", "vscan_budget", "vscan_budget_solve_r1", "vscan_flops",
-           "vscan_llm_prune_ragged", "vscan_llm_fused_workspace_size", "vscan_llm_prune_fused")
+           "vscan_llm_prune_ragged", "vscan_llm_fused_workspace_size", "vscan_llm_prune_fused",
+           "vscan_encoder_fused_workspace_size", "vscan_encoder_reduce_fused")
 
 
 class EncoderDesc(ctypes.Structure):
@@ -91,6 +92,12 @@ def lib():
         L.vscan_llm_prune_fused.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, i32p, vp, f32p, vp,
                                             ctypes.c_size_t, vp]
         L.vscan_llm_prune_fused.restype = ctypes.c_int
+        L.vscan_encoder_fused_workspace_size.argtypes = [ctypes.POINTER(EncoderDesc), ctypes.c_int,
+                                                         ctypes.POINTER(ctypes.c_size_t)]
+        L.vscan_encoder_fused_workspace_size.restype = ctypes.c_int
+        L.vscan_encoder_reduce_fused.argtypes = [ctypes.POINTER(EncoderDesc), vp, vp, vp, vp, vp, vp,
+                                                 vp, i32p, vp, i32p, f32p, vp, ctypes.c_size_t, vp]
+        L.vscan_encoder_reduce_fused.restype = ctypes.c_int
         L.vscan_profile_enable.argtypes = [ctypes.c_int]
         L.vscan_profile_enable.restype = ctypes.c_int
         L.vscan_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int,
@@ -379,5 +386,55 @@ def llm_prune_fused(shape, hidden, w_q, w_k_t, want_scores: bool = False, worksp
     if rc != VSCAN_OK:
         raise VscanError(rc, "vscan_llm_prune_fused")
     out["hidden"] = hidden[:, :So] if shape.in_place else ho
+    out["workspace"] = workspace
+    return out
+
+
+def encoder_fused_workspace_size(desc: EncoderDesc, with_local_triple: bool = False) -> int:
+    n = ctypes.c_size_t(0)
+    rc = lib().vscan_encoder_fused_workspace_size(ctypes.byref(desc), int(with_local_triple),
+                                                  ctypes.byref(n))
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_encoder_fused_workspace_size")
+    return int(n.value)
+
+
+def encoder_reduce_fused(shape, hidden, w_q, w_k_t, x, local=None, want_assign: bool = False,
+                         want_scores: bool = False, workspace=None, out=None) -> Dict[str, object]:
+    """vscan_encoder_reduce_fused on CUDA bf16 tensors hidden [B,C,S,D] ([CLS] row first), w_q
+    [H*dh, D], w_k_t [D, H*dh], x [B,C*N,D]; `local` is an optional (hidden, w_q, w_k_t) triple
+    of the shallow layer."""
+    import torch
+    desc = encoder_desc(shape)
+    need = encoder_fused_workspace_size(desc, local is not None)
+    dev = hidden.device
+    B, T, D = shape.batch, shape.tokens_per_image, shape.feat_dim
+    hd = shape.heads * shape.head_dim
+    triples = [(hidden, w_q, w_k_t)] + ([tuple(local)] if local is not None else [])
+    for h, a, b in triples:
+        for t in (h, a, b):
+            assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16
+        assert tuple(h.shape) == (B, shape.n_segments, shape.rows, D)
+        assert tuple(a.shape) == (hd, D) and tuple(b.shape) == (D, hd)
+    assert x.is_cuda and x.is_contiguous() and tuple(x.shape) == (B, T, D)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = dict(out) if out else {}
+    if "kept_idx" not in out:
+        out["kept_idx"] = torch.empty((B, shape.keep), dtype=torch.int32, device=dev)
+    if "merged" not in out:
+        out["merged"] = torch.empty((B, shape.keep, D), dtype=x.dtype, device=dev)
+    if want_assign and "assign" not in out:
+        out["assign"] = torch.empty((B, T), dtype=torch.int32, device=dev)
+    if want_scores and "scores" not in out:
+        out["scores"] = torch.empty((B, T), dtype=torch.float32, device=dev)
+    loc = triples[1] if local is not None else (None, None, None)
+    rc = lib().vscan_encoder_reduce_fused(ctypes.byref(desc), _ptr(hidden), _ptr(w_q), _ptr(w_k_t),
+                                          _ptr(loc[0]), _ptr(loc[1]), _ptr(loc[2]), _ptr(x),
+                                          _ptr(out["kept_idx"]), _ptr(out["merged"]),
+                                          _ptr(out.get("assign")), _ptr(out.get("scores")),
+                                          _ptr(workspace), workspace.numel(), _stream_handle())
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_encoder_reduce_fused")
     out["workspace"] = workspace
     return out

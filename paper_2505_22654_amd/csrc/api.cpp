@@ -119,9 +119,42 @@ int plan_llm(const vscan_llm_desc *d, LlmPlan *p) {
     return VSCAN_OK;
 }
 
+// Scratch of the score chain that starts from hidden states and projection weights:
+// `seqs` sequences of S rows of `hidden` features, Tq query rows each, nk keys in the domain.
+struct FusedScratch {
+    int ks_q, ks_l;
+    size_t off_cq, off_qpl, off_qtpl, off_cl, end;
+};
+
+int plan_fused_scratch(int64_t seqs, int S, int hidden, int q_heads, int kv_heads, int head_dim,
+                       int n_query, int nk, size_t base, FusedScratch *f) {
+    // 32-bit row offsets inside the kernels
+    const int64_t lim = (int64_t)1 << 32;
+    const int64_t Dh = hidden, N = (int64_t)q_heads * head_dim, R = (int64_t)q_heads * n_query;
+    if (seqs * S * Dh * 2 >= lim || N * Dh * 2 >= lim || Dh * kv_heads * head_dim * 2 >= lim ||
+        seqs * n_query * N * 2 >= lim || seqs * R * Dh * 2 >= lim || seqs * R > (1 << 24) ||
+        R > 65535 || seqs > (1 << 24))
+        return VSCAN_ERR_UNSUPPORTED;
+    const int M = (int)(seqs * n_query);
+    f->ks_q = fused_ksplit((int)N, M, 1, hidden);
+    f->ks_l = fused_ksplit(nk, (int)R, (int)seqs, hidden);
+    size_t off = base;
+    f->off_cq = off;
+    off += align_up((size_t)f->ks_q * M * N * sizeof(float));
+    f->off_qpl = off;
+    off += align_up((size_t)3 * M * N * 2);
+    f->off_qtpl = off;
+    off += align_up((size_t)kFusedQtPlanes * seqs * R * Dh * 2);
+    f->off_cl = off;
+    off += align_up((size_t)f->ks_l * seqs * R * nk * sizeof(float));
+    f->end = off;
+    return VSCAN_OK;
+}
+
 struct FusedPlan {
-    int k0, nk, S_out, ks_q, ks_l, R;
-    size_t off_cq, off_qpl, off_qtpl, off_cl, off_part, bytes;
+    int k0, nk, S_out, R;
+    FusedScratch f;
+    size_t off_part, bytes;
 };
 
 int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
@@ -143,29 +176,33 @@ int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
     p->nk = d->softmax_domain == VSCAN_KEYS_ALL ? d->seq_len : d->vis_len;
     p->S_out = d->seq_len - d->vis_len + d->keep;
     p->R = d->q_heads * d->n_query;
-    // 32-bit row offsets inside the kernels
-    const int64_t lim = (int64_t)1 << 32;
-    const int64_t B = d->batch, Dh = d->hidden, N = (int64_t)d->q_heads * d->head_dim;
-    if (B * d->seq_len * Dh * 2 >= lim || N * Dh * 2 >= lim ||
-        Dh * d->kv_heads * d->head_dim * 2 >= lim || B * d->n_query * N * 2 >= lim ||
-        B * p->R * Dh * 2 >= lim || B * p->R > (1 << 24) || (int64_t)p->R > 65535)
-        return VSCAN_ERR_UNSUPPORTED;
     if (llm_select_lds_bytes(d->vis_len) > kLdsBudget) return VSCAN_ERR_UNSUPPORTED;
-    const int M = d->batch * d->n_query;
-    p->ks_q = fused_ksplit((int)N, M, 1, d->hidden);
-    p->ks_l = fused_ksplit(p->nk, p->R, d->batch, d->hidden);
-    size_t off = 0;
-    p->off_cq = off;
-    off += align_up((size_t)p->ks_q * M * N * sizeof(float));
-    p->off_qpl = off;
-    off += align_up((size_t)3 * M * N * 2);
-    p->off_qtpl = off;
-    off += align_up((size_t)kFusedQtPlanes * B * p->R * Dh * 2);
-    p->off_cl = off;
-    off += align_up((size_t)p->ks_l * B * p->R * p->nk * sizeof(float));
-    p->off_part = off;
-    off += align_up((size_t)B * d->vis_len * sizeof(float));
-    p->bytes = off ? off : kAlign;
+    const int rc = plan_fused_scratch(d->batch, d->seq_len, d->hidden, d->q_heads, d->kv_heads,
+                                      d->head_dim, d->n_query, p->nk, 0, &p->f);
+    if (rc != VSCAN_OK) return rc;
+    p->off_part = p->f.end;
+    p->bytes = p->off_part + align_up((size_t)d->batch * d->vis_len * sizeof(float));
+    return VSCAN_OK;
+}
+
+// Stage 1 scored from hidden states: the ordinary encoder plan, the scratch above behind it.
+struct EncoderFusedPlan {
+    EncoderPlan e;
+    FusedScratch f;
+    int k0, nk;
+    size_t bytes;
+};
+
+int plan_encoder_fused(const vscan_encoder_desc *d, int with_local, EncoderFusedPlan *p) {
+    const int rc = plan_encoder(d, with_local, &p->e);
+    if (rc != VSCAN_OK) return rc;
+    if (d->dtype != VSCAN_BF16 || d->score_mode != VSCAN_SCORE_CLS_ROW) return VSCAN_ERR_UNSUPPORTED;
+    p->k0 = d->softmax_domain == VSCAN_KEYS_ALL ? 0 : 1;
+    p->nk = d->softmax_domain == VSCAN_KEYS_ALL ? p->e.S : p->e.N;
+    const int rc2 = plan_fused_scratch(p->e.BC, p->e.S, d->feat_dim, d->heads, d->heads,
+                                       d->head_dim, 1, p->nk, p->e.bytes, &p->f);
+    if (rc2 != VSCAN_OK) return rc2;
+    p->bytes = p->f.end;
     return VSCAN_OK;
 }
 
@@ -211,6 +248,64 @@ struct ProfScope {
         }                                                 \
         if (e_ != hipSuccess) return VSCAN_ERR_HIP;       \
     } while (0)
+
+// The score chain: part[seq][token] = sum over the query rows of their softmax weights.
+int enqueue_fused_scores(FusedArgs &fa, const FusedScratch &f, unsigned char *ws, hipStream_t s) {
+    fa.c_q = reinterpret_cast<float *>(ws + f.off_cq);
+    fa.q_planes = reinterpret_cast<uint16_t *>(ws + f.off_qpl);
+    fa.qt_planes = reinterpret_cast<uint16_t *>(ws + f.off_qtpl);
+    fa.c_l = reinterpret_cast<float *>(ws + f.off_cl);
+    fa.ks_q = f.ks_q;
+    fa.ks_l = f.ks_l;
+    VSCAN_LAUNCH("fused_q", launch_fused_q(fa, s));
+    VSCAN_LAUNCH("fused_split_q", launch_fused_split_q(fa, s));
+    VSCAN_LAUNCH("fused_qt", launch_fused_qt(fa, s));
+    VSCAN_LAUNCH("fused_logits", launch_fused_logits(fa, s));
+    VSCAN_LAUNCH("fused_softmax", launch_fused_softmax(fa, s));
+    VSCAN_LAUNCH("fused_colsum", launch_fused_colsum(fa, s));
+    return VSCAN_OK;
+}
+
+// Selection, assignment and merge of stage 1 from per-head scores in the workspace.
+int enqueue_encoder_tail(const vscan_encoder_desc *d, const EncoderPlan &p, bool with_local,
+                         int score_heads, float norm, const void *x, int32_t *kept_idx,
+                         void *merged, int32_t *assign_out, float *scores_out, unsigned char *ws,
+                         hipStream_t s) {
+    EncSelectArgs se;
+    se.head_global = reinterpret_cast<const float *>(ws + p.off_head_global);
+    se.head_local = with_local ? reinterpret_cast<const float *>(ws + p.off_head_local) : nullptr;
+    se.B = d->batch;
+    se.C = d->n_segments;
+    se.H = score_heads;
+    se.gh = d->grid_h;
+    se.gw = d->grid_w;
+    se.wr = d->win_rows;
+    se.wc = d->win_cols;
+    se.kw = p.kw;
+    se.kg = p.kg;
+    se.norm = norm;
+    se.kept_idx = kept_idx;
+    se.drop_idx = reinterpret_cast<int32_t *>(ws + p.off_drop);
+    se.best = reinterpret_cast<uint64_t *>(ws + p.off_best);
+    se.scores_out = scores_out;
+    VSCAN_LAUNCH("encoder_select", launch_encoder_select(se, s));
+
+    MergeArgs ma;
+    ma.x = x;
+    ma.kept_idx = kept_idx;
+    ma.drop_idx = se.drop_idx;
+    ma.best = se.best;
+    ma.merged = merged;
+    ma.assign_out = assign_out;
+    ma.B = d->batch;
+    ma.T = p.T;
+    ma.D = d->feat_dim;
+    ma.K = p.K;
+    ma.is_bf16 = d->dtype == VSCAN_BF16;
+    if (p.U > 0) VSCAN_LAUNCH("sim_argmax", launch_sim_argmax(ma, s));
+    VSCAN_LAUNCH("merge", launch_merge(ma, s));
+    return VSCAN_OK;
+}
 
 }  // namespace
 
@@ -278,40 +373,70 @@ int vscan_encoder_reduce(const vscan_encoder_desc *d, const void *q, const void 
         }
     }
 
-    EncSelectArgs se;
-    se.head_global = reinterpret_cast<const float *>(ws + p.off_head_global);
-    se.head_local = with_local ? reinterpret_cast<const float *>(ws + p.off_head_local) : nullptr;
-    se.B = d->batch;
-    se.C = d->n_segments;
-    se.H = d->heads;
-    se.gh = d->grid_h;
-    se.gw = d->grid_w;
-    se.wr = d->win_rows;
-    se.wc = d->win_cols;
-    se.kw = p.kw;
-    se.kg = p.kg;
-    se.norm = mean ? 1.0f / ((float)d->heads * (float)p.N) : 1.0f / (float)d->heads;
-    se.kept_idx = kept_idx;
-    se.drop_idx = reinterpret_cast<int32_t *>(ws + p.off_drop);
-    se.best = reinterpret_cast<uint64_t *>(ws + p.off_best);
-    se.scores_out = scores_out;
-    VSCAN_LAUNCH("encoder_select", launch_encoder_select(se, s));
+    return enqueue_encoder_tail(d, p, with_local, d->heads,
+                                mean ? 1.0f / ((float)d->heads * (float)p.N) : 1.0f / (float)d->heads,
+                                x, kept_idx, merged, assign_out, scores_out, ws, s);
+}
 
-    MergeArgs ma;
-    ma.x = x;
-    ma.kept_idx = kept_idx;
-    ma.drop_idx = se.drop_idx;
-    ma.best = se.best;
-    ma.merged = merged;
-    ma.assign_out = assign_out;
-    ma.B = d->batch;
-    ma.T = p.T;
-    ma.D = d->feat_dim;
-    ma.K = p.K;
-    ma.is_bf16 = sa.is_bf16;
-    if (p.U > 0) VSCAN_LAUNCH("sim_argmax", launch_sim_argmax(ma, s));
-    VSCAN_LAUNCH("merge", launch_merge(ma, s));
+int vscan_encoder_fused_workspace_size(const vscan_encoder_desc *desc, int with_local_triple,
+                                       size_t *bytes) {
+    if (!bytes) return VSCAN_ERR_NULL;
+    EncoderFusedPlan p;
+    const int rc = plan_encoder_fused(desc, with_local_triple != 0, &p);
+    if (rc != VSCAN_OK) return rc;
+    *bytes = p.bytes;
     return VSCAN_OK;
+}
+
+int vscan_encoder_reduce_fused(const vscan_encoder_desc *d, const void *hidden, const void *w_q,
+                               const void *w_k_t, const void *hidden_local,
+                               const void *w_q_local, const void *w_k_t_local, const void *x,
+                               int32_t *kept_idx, void *merged, int32_t *assign_out,
+                               float *scores_out, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+    const int n_local = (hidden_local != nullptr) + (w_q_local != nullptr) + (w_k_t_local != nullptr);
+    if (n_local != 0 && n_local != 3) return VSCAN_ERR_NULL;
+    const bool with_local = n_local == 3;
+    EncoderFusedPlan p;
+    const int rc = plan_encoder_fused(d, with_local, &p);
+    if (rc != VSCAN_OK) return rc;
+    if (!hidden || !w_q || !w_k_t || !x || !kept_idx || !merged) return VSCAN_ERR_NULL;
+    if (!aligned16(hidden) || !aligned16(w_q) || !aligned16(w_k_t) || !aligned16(hidden_local) ||
+        !aligned16(w_q_local) || !aligned16(w_k_t_local) || !aligned16(x) || !aligned16(merged))
+        return VSCAN_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(kept_idx) & 3u) || (reinterpret_cast<uintptr_t>(assign_out) & 3u) ||
+        (reinterpret_cast<uintptr_t>(scores_out) & 3u))
+        return VSCAN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < p.bytes) return VSCAN_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return VSCAN_ERR_ALIGN;
+    if (d->batch == 0) return VSCAN_OK;
+
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+    for (int pass = 0; pass < (with_local ? 2 : 1); ++pass) {
+        FusedArgs fa;
+        fa.hidden = pass ? hidden_local : hidden;
+        fa.w_q = pass ? w_q_local : w_q;
+        fa.w_k_t = pass ? w_k_t_local : w_k_t;
+        fa.part = reinterpret_cast<float *>(ws + (pass ? p.e.off_head_local : p.e.off_head_global));
+        fa.B = p.e.BC;
+        fa.S = p.e.S;
+        fa.Dh = d->feat_dim;
+        fa.Hq = fa.Hkv = d->heads;
+        fa.dh = d->head_dim;
+        fa.Tq = 1;
+        fa.q_row0 = 0;  // the [CLS] row
+        fa.vis_start = 1;
+        fa.V = p.e.N;
+        fa.k0 = p.k0;
+        fa.nk = p.nk;
+        fa.scale = resolve_scale(d->scale, d->head_dim);
+        const int rc2 = enqueue_fused_scores(fa, p.f, ws, s);
+        if (rc2 != VSCAN_OK) return rc2;
+    }
+    // the chain leaves one row of head sums per segment: [BC, 1, N]
+    return enqueue_encoder_tail(d, p.e, with_local, 1, 1.0f / (float)d->heads, x, kept_idx, merged,
+                                assign_out, scores_out, ws, s);
 }
 
 int vscan_llm_workspace_size(const vscan_llm_desc *desc, size_t *bytes) {
@@ -478,10 +603,6 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     fa.hidden = hidden;
     fa.w_q = w_q;
     fa.w_k_t = w_k_t;
-    fa.c_q = reinterpret_cast<float *>(ws + p.off_cq);
-    fa.q_planes = reinterpret_cast<uint16_t *>(ws + p.off_qpl);
-    fa.qt_planes = reinterpret_cast<uint16_t *>(ws + p.off_qtpl);
-    fa.c_l = reinterpret_cast<float *>(ws + p.off_cl);
     fa.part = reinterpret_cast<float *>(ws + p.off_part);
     fa.B = d->batch;
     fa.S = d->seq_len;
@@ -490,19 +611,14 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     fa.Hkv = d->kv_heads;
     fa.dh = d->head_dim;
     fa.Tq = d->n_query;
+    fa.q_row0 = d->seq_len - d->n_query;  // the last positions
     fa.vis_start = d->vis_start;
     fa.V = d->vis_len;
     fa.k0 = p.k0;
     fa.nk = p.nk;
-    fa.ks_q = p.ks_q;
-    fa.ks_l = p.ks_l;
     fa.scale = resolve_scale(d->scale, d->head_dim);
-    VSCAN_LAUNCH("fused_q", launch_fused_q(fa, s));
-    VSCAN_LAUNCH("fused_split_q", launch_fused_split_q(fa, s));
-    VSCAN_LAUNCH("fused_qt", launch_fused_qt(fa, s));
-    VSCAN_LAUNCH("fused_logits", launch_fused_logits(fa, s));
-    VSCAN_LAUNCH("fused_softmax", launch_fused_softmax(fa, s));
-    VSCAN_LAUNCH("fused_colsum", launch_fused_colsum(fa, s));
+    const int rc2 = enqueue_fused_scores(fa, p.f, ws, s);
+    if (rc2 != VSCAN_OK) return rc2;
 
     LlmSelectArgs se;
     se.part = fa.part;

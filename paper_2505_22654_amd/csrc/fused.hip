@@ -19,7 +19,7 @@
 //
 // Steps (every contraction is C[p][s] = sum_k P[p][k] * S[s][k], both operands with the
 // contraction axis contiguous; S is the large, streamed operand):
-//   1. q   [B*Tq, Hq*dh]        P = last Tq hidden rows of every sequence, S = W_Q rows
+//   1. q   [B*Tq, Hq*dh]        P = the Tq query rows of every sequence,   S = W_Q rows
 //   2. qt  [Hkv][B*g*Tq, Dh]    P = q planes of the group's heads,         S = W_K^T rows
 //      (stored as bf16 planes straight from the accumulators)
 //   3. l   [B][Hq*Tq, nk]       P = qt planes,                             S = hidden rows
@@ -58,15 +58,16 @@ __device__ __forceinline__ void emit_partial(const GemmDims &d, int ks, int z, i
 
 struct ProbQ {
     static constexpr int PL = 1;
+    static constexpr bool kStreamS = false;
     GemmDims d;
     const char *hidden, *w_q;
-    int Tq, S, row_bytes;  // row_bytes = Dh * 2
+    int Tq, S, q_row0, row_bytes;  // row_bytes = Dh * 2
     __device__ const char *s_base(int) const { return w_q; }
     __device__ uint32_t s_off(int n) const { return (uint32_t)n * (uint32_t)row_bytes; }
     __device__ const char *p_base(int, int) const { return hidden; }
     __device__ uint32_t p_off(int m) const {
         const int b = m / Tq, t = m - b * Tq;
-        return (uint32_t)(b * S + S - Tq + t) * (uint32_t)row_bytes;
+        return (uint32_t)(b * S + q_row0 + t) * (uint32_t)row_bytes;
     }
     __device__ void emit(int ks, int z, int p, int s_row, float v) const {
         emit_partial(d, ks, z, p, s_row, v);
@@ -75,6 +76,7 @@ struct ProbQ {
 
 struct ProbQt {
     static constexpr int PL = 3;
+    static constexpr bool kStreamS = false;
     GemmDims d;
     const char *q_planes, *w_k_t;
     int Tq, group, dh, Hq, Hkv;
@@ -103,9 +105,10 @@ struct ProbQt {
     }
 };
 
-template <int PLANES>
+template <int PLANES, bool STREAM>
 struct ProbLogit {
     static constexpr int PL = PLANES;
+    static constexpr bool kStreamS = STREAM;
     GemmDims d;
     const char *hidden, *qt_planes;
     int Tq, group, S, k0, row_bytes, Mg;  // Mg = B*group*Tq rows of qt per kv head
@@ -181,7 +184,9 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
     auto fetch = [&](int c) {
         const uint32_t col = (uint32_t)min(c * kChunkBytes + piece * 16, d.k_bytes - 16);
 #pragma unroll
-        for (int i = 0; i < NS; ++i) rs[i] = load16(sb, (int64_t)s_off[i] + col);
+        for (int i = 0; i < NS; ++i)
+            rs[i] = Prob::kStreamS ? load16_stream(sb, (int64_t)s_off[i] + col)
+                                   : load16(sb, (int64_t)s_off[i] + col);
 #pragma unroll
         for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
@@ -409,6 +414,7 @@ hipError_t launch_fused_q(const FusedArgs &a, hipStream_t s) {
     pr.w_q = reinterpret_cast<const char *>(a.w_q);
     pr.Tq = a.Tq;
     pr.S = a.S;
+    pr.q_row0 = a.q_row0;
     pr.row_bytes = a.Dh * 2;
     return launch_gemm(pr, 1, s);
 }
@@ -437,9 +443,16 @@ hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s) {
     return launch_gemm(pr, a.Hkv, s);
 }
 
-hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s) {
+// Hidden states beyond this size cannot stay in the last-level cache between this pass and
+// the compaction that follows; they are then fetched with the streaming hint, which a cold
+// one-pass read is faster with.  Smaller ones keep plain loads, so the compaction finds them
+// cached.
+constexpr int64_t kStreamHiddenBytes = (int64_t)128 << 20;
+
+template <bool STREAM>
+hipError_t launch_logits(const FusedArgs &a, hipStream_t s) {
     const int group = a.Hq / a.Hkv;
-    ProbLogit<kFusedQtPlanes> pr;
+    ProbLogit<kFusedQtPlanes, STREAM> pr;
     pr.d = dims(a.nk, a.Hq * a.Tq, a.Dh, a.ks_l, a.c_l);
     pr.hidden = reinterpret_cast<const char *>(a.hidden);
     pr.qt_planes = reinterpret_cast<const char *>(a.qt_planes);
@@ -451,6 +464,11 @@ hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s) {
     pr.Mg = a.B * group * a.Tq;
     pr.plane_bytes = (int64_t)a.Hkv * pr.Mg * a.Dh * 2;
     return launch_gemm(pr, a.B, s);
+}
+
+hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s) {
+    return (int64_t)a.B * a.S * a.Dh * 2 > kStreamHiddenBytes ? launch_logits<true>(a, s)
+                                                             : launch_logits<false>(a, s);
 }
 
 hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {

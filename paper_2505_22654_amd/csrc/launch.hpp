@@ -97,9 +97,9 @@ struct CompactArgs {
 hipError_t launch_compact(const CompactArgs &a, hipStream_t s);
 
 // stage 2 scored from hidden states and projection weights (Eq. 5 as written), bf16 only
-constexpr int kFusedQtPlanes = 2;  // bf16 planes carrying the hidden-space query
+constexpr int kFusedQtPlanes = 3;  // bf16 planes carrying the hidden-space query (all 24 bits)
 struct FusedArgs {
-    const void *hidden;        // [B, S, Dh]
+    const void *hidden;        // [B, S, Dh]; visual tokens are rows vis_start .. vis_start+V
     const void *w_q;           // [Hq*dh, Dh]   rows = output features
     const void *w_k_t;         // [Dh, Hkv*dh]  rows = input features
     float *c_q;                // [ks_q][B*Tq][Hq*dh] partial sums of q
@@ -109,6 +109,7 @@ struct FusedArgs {
                                // first slot becomes the softmax weights
     float *part;               // [B][V] sums over the query rows
     int B, S, Dh, Hq, Hkv, dh, Tq, vis_start, V, k0, nk;
+    int q_row0;                // first of the Tq query rows of a sequence
     int ks_q, ks_l;            // shares of the contraction axis (fused_ksplit)
     float scale;
 };

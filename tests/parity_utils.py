@@ -280,3 +280,20 @@ def check_fused(shape, ref, out, what=""):
     assert got.shape == ref["hidden"].shape, f"{what}: hidden shape"
     assert np.array_equal(got, ref["hidden"]), f"{what}: compacted hidden differs"
     return report
+
+
+def screened_encoder_fused_case(shape, seed, logit_gain=1.0, with_local=False, max_tries=16):
+    """Hidden rows, weights and oracle result for the first seed whose boundaries clear MARGIN."""
+    for attempt in range(max_tries):
+        inp = wl.encoder_hidden_inputs(shape, seed + attempt, logit_gain)
+        loc = (wl.encoder_hidden_inputs(shape, seed + attempt, logit_gain, stream=1)
+               if with_local else None)
+        ref = vo.encoder_reduce_fused(shape, inp["hidden"], inp["w_q"], inp["w_k"], inp["x"],
+                                      *((loc["hidden"], loc["w_q"], loc["w_k"]) if loc else ()))
+        N = shape.n_tokens
+        sg = ref["scores"].reshape(shape.batch, shape.n_segments, N)
+        sl = ref["scores_local"].reshape(shape.batch, shape.n_segments, N)
+        gap = encoder_boundary_gap(shape, sl, sg)
+        if gap > MARGIN:
+            return inp, loc, ref, {"seed": seed + attempt, "attempts": attempt + 1, "gap": gap}
+    raise AssertionError(f"no seed in {max_tries} tries clears the boundary margin")

@@ -117,3 +117,69 @@ def test_fused_config2_shape():
     print("case", info, flush=True)
     out = _run(shape, inp)
     print("cfg2 stage-2 shape", pu.check_fused(shape, ref, out, "cfg2 fused"))
+
+
+# ---- stage 1 scored from the layer's input rows and projection weights -------------------------
+
+def _run_encoder(shape, inp, loc=None):
+    import torch
+    dev = lambda a: pu.to_device(a, wl.BF16)
+    triple = lambda d: (dev(d["hidden"]), dev(d["w_q"]), dev(np.ascontiguousarray(d["w_k"].T)))
+    h, wq, wkt = triple(inp)
+    out = vb.encoder_reduce_fused(shape, h, wq, wkt, dev(inp["x"]),
+                                  local=None if loc is None else triple(loc), want_assign=True,
+                                  want_scores=True)
+    torch.cuda.synchronize()
+    return out
+
+
+def _enc(**kw):
+    base = dict(dtype=wl.BF16, batch=2, n_segments=1, grid_h=12, grid_w=12, has_cls=1, score_mode=0,
+                heads=4, head_dim=32, feat_dim=128, win_rows=2, win_cols=2, keep_global=10,
+                keep_local=8)
+    base.update(kw)
+    return wl.EncoderShape(**base)
+
+
+FUSED_ENCODER = {
+    "ragged": _enc(batch=3, n_segments=2, grid_h=13, grid_w=11, heads=3, head_dim=40, feat_dim=200,
+                   win_rows=3, win_cols=2, keep_global=17, keep_local=13),
+    "all-keys": _enc(softmax_domain=1, keep_global=30, keep_local=16),
+    "global-only": _enc(keep_local=0, keep_global=21),
+    "many-segments": _enc(batch=2, n_segments=5, grid_h=8, grid_w=8, keep_global=6, keep_local=4),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FUSED_ENCODER))
+def test_fused_encoder_small(name):
+    shape = FUSED_ENCODER[name]
+    inp, _, ref, info = pu.screened_encoder_fused_case(shape, 9700 + sorted(FUSED_ENCODER).index(name) * 17)
+    print("case", name, info, flush=True)
+    out = _run_encoder(shape, inp)
+    print(name, pu.check_encoder(shape, inp, ref, out, name))
+
+
+def test_fused_encoder_local_scan_from_shallow_layer():
+    shape = _enc(batch=2, grid_h=12, grid_w=12, keep_global=14, keep_local=12)
+    inp, loc, ref, info = pu.screened_encoder_fused_case(shape, 9800, with_local=True)
+    print("case", info, flush=True)
+    assert not np.array_equal(ref["scores"], ref["scores_local"])
+    out = _run_encoder(shape, inp, loc)
+    print(pu.check_encoder(shape, inp, ref, out, "fused encoder, shallow-layer local scan"))
+
+
+def test_fused_encoder_rejects_mean_mode_and_fp32():
+    for shape in (_enc(has_cls=0, score_mode=1), _enc(dtype=wl.F32)):
+        with pytest.raises(vb.VscanError) as e:
+            vb.encoder_fused_workspace_size(vb.encoder_desc(shape))
+        assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
+
+
+def test_fused_encoder_config2_shape():
+    """The stage-1 shape of the headline configuration (16 images, 576 patches + [CLS], 16 heads
+    of 64, 1024 features), every image checked against the oracle."""
+    shape = wl.config(2).encoder
+    inp, _, ref, info = pu.screened_encoder_fused_case(shape, 9850, max_tries=6)
+    print("case", info, flush=True)
+    out = _run_encoder(shape, inp)
+    print("cfg2 stage-1 shape", pu.check_encoder(shape, inp, ref, out, "cfg2 fused encoder"))
