@@ -47,7 +47,26 @@ def sweep_points(index: int):
     return [wl.config(index)]
 
 
-def algorithmic_work(w: wl.Workload, stage2: str = "qk"):
+def _score_chain_work(out, seqs, Dh, Hq, Hkv, dh, Tq, V):
+    """Adds the kernels of the score chain that starts from hidden states: each operand read
+    once, each result written once; the logit contraction counts as matrix-core work once its
+    flops per byte exceed the chip's ridge (2.5 PFLOP/s over 8 TB/s)."""
+    R, nq, nkv = Hq * Tq, Hq * dh, Hkv * dh
+    flops, byts = 2.0 * seqs * V * Dh * R, seqs * V * (Dh * 2 + R * 4) + seqs * R * Dh * 6
+    add = {
+        "fused_q": ("hbm", nq * Dh * 2 + seqs * Tq * (Dh * 2 + nq * 4)),
+        "fused_split_q": ("hbm", seqs * Tq * nq * (4 + 6)),
+        "fused_qt": ("hbm", nkv * Dh * 2 + seqs * Tq * nq * 6 + seqs * R * Dh * 6),
+        "fused_logits": ("mfma", flops) if flops / byts > 312 else ("hbm", byts),
+        "fused_softmax": ("hbm", seqs * R * V * 8),
+        "fused_colsum": ("hbm", seqs * R * V * 4 + seqs * V * 4),
+    }
+    for name, (bound, amount) in add.items():
+        b0, a0 = out.get(name, (bound, 0.0))
+        out[name] = (b0, a0 + amount)
+
+
+def algorithmic_work(w: wl.Workload, inputs: str = "qk"):
     """Per-kernel algorithmic work of ONE call pair on this workload:
     {kernel: (bound, amount)} with bytes for "hbm" and flops for "mfma"."""
     out = {}
@@ -57,7 +76,9 @@ def algorithmic_work(w: wl.Workload, stage2: str = "qk"):
         B, C, N, S, H, dh, D = e.batch, e.n_segments, e.n_tokens, e.rows, e.heads, e.head_dim, e.feat_dim
         K, T = e.keep, e.tokens_per_image
         U = T - K
-        if e.score_mode == 0:
+        if inputs == "hidden":
+            _score_chain_work(out, B * C, D, H, H, dh, 1, N)
+        elif e.score_mode == 0:
             out["score_cls"] = ("hbm", B * C * H * S * dh * es)
         else:
             out["score_mean_lse"] = ("mfma", 2.0 * B * C * H * N * N * dh)
@@ -71,22 +92,12 @@ def algorithmic_work(w: wl.Workload, stage2: str = "qk"):
         row = (l.hidden + 2 * l.kv_heads * l.head_dim) * es
         out["llm_select"] = ("hbm", l.batch * l.vis_len * 4 + l.batch * l.keep * 4)
         moved = (l.keep + l.text) if l.in_place else l.seq_out
-        if stage2 == "qk":
+        if inputs == "qk":
             out["llm_score"] = ("hbm", l.batch * l.kv_heads * l.vis_len * l.head_dim * es)
             out["compact"] = ("hbm", l.batch * moved * row * 2)
         else:
-            # scored from hidden states and weights: each operand read once, each result
-            # written once; the logit contraction counts as matrix-core work once its flops
-            # per byte exceed the chip's ridge (2.5 PFLOP/s over 8 TB/s)
-            B, Dh, R, V = l.batch, l.hidden, l.q_heads * l.n_query, l.vis_len
-            nq, nkv = l.q_heads * l.head_dim, l.kv_heads * l.head_dim
-            out["fused_q"] = ("hbm", nq * Dh * 2 + B * l.n_query * (Dh * 2 + nq * 4))
-            out["fused_split_q"] = ("hbm", B * l.n_query * nq * (4 + 6))
-            out["fused_qt"] = ("hbm", nkv * Dh * 2 + B * l.n_query * nq * 6 + B * R * Dh * 4)
-            flops, byts = 2.0 * B * V * Dh * R, B * V * (Dh * 2 + R * 4) + B * R * Dh * 4
-            out["fused_logits"] = ("mfma", flops) if flops / byts > 312 else ("hbm", byts)
-            out["fused_softmax"] = ("hbm", B * R * V * 8)
-            out["fused_colsum"] = ("hbm", B * R * V * 4 + B * V * 4)
+            _score_chain_work(out, l.batch, l.hidden, l.q_heads, l.kv_heads, l.head_dim,
+                              l.n_query, l.vis_len)
             out["compact"] = ("hbm", l.batch * moved * l.hidden * es * 2)
     return out
 
@@ -103,15 +114,24 @@ def tokens_reduced(w: wl.Workload) -> int:
 class DeviceCase:
     """Device-resident inputs, outputs and workspaces of one sweep point."""
 
-    def __init__(self, w: wl.Workload, host, ring: int, stage2: str = "qk"):
+    def __init__(self, w: wl.Workload, host, ring: int, inputs: str = "qk"):
         import torch
         from paper_2505_22654_amd import binding as vb
-        self.w, self.vb, self.torch, self.stage2 = w, vb, torch, stage2
+        self.w, self.vb, self.torch, self.inputs = w, vb, torch, inputs
         self.enc_in = self.enc_out = self.enc_ws = None
         if w.encoder is not None:
             e = w.encoder
-            self.enc_in = {n: _to_device(host["enc"][n], e.dtype) for n in ("q", "k", "x")}
-            need = vb.encoder_workspace_size(vb.encoder_desc(e))
+            if inputs == "hidden":
+                import numpy as np
+                hh = host["enc_hidden"]
+                self.enc_in = {"hidden": _to_device(hh["hidden"], e.dtype),
+                               "w_q": _to_device(hh["w_q"], e.dtype),
+                               "w_k_t": _to_device(np.ascontiguousarray(hh["w_k"].T), e.dtype),
+                               "x": _to_device(hh["x"], e.dtype)}
+                need = vb.encoder_fused_workspace_size(vb.encoder_desc(e))
+            else:
+                self.enc_in = {n: _to_device(host["enc"][n], e.dtype) for n in ("q", "k", "x")}
+                need = vb.encoder_workspace_size(vb.encoder_desc(e))
             self.enc_ws = torch.empty(need, dtype=torch.uint8, device="cuda")
             self.enc_out = {
                 "kept_idx": torch.empty((e.batch, e.keep), dtype=torch.int32, device="cuda"),
@@ -125,7 +145,7 @@ class DeviceCase:
             self.llm_in = [base] + [{n: (t if n == "q" else t.clone()) for n, t in base.items()}
                                     for _ in range(sets - 1)]
             need = vb.llm_workspace_size(vb.llm_desc(l))
-            if stage2 == "hidden":
+            if inputs == "hidden":
                 import numpy as np
                 need = vb.llm_fused_workspace_size(vb.llm_desc(l))
                 self.w_q = _to_device(host["weights"]["w_q"], l.dtype)
@@ -150,14 +170,18 @@ class DeviceCase:
                     s[n].copy_(t)
 
     def run_encoder(self):
-        if self.enc_in is not None:
+        if self.enc_in is not None and self.inputs == "hidden":
+            self.vb.encoder_reduce_fused(self.w.encoder, self.enc_in["hidden"], self.enc_in["w_q"],
+                                         self.enc_in["w_k_t"], self.enc_in["x"],
+                                         workspace=self.enc_ws, out=self.enc_out)
+        elif self.enc_in is not None:
             self.vb.encoder_reduce(self.w.encoder, self.enc_in["q"], self.enc_in["k"],
                                    self.enc_in["x"], workspace=self.enc_ws, out=self.enc_out)
 
     def run_llm(self, i: int):
         if self.llm_in:
             s = self.llm_in[i % len(self.llm_in)]
-            if self.stage2 == "hidden":
+            if self.inputs == "hidden":
                 self.vb.llm_prune_fused(self.w.llm, s["hidden"], self.w_q, self.w_k_t,
                                         workspace=self.llm_ws, out=self.llm_out)
                 return
@@ -177,22 +201,27 @@ def _to_device(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-def host_inputs(points, stage2: str = "qk"):
+def host_inputs(points, inputs: str = "qk"):
     """Seeded inputs per sweep point; tensors that do not depend on the budget are shared."""
     cache, hosts = {}, []
     for w in points:
         h = {}
         if w.encoder is not None:
             key = ("enc", dataclasses.replace(w.encoder, keep_global=0, keep_local=0))
-            if key not in cache:
-                cache[key] = wl.encoder_inputs(w.encoder, w.seed)
-            h["enc"] = cache[key]
+            if inputs == "hidden":
+                if ("hid",) + key not in cache:
+                    cache[("hid",) + key] = wl.encoder_hidden_inputs(w.encoder, w.seed)
+                h["enc_hidden"] = cache[("hid",) + key]
+            else:
+                if key not in cache:
+                    cache[key] = wl.encoder_inputs(w.encoder, w.seed)
+                h["enc"] = cache[key]
         if w.llm is not None:
             key = ("llm", dataclasses.replace(w.llm, keep=0))
             if key not in cache:
                 cache[key] = wl.llm_inputs(w.llm, w.seed)
             h["llm"] = cache[key]
-            if stage2 == "hidden":
+            if inputs == "hidden":
                 if ("weights", key) not in cache:
                     cache[("weights", key)] = wl.llm_weights(w.llm, w.seed)
                 h["weights"] = cache[("weights", key)]
@@ -200,15 +229,18 @@ def host_inputs(points, stage2: str = "qk"):
     return hosts
 
 
-def cpu_baseline(points, hosts, budget_s=12.0, stage2: str = "qk"):
+def cpu_baseline(points, hosts, budget_s=12.0, inputs: str = "qk"):
     """The CPU oracle on this host's cores over whole steps of the same inputs."""
     from oracle import vscan_oracle as vo
 
     def one_step():
         for w, h in zip(points, hosts):
-            if w.encoder is not None:
+            if w.encoder is not None and inputs == "hidden":
+                hh = h["enc_hidden"]
+                vo.encoder_reduce_fused(w.encoder, hh["hidden"], hh["w_q"], hh["w_k"], hh["x"])
+            elif w.encoder is not None:
                 vo.encoder_reduce(w.encoder, h["enc"]["q"], h["enc"]["k"], h["enc"]["x"])
-            if w.llm is not None and stage2 == "hidden":
+            if w.llm is not None and inputs == "hidden":
                 vo.llm_prune_fused(w.llm, h["llm"]["hidden"], h["weights"]["w_q"],
                                    h["weights"]["w_k"])
             elif w.llm is not None:
@@ -262,9 +294,10 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
                     help="also run N plain device copies of 256 MiB (a kernel of known traffic "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--stage2", default="qk", choices=["qk", "hidden"],
-                    help="qk: vscan_llm_prune on the layer's Q and K (the default step); "
-                         "hidden: vscan_llm_prune_fused on hidden states and projection weights")
+    ap.add_argument("--inputs", default="qk", choices=["qk", "hidden"],
+                    help="qk: both stages score from the layers' Q and K (the default step); "
+                         "hidden: vscan_encoder_reduce_fused + vscan_llm_prune_fused, which score "
+                         "from hidden states and projection weights ([CLS] encoders only)")
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="2: issue the encoder calls and the LLM calls of a step on two streams "
                          "(they are independent in this benchmark); default 1 = strictly serial")
@@ -289,13 +322,17 @@ def main():
 
     index = int(args.workload[3:])
     points = sweep_points(index)
-    hosts = host_inputs(points, args.stage2)
+    if args.inputs == "hidden" and any(w.encoder is not None and w.encoder.score_mode != 0
+                                       for w in points):
+        sys.exit("bench.py: --inputs hidden needs a [CLS] encoder (mean-attention scoring has one "
+                 "query per token and is served by the Q/K form only)")
+    hosts = host_inputs(points, args.inputs)
     in_place = any(w.llm is not None and w.llm.in_place for w in points)
     steps, warmup = args.steps, args.warmup
     if index in (4, 5):
         steps, warmup = min(steps, 20), min(warmup, 3)
     ring = steps if in_place else 1
-    cases = [DeviceCase(w, h, ring, args.stage2) for w, h in zip(points, hosts)]
+    cases = [DeviceCase(w, h, ring, args.inputs) for w, h in zip(points, hosts)]
 
     side = torch.cuda.Stream() if args.streams == 2 else None
 
@@ -340,7 +377,7 @@ def main():
 
     work = {}
     for w in points:
-        for name, (bound, amount) in algorithmic_work(w, args.stage2).items():
+        for name, (bound, amount) in algorithmic_work(w, args.inputs).items():
             b, a = work.get(name, (bound, 0.0))
             work[name] = (bound, a + amount)
     dtype = (points[0].encoder or points[0].llm).dtype
@@ -378,14 +415,14 @@ def main():
         "config": {"workload": args.workload + ": " + ", ".join(w.name for w in points),
                    "streams": args.streams,
                    "tokens_reduced_per_step": reduced,
-                   "step": "encoder_reduce + " + ("llm_prune" if args.stage2 == "qk" else
-                                                  "llm_prune_fused")
+                   "step": ("encoder_reduce + llm_prune" if args.inputs == "qk" else
+                            "encoder_reduce_fused + llm_prune_fused")
                            + " for every keep budget of the sweep"},
         "roofline": roof,
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(points, hosts, stage2=args.stage2)
+        result["cpu_baseline"] = cpu_baseline(points, hosts, inputs=args.inputs)
     print(json.dumps(result))
 
 

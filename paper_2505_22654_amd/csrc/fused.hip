@@ -33,8 +33,6 @@
 namespace vscan {
 namespace {
 
-constexpr int kChunkBytes = 128;              // contraction bytes staged per step (64 bf16)
-constexpr int kRowPitch = kChunkBytes + 16;   // LDS row pitch: 36 words, conflict-free b128 reads
 constexpr int kTargetWorkgroups = 512;        // two per compute unit before the axis is split
 
 struct GemmDims {
@@ -136,12 +134,13 @@ struct ProbLogit {
 // lanes per row) while the matrix cores work on the current one.  Row indices past the
 // operand's end are clamped (the rows are computed and not stored); chunk pieces past the
 // contraction length are fetched from a clamped offset and zeroed on their way into LDS.
-template <class Prob, int WS, int WP, int FS, int FP>
+template <class Prob, int WS, int WP, int FS, int FP, int CH>
 __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
+    constexpr int kChunkBytes = CH, kRowPitch = CH + 16, PIECES = CH / 16;
     constexpr int PL = Prob::PL;
     constexpr int THREADS = 64 * WS * WP;
     constexpr int TS = 32 * FS * WS, TP = 32 * FP * WP;
-    constexpr int ROWS_PER_PASS = THREADS / 8;           // rows one staging pass covers
+    constexpr int ROWS_PER_PASS = THREADS / PIECES;      // rows one staging pass covers
     constexpr int NS = TS / ROWS_PER_PASS, NP = TP / ROWS_PER_PASS;
     static_assert(TS % ROWS_PER_PASS == 0 && TP % ROWS_PER_PASS == 0, "staging covers whole tiles");
     __shared__ __attribute__((aligned(16))) unsigned char lds_s[TS * kRowPitch];
@@ -159,7 +158,7 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
     const int cps = (nchunks + d.ksplit - 1) / d.ksplit;
     const int c_begin = ks * cps, c_end = min(nchunks, c_begin + cps);
 
-    const int piece = tid & 7, srow = tid >> 3;
+    const int piece = tid % PIECES, srow = tid / PIECES;
     const char *sb = pr.s_base(z);
     const char *pb[PL];
 #pragma unroll
@@ -193,8 +192,19 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
             for (int i = 0; i < NP; ++i) rp[pl * NP + i] = load16(pb[pl], (int64_t)p_off[i] + col);
     };
 
-    if (c_begin < c_end) fetch(c_begin);
-    for (int c = c_begin; c < c_end; ++c) {
+    // Workgroups walk their share of the contraction axis from staggered starting points (and
+    // wrap around), so that at any moment the chip reads many different column ranges of the
+    // row-strided operand rather than one (measured: a quarter faster on a cold pass over
+    // 0.7 GB of hidden states).  The order depends on the grid position only.
+    const int span = c_end - c_begin;
+    // With many plane rows the workgroups of one batch entry keep a common order: they share
+    // the plane operand's current chunk through L2.
+    const unsigned start = (unsigned)z * 3u + (TP <= 64 ? (unsigned)s_tile * 5u : 0u);
+    const int rot = span > 0 ? (int)(start % (unsigned)span) : 0;
+    auto chunk_at = [&](int i) { const int r = i + rot; return c_begin + (r >= span ? r - span : r); };
+    if (span > 0) fetch(chunk_at(0));
+    for (int i = 0; i < span; ++i) {
+        const int c = chunk_at(i);
         const bool valid = c * kChunkBytes + piece * 16 < d.k_bytes;
 #pragma unroll
         for (int i = 0; i < NS; ++i)
@@ -207,7 +217,7 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
                 *reinterpret_cast<uint4 *>(lds_p + (pl * TP + srow + ROWS_PER_PASS * i) * kRowPitch +
                                            piece * 16) = valid ? rp[pl * NP + i] : zero16();
         __syncthreads();
-        fetch(min(c + 1, c_end - 1));  // unconditional; the last round re-reads its own chunk
+        fetch(chunk_at(min(i + 1, span - 1)));  // unconditional; the last round re-reads its chunk
 #pragma unroll
         for (int sub = 0; sub < kChunkBytes / 32; ++sub) {
             const int colb = sub * 32 + 16 * (lane >> 5);
@@ -245,15 +255,19 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
     }
 }
 
-// Tile shapes by the number of plane-operand rows: <= 32, <= 64, <= 128, more.
+// Tile shapes by the number of plane-operand rows: <= 32, <= 64, <= 128, more.  `ch` is the
+// number of contraction bytes staged per step: the LDS row pitch is ch + 16 bytes (36 or 68
+// words, so the 16-byte reads of eight consecutive rows fall into distinct banks).  With few
+// plane rows the kernel streams the other operand from HBM, and longer contiguous pieces of
+// its rows serve that better.
 struct TileShape {
-    int ts, tp;
+    int ts, tp, ch;
 };
 TileShape tile_shape(int rows_p) {
-    if (rows_p <= 32) return {128, 32};
-    if (rows_p <= 64) return {128, 64};
-    if (rows_p <= 128) return {256, 128};
-    return {256, 256};
+    if (rows_p <= 32) return {256, 32, 128};
+    if (rows_p <= 64) return {256, 64, 128};
+    if (rows_p <= 128) return {256, 128, 128};
+    return {256, 256, 128};
 }
 
 template <class Prob>
@@ -268,13 +282,13 @@ hipError_t launch_gemm(Prob pr, int Z, hipStream_t s) {
     d.affine = Z >= kXcds;
     const dim3 grid(image_affine_grid(Z, d.s_tiles * d.p_tiles * d.ksplit, d.affine != 0));
     if (t.tp == 32)
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4, 1, 1, 1>), grid, dim3(256), 0, s, pr);
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4, 1, 2, 1, 128>), grid, dim3(256), 0, s, pr);
     else if (t.tp == 64)
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4, 1, 1, 2>), grid, dim3(256), 0, s, pr);
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4, 1, 2, 2, 128>), grid, dim3(256), 0, s, pr);
     else if (t.tp == 128)
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2, 2, 4, 2>), grid, dim3(256), 0, s, pr);
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2, 2, 4, 2, 128>), grid, dim3(256), 0, s, pr);
     else
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2, 4, 4, 2>), grid, dim3(512), 0, s, pr);
+        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2, 4, 4, 2, 128>), grid, dim3(512), 0, s, pr);
     return hipGetLastError();
 }
 
@@ -401,7 +415,7 @@ GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
 int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems) {
     const TileShape t = tile_shape(rows_p);
     const int64_t tiles = (int64_t)((rows_s + t.ts - 1) / t.ts) * ((rows_p + t.tp - 1) / t.tp) * Z;
-    const int nchunks = (k_elems * 2 + kChunkBytes - 1) / kChunkBytes;
+    const int nchunks = (k_elems * 2 + t.ch - 1) / t.ch;
     int ks = (int)((kTargetWorkgroups + tiles - 1) / tiles);
     ks = max(1, min(ks, min(16, nchunks / 2)));
     return ks;
@@ -482,6 +496,8 @@ hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
         VSCAN_SOFTMAX(256, 1);
     else if (a.nk <= 1024)
         VSCAN_SOFTMAX(256, 4);
+    else if (a.nk <= 4096 && (int64_t)R * a.B >= 1024)
+        VSCAN_SOFTMAX(256, 16);  // enough rows to fill the chip with small workgroups
     else if (a.nk <= 4096)
         VSCAN_SOFTMAX(1024, 4);
     else if (a.nk <= 16384)
