@@ -496,8 +496,6 @@ hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
         VSCAN_SOFTMAX(256, 1);
     else if (a.nk <= 1024)
         VSCAN_SOFTMAX(256, 4);
-    else if (a.nk <= 4096 && (int64_t)R * a.B >= 1024)
-        VSCAN_SOFTMAX(256, 16);  // enough rows to fill the chip with small workgroups
     else if (a.nk <= 4096)
         VSCAN_SOFTMAX(1024, 4);
     else if (a.nk <= 16384)

@@ -48,7 +48,7 @@ SMALL_FUSED = {
     # key domains of every softmax form: up to 1024, up to 4096, longer
     "domain-1k": _shape(batch=1, vis_len=700, keep=200, hidden=128, q_heads=4, kv_heads=4, head_dim=32),
     "domain-4k": _shape(batch=1, vis_len=2500, keep=700, hidden=64, q_heads=2, kv_heads=1, head_dim=32),
-    # many rows of a long domain: the small-workgroup softmax with 16 values per thread
+    # many rows of a long domain
     "domain-4k-many-rows": _shape(batch=8, vis_len=1100, keep=40, hidden=64, q_heads=16, kv_heads=4,
                                   head_dim=16, n_query=8),
     "domain-long": _shape(batch=1, vis_len=4300, keep=1000, hidden=64, q_heads=2, kv_heads=2,
