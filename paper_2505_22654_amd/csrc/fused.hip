@@ -27,6 +27,8 @@
 // Contractions with few output tiles split the contraction axis over `ksplit` workgroups;
 // partial results are stored side by side and summed, in fixed order, by whichever kernel reads
 // them next.
+#include <algorithm>
+
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -414,7 +416,8 @@ GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
 
 int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems) {
     const TileShape t = tile_shape(rows_p);
-    const int64_t tiles = (int64_t)((rows_s + t.ts - 1) / t.ts) * ((rows_p + t.tp - 1) / t.tp) * Z;
+    const int64_t tiles = std::max<int64_t>(
+        1, (int64_t)((rows_s + t.ts - 1) / t.ts) * ((rows_p + t.tp - 1) / t.tp) * Z);  // empty batch: 1
     const int nchunks = (k_elems * 2 + t.ch - 1) / t.ch;
     int ks = (int)((kTargetWorkgroups + tiles - 1) / tiles);
     ks = max(1, min(ks, min(16, nchunks / 2)));

@@ -210,6 +210,55 @@ def test_ragged_pointer_checks_and_empty_batch():
     assert _ragged_call(vb.llm_desc(_llm_shape(head_dim=100)), good) == vb.VSCAN_ERR_SHAPE
 
 
+def _fused_llm_call(desc, hidden=FAKE, wq=FAKE, wkt=FAKE, kept=FAKE, ho=FAKE, ws=FAKE,
+                    ws_bytes=1 << 40):
+    return vb.lib().vscan_llm_prune_fused(ctypes.byref(desc) if desc is not None else None, hidden,
+                                          wq, wkt, kept, ho, None, ws, ws_bytes, None)
+
+
+def _fused_enc_call(desc, hidden=FAKE, wq=FAKE, wkt=FAKE, local=(None, None, None), x=FAKE,
+                    kept=FAKE, merged=FAKE, ws=FAKE, ws_bytes=1 << 40):
+    return vb.lib().vscan_encoder_reduce_fused(ctypes.byref(desc) if desc is not None else None,
+                                               hidden, wq, wkt, local[0], local[1], local[2], x,
+                                               kept, merged, None, None, ws, ws_bytes, None)
+
+
+def test_fused_entry_points_validate_on_the_host():
+    """Scoring from hidden states: bf16 and [CLS] only; the usual pointer, alignment and
+    workspace checks; nothing is launched by any of these calls."""
+    bf = lambda sh: dataclasses.replace(sh, dtype=wl.BF16)
+    ldesc = vb.llm_desc(bf(_llm_shape()))
+    need = vb.llm_fused_workspace_size(ldesc)
+    assert need > vb.llm_workspace_size(ldesc)
+    assert _fused_llm_call(None) == vb.VSCAN_ERR_NULL
+    assert _fused_llm_call(vb.llm_desc(_llm_shape())) == vb.VSCAN_ERR_UNSUPPORTED     # fp32
+    assert _fused_llm_call(vb.llm_desc(bf(_llm_shape(head_dim=100)))) == vb.VSCAN_ERR_SHAPE
+    assert _fused_llm_call(vb.llm_desc(bf(_llm_shape(keep=65)))) == vb.VSCAN_ERR_BUDGET
+    assert _fused_llm_call(ldesc, wq=None) == vb.VSCAN_ERR_NULL
+    assert _fused_llm_call(ldesc, ho=None) == vb.VSCAN_ERR_NULL                        # out of place
+    assert _fused_llm_call(vb.llm_desc(bf(_llm_shape(in_place=1)))) == vb.VSCAN_ERR_NULL   # ho given
+    assert _fused_llm_call(ldesc, wkt=FAKE + 8) == vb.VSCAN_ERR_ALIGN
+    assert _fused_llm_call(ldesc, ws_bytes=need - 1) == vb.VSCAN_ERR_WORKSPACE
+    assert _fused_llm_call(vb.llm_desc(bf(_llm_shape(batch=0)))) == vb.VSCAN_OK
+    # 4 GiB of hidden states and more: byte offsets no longer fit the kernels' 32-bit row offsets
+    big = bf(_llm_shape(batch=64, prefix=0, vis_len=8192, text=8, keep=10))
+    assert _fused_llm_call(vb.llm_desc(big)) == vb.VSCAN_ERR_UNSUPPORTED
+
+    edesc = vb.encoder_desc(bf(_enc_shape()))
+    eneed = vb.encoder_fused_workspace_size(edesc)
+    assert eneed > vb.encoder_workspace_size(edesc)
+    assert vb.encoder_fused_workspace_size(edesc, True) > eneed
+    assert _fused_enc_call(vb.encoder_desc(_enc_shape())) == vb.VSCAN_ERR_UNSUPPORTED   # fp32
+    mean = bf(_enc_shape(has_cls=0, score_mode=1))
+    assert _fused_enc_call(vb.encoder_desc(mean)) == vb.VSCAN_ERR_UNSUPPORTED
+    assert _fused_enc_call(edesc, local=(FAKE, FAKE, None)) == vb.VSCAN_ERR_NULL       # partial triple
+    assert _fused_enc_call(edesc, x=None) == vb.VSCAN_ERR_NULL
+    assert _fused_enc_call(edesc, hidden=FAKE + 4) == vb.VSCAN_ERR_ALIGN
+    assert _fused_enc_call(edesc, ws_bytes=eneed - 1) == vb.VSCAN_ERR_WORKSPACE
+    assert _fused_enc_call(edesc, local=(FAKE, FAKE, FAKE), ws_bytes=eneed) == vb.VSCAN_ERR_WORKSPACE
+    assert _fused_enc_call(vb.encoder_desc(bf(_enc_shape(batch=0)))) == vb.VSCAN_OK
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(vb, "_lib", None)
     monkeypatch.setattr(vb, "LIB_PATH", "/nonexistent/libvscan.so")
