@@ -122,6 +122,75 @@ def test_fused_config2_shape():
     print("cfg2 stage-2 shape", pu.check_fused(shape, ref, out, "cfg2 fused"))
 
 
+def test_fused_more_sequences_than_one_row_tile():
+    """33 sequences of 4 query positions: 132 query rows in the query projection (its largest
+    tile shape), 33 rows per kv head in the hidden-space step."""
+    shape = _shape(batch=33, n_query=4, vis_len=90, keep=20, hidden=128, q_heads=4, kv_heads=4,
+                   head_dim=16, prefix=3, text=6)
+    inp, ref, info = pu.screened_fused_case(shape, 9650)
+    print("case", info, flush=True)
+    print(pu.check_fused(shape, ref, _run(shape, inp), "33 sequences"))
+    shape = dataclasses.replace(shape, batch=20)      # 80 query rows: the 128-row tile shape
+    inp, ref, info = pu.screened_fused_case(shape, 9660)
+    print("case", info, flush=True)
+    print(pu.check_fused(shape, ref, _run(shape, inp), "20 sequences"))
+
+
+def test_fused_config5_full():
+    """Full-size stage-2 stress shape (32 sequences, 2880 visual tokens, 8 query positions = 256
+    query rows, hidden 4096), in place, all three budgets.  Every sequence is checked on the device
+    against the returned indices; the oracle checks, element by element, the sequences whose
+    selection boundary clears the margin (decided from the oracle's own scores)."""
+    import torch
+    base = wl.config(5)
+    shape = base.llm
+    B, S, V, vs = shape.batch, shape.seq_len, shape.vis_len, shape.vis_start
+    keeps = (720, 288, 144)
+    w = wl.llm_weights(shape, base.seed)
+    wq = pu.to_device(w["w_q"], wl.BF16)
+    wkt = pu.to_device(np.ascontiguousarray(w["w_k"].T), wl.BF16)
+    hidden = torch.empty((B, S, shape.hidden), dtype=torch.bfloat16, device="cuda")
+    host, scores, wanted = {}, {}, {k: [] for k in keeps}
+    for b in range(B):
+        item = wl.llm_item(shape, base.seed, b)["hidden"]
+        hidden[b].copy_(pu.to_device(item, wl.BF16))
+        if all(len(v) >= 2 for v in wanted.values()):
+            continue
+        s_ref = vo.llm_scores_from_hidden(item[None], w["w_q"], w["w_k"], vs, V, shape.n_query,
+                                          shape.q_heads, shape.kv_heads, shape.head_dim)
+        for k in keeps:
+            if len(wanted[k]) < 2 and pu.topk_boundary_gap(s_ref, k) > pu.MARGIN:
+                wanted[k].append(b)
+                host[b], scores[b] = item, s_ref
+    orig = hidden.clone()
+    print("sequences with a clear boundary per budget:", wanted, flush=True)
+
+    for keep in keeps:
+        sh = dataclasses.replace(shape, keep=keep)
+        So = sh.seq_out
+        hidden.copy_(orig)
+        out = vb.llm_prune_fused(sh, hidden, wq, wkt, want_scores=True)
+        torch.cuda.synchronize()
+        kept = out["kept_idx"].long()
+        assert bool((kept[:, 1:] > kept[:, :-1]).all())
+        assert int(kept.min()) >= 0 and int(kept.max()) < V
+        rows = torch.cat([torch.arange(vs, device="cuda").expand(B, vs), vs + kept,
+                          torch.arange(vs + V, S, device="cuda").expand(B, S - vs - V)], dim=1)
+        assert rows.shape == (B, So)
+        want_h = torch.gather(orig, 1, rows[:, :, None].expand(B, So, sh.hidden))
+        assert torch.equal(out["hidden"], want_h)
+        np.testing.assert_allclose(pu.to_host(out["scores"]).sum(1), 1.0, rtol=1e-5)
+        assert wanted[keep], "no sequence with a clear boundary for this budget"
+        for b in wanted[keep]:
+            want_kept = vo.topk(scores[b], keep)
+            assert np.array_equal(pu.to_host(out["kept_idx"][b:b + 1]), want_kept), (keep, b)
+            err = pu.check_scores(pu.to_host(out["scores"][b:b + 1]), scores[b],
+                                  f"cfg5 fused keep {keep} sequence {b}")
+            ref_h = vo.compact(host[b][None], want_kept, vs, V)
+            assert np.array_equal(pu.to_host(out["hidden"][b:b + 1]), ref_h)
+            print("cfg5 fused keep", keep, "sequence", b, "score_rel_err", err)
+
+
 # ---- stage 1 scored from the layer's input rows and projection weights -------------------------
 
 def _run_encoder(shape, inp, loc=None):
@@ -145,6 +214,9 @@ def _enc(**kw):
 
 
 FUSED_ENCODER = {
+    # 36 segments: more than one 32-row tile of [CLS] queries
+    "many-images": _enc(batch=12, n_segments=3, grid_h=6, grid_w=6, heads=2, head_dim=16,
+                        feat_dim=64, win_rows=1, win_cols=1, keep_global=5, keep_local=0),
     "ragged": _enc(batch=3, n_segments=2, grid_h=13, grid_w=11, heads=3, head_dim=40, feat_dim=200,
                    win_rows=3, win_cols=2, keep_global=17, keep_local=13),
     "all-keys": _enc(softmax_domain=1, keep_global=30, keep_local=16),
