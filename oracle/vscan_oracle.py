@@ -209,7 +209,8 @@ def llm_scores_from_hidden(hidden, w_q, w_k, vis_start, V, n_query, q_heads, kv_
     then the mean over query heads (and over the last n_query positions, an extension of the
     paper's single last token).  hidden [B,S,Dh] -> scores [B,V] fp64.  Plain numpy in fp64.
     domain 0: the softmax runs over the visual keys only, as the equation is written;
-    domain 1: over all S keys, and the visual columns are taken (same two readings as
+    domain 1: over the causal row of each query - query t of the last n_query positions sees
+    keys 0 .. S - n_query + t - and the visual columns are taken (the two readings of
     llm_scores)."""
     x = np.asarray(hidden, dtype=np.float64)
     wq = np.asarray(w_q, dtype=np.float64)
@@ -217,15 +218,14 @@ def llm_scores_from_hidden(hidden, w_q, w_k, vis_start, V, n_query, q_heads, kv_
     B, S, Dh = x.shape
     sc = default_scale(head_dim, scale)
     group = q_heads // kv_heads
-    k0, nk = (0, S) if domain else (vis_start, V)
     q = (x[:, S - n_query:, :] @ wq.T).reshape(B, n_query, q_heads, head_dim)
-    k = (x[:, k0:k0 + nk, :] @ wk.T).reshape(B, nk, kv_heads, head_dim)
+    k = (x @ wk.T).reshape(B, S, kv_heads, head_dim)
     out = np.zeros((B, V), dtype=np.float64)
     for b in range(B):
         for h in range(q_heads):
-            kh = k[b, :, h // group, :]                      # [nk, dh]
             for t in range(n_query):
-                logit = kh @ q[b, t, h] * sc                 # [nk]
+                k0, nk = (0, S - n_query + t + 1) if domain else (vis_start, V)
+                logit = k[b, k0:k0 + nk, h // group, :] @ q[b, t, h] * sc
                 e = np.exp(logit - logit.max())
                 out[b] += (e / e.sum())[vis_start - k0:vis_start - k0 + V]
     return out / (q_heads * n_query)

@@ -442,6 +442,13 @@ def test_scores_from_hidden_agree_with_projected_form():
                          shape.vis_len)
     np.testing.assert_allclose(got, want, rtol=5e-6)
     np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-12)
+    # the all-keys reading: causal rows, one key fewer for the earlier of the two queries
+    got = vo.llm_scores_from_hidden(x, w["w_q"], w["w_k"], shape.vis_start, shape.vis_len,
+                                    shape.n_query, shape.q_heads, shape.kv_heads, shape.head_dim,
+                                    domain=1)
+    want = vo.llm_scores(q.astype(np.float32), k.astype(np.float32), shape.vis_start,
+                         shape.vis_len, 1)
+    np.testing.assert_allclose(got, want, rtol=5e-6)
 
 
 def test_scores_from_hidden_closed_form():
@@ -457,6 +464,13 @@ def test_scores_from_hidden_closed_form():
     # all-keys domain: the last token's own key (logit 1) joins the denominator
     got_all = vo.llm_scores_from_hidden(x, eye, eye, 0, V, 1, 1, 1, Dh, domain=1, scale=1.0)
     np.testing.assert_allclose(got_all[0], np.arange(1, V + 1) / (np.arange(1, V + 1).sum() + np.e),
+                               rtol=1e-12)
+    # two query positions, both e_0: the earlier one does not see the later one's key, so its
+    # denominator lacks one e; the score is the mean of the two rows
+    x3 = np.zeros((1, V + 2, Dh)); x3[0, :V, 0] = a; x3[0, V:, 0] = 1.0
+    got2q = vo.llm_scores_from_hidden(x3, eye, eye, 0, V, 2, 1, 1, Dh, domain=1, scale=1.0)
+    tot = np.arange(1, V + 1).sum()
+    np.testing.assert_allclose(got2q[0], np.arange(1, V + 1) * 0.5 * (1 / (tot + np.e) + 1 / (tot + 2 * np.e)),
                                rtol=1e-12)
     np.testing.assert_allclose(got[0], np.arange(1, V + 1) / np.arange(1, V + 1).sum(), rtol=1e-12)
     # a transposed weight would contract the wrong axis: a non-symmetric W_K catches it
