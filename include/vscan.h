@@ -220,7 +220,8 @@ int vscan_llm_prune_ragged(const vscan_llm_desc *desc, const vscan_seq_meta *met
  * K_V = x_V W_K^h per head h, softmax over the key domain, mean over heads),
  * then the same top-`keep` selection, and the compaction applied to the hidden
  * states only (K and V of this layer do not exist yet; the caller computes them
- * for the tokens that are left).  No positional rotation is applied to Q or K,
+ * for the tokens that are left).  With VSCAN_KEYS_ALL every query position
+ * attends causally, to the keys up to and including its own position.  No positional rotation is applied to Q or K,
  * as in the equation.  bf16 only (VSCAN_ERR_UNSUPPORTED for fp32).
  *
  * desc        HOST; as for vscan_llm_prune.  `hidden` and `head_dim` must be

@@ -426,6 +426,7 @@ int vscan_encoder_reduce_fused(const vscan_encoder_desc *d, const void *hidden, 
         fa.dh = d->head_dim;
         fa.Tq = 1;
         fa.q_row0 = 0;  // the [CLS] row
+        fa.causal = 0;
         fa.vis_start = 1;
         fa.V = p.e.N;
         fa.k0 = p.k0;
@@ -612,6 +613,8 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     fa.dh = d->head_dim;
     fa.Tq = d->n_query;
     fa.q_row0 = d->seq_len - d->n_query;  // the last positions
+    // over all keys each query attends causally: up to and including its own position
+    fa.causal = d->softmax_domain == VSCAN_KEYS_ALL;
     fa.vis_start = d->vis_start;
     fa.V = d->vis_len;
     fa.k0 = p.k0;

@@ -314,15 +314,21 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
 // Softmax of one (sequence, query row) over the key domain.  The scaled logits of the row
 // (partial sums added in fixed order) stay in registers between the maximum, the sum of
 // exponentials and the normalised weights, which overwrite the row's first partial slot.
-// NREG * THREADS >= nk.
+// NREG * THREADS >= nk.  With `causal`, query position t of the Tq positions of a row index
+// r = h*Tq + t sees all but the last Tq-1-t keys of the domain; the others get weight zero.
+__device__ __forceinline__ int row_keys(int r, int nk, int Tq, int causal) {
+    return causal ? nk - (Tq - 1 - r % Tq) : nk;
+}
+
 template <int THREADS, int NREG>
 __global__ __launch_bounds__(THREADS) void fused_softmax_kernel(float *__restrict__ c, int ksplit,
                                                                 int64_t ks_stride, int nk,
-                                                                float scale) {
+                                                                float scale, int Tq, int causal) {
     __shared__ float red[16];
     const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
     float *l = c + row * nk;
     const int tid = threadIdx.x;
+    const int nv = row_keys(blockIdx.x, nk, Tq, causal);
     float v[NREG];
 #pragma unroll
     for (int i = 0; i < NREG; ++i) v[i] = 0.f;
@@ -333,14 +339,14 @@ __global__ __launch_bounds__(THREADS) void fused_softmax_kernel(float *__restric
 #pragma unroll
     for (int i = 0; i < NREG; ++i) {
         v[i] *= scale;
-        if (tid + THREADS * i < nk) m = fmaxf(m, v[i]);
+        if (tid + THREADS * i < nv) m = fmaxf(m, v[i]);
     }
     m = block_max(m, red);
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < NREG; ++i) {
-        v[i] = __expf(v[i] - m);
-        if (tid + THREADS * i < nk) sum += v[i];
+        v[i] = tid + THREADS * i < nv ? __expf(v[i] - m) : 0.f;
+        sum += v[i];
     }
     sum = block_sum(sum, red);
     const float inv = 1.0f / sum;
@@ -352,12 +358,13 @@ __global__ __launch_bounds__(THREADS) void fused_softmax_kernel(float *__restric
 // Rows too long for the register form: three passes over the row.
 __global__ __launch_bounds__(1024) void fused_softmax_long_kernel(float *__restrict__ c, int ksplit,
                                                                   int64_t ks_stride, int nk,
-                                                                  float scale) {
+                                                                  float scale, int Tq, int causal) {
     __shared__ float red[16];
     const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
     float *l = c + row * nk;
+    const int nv = row_keys(blockIdx.x, nk, Tq, causal);
     float m = -INFINITY;
-    for (int j = threadIdx.x; j < nk; j += 1024) {
+    for (int j = threadIdx.x; j < nv; j += 1024) {
         float v = 0.f;
         for (int ks = 0; ks < ksplit; ++ks) v += l[ks * ks_stride + j];
         v *= scale;
@@ -366,10 +373,10 @@ __global__ __launch_bounds__(1024) void fused_softmax_long_kernel(float *__restr
     }
     m = block_max(m, red);
     float sum = 0.f;
-    for (int j = threadIdx.x; j < nk; j += 1024) sum += __expf(l[j] - m);
+    for (int j = threadIdx.x; j < nv; j += 1024) sum += __expf(l[j] - m);
     sum = block_sum(sum, red);
     const float inv = 1.0f / sum;
-    for (int j = threadIdx.x; j < nk; j += 1024) l[j] = __expf(l[j] - m) * inv;
+    for (int j = threadIdx.x; j < nk; j += 1024) l[j] = j < nv ? __expf(l[j] - m) * inv : 0.f;
 }
 
 // part[b][j] = sum over the query rows of the softmax weight of visual token j (Eq. 5 before
@@ -494,7 +501,7 @@ hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
     const dim3 grid(R, a.B);
 #define VSCAN_SOFTMAX(T, N)                                                                      \
     hipLaunchKernelGGL((fused_softmax_kernel<T, N>), grid, dim3(T), 0, s, a.c_l, a.ks_l, ks_stride, \
-                       a.nk, a.scale)
+                       a.nk, a.scale, a.Tq, a.causal)
     if (a.nk <= 256)
         VSCAN_SOFTMAX(256, 1);
     else if (a.nk <= 1024)
@@ -505,7 +512,7 @@ hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
         VSCAN_SOFTMAX(1024, 16);
     else
         hipLaunchKernelGGL(fused_softmax_long_kernel, grid, dim3(1024), 0, s, a.c_l, a.ks_l,
-                           ks_stride, a.nk, a.scale);
+                           ks_stride, a.nk, a.scale, a.Tq, a.causal);
 #undef VSCAN_SOFTMAX
     return hipGetLastError();
 }

@@ -110,6 +110,7 @@ struct FusedArgs {
     float *part;               // [B][V] sums over the query rows
     int B, S, Dh, Hq, Hkv, dh, Tq, vis_start, V, k0, nk;
     int q_row0;                // first of the Tq query rows of a sequence
+    int causal;                // query position t sees all but the last Tq-1-t keys of the domain
     int ks_q, ks_l;            // shares of the contraction axis (fused_ksplit)
     float scale;
 };

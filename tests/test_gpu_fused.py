@@ -35,6 +35,8 @@ SMALL_FUSED = {
     "ragged-tiles": _shape(batch=3, vis_len=300, hidden=520, keep=100),
     "in-place": _shape(in_place=1),
     "all-keys": _shape(softmax_domain=1, prefix=37, text=21),
+    # all keys and several query positions: each position's row is causal
+    "all-keys-queries": _shape(softmax_domain=1, n_query=3, q_heads=8, kv_heads=4, text=11),
     # grouped heads and several query positions: 24 query rows
     "gqa-queries": _shape(q_heads=8, kv_heads=2, n_query=3, head_dim=32, hidden=256),
     # more query rows than one 128-row tile of the plane operand
