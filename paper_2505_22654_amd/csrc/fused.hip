@@ -1,12 +1,15 @@
-// Stage-2 scores computed from the hidden states and the layer's projection weights
-// (Eq. 5 as written: Q = x_last W_Q^h, K_V = x_V W_K^h), for a caller that has no Q and K yet.
+// Attention scores computed from hidden states and the layer's projection weights, for a
+// caller that has no Q and K yet: Eq. 5 as written (Q = x_last W_Q^h, K = x W_K^h; the queries
+// are the last Tq positions of a sequence) and the [CLS] row of Eq. 1 (the query is row 0 of a
+// segment).  The result is, per sequence, the sum over the query rows of their softmax weights
+// on every visual token; selection and everything after it are the kernels of the Q/K form.
 //
 // The keys are never projected.  For one query row q of head h,
 //     q . (W_K^h x_j) = (W_K^hT q) . x_j ,
 // so the query is carried into hidden space once (qt = W_K^hT q, one vector of `hidden`
 // entries per head and query position) and the logits are a single contraction of qt
-// with the visual span of the hidden states: B*V*hidden*Hq*Tq multiply-adds instead of the
-// B*V*hidden*Hkv*dh of a key projection (a factor dh*Hkv/(Hq*Tq), 128 for an MHA layer of
+// with the hidden states of the key domain: B*nk*hidden*Hq*Tq multiply-adds instead of the
+// B*nk*hidden*Hkv*dh of a key projection (a factor dh*Hkv/(Hq*Tq), 128 for an MHA layer of
 // head size 128 and one query position).
 //
 // Precision.  Inputs are bf16.  All three contractions run on the matrix cores with bf16
@@ -132,8 +135,8 @@ struct ProbLogit {
 
 // One workgroup of WS x WP waves: 32*FS*WS streamed rows x 32*FP*WP plane-operand rows, one
 // share of the contraction axis; a wave owns FS x FP tiles of 32 x 32.  Both operands pass
-// through LDS in 128-byte row chunks: the next chunk is fetched into registers (coalesced, 8
-// lanes per row) while the matrix cores work on the current one.  Row indices past the
+// through LDS in CH-byte row chunks: the next chunk is fetched into registers (coalesced,
+// CH/16 lanes per row) while the matrix cores work on the current one.  Row indices past the
 // operand's end are clamped (the rows are computed and not stored); chunk pieces past the
 // contraction length are fetched from a clamped offset and zeroed on their way into LDS.
 template <class Prob, int WS, int WP, int FS, int FP, int CH>
