@@ -213,6 +213,16 @@ int vscan_llm_prune_ragged(const vscan_llm_desc *desc, const vscan_seq_meta *met
                            void *hidden_out, float *scores_out, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* vscan_llm_prune_fused for a ragged batch: the table, the capacities and the shape of
+ * hidden_out ([B, seq_len, hidden], rows past a sequence's result untouched) follow the
+ * conventions above; everything else is as for vscan_llm_prune_fused (workspace from
+ * vscan_llm_fused_workspace_size with the capacities). */
+int vscan_llm_prune_fused_ragged(const vscan_llm_desc *desc, const vscan_seq_meta *meta_host,
+                                 const vscan_seq_meta *meta_device, void *hidden, const void *w_q,
+                                 const void *w_k_t, int32_t *kept_idx, void *hidden_out,
+                                 float *scores_out, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
 /* ---------------------------------------------------------------------------
  * Stage 2 for a caller that does not hold the layer's queries and keys: the
  * scores of Eq. 5 computed as the equation is written, from the hidden states

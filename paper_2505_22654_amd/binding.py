@@ -25,7 +25,8 @@ EXPORTS = ("vscan_encoder_workspace_size", "vscan_encoder_reduce", "vscan_llm_wo
            "vscan_llm_prune", "vscan_profile_enable", "vscan_profile_read", "vscan_status_string",
            "vscan_version", "vscan_budget", "vscan_budget_solve_r1", "vscan_flops",
            "vscan_llm_prune_ragged", "vscan_llm_fused_workspace_size", "vscan_llm_prune_fused",
-           "vscan_encoder_fused_workspace_size", "vscan_encoder_reduce_fused")
+           "vscan_encoder_fused_workspace_size", "vscan_encoder_reduce_fused",
+           "vscan_llm_prune_fused_ragged")
 
 
 class EncoderDesc(ctypes.Structure):
@@ -98,6 +99,9 @@ def lib():
         L.vscan_encoder_reduce_fused.argtypes = [ctypes.POINTER(EncoderDesc), vp, vp, vp, vp, vp, vp,
                                                  vp, i32p, vp, i32p, f32p, vp, ctypes.c_size_t, vp]
         L.vscan_encoder_reduce_fused.restype = ctypes.c_int
+        L.vscan_llm_prune_fused_ragged.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, vp, vp, i32p,
+                                                   vp, f32p, vp, ctypes.c_size_t, vp]
+        L.vscan_llm_prune_fused_ragged.restype = ctypes.c_int
         L.vscan_profile_enable.argtypes = [ctypes.c_int]
         L.vscan_profile_enable.restype = ctypes.c_int
         L.vscan_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int,
@@ -437,4 +441,35 @@ def encoder_reduce_fused(shape, hidden, w_q, w_k_t, x, local=None, want_assign: 
     if rc != VSCAN_OK:
         raise VscanError(rc, "vscan_encoder_reduce_fused")
     out["workspace"] = workspace
+    return out
+
+
+def llm_prune_fused_ragged(shape, meta, hidden, w_q, w_k_t, want_scores: bool = False) -> Dict[str, object]:
+    """vscan_llm_prune_fused_ragged.  `shape` carries the shared fields and the capacities;
+    `meta` lists (seq_len, vis_start, vis_len, keep) per sequence.  The out-of-place result is
+    shaped like `hidden` (zero-filled here past a sequence's result); `out_len` lists the
+    result lengths."""
+    import torch
+    desc = llm_desc(shape)
+    need = llm_fused_workspace_size(desc)
+    dev = hidden.device
+    B = shape.batch
+    assert len(meta) == B
+    host = (ctypes.c_int32 * (4 * max(B, 1)))(*[int(x) for m in meta for x in m])
+    meta_dev = torch.tensor([list(map(int, m)) for m in meta], dtype=torch.int32,
+                            device=dev).reshape(B, 4).contiguous()
+    workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = {"kept_idx": torch.empty((B, shape.keep), dtype=torch.int32, device=dev)}
+    if want_scores:
+        out["scores"] = torch.zeros((B, shape.vis_len), dtype=torch.float32, device=dev)
+    ho = None if shape.in_place else torch.zeros_like(hidden)
+    rc = lib().vscan_llm_prune_fused_ragged(ctypes.byref(desc), ctypes.cast(host, ctypes.c_void_p),
+                                            _ptr(meta_dev), _ptr(hidden), _ptr(w_q), _ptr(w_k_t),
+                                            _ptr(out["kept_idx"]), _ptr(ho), _ptr(out.get("scores")),
+                                            _ptr(workspace), workspace.numel(), _stream_handle())
+    if rc != VSCAN_OK:
+        raise VscanError(rc, "vscan_llm_prune_fused_ragged")
+    out["hidden"] = hidden if shape.in_place else ho
+    out["out_len"] = [m[0] - m[2] + m[3] for m in meta]
+    out["meta_device"], out["workspace"] = meta_dev, workspace  # alive until the work has run
     return out

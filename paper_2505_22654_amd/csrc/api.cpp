@@ -540,6 +540,9 @@ int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, vo
                    stream);
 }
 
+static int check_seq_meta(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
+                          const vscan_seq_meta *meta_device, int *max_out_rows);
+
 int vscan_llm_prune_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
                            const vscan_seq_meta *meta_device, const void *q, void *k, void *v,
                            void *hidden, int32_t *kept_idx, void *k_out, void *v_out,
@@ -553,18 +556,9 @@ int vscan_llm_prune_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_h
     LlmPlan p;
     const int rc = plan_llm(&caps, &p);
     if (rc != VSCAN_OK) return rc;
-    if (d->batch > 0 && (!meta_host || !meta_device)) return VSCAN_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(meta_device) & 3u) return VSCAN_ERR_ALIGN;
     int max_out_rows = 0;
-    for (int b = 0; b < d->batch; ++b) {
-        const vscan_seq_meta &m = meta_host[b];
-        if (m.seq_len < 1 || m.seq_len > d->seq_len || m.vis_start < 0 || m.vis_len < 1 ||
-            m.vis_len > d->vis_len)
-            return VSCAN_ERR_SHAPE;
-        if ((int64_t)m.vis_start + m.vis_len + d->n_query > m.seq_len) return VSCAN_ERR_SHAPE;
-        if (m.keep < 0 || m.keep > m.vis_len || m.keep > d->keep) return VSCAN_ERR_BUDGET;
-        max_out_rows = std::max(max_out_rows, m.seq_len - m.vis_len + m.keep);
-    }
+    const int rc2 = check_seq_meta(d, meta_host, meta_device, &max_out_rows);
+    if (rc2 != VSCAN_OK) return rc2;
     static_assert(sizeof(SeqMeta) == sizeof(vscan_seq_meta), "same layout");
     return run_llm(&caps, p, reinterpret_cast<const SeqMeta *>(meta_device), max_out_rows,
                    d->seq_len, q, k, v, hidden, kept_idx, k_out, v_out, hidden_out, scores_out,
@@ -580,13 +574,12 @@ int vscan_llm_fused_workspace_size(const vscan_llm_desc *desc, size_t *bytes) {
     return VSCAN_OK;
 }
 
-int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q,
-                          const void *w_k_t, int32_t *kept_idx, void *hidden_out,
-                          float *scores_out, void *workspace, size_t workspace_bytes,
-                          void *stream) {
-    FusedPlan p;
-    const int rc = plan_fused(d, &p);
-    if (rc != VSCAN_OK) return rc;
+// Shared by the uniform and the ragged form.  `meta` (device) is NULL for a uniform batch;
+// `max_out_rows` is the longest result, `out_rows` the row stride of hidden_out.
+static int run_llm_fused(const vscan_llm_desc *d, const FusedPlan &p, const SeqMeta *meta,
+                         int max_out_rows, int out_rows, void *hidden, const void *w_q,
+                         const void *w_k_t, int32_t *kept_idx, void *hidden_out, float *scores_out,
+                         void *workspace, size_t workspace_bytes, void *stream) {
     if (!hidden || !w_q || !w_k_t || (!kept_idx && d->keep > 0)) return VSCAN_ERR_NULL;
     if (d->in_place ? hidden_out != nullptr : hidden_out == nullptr) return VSCAN_ERR_NULL;
     if (!aligned16(hidden) || !aligned16(w_q) || !aligned16(w_k_t) || !aligned16(hidden_out))
@@ -620,6 +613,7 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     fa.k0 = p.k0;
     fa.nk = p.nk;
     fa.scale = resolve_scale(d->scale, d->head_dim);
+    fa.meta = meta;
     const int rc2 = enqueue_fused_scores(fa, p.f, ws, s);
     if (rc2 != VSCAN_OK) return rc2;
 
@@ -632,6 +626,7 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     se.norm = 1.0f / (float)p.R;
     se.kept_idx = kept_idx;
     se.scores_out = scores_out;
+    se.meta = meta;
     VSCAN_LAUNCH("llm_select", launch_llm_select(se, s));
 
     CompactArgs ca;
@@ -649,10 +644,62 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     ca.keep = d->keep;
     ca.elem_bytes = 2;
     ca.in_place = d->in_place;
-    ca.out_rows = d->in_place ? d->seq_len : p.S_out;
-    ca.max_out_rows = p.S_out;
+    ca.out_rows = out_rows;
+    ca.max_out_rows = max_out_rows;
+    ca.meta = meta;
     VSCAN_LAUNCH("compact", launch_compact(ca, s));
     return VSCAN_OK;
+}
+
+int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q,
+                          const void *w_k_t, int32_t *kept_idx, void *hidden_out,
+                          float *scores_out, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+    FusedPlan p;
+    const int rc = plan_fused(d, &p);
+    if (rc != VSCAN_OK) return rc;
+    return run_llm_fused(d, p, nullptr, p.S_out, d->in_place ? d->seq_len : p.S_out, hidden, w_q,
+                         w_k_t, kept_idx, hidden_out, scores_out, workspace, workspace_bytes,
+                         stream);
+}
+
+// Validation of a ragged batch's host table against the capacities; *max_out_rows receives the
+// longest result.
+static int check_seq_meta(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
+                          const vscan_seq_meta *meta_device, int *max_out_rows) {
+    if (d->batch > 0 && (!meta_host || !meta_device)) return VSCAN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(meta_device) & 3u) return VSCAN_ERR_ALIGN;
+    *max_out_rows = 0;
+    for (int b = 0; b < d->batch; ++b) {
+        const vscan_seq_meta &m = meta_host[b];
+        if (m.seq_len < 1 || m.seq_len > d->seq_len || m.vis_start < 0 || m.vis_len < 1 ||
+            m.vis_len > d->vis_len)
+            return VSCAN_ERR_SHAPE;
+        if ((int64_t)m.vis_start + m.vis_len + d->n_query > m.seq_len) return VSCAN_ERR_SHAPE;
+        if (m.keep < 0 || m.keep > m.vis_len || m.keep > d->keep) return VSCAN_ERR_BUDGET;
+        *max_out_rows = std::max(*max_out_rows, m.seq_len - m.vis_len + m.keep);
+    }
+    return VSCAN_OK;
+}
+
+int vscan_llm_prune_fused_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
+                                 const vscan_seq_meta *meta_device, void *hidden, const void *w_q,
+                                 const void *w_k_t, int32_t *kept_idx, void *hidden_out,
+                                 float *scores_out, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+    if (!d) return VSCAN_ERR_NULL;
+    if (d->struct_size != sizeof(vscan_llm_desc)) return VSCAN_ERR_VERSION;
+    vscan_llm_desc caps = *d;  // lengths are capacities; vis_start has no meaning
+    caps.vis_start = 0;
+    FusedPlan p;
+    const int rc = plan_fused(&caps, &p);
+    if (rc != VSCAN_OK) return rc;
+    int max_out_rows = 0;
+    const int rc2 = check_seq_meta(d, meta_host, meta_device, &max_out_rows);
+    if (rc2 != VSCAN_OK) return rc2;
+    return run_llm_fused(&caps, p, reinterpret_cast<const SeqMeta *>(meta_device), max_out_rows,
+                         d->seq_len, hidden, w_q, w_k_t, kept_idx, hidden_out, scores_out,
+                         workspace, workspace_bytes, stream);
 }
 
 int vscan_profile_enable(int on) {

@@ -65,12 +65,15 @@ struct ProbQ {
     GemmDims d;
     const char *hidden, *w_q;
     int Tq, S, q_row0, row_bytes;  // row_bytes = Dh * 2
+    const SeqMeta *meta;           // ragged batch: the queries are a sequence's own last rows
+    __device__ int rows_s(int) const { return d.rows_s; }
     __device__ const char *s_base(int) const { return w_q; }
     __device__ uint32_t s_off(int n) const { return (uint32_t)n * (uint32_t)row_bytes; }
     __device__ const char *p_base(int, int) const { return hidden; }
     __device__ uint32_t p_off(int m) const {
         const int b = m / Tq, t = m - b * Tq;
-        return (uint32_t)(b * S + q_row0 + t) * (uint32_t)row_bytes;
+        const int first = meta ? meta[b].seq_len - Tq : q_row0;
+        return (uint32_t)(b * S + first + t) * (uint32_t)row_bytes;
     }
     __device__ void emit(int ks, int z, int p, int s_row, float v) const {
         emit_partial(d, ks, z, p, s_row, v);
@@ -84,6 +87,7 @@ struct ProbQt {
     const char *q_planes, *w_k_t;
     int Tq, group, dh, Hq, Hkv;
     int64_t plane_bytes;  // B*Tq*Hq*dh*2
+    __device__ int rows_s(int) const { return d.rows_s; }
     __device__ const char *s_base(int g) const { return w_k_t + (int64_t)g * dh * 2; }
     __device__ uint32_t s_off(int c) const { return (uint32_t)c * (uint32_t)(Hkv * dh * 2); }
     __device__ const char *p_base(int g, int pl) const {
@@ -116,8 +120,14 @@ struct ProbLogit {
     const char *hidden, *qt_planes;
     int Tq, group, S, k0, row_bytes, Mg;  // Mg = B*group*Tq rows of qt per kv head
     int64_t plane_bytes;                  // Hkv*Mg*Dh*2
+    const SeqMeta *meta;                  // ragged batch: key domain of sequence b from meta[b]
+    int domain_all;
+    __device__ int rows_s(int b) const {
+        return meta ? (domain_all ? meta[b].seq_len : meta[b].vis_len) : d.rows_s;
+    }
     __device__ const char *s_base(int b) const {
-        return hidden + ((int64_t)b * S + k0) * row_bytes;
+        const int first = meta ? (domain_all ? 0 : meta[b].vis_start) : k0;
+        return hidden + ((int64_t)b * S + first) * row_bytes;
     }
     __device__ uint32_t s_off(int j) const { return (uint32_t)j * (uint32_t)row_bytes; }
     __device__ const char *p_base(int b, int pl) const {
@@ -159,6 +169,8 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
     const int s_tile = item % d.s_tiles, rest = item / d.s_tiles;
     const int ptile = rest / d.ksplit, ks = rest - ptile * d.ksplit;
     const int s0 = s_tile * TS, p0 = ptile * TP;
+    const int rows_s = pr.rows_s(z);  // this batch entry's own count (d.rows_s is the capacity)
+    if (s0 >= rows_s) return;         // the whole workgroup: nothing of this tile exists
     const int nchunks = (d.k_bytes + kChunkBytes - 1) / kChunkBytes;
     const int cps = (nchunks + d.ksplit - 1) / d.ksplit;
     const int c_begin = ks * cps, c_end = min(nchunks, c_begin + cps);
@@ -171,7 +183,7 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
     uint32_t s_off[NS], p_off[NP];
 #pragma unroll
     for (int i = 0; i < NS; ++i)
-        s_off[i] = pr.s_off(min(s0 + srow + ROWS_PER_PASS * i, d.rows_s - 1));
+        s_off[i] = pr.s_off(min(s0 + srow + ROWS_PER_PASS * i, rows_s - 1));
 #pragma unroll
     for (int i = 0; i < NP; ++i)
         p_off[i] = pr.p_off(min(p0 + srow + ROWS_PER_PASS * i, d.rows_p - 1));
@@ -249,7 +261,7 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
 #pragma unroll
     for (int j = 0; j < FS; ++j) {
         const int s_out = s0 + (ws * FS + j) * 32 + (lane & 31);
-        if (s_out >= d.rows_s) continue;
+        if (s_out >= rows_s) continue;
 #pragma unroll
         for (int i = 0; i < FP; ++i)
 #pragma unroll
@@ -322,15 +334,22 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
 __device__ __forceinline__ int row_keys(int r, int nk, int Tq, int causal) {
     return causal ? nk - (Tq - 1 - r % Tq) : nk;
 }
+// Keys in the domain of sequence b: from the table of a ragged batch, else the common count.
+// (With `causal` the domain is the whole sequence.)
+__device__ __forceinline__ int domain_keys(const SeqMeta *meta, int b, int causal, int nk) {
+    return meta ? (causal ? meta[b].seq_len : meta[b].vis_len) : nk;
+}
 
 template <int THREADS, int NREG>
 __global__ __launch_bounds__(THREADS) void fused_softmax_kernel(float *__restrict__ c, int ksplit,
-                                                                int64_t ks_stride, int nk,
-                                                                float scale, int Tq, int causal) {
+                                                                int64_t ks_stride, int nk_cap,
+                                                                float scale, int Tq, int causal,
+                                                                const SeqMeta *meta) {
     __shared__ float red[16];
     const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-    float *l = c + row * nk;
+    float *l = c + row * nk_cap;
     const int tid = threadIdx.x;
+    const int nk = domain_keys(meta, blockIdx.y, causal, nk_cap);
     const int nv = row_keys(blockIdx.x, nk, Tq, causal);
     float v[NREG];
 #pragma unroll
@@ -360,11 +379,13 @@ __global__ __launch_bounds__(THREADS) void fused_softmax_kernel(float *__restric
 
 // Rows too long for the register form: three passes over the row.
 __global__ __launch_bounds__(1024) void fused_softmax_long_kernel(float *__restrict__ c, int ksplit,
-                                                                  int64_t ks_stride, int nk,
-                                                                  float scale, int Tq, int causal) {
+                                                                  int64_t ks_stride, int nk_cap,
+                                                                  float scale, int Tq, int causal,
+                                                                  const SeqMeta *meta) {
     __shared__ float red[16];
     const int64_t row = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-    float *l = c + row * nk;
+    float *l = c + row * nk_cap;
+    const int nk = domain_keys(meta, blockIdx.y, causal, nk_cap);
     const int nv = row_keys(blockIdx.x, nk, Tq, causal);
     float m = -INFINITY;
     for (int j = threadIdx.x; j < nv; j += 1024) {
@@ -385,28 +406,35 @@ __global__ __launch_bounds__(1024) void fused_softmax_long_kernel(float *__restr
 // part[b][j] = sum over the query rows of the softmax weight of visual token j (Eq. 5 before
 // the division by the number of rows).  A workgroup owns 64 keys; its four waves take every
 // fourth row and their sums are added in wave order.
-__global__ __launch_bounds__(256) void fused_colsum_kernel(const float *__restrict__ p, int R, int nk,
-                                                           int vis_off, int V,
+__global__ __launch_bounds__(256) void fused_colsum_kernel(const float *__restrict__ p, int R,
+                                                           int nk_cap, int vis_off, int V_cap,
+                                                           int causal, const SeqMeta *meta,
                                                            float *__restrict__ part) {
     __shared__ float red[4][64];
     const int b = blockIdx.y;
+    const int nk = domain_keys(meta, b, causal, nk_cap);
+    int V = V_cap;
+    if (meta) {
+        V = meta[b].vis_len;
+        vis_off = causal ? meta[b].vis_start : 0;
+    }
     const int j = blockIdx.x * 64 + lane_id();
-    const float *col = p + (int64_t)b * R * nk + min(j, nk - 1);
+    const float *col = p + (int64_t)b * R * nk_cap + min(j, nk - 1);
     float acc = 0.f;
     int r = wave_id();
     for (; r + 28 < R; r += 32) {
         float t[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = col[(int64_t)(r + 4 * u) * nk];
+        for (int u = 0; u < 8; ++u) t[u] = col[(int64_t)(r + 4 * u) * nk_cap];
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += t[u];
     }
-    for (; r < R; r += 4) acc += col[(int64_t)r * nk];
+    for (; r < R; r += 4) acc += col[(int64_t)r * nk_cap];
     red[wave_id()][lane_id()] = acc;
     __syncthreads();
     const int t = j - vis_off;
     if (wave_id() == 0 && j < nk && t >= 0 && t < V)
-        part[(int64_t)b * V + t] =
+        part[(int64_t)b * V_cap + t] =
             ((red[0][lane_id()] + red[1][lane_id()]) + red[2][lane_id()]) + red[3][lane_id()];
 }
 
@@ -442,6 +470,7 @@ hipError_t launch_fused_q(const FusedArgs &a, hipStream_t s) {
     pr.Tq = a.Tq;
     pr.S = a.S;
     pr.q_row0 = a.q_row0;
+    pr.meta = a.meta;
     pr.row_bytes = a.Dh * 2;
     return launch_gemm(pr, 1, s);
 }
@@ -490,6 +519,8 @@ hipError_t launch_logits(const FusedArgs &a, hipStream_t s) {
     pr.row_bytes = a.Dh * 2;
     pr.Mg = a.B * group * a.Tq;
     pr.plane_bytes = (int64_t)a.Hkv * pr.Mg * a.Dh * 2;
+    pr.meta = a.meta;
+    pr.domain_all = a.causal;
     return launch_gemm(pr, a.B, s);
 }
 
@@ -504,7 +535,7 @@ hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
     const dim3 grid(R, a.B);
 #define VSCAN_SOFTMAX(T, N)                                                                      \
     hipLaunchKernelGGL((fused_softmax_kernel<T, N>), grid, dim3(T), 0, s, a.c_l, a.ks_l, ks_stride, \
-                       a.nk, a.scale, a.Tq, a.causal)
+                       a.nk, a.scale, a.Tq, a.causal, a.meta)
     if (a.nk <= 256)
         VSCAN_SOFTMAX(256, 1);
     else if (a.nk <= 1024)
@@ -515,14 +546,14 @@ hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
         VSCAN_SOFTMAX(1024, 16);
     else
         hipLaunchKernelGGL(fused_softmax_long_kernel, grid, dim3(1024), 0, s, a.c_l, a.ks_l,
-                           ks_stride, a.nk, a.scale, a.Tq, a.causal);
+                           ks_stride, a.nk, a.scale, a.Tq, a.causal, a.meta);
 #undef VSCAN_SOFTMAX
     return hipGetLastError();
 }
 
 hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(fused_colsum_kernel, dim3((a.nk + 63) / 64, a.B), dim3(256), 0, s, a.c_l,
-                       a.Hq * a.Tq, a.nk, a.vis_start - a.k0, a.V, a.part);
+                       a.Hq * a.Tq, a.nk, a.vis_start - a.k0, a.V, a.causal, a.meta, a.part);
     return hipGetLastError();
 }
 

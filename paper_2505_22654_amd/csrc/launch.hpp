@@ -111,6 +111,10 @@ struct FusedArgs {
     int B, S, Dh, Hq, Hkv, dh, Tq, vis_start, V, k0, nk;
     int q_row0;                // first of the Tq query rows of a sequence
     int causal;                // query position t sees all but the last Tq-1-t keys of the domain
+    // ragged batch (device table, else NULL): a sequence's query rows are its own last Tq rows,
+    // its key domain is its visual span, or with `causal` its whole length; S, V, nk are then
+    // capacities (tensor strides)
+    const SeqMeta *meta = nullptr;
     int ks_q, ks_l;            // shares of the contraction axis (fused_ksplit)
     float scale;
 };

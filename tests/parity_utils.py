@@ -297,3 +297,51 @@ def screened_encoder_fused_case(shape, seed, logit_gain=1.0, with_local=False, m
         if gap > MARGIN:
             return inp, loc, ref, {"seed": seed + attempt, "attempts": attempt + 1, "gap": gap}
     raise AssertionError(f"no seed in {max_tries} tries clears the boundary margin")
+
+
+def ragged_fused_case(base, seqs, seed):
+    """A ragged batch for the stage-2 form that scores from hidden states.  `seqs`: list of
+    (prefix, vis_len, text, keep).  One set of weights; every sequence is generated and screened
+    on its own (batch-1 shapes) and padded with noise to the common capacity."""
+    from dataclasses import replace
+    cap_S = max(p + v + t for p, v, t, _ in seqs)
+    cap_V = max(v for _, v, _, _ in seqs)
+    caps = replace(base, batch=len(seqs), prefix=0, vis_len=cap_V, text=cap_S - cap_V,
+                   keep=max(kp for *_, kp in seqs))
+    rng = np.random.default_rng(seed)
+    w = wl.llm_weights(base, seed)
+    hidden = wl._finish(rng.standard_normal((len(seqs), cap_S, base.hidden)).astype(np.float32),
+                        base.dtype)
+    meta, refs = [], []
+    for b, (p, v, t, kp) in enumerate(seqs):
+        one = replace(base, batch=1, prefix=p, vis_len=v, text=t, keep=kp)
+        for attempt in range(32):
+            item = wl.llm_inputs(one, seed + 100 * b + attempt)["hidden"]
+            ref = vo.llm_prune_fused(one, item, w["w_q"], w["w_k"])
+            if topk_boundary_gap(ref["scores"], kp) > MARGIN:
+                break
+        else:
+            raise AssertionError("no seed clears the boundary margin")
+        hidden[b, :one.seq_len] = item[0]
+        meta.append((one.seq_len, p, v, kp))
+        refs.append(ref)
+    return caps, meta, {"hidden": hidden, "w_q": w["w_q"], "w_k": w["w_k"]}, refs
+
+
+def check_fused_ragged(caps, meta, inp, refs, out, in_place, what=""):
+    kept = to_host(out["kept_idx"])
+    scores = to_host(out["scores"])
+    got = to_host(out["hidden"])
+    worst = 0.0
+    for b, (S, vs, V, kp) in enumerate(meta):
+        ref = refs[b]
+        assert np.array_equal(kept[b, :kp], ref["kept"][0]), f"{what}[{b}]: kept indices differ"
+        assert np.all(kept[b, kp:] == -1), f"{what}[{b}]: index padding"
+        worst = max(worst, check_scores(scores[b:b + 1, :V], ref["scores"], f"{what}[{b}]"))
+        So = S - V + kp
+        assert np.array_equal(got[b, :So], ref["hidden"][0]), f"{what}[{b}]: hidden"
+        if in_place:
+            assert np.array_equal(got[b, S:], inp["hidden"][b, S:]), f"{what}[{b}]: padding rows"
+        else:
+            assert not got[b, So:].any(), f"{what}[{b}]: rows past the result were written"
+    return {"score_rel_err": worst}

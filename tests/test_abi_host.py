@@ -259,6 +259,25 @@ def test_fused_entry_points_validate_on_the_host():
     assert _fused_enc_call(vb.encoder_desc(bf(_enc_shape(batch=0)))) == vb.VSCAN_OK
 
 
+def test_fused_ragged_validates_the_table_on_the_host():
+    desc = vb.llm_desc(dataclasses.replace(_llm_shape(batch=2), dtype=wl.BF16))
+
+    def call(rows, meta_dev=FAKE, hidden=FAKE, ho=FAKE, ws=FAKE):
+        host = (ctypes.c_int32 * (4 * max(len(rows), 1)))(*[x for r in rows for x in r])
+        return vb.lib().vscan_llm_prune_fused_ragged(ctypes.byref(desc), host, meta_dev, hidden, FAKE,
+                                                     FAKE, FAKE, ho, None, ws, 1 << 40, None)
+    good = (139, 35, 64, 32)
+    assert call([good, (140, 35, 64, 32)]) == vb.VSCAN_ERR_SHAPE     # longer than the capacity
+    assert call([good, (139, 35, 65, 32)]) == vb.VSCAN_ERR_SHAPE     # span beyond the capacity
+    assert call([good, (99, 35, 64, 32)]) == vb.VSCAN_ERR_SHAPE      # span and query overlap
+    assert call([good, (139, 35, 64, 33)]) == vb.VSCAN_ERR_BUDGET    # budget beyond the capacity
+    assert call([good, good], meta_dev=None) == vb.VSCAN_ERR_NULL
+    assert call([good, good], meta_dev=FAKE + 2) == vb.VSCAN_ERR_ALIGN
+    assert call([good, good], hidden=None) == vb.VSCAN_ERR_NULL
+    assert call([good, good], ho=None) == vb.VSCAN_ERR_NULL
+    assert call([good, good], ws=None) == vb.VSCAN_ERR_WORKSPACE
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(vb, "_lib", None)
     monkeypatch.setattr(vb, "LIB_PATH", "/nonexistent/libvscan.so")

@@ -193,6 +193,50 @@ def test_fused_config5_full():
             print("cfg5 fused keep", keep, "sequence", b, "score_rel_err", err)
 
 
+RAGGED_SEQS = [
+    # (prefix, vis_len, text, keep): long and short spans, nothing kept, everything kept, a span
+    # shorter than one tile, the longest sequence not the one with the longest span
+    (35, 600, 70, 200), (3, 5, 9, 2), (0, 333, 41, 0), (12, 257, 300, 257), (7, 700, 13, 1),
+    (20, 64, 20, 63), (1, 130, 4, 30), (9, 40, 6, 11), (2, 300, 3, 150),
+]
+
+
+@pytest.mark.parametrize("variant", ["plain", "in-place-queries", "all-keys-gqa"])
+def test_fused_ragged(variant):
+    """Per-sequence lengths, spans and budgets in one call, each sequence against the oracle run
+    on that sequence alone (nine sequences: each stays on one XCD)."""
+    import torch
+    base = {
+        "plain": _shape(hidden=256, q_heads=4, kv_heads=4, head_dim=32),
+        "in-place-queries": _shape(in_place=1, n_query=2, hidden=136, q_heads=4, kv_heads=4, head_dim=32),
+        "all-keys-gqa": _shape(softmax_domain=1, n_query=3, q_heads=8, kv_heads=2, head_dim=16,
+                               hidden=128),
+    }[variant]
+    seqs = [(p, v, max(t, base.n_query), k) for p, v, t, k in RAGGED_SEQS]
+    caps, meta, inp, refs = pu.ragged_fused_case(base, seqs, seed=9900 + len(variant))
+    h, wq = pu.to_device(inp["hidden"], wl.BF16), pu.to_device(inp["w_q"], wl.BF16)
+    wkt = pu.to_device(np.ascontiguousarray(inp["w_k"].T), wl.BF16)
+    out = vb.llm_prune_fused_ragged(caps, meta, h, wq, wkt, want_scores=True)
+    torch.cuda.synchronize()
+    print(variant, pu.check_fused_ragged(caps, meta, inp, refs, out, caps.in_place, variant))
+
+
+def test_fused_ragged_matches_uniform():
+    import torch
+    shape = _shape(batch=4, prefix=9, vis_len=400, text=33, keep=100, n_query=2, hidden=128,
+                   q_heads=4, kv_heads=2, head_dim=32)
+    inp, ref, info = pu.screened_fused_case(shape, 9950)
+    dev = lambda: (pu.to_device(inp["hidden"], wl.BF16), pu.to_device(inp["w_q"], wl.BF16),
+                   pu.to_device(np.ascontiguousarray(inp["w_k"].T), wl.BF16))
+    uni = vb.llm_prune_fused(shape, *dev(), want_scores=True)
+    meta = [(shape.seq_len, shape.vis_start, shape.vis_len, shape.keep)] * shape.batch
+    rag = vb.llm_prune_fused_ragged(shape, meta, *dev(), want_scores=True)
+    torch.cuda.synchronize()
+    assert torch.equal(uni["kept_idx"], rag["kept_idx"]) and torch.equal(uni["scores"], rag["scores"])
+    assert torch.equal(uni["hidden"], rag["hidden"][:, :shape.seq_out])
+    print("ragged == uniform", info, pu.check_fused(shape, ref, uni, "uniform"))
+
+
 # ---- stage 1 scored from the layer's input rows and projection weights -------------------------
 
 def _run_encoder(shape, inp, loc=None):
