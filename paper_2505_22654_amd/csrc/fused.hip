@@ -280,9 +280,14 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
 struct TileShape {
     int ts, tp, ch;
 };
-TileShape tile_shape(int rows_p) {
-    if (rows_p <= 32) return {256, 32, 128};
-    if (rows_p <= 64) return {256, 64, 128};
+TileShape tile_shape(int rows_p, int rows_s, int Z) {
+    if (rows_p <= 64) {
+        // few plane rows: 256 streamed rows per workgroup when that still leaves a workgroup or
+        // two per compute unit, else 128 (twice the workgroups, each with half the rows in flight)
+        const int tp = rows_p <= 32 ? 32 : 64;
+        const int64_t tiles = (int64_t)((rows_s + 255) / 256) * Z;
+        return {tiles >= kTargetWorkgroups ? 256 : 128, tp, 128};
+    }
     if (rows_p <= 128) return {256, 128, 128};
     return {256, 256, 128};
 }
@@ -290,7 +295,7 @@ TileShape tile_shape(int rows_p) {
 template <class Prob>
 hipError_t launch_gemm(Prob pr, int Z, hipStream_t s) {
     GemmDims &d = pr.d;
-    const TileShape t = tile_shape(d.rows_p);
+    const TileShape t = tile_shape(d.rows_p, d.rows_s, Z);
     d.Z = Z;
     d.s_tiles = (d.rows_s + t.ts - 1) / t.ts;
     d.p_tiles = (d.rows_p + t.tp - 1) / t.tp;
@@ -298,14 +303,21 @@ hipError_t launch_gemm(Prob pr, int Z, hipStream_t s) {
     // through that XCD's L2
     d.affine = Z >= kXcds;
     const dim3 grid(image_affine_grid(Z, d.s_tiles * d.p_tiles * d.ksplit, d.affine != 0));
-    if (t.tp == 32)
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4, 1, 2, 1, 128>), grid, dim3(256), 0, s, pr);
+#define VSCAN_GEMM(WS, WP, FS, FP, CH) \
+    hipLaunchKernelGGL((nt_gemm_kernel<Prob, WS, WP, FS, FP, CH>), grid, dim3(64 * WS * WP), 0, s, pr)
+    if (t.tp == 32 && t.ts == 128)
+        VSCAN_GEMM(4, 1, 1, 1, 128);
+    else if (t.tp == 32)
+        VSCAN_GEMM(4, 1, 2, 1, 128);
+    else if (t.tp == 64 && t.ts == 128)
+        VSCAN_GEMM(4, 1, 1, 2, 128);
     else if (t.tp == 64)
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 4, 1, 2, 2, 128>), grid, dim3(256), 0, s, pr);
+        VSCAN_GEMM(4, 1, 2, 2, 128);
     else if (t.tp == 128)
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2, 2, 4, 2, 128>), grid, dim3(256), 0, s, pr);
+        VSCAN_GEMM(2, 2, 4, 2, 128);
     else
-        hipLaunchKernelGGL((nt_gemm_kernel<Prob, 2, 4, 4, 2, 128>), grid, dim3(512), 0, s, pr);
+        VSCAN_GEMM(2, 4, 4, 2, 128);
+#undef VSCAN_GEMM
     return hipGetLastError();
 }
 
@@ -453,7 +465,7 @@ GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
 }  // namespace
 
 int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems) {
-    const TileShape t = tile_shape(rows_p);
+    const TileShape t = tile_shape(rows_p, rows_s, Z);
     const int64_t tiles = std::max<int64_t>(
         1, (int64_t)((rows_s + t.ts - 1) / t.ts) * ((rows_p + t.tp - 1) / t.tp) * Z);  // empty batch: 1
     const int nchunks = (k_elems * 2 + t.ch - 1) / t.ch;
