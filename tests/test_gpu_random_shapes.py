@@ -116,3 +116,49 @@ def test_random_fused_encoder_shapes():
     _sweep(lambda r: _encoder_shape(r, fused=True),
            lambda s, seed: pu.screened_encoder_fused_case(s, seed, 0.25, max_tries=4), run,
            lambda s, case, out: pu.check_encoder(s, case[0], case[2], out, str(s)))
+
+
+def test_random_encoder_shapes_with_shallow_layer_pair():
+    def run(shape, case):
+        inp, loc = case[0], case[1]
+        q, k, x = (pu.to_device(inp[n], shape.dtype) for n in ("q", "k", "x"))
+        ql, kl = pu.to_device(loc["q"], shape.dtype), pu.to_device(loc["k"], shape.dtype)
+        out = vb.encoder_reduce(shape, q, k, x, ql, kl, want_assign=True, want_scores=True)
+        _sync()
+        return out
+    _sweep(_encoder_shape,
+           lambda s, seed: pu.screened_encoder_case(s, seed, 0.25, with_local=True, max_tries=4), run,
+           lambda s, case, out: pu.check_encoder(s, case[0], case[2], out, str(s)))
+
+
+def _ragged_draw(r, fused):
+    base = _llm_shape(r, fused)
+    seqs = []
+    for _ in range(int(r.integers(2, 7))):
+        vis = int(r.integers(1, 400))
+        seqs.append((int(r.integers(0, 10)), vis, base.n_query + int(r.integers(0, 20)),
+                     int(r.integers(0, vis + 1))))
+    return base, seqs
+
+
+def test_random_ragged_batches():
+    """Random per-sequence lengths, spans and budgets through both ragged entry points."""
+    import torch
+    r = np.random.default_rng(20250523)
+    for i in range(16):
+        fused = i % 2 == 1
+        base, seqs = _ragged_draw(r, fused)
+        print("ragged", i, "fused" if fused else "qk", base, seqs, flush=True)
+        if fused:
+            caps, meta, inp, refs = pu.ragged_fused_case(base, seqs, seed=33000 + 53 * i)
+            out = vb.llm_prune_fused_ragged(
+                caps, meta, pu.to_device(inp["hidden"], wl.BF16), pu.to_device(inp["w_q"], wl.BF16),
+                pu.to_device(np.ascontiguousarray(inp["w_k"].T), wl.BF16), want_scores=True)
+            torch.cuda.synchronize()
+            pu.check_fused_ragged(caps, meta, inp, refs, out, caps.in_place, f"ragged {i}")
+        else:
+            caps, meta, inp, refs = pu.ragged_llm_case(base, seqs, seed=33000 + 53 * i)
+            q, k, v, h = (pu.to_device(inp[n], caps.dtype) for n in ("q", "k", "v", "hidden"))
+            out = vb.llm_prune_ragged(caps, meta, q, k, v, h, want_scores=True)
+            torch.cuda.synchronize()
+            pu.check_llm_ragged(caps, meta, inp, refs, out, caps.in_place, f"ragged {i}")
