@@ -1,10 +1,13 @@
 """ctypes front end of the CPU oracle (oracle/vscan_oracle.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
-benchmark's CPU-baseline leg, never by the product path.  It contains no
-arithmetic of its own beyond chaining the C functions in the paper's order
-(Sec. 4.1: score -> local/global select -> assign -> merge; Sec. 4.2: score ->
-top-k -> compaction); it marshals numpy arrays.
+benchmark's CPU-baseline leg, never by the product path.  It marshals numpy
+arrays and chains the C functions in the paper's order (Sec. 4.1: score ->
+local/global select -> assign -> merge; Sec. 4.2: score -> top-k -> compaction).
+Its own arithmetic is limited to the two functions that write Eq. 1 and Eq. 5 out
+from hidden states and projection weights (`encoder_scores_from_hidden`,
+`llm_scores_from_hidden`: project, softmax, head mean, in numpy fp64), pinned
+in tests/test_oracle_pins.py by closed forms and against the C functions.
 """
 from __future__ import annotations
 
