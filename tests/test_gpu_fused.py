@@ -304,3 +304,78 @@ def test_fused_encoder_config2_shape():
     print("case", info, flush=True)
     out = _run_encoder(shape, inp)
     print("cfg2 stage-1 shape", pu.check_encoder(shape, inp, ref, out, "cfg2 fused encoder"))
+
+
+def test_both_forms_replay_from_a_captured_graph():
+    """The entry points allocate nothing, never synchronise and clear their own scratch words, so
+    a call sequence can be captured once and replayed: three replays on fresh inputs, with eager
+    work in between, each bit-identical to the eager calls on the same inputs."""
+    import torch
+    enc = _enc(batch=3, n_segments=2, grid_h=13, grid_w=11, heads=3, head_dim=40, feat_dim=200,
+               win_rows=3, win_cols=2, keep_global=17, keep_local=13)
+    llm = _shape(batch=3, vis_len=300, hidden=264, keep=100, n_query=2, q_heads=8, kv_heads=4,
+                 head_dim=32)
+
+    def host(trial):
+        e = wl.encoder_inputs(enc, 4100 + trial, 0.25)
+        l = wl.llm_inputs(llm, 4200 + trial)
+        w = wl.llm_weights(llm, 4200 + trial)
+        return {"eq": e["q"], "ek": e["k"], "ex": e["x"], "lq": l["q"], "lk": l["k"], "lv": l["v"],
+                "lh": l["hidden"], "wq": w["w_q"], "wkt": np.ascontiguousarray(w["w_k"].T)}
+
+    dev = {n: pu.to_device(a, wl.BF16) for n, a in host(0).items()}
+
+    def outputs():
+        z = lambda shape, dt: torch.zeros(shape, dtype=dt, device="cuda")
+        bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+        So = llm.seq_out
+        return ({"kept_idx": z((enc.batch, enc.keep), i32), "merged": z((enc.batch, enc.keep, enc.feat_dim), bf),
+                 "assign": z((enc.batch, enc.tokens_per_image), i32),
+                 "scores": z((enc.batch, enc.tokens_per_image), f32)},
+                {"kept_idx": z((llm.batch, llm.keep), i32), "scores": z((llm.batch, llm.vis_len), f32),
+                 "k": z((llm.batch, llm.kv_heads, So, llm.head_dim), bf),
+                 "v": z((llm.batch, llm.kv_heads, So, llm.head_dim), bf),
+                 "hidden": z((llm.batch, So, llm.hidden), bf)},
+                {"kept_idx": z((llm.batch, llm.keep), i32), "scores": z((llm.batch, llm.vis_len), f32),
+                 "hidden": z((llm.batch, So, llm.hidden), bf)})
+
+    ws = [torch.empty(n, dtype=torch.uint8, device="cuda") for n in (
+        vb.encoder_workspace_size(vb.encoder_desc(enc)), vb.llm_workspace_size(vb.llm_desc(llm)),
+        vb.llm_fused_workspace_size(vb.llm_desc(llm)))]
+
+    def calls(outs):
+        vb.encoder_reduce(enc, dev["eq"], dev["ek"], dev["ex"], want_assign=True, want_scores=True,
+                          workspace=ws[0], out=outs[0])
+        vb.llm_prune(llm, dev["lq"], dev["lk"], dev["lv"], dev["lh"], want_scores=True,
+                     workspace=ws[1], out=outs[1])
+        vb.llm_prune_fused(llm, dev["lh"], dev["wq"], dev["wkt"], want_scores=True,
+                           workspace=ws[2], out=outs[2])
+
+    graph_out = outputs()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        calls(graph_out)                      # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        calls(graph_out)
+    torch.cuda.synchronize()
+
+    for trial in range(1, 4):
+        for n, a in host(trial).items():
+            dev[n].copy_(pu.to_device(a, wl.BF16))
+        for o in graph_out:                   # stale results must not pass for fresh ones
+            for t in o.values():
+                if torch.is_tensor(t):
+                    t.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        eager_out = outputs()
+        calls(eager_out)
+        torch.cuda.synchronize()
+        for got, want in zip(graph_out, eager_out):
+            for name in want:
+                if torch.is_tensor(want[name]) and name != "workspace":
+                    assert torch.equal(got[name], want[name]), (trial, name)
+        assert int(eager_out[1]["kept_idx"].max()) > 0
