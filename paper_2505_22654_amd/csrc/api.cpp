@@ -133,7 +133,7 @@ int plan_fused_scratch(int64_t seqs, int S, int hidden, int q_heads, int kv_head
     const int64_t Dh = hidden, N = (int64_t)q_heads * head_dim, R = (int64_t)q_heads * n_query;
     if (seqs * S * Dh * 2 >= lim || N * Dh * 2 >= lim || Dh * kv_heads * head_dim * 2 >= lim ||
         seqs * n_query * N * 2 >= lim || seqs * R * Dh * 2 >= lim || seqs * R > (1 << 24) ||
-        R > 65535 || seqs > (1 << 24))
+        R > 65535 || seqs > 65535)  // sequences and query rows index the softmax grid
         return VSCAN_ERR_UNSUPPORTED;
     const int M = (int)(seqs * n_query);
     f->ks_q = fused_ksplit((int)N, M, 1, hidden);
