@@ -263,7 +263,10 @@ def cpu_baseline(points, hosts, budget_s=12.0, inputs: str = "qk"):
 def kernel_source_digest(kernel: str) -> str:
     """sha256 over the kernel's source file and the headers every kernel includes."""
     h = hashlib.sha256()
-    for name in (KERNEL_SOURCE[kernel], "common.hpp", "launch.hpp"):
+    names = [KERNEL_SOURCE[kernel], "common.hpp", "launch.hpp"]
+    if KERNEL_SOURCE[kernel] == "fused.hip":
+        names.append("fused.hpp")
+    for name in names:
         with open(os.path.join(ROOT, "paper_2505_22654_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()

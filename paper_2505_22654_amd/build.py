@@ -12,7 +12,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvscan.so")
 
 SOURCES = ["api.cpp", "budget.cpp", "encoder_score.hip", "select.hip", "sim_merge.hip", "llm.hip", "fused.hip"]
-HEADERS = ["common.hpp", "launch.hpp", os.path.join("..", "..", "include", "vscan.h")]
+HEADERS = ["common.hpp", "launch.hpp", "fused.hpp", os.path.join("..", "..", "include", "vscan.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -10,6 +10,7 @@
 #include <mutex>
 #include <vector>
 
+#include "fused.hpp"
 #include "launch.hpp"
 
 namespace {

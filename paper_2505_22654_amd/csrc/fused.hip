@@ -33,6 +33,7 @@
 #include <algorithm>
 
 #include "common.hpp"
+#include "fused.hpp"
 #include "launch.hpp"
 
 namespace vscan {

@@ -96,35 +96,4 @@ struct CompactArgs {
 };
 hipError_t launch_compact(const CompactArgs &a, hipStream_t s);
 
-// stage 2 scored from hidden states and projection weights (Eq. 5 as written), bf16 only
-constexpr int kFusedQtPlanes = 3;  // bf16 planes carrying the hidden-space query (all 24 bits)
-struct FusedArgs {
-    const void *hidden;        // [B, S, Dh]; visual tokens are rows vis_start .. vis_start+V
-    const void *w_q;           // [Hq*dh, Dh]   rows = output features
-    const void *w_k_t;         // [Dh, Hkv*dh]  rows = input features
-    float *c_q;                // [ks_q][B*Tq][Hq*dh] partial sums of q
-    uint16_t *q_planes;        // [3][B*Tq][Hq*dh] bf16
-    uint16_t *qt_planes;       // [kFusedQtPlanes][Hkv][B*(Hq/Hkv)*Tq][Dh] bf16
-    float *c_l;                // [ks_l][B][Hq*Tq][nk] partial sums of the unscaled logits; the
-                               // first slot becomes the softmax weights
-    float *part;               // [B][V] sums over the query rows
-    int B, S, Dh, Hq, Hkv, dh, Tq, vis_start, V, k0, nk;
-    int q_row0;                // first of the Tq query rows of a sequence
-    int causal;                // query position t sees all but the last Tq-1-t keys of the domain
-    // ragged batch (device table, else NULL): a sequence's query rows are its own last Tq rows,
-    // its key domain is its visual span, or with `causal` its whole length; S, V, nk are then
-    // capacities (tensor strides)
-    const SeqMeta *meta = nullptr;
-    int ks_q, ks_l;            // shares of the contraction axis (fused_ksplit)
-    float scale;
-};
-// shares of the contraction axis for a contraction of Z problems of rows_s x rows_p outputs
-int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems);
-hipError_t launch_fused_q(const FusedArgs &a, hipStream_t s);
-hipError_t launch_fused_split_q(const FusedArgs &a, hipStream_t s);
-hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s);
-hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s);
-hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s);
-hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s);
-
 }  // namespace vscan
