@@ -252,7 +252,8 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
 // counter, so the order inside a list is arbitrary at this point).
 // Phase 2 (one wave per slot, spw slots one after the other): the list is sorted by token index
 // (rank by counting); a group of up to kMergeAloneCap members is added up by that wave right
-// away, one batch of row loads in flight together.
+// away, eight rows in flight at a time (a shared group costs the workgroup about 4 us of
+// barriers and serial combination, which is why groups of a few dozen are still added alone).
 // Phase 3 (whole workgroup, one larger group after the other): group sizes are heavy-tailed
 // (many dropped tokens look like the same kept token), and one wave adding dozens or hundreds
 // of rows would set the kernel's time.  The four waves share such a group: each takes a quarter
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
 // Lane l owns the 16-byte pieces l, l+64, ... of the feature row.
 // ---------------------------------------------------------------------------
 constexpr int kMergeListCap = 128;  // ints of LDS per list
-constexpr int kMergeAloneCap = 16;  // longest group that one wave adds alone (one batch of rows)
+constexpr int kMergeAloneCap = 32;  // longest group that one wave adds alone (a few batches of rows)
 constexpr int kMergeMaxSpw = 4;     // slots a wave handles one after the other, at most
 
 template <typename T, int PIECES>
@@ -273,7 +274,10 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
                                                     int32_t *__restrict__ assign_out, int T_img,
                                                     int D, int K, int B, int affine, int spw) {
     constexpr int E = ElemTraits<T>::kPer16B;
-    constexpr int BATCH = PIECES <= 2 ? 16 : 8;  // rows fetched together (register budget)
+    // rows fetched together.  Eight keep the kernel within 128 registers for rows of up to 2 KiB,
+    // so that four workgroups fit a compute unit and a launch of several hundred starts at once
+    // (measured: with 16 the third wave of workgroups started 7 us late).
+    constexpr int BATCH = 8;
     __shared__ int cnt[4 * kMergeMaxSpw];
     __shared__ int lists[4 * kMergeMaxSpw][kMergeListCap];
     __shared__ int scratch_lists[4][kMergeListCap];  // per wave, for the scans of phase 3
