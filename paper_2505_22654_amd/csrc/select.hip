@@ -239,12 +239,15 @@ __device__ __forceinline__ WindowGeom window_geom(const EncSelectArgs &a, int w)
 // Encoder selection, one workgroup per segment.
 //   WIN_MODE 0: every token ranks itself inside its own window by counting (windows of at
 //               most 256 slots: a few dozen pipelined LDS reads, no serial search)
+//   WIN_MODE 3: the same ranking for segments with one thread per token: keys are first copied
+//               window by window, so that a token reads its rivals 16 bytes at a time, and
+//               the window geometry comes from two small tables instead of divisions
 //   WIN_MODE 1: one wave per window, wave_topk_regs<NREG_W>
 //   WIN_MODE 2: windows one after the other, block_topk_regs<NREG_G>
 // Global scan: wave 0 alone when the segment fits its registers (GLOBAL_WAVE), else the block.
 // ---------------------------------------------------------------------------
 template <int WIN_MODE, int NREG_W, bool GLOBAL_WAVE, int NREG_G>
-__global__ __launch_bounds__(1024) void encoder_select_kernel(EncSelectArgs a) {
+__global__ __launch_bounds__(1024) void encoder_select_kernel(EncSelectArgs a, int win_pitch) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int N = a.gh * a.gw;
     SelectSmem &sm = *reinterpret_cast<SelectSmem *>(smem);
@@ -270,7 +273,57 @@ __global__ __launch_bounds__(1024) void encoder_select_kernel(EncSelectArgs a) {
     // ---- local scan (Eq. 3) ----
     const int nW = a.wr * a.wc;
     if (a.kw > 0) {
-        if (WIN_MODE == 0) {
+        if (WIN_MODE == 3) {
+            // LDS behind the flags: the window-major keys (`win_pitch` slots per window, unused
+            // slots zero: no real key is zero), then per grid row and per grid column the window
+            // coordinate, the offset inside the window, and the window's extent along that axis.
+            uint32_t *wk = reinterpret_cast<uint32_t *>(
+                smem + (((size_t)(flag - smem) + N + 15) & ~(size_t)15));
+            int *row_tab = reinterpret_cast<int *>(wk + nW * win_pitch);  // [gh][3]
+            int *col_tab = row_tab + 3 * a.gh;                             // [gw][3]
+            for (int i = tid; i < nW * win_pitch; i += nt) wk[i] = 0u;
+            for (int i = tid; i < a.gh + a.gw; i += nt) {
+                const bool is_row = i < a.gh;
+                const int p = is_row ? i : i - a.gh;        // position along the axis
+                const int n = is_row ? a.gh : a.gw, nwin = is_row ? a.wr : a.wc;
+                const int wi = p * nwin / n;                // window coordinate of this position
+                const int first = ceil_div(wi * n, nwin);
+                int *t = (is_row ? row_tab : col_tab) + 3 * p;
+                t[0] = wi;
+                t[1] = p - first;
+                t[2] = ceil_div((wi + 1) * n, nwin) - first;
+            }
+            __syncthreads();
+            int w = 0, slot = 0;
+            uint32_t kj = 0u;
+            if (tid < N) {
+                // tid / gw without an integer division: exact for tid < 2^20 (the half keeps the
+                // product clear of the integer boundaries)
+                const int r = (int)(((float)tid + 0.5f) * (1.0f / (float)a.gw));
+                const int col = tid - r * a.gw;
+                const int *rt = row_tab + 3 * r, *ct = col_tab + 3 * col;
+                w = rt[0] * a.wc + ct[0];
+                slot = rt[1] * ct[2] + ct[1];               // row-major inside the window
+                kj = keyl[tid];
+                wk[w * win_pitch + slot] = kj;
+            }
+            __syncthreads();
+            if (tid < N) {
+                // rank among the window's slots; row-major slot order is ascending token order,
+                // which is what ties are broken by
+                const uint4 *row = reinterpret_cast<const uint4 *>(wk + w * win_pitch);
+                int cnt = 0;
+                for (int i = 0; i < win_pitch / 4; ++i) {
+                    const uint4 k4 = row[i];
+                    const int s0 = 4 * i;
+                    cnt += (k4.x > kj) || (k4.x == kj && s0 < slot);
+                    cnt += (k4.y > kj) || (k4.y == kj && s0 + 1 < slot);
+                    cnt += (k4.z > kj) || (k4.z == kj && s0 + 2 < slot);
+                    cnt += (k4.w > kj) || (k4.w == kj && s0 + 3 < slot);
+                }
+                if (cnt < a.kw) flag[tid] = 1;
+            }
+        } else if (WIN_MODE == 0) {
             for (int j = tid; j < N; j += nt) {
                 const int r = j / a.gw, col = j - r * a.gw;
                 const WindowGeom g = window_geom(a, (r * a.wr / a.gh) * a.wc + col * a.wc / a.gw);
@@ -402,15 +455,15 @@ size_t encoder_select_lds_bytes(int N, int has_local) {
 }
 size_t llm_select_lds_bytes(int V) { return sizeof(SelectSmem) + (size_t)V * 4 + round16((size_t)V); }
 
-template <typename Kernel, typename Args>
-static hipError_t launch_select(Kernel kernel, int blocks, int threads, size_t smem, const Args &a,
-                                hipStream_t s) {
+template <typename Kernel, typename... Args>
+static hipError_t launch_select(Kernel kernel, int blocks, int threads, size_t smem, hipStream_t s,
+                                const Args &...args) {
     if (smem > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), smem, s, a);
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), smem, s, args...);
     return hipGetLastError();
 }
 
@@ -422,14 +475,22 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
     while (wcols < (a.gw + a.wc - 1) / a.wc) wcols <<= 1;
     const int win_slots = a.kw > 0 ? ((a.gh + a.wr - 1) / a.wr) * wcols : 0;
 #define VSCAN_SEL(...) \
-    return launch_select(encoder_select_kernel<__VA_ARGS__>, blocks, threads, smem, a, s)
+    return launch_select(encoder_select_kernel<__VA_ARGS__>, blocks, threads, smem, s, a, 0)
+    // WIN_MODE 3 keeps, behind the usual state, a window-major copy of the keys (pitch = slots of
+    // the largest window, in whole 16-byte reads) and the two geometry tables
+    const int win_pitch = ((((a.gh + a.wr - 1) / a.wr) * ((a.gw + a.wc - 1) / a.wc)) + 3) & ~3;
+    const size_t smem_wm = round16(sizeof(SelectSmem) + (size_t)N * 4 * (a.head_local ? 2 : 1) + N) +
+                           (size_t)a.wr * a.wc * win_pitch * 4 + (size_t)3 * (a.gh + a.gw) * 4;
+#define VSCAN_SEL_WM(...)                                                                      \
+    return launch_select(encoder_select_kernel<__VA_ARGS__>, blocks, threads, smem_wm, s, a, \
+                         win_pitch)
     if (N <= 1024) {
         // small segment: one thread per token, wave 0 does the global scan from registers
         int threads = (N + kWave - 1) / kWave * kWave;
         if (win_slots <= 128) {  // ranking by counting costs ~win_slots compares per token
-            if (N <= 256) VSCAN_SEL(0, 1, true, 4);
-            if (N <= 640) VSCAN_SEL(0, 1, true, 10);
-            VSCAN_SEL(0, 1, true, 16);
+            if (N <= 256) VSCAN_SEL_WM(3, 1, true, 4);
+            if (N <= 640) VSCAN_SEL_WM(3, 1, true, 10);
+            VSCAN_SEL_WM(3, 1, true, 16);
         }
         const int want = a.wr * a.wc * kWave;  // one wave per window where that fits
         if (want > threads) threads = want < 1024 ? want : 1024;
@@ -466,6 +527,7 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
     if (nreg_both <= 32) VSCAN_SEL(2, 1, false, 32);
     VSCAN_SEL(2, 1, false, 64);
 #undef VSCAN_SEL
+#undef VSCAN_SEL_WM
 }
 
 hipError_t launch_llm_select(const LlmSelectArgs &a, hipStream_t s) {
@@ -473,13 +535,13 @@ hipError_t launch_llm_select(const LlmSelectArgs &a, hipStream_t s) {
     if (a.V <= 1024) {
         const int threads = (a.V + kWave - 1) / kWave * kWave;
         if (a.V <= 256)
-            return launch_select(llm_select_kernel<true, 4>, a.B, threads, smem, a, s);
-        return launch_select(llm_select_kernel<true, 16>, a.B, threads, smem, a, s);
+            return launch_select(llm_select_kernel<true, 4>, a.B, threads, smem, s, a);
+        return launch_select(llm_select_kernel<true, 16>, a.B, threads, smem, s, a);
     }
     const int nreg = (a.V + 1023) / 1024;
-    if (nreg <= 4) return launch_select(llm_select_kernel<false, 4>, a.B, 1024, smem, a, s);
-    if (nreg <= 16) return launch_select(llm_select_kernel<false, 16>, a.B, 1024, smem, a, s);
-    return launch_select(llm_select_kernel<false, 32>, a.B, 1024, smem, a, s);
+    if (nreg <= 4) return launch_select(llm_select_kernel<false, 4>, a.B, 1024, smem, s, a);
+    if (nreg <= 16) return launch_select(llm_select_kernel<false, 16>, a.B, 1024, smem, s, a);
+    return launch_select(llm_select_kernel<false, 32>, a.B, 1024, smem, s, a);
 }
 
 }  // namespace vscan
