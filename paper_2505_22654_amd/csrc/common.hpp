@@ -83,16 +83,6 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
     return (1ull << lane_id()) - 1ull;
 }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-    return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
-}
 
 // Wave-wide integer sum through DPP row operations only (no LDS crossbar, no scalar
 // round-trip per step); every lane gets the total.
@@ -105,6 +95,36 @@ __device__ __forceinline__ int wave_sum_dpp(int v) {
     v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, true);  // row_bcast31 -> rows 2, 3
     return __builtin_amdgcn_readlane(v, 63);
 }
+
+// Reduction over aligned groups of G adjacent lanes (G a power of two); every lane of a group
+// gets the group's result.  Groups of up to 16 lanes use DPP row operations only (quad permutes,
+// then the half-row and row mirrors: once the lanes of a quad, or of a half row, all hold the
+// same partial result, the mirrored lane supplies the other half's); wider groups finish through
+// the LDS crossbar.  The pairs combined at every step are those of an xor butterfly, so a sum is
+// bit-identical to one.
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+template <int G, typename Op>
+__device__ __forceinline__ float group_reduce(float v, Op op) {
+    static_assert(G >= 1 && G <= 64 && (G & (G - 1)) == 0, "power of two up to the wave size");
+    if constexpr (G >= 2) v = op(v, dpp_lane<0xB1>(v));    // quad_perm [1,0,3,2]
+    if constexpr (G >= 4) v = op(v, dpp_lane<0x4E>(v));    // quad_perm [2,3,0,1]
+    if constexpr (G >= 8) v = op(v, dpp_lane<0x141>(v));   // row_half_mirror
+    if constexpr (G >= 16) v = op(v, dpp_lane<0x140>(v));  // row_mirror
+    if constexpr (G >= 32) v = op(v, __shfl_xor(v, 16, kWave));
+    if constexpr (G >= 64) v = op(v, __shfl_xor(v, 32, kWave));
+    return v;
+}
+template <int G>
+__device__ __forceinline__ float group_sum(float v) {
+    return group_reduce<G>(v, [](float a, float b) { return a + b; });
+}
+__device__ __forceinline__ float wave_max(float v) {
+    return group_reduce<kWave>(v, [](float a, float b) { return fmaxf(a, b); });
+}
+__device__ __forceinline__ float wave_sum(float v) { return group_sum<kWave>(v); }
 
 // Block-wide reductions through a small LDS buffer (>= 16 floats); every thread
 // gets the result.  Order of combination is fixed, so results are reproducible.

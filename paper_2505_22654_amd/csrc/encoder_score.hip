@@ -150,8 +150,7 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
             float part = 0.f;
 #pragma unroll
             for (int e = 0; e < E; ++e) part = fmaf(kv[e], qreg[e], part);
-#pragma unroll
-            for (int o = cpr >> 1; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
+            part = group_sum<cpr>(part);
             if (piece == 0 && p < total) z[p >> shift] = part;
         }
 #pragma unroll

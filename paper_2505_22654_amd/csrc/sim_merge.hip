@@ -201,9 +201,7 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
     // 1 / max(||x_s||, eps): add the PPR partial sums of each kept row (adjacent lanes)
 #pragma unroll
     for (int it = 0; it < A_PIECES; ++it) {
-        float v = ss[it];
-#pragma unroll
-        for (int o = PPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+        const float v = group_sum<PPR>(ss[it]);
         const int p = tid + it * THREADS;
         if (p % PPR == 0) inv_s[p / PPR] = 1.0f / fmaxf(sqrtf(v), kNormEps);
     }
