@@ -96,6 +96,19 @@ __device__ __forceinline__ int wave_sum_dpp(int v) {
     return __builtin_amdgcn_readlane(v, 63);
 }
 
+// Wave-wide unsigned maximum through DPP row operations; every lane gets the result.
+__device__ __forceinline__ uint32_t wave_umax_dpp(uint32_t x) {
+    int v = (int)x;
+    auto mx = [](int a, int b) { return (int)max((uint32_t)a, (uint32_t)b); };
+    v = mx(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+    v = mx(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true));   // quad_perm [2,3,0,1]
+    v = mx(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true));  // row_half_mirror
+    v = mx(v, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true));  // row_mirror
+    v = mx(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, true));  // row_bcast15 -> rows 1, 3
+    v = mx(v, __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, true));  // row_bcast31 -> rows 2, 3
+    return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+}
+
 // Reduction over aligned groups of G adjacent lanes (G a power of two); every lane of a group
 // gets the group's result.  Groups of up to 16 lanes use DPP row operations only (quad permutes,
 // then the half-row and row mirrors: once the lanes of a quad, or of a half row, all hold the

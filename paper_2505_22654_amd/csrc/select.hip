@@ -81,8 +81,21 @@ __device__ __forceinline__ void wave_topk_regs(SlotFn slot_fn, int nslots, int k
         const int sl = r * kWave + lane;
         if (sl < nslots) key[r] = slot_fn(sl, idx[r]);
     }
-    uint32_t T = 0;
-    for (int shift = 30; shift >= 0; shift -= 2) {
+    // The candidates' keys share their leading bits (the scores of one segment span a few
+    // binades), and so does the threshold, which lies between the smallest and the largest of
+    // them: the search starts at the highest bit in which those two differ.
+    uint32_t kmax = 0u, inv_min = 0u;
+#pragma unroll
+    for (int r = 0; r < NREG; ++r) {
+        kmax = max(kmax, key[r]);
+        if (key[r] != 0u) inv_min = max(inv_min, ~key[r]);
+    }
+    kmax = wave_umax_dpp(kmax);
+    if (kmax == 0u) return;  // no candidate at all
+    const uint32_t diff = kmax ^ ~wave_umax_dpp(inv_min);
+    const int top = diff ? (31 - __clz(diff)) & ~1 : -2;  // first pair of bits to decide
+    uint32_t T = top >= 30 ? 0u : (top < 0 ? kmax : (kmax >> (top + 2)) << (top + 2));
+    for (int shift = top; shift >= 0; shift -= 2) {
         const uint32_t c1 = T | (1u << shift), c2 = T | (2u << shift), c3 = T | (3u << shift);
         int n1 = 0, n2 = 0, n3 = 0;  // registers past the last slot hold key 0 and never count
 #pragma unroll
