@@ -179,9 +179,34 @@ __device__ __forceinline__ void block_topk_regs(SlotFn slot_fn, int nslots, int 
             tc += sm.cnt[buf][i][2];
         }
     };
-    uint32_t T = 0;
-    int buf = 0;
-    for (int shift = 30; shift >= 0; shift -= 2) {
+    // As in the wave-level search: start at the highest bit in which the largest and the
+    // smallest candidate differ (one exchange of per-wave maxima through LDS).
+    uint32_t kmax = 0u, inv_min = 0u;
+#pragma unroll
+    for (int r = 0; r < NREG; ++r) {
+        kmax = max(kmax, key[r]);
+        if (key[r] != 0u) inv_min = max(inv_min, ~key[r]);
+    }
+    kmax = wave_umax_dpp(kmax);
+    inv_min = wave_umax_dpp(inv_min);
+    if (lane_id() == 0) {
+        sm.cnt[0][w][0] = (int)kmax;
+        sm.cnt[0][w][1] = (int)inv_min;
+    }
+    __syncthreads();
+    for (int i = 0; i < nw; ++i) {
+        kmax = max(kmax, (uint32_t)sm.cnt[0][i][0]);
+        inv_min = max(inv_min, (uint32_t)sm.cnt[0][i][1]);
+    }
+    if (kmax == 0u) {  // no candidate at all (uniform over the block)
+        __syncthreads();
+        return;
+    }
+    const uint32_t diff = kmax ^ ~inv_min;
+    const int top = diff ? (31 - __clz(diff)) & ~1 : -2;  // first pair of bits to decide
+    uint32_t T = top >= 30 ? 0u : (top < 0 ? kmax : (kmax >> (top + 2)) << (top + 2));
+    int buf = 1;  // buffer 0 was just read: the first exchange writes the other one
+    for (int shift = top; shift >= 0; shift -= 2) {
         const uint32_t c1 = T | (1u << shift), c2 = T | (2u << shift), c3 = T | (3u << shift);
         int n1 = 0, n2 = 0, n3 = 0;
 #pragma unroll
