@@ -158,19 +158,32 @@ __global__ __launch_bounds__(256) void score_cls_kernel(const T *__restrict__ q,
     }
     __syncthreads();
 
+    // softmax with one exchange between the waves: every wave normalises against its own
+    // maximum, posts (maximum, sum) and rescales by what the four pairs combine to
     float m = -INFINITY;
     for (int j = tid; j < n_keys; j += 256) m = fmaxf(m, z[j]);
-    m = block_max(m, red);
+    m = wave_max(m);
     float sum = 0.f;
     for (int j = tid; j < n_keys; j += 256) {
         const float e = __builtin_amdgcn_exp2f(z[j] - m);
-        z[j] = e;
+        z[j] = e;  // read again below by this same thread only
         sum += e;
     }
-    sum = block_sum(sum, red);
-    const float inv = 1.0f / sum;
+    sum = wave_sum(sum);
+    if (lane_id() == 0) {
+        red[wave_id()] = m;
+        red[4 + wave_id()] = sum;
+    }
+    __syncthreads();
+    const float mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float denom = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) denom += red[4 + w] * __builtin_amdgcn_exp2f(red[w] - mx);
+    // a wave without keys posted (-inf, 0): its term is 0 * 0
+    const float f = __builtin_amdgcn_exp2f(m - mx) / denom;
     float *out = head_scores + ((int64_t)bc * H + h) * N;
-    for (int j = tid; j < N; j += 256) out[j] = z[col0 + j] * inv;
+    for (int j = tid; j < n_keys; j += 256)
+        if (j >= col0 && j - col0 < N) out[j - col0] = z[j] * f;
 }
 
 // ---------------------------------------------------------------------------
