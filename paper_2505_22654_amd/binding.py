@@ -70,6 +70,12 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with "
                                "`python -m paper_2505_22654_amd.build` (no CPU fallback exists)")
+        # torch first: its wheel carries its own HIP runtime, found through the file name
+        # libamdhip64.so, while this library asks for the soname libamdhip64.so.7.  Loaded in
+        # that order the second request is satisfied by the runtime already in the process;
+        # the other way round the process ends up with two runtimes (streams and device
+        # pointers of one mean nothing to the other).
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
         L.vscan_encoder_workspace_size.argtypes = [ctypes.POINTER(EncoderDesc), ctypes.c_int,

@@ -12,6 +12,7 @@
 
 #include "fused.hpp"
 #include "launch.hpp"
+#include "log.hpp"
 
 namespace {
 
@@ -211,6 +212,12 @@ inline float resolve_scale(float scale, int head_dim) {
     return scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
 }
 
+// Logs a failing entry point (debug log only) and passes its status through.
+inline int finish(const char *entry, int rc) {
+    if (rc != VSCAN_OK) logf("%s -> %d (%s)", entry, rc, vscan_status_string(rc));
+    return rc;
+}
+
 // ---- per-kernel event timing (measurement aid) ------------------------------
 struct ProfRecord {
     const char *name;
@@ -240,14 +247,18 @@ struct ProfScope {
     }
 };
 
-#define VSCAN_LAUNCH(name, call)                          \
-    do {                                                  \
-        hipError_t e_;                                    \
-        {                                                 \
-            ProfScope scope_(name, s);                    \
-            e_ = (call);                                  \
-        }                                                 \
-        if (e_ != hipSuccess) return VSCAN_ERR_HIP;       \
+#define VSCAN_LAUNCH(name, call)                                                  \
+    do {                                                                          \
+        hipError_t e_;                                                            \
+        {                                                                         \
+            ProfScope scope_(name, s);                                            \
+            e_ = (call);                                                          \
+        }                                                                         \
+        if (e_ != hipSuccess) {                                                   \
+            logf("launch of %s failed: %s", name, hipGetErrorString(e_));         \
+            return VSCAN_ERR_HIP;                                                 \
+        }                                                                         \
+        logf("enqueued %s", name);                                                \
     } while (0)
 
 // The score chain: part[seq][token] = sum over the query rows of their softmax weights.
@@ -310,6 +321,37 @@ int enqueue_encoder_tail(const vscan_encoder_desc *d, const EncoderPlan &p, bool
 
 }  // namespace
 
+// Pointer checks of the stage-2 tensors (host only).
+static int check_llm_tensors(const vscan_llm_desc *d, const void *q, const void *k, const void *v,
+                             const void *hidden, const int32_t *kept_idx, const void *k_out,
+                             const void *v_out, const void *hidden_out, const float *scores_out) {
+    if (!q || !k || !v || !hidden || (!kept_idx && d->keep > 0)) return VSCAN_ERR_NULL;
+    const bool outs_null = !k_out && !v_out && !hidden_out;
+    const bool outs_all = k_out && v_out && hidden_out;
+    if (d->in_place ? !outs_null : !outs_all) return VSCAN_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(hidden) ||
+        !aligned16(k_out) || !aligned16(v_out) || !aligned16(hidden_out))
+        return VSCAN_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(kept_idx) & 3u) || (reinterpret_cast<uintptr_t>(scores_out) & 3u))
+        return VSCAN_ERR_ALIGN;
+    return VSCAN_OK;
+}
+
+namespace vscan {
+// Everything vscan_llm_prune checks before it looks at its workspace, for the entry point that
+// brings its own scratch.
+int llm_prune_validate(const vscan_llm_desc *d, const void *q, const void *k, const void *v,
+                       const void *hidden, const int32_t *kept_idx, const void *k_out,
+                       const void *v_out, const void *hidden_out, const float *scores_out,
+                       size_t *workspace_bytes) {
+    LlmPlan p;
+    const int rc = plan_llm(d, &p);
+    if (rc != VSCAN_OK) return rc;
+    *workspace_bytes = p.bytes;
+    return check_llm_tensors(d, q, k, v, hidden, kept_idx, k_out, v_out, hidden_out, scores_out);
+}
+}  // namespace vscan
+
 extern "C" {
 
 int vscan_encoder_workspace_size(const vscan_encoder_desc *desc, int with_local_pair,
@@ -322,7 +364,7 @@ int vscan_encoder_workspace_size(const vscan_encoder_desc *desc, int with_local_
     return VSCAN_OK;
 }
 
-int vscan_encoder_reduce(const vscan_encoder_desc *d, const void *q, const void *k,
+static int encoder_reduce_impl(const vscan_encoder_desc *d, const void *q, const void *k,
                          const void *q_local, const void *k_local, const void *x,
                          int32_t *kept_idx, void *merged, int32_t *assign_out, float *scores_out,
                          void *workspace, size_t workspace_bytes, void *stream) {
@@ -379,6 +421,13 @@ int vscan_encoder_reduce(const vscan_encoder_desc *d, const void *q, const void 
                                 x, kept_idx, merged, assign_out, scores_out, ws, s);
 }
 
+int vscan_encoder_reduce(const vscan_encoder_desc *d, const void *q, const void *k,
+                         const void *q_local, const void *k_local, const void *x,
+                         int32_t *kept_idx, void *merged, int32_t *assign_out, float *scores_out,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    return finish("vscan_encoder_reduce", encoder_reduce_impl(d, q, k, q_local, k_local, x, kept_idx, merged, assign_out, scores_out, workspace, workspace_bytes, stream));
+}
+
 int vscan_encoder_fused_workspace_size(const vscan_encoder_desc *desc, int with_local_triple,
                                        size_t *bytes) {
     if (!bytes) return VSCAN_ERR_NULL;
@@ -389,7 +438,7 @@ int vscan_encoder_fused_workspace_size(const vscan_encoder_desc *desc, int with_
     return VSCAN_OK;
 }
 
-int vscan_encoder_reduce_fused(const vscan_encoder_desc *d, const void *hidden, const void *w_q,
+static int encoder_reduce_fused_impl(const vscan_encoder_desc *d, const void *hidden, const void *w_q,
                                const void *w_k_t, const void *hidden_local,
                                const void *w_q_local, const void *w_k_t_local, const void *x,
                                int32_t *kept_idx, void *merged, int32_t *assign_out,
@@ -441,6 +490,15 @@ int vscan_encoder_reduce_fused(const vscan_encoder_desc *d, const void *hidden, 
                                 assign_out, scores_out, ws, s);
 }
 
+int vscan_encoder_reduce_fused(const vscan_encoder_desc *d, const void *hidden, const void *w_q,
+                               const void *w_k_t, const void *hidden_local,
+                               const void *w_q_local, const void *w_k_t_local, const void *x,
+                               int32_t *kept_idx, void *merged, int32_t *assign_out,
+                               float *scores_out, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+    return finish("vscan_encoder_reduce_fused", encoder_reduce_fused_impl(d, hidden, w_q, w_k_t, hidden_local, w_q_local, w_k_t_local, x, kept_idx, merged, assign_out, scores_out, workspace, workspace_bytes, stream));
+}
+
 int vscan_llm_workspace_size(const vscan_llm_desc *desc, size_t *bytes) {
     if (!bytes) return VSCAN_ERR_NULL;
     LlmPlan p;
@@ -456,15 +514,9 @@ static int run_llm(const vscan_llm_desc *d, const LlmPlan &p, const SeqMeta *met
                    int out_rows, const void *q, void *k, void *v, void *hidden, int32_t *kept_idx,
                    void *k_out, void *v_out, void *hidden_out, float *scores_out, void *workspace,
                    size_t workspace_bytes, void *stream) {
-    if (!q || !k || !v || !hidden || (!kept_idx && d->keep > 0)) return VSCAN_ERR_NULL;
-    const bool outs_null = !k_out && !v_out && !hidden_out;
-    const bool outs_all = k_out && v_out && hidden_out;
-    if (d->in_place ? !outs_null : !outs_all) return VSCAN_ERR_NULL;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(hidden) ||
-        !aligned16(k_out) || !aligned16(v_out) || !aligned16(hidden_out))
-        return VSCAN_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(kept_idx) & 3u) || (reinterpret_cast<uintptr_t>(scores_out) & 3u))
-        return VSCAN_ERR_ALIGN;
+    const int rc_args = check_llm_tensors(d, q, k, v, hidden, kept_idx, k_out, v_out, hidden_out,
+                                          scores_out);
+    if (rc_args != VSCAN_OK) return rc_args;
     if (!workspace || workspace_bytes < p.bytes) return VSCAN_ERR_WORKSPACE;
     if (!aligned16(workspace)) return VSCAN_ERR_ALIGN;
     if (d->batch == 0) return VSCAN_OK;
@@ -530,7 +582,7 @@ static int run_llm(const vscan_llm_desc *d, const LlmPlan &p, const SeqMeta *met
     return VSCAN_OK;
 }
 
-int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, void *hidden,
+static int llm_prune_impl(const vscan_llm_desc *d, const void *q, void *k, void *v, void *hidden,
                     int32_t *kept_idx, void *k_out, void *v_out, void *hidden_out,
                     float *scores_out, void *workspace, size_t workspace_bytes, void *stream) {
     LlmPlan p;
@@ -541,10 +593,16 @@ int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, vo
                    stream);
 }
 
+int vscan_llm_prune(const vscan_llm_desc *d, const void *q, void *k, void *v, void *hidden,
+                    int32_t *kept_idx, void *k_out, void *v_out, void *hidden_out,
+                    float *scores_out, void *workspace, size_t workspace_bytes, void *stream) {
+    return finish("vscan_llm_prune", llm_prune_impl(d, q, k, v, hidden, kept_idx, k_out, v_out, hidden_out, scores_out, workspace, workspace_bytes, stream));
+}
+
 static int check_seq_meta(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
                           const vscan_seq_meta *meta_device, int *max_out_rows);
 
-int vscan_llm_prune_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
+static int llm_prune_ragged_impl(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
                            const vscan_seq_meta *meta_device, const void *q, void *k, void *v,
                            void *hidden, int32_t *kept_idx, void *k_out, void *v_out,
                            void *hidden_out, float *scores_out, void *workspace,
@@ -564,6 +622,14 @@ int vscan_llm_prune_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_h
     return run_llm(&caps, p, reinterpret_cast<const SeqMeta *>(meta_device), max_out_rows,
                    d->seq_len, q, k, v, hidden, kept_idx, k_out, v_out, hidden_out, scores_out,
                    workspace, workspace_bytes, stream);
+}
+
+int vscan_llm_prune_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
+                           const vscan_seq_meta *meta_device, const void *q, void *k, void *v,
+                           void *hidden, int32_t *kept_idx, void *k_out, void *v_out,
+                           void *hidden_out, float *scores_out, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+    return finish("vscan_llm_prune_ragged", llm_prune_ragged_impl(d, meta_host, meta_device, q, k, v, hidden, kept_idx, k_out, v_out, hidden_out, scores_out, workspace, workspace_bytes, stream));
 }
 
 int vscan_llm_fused_workspace_size(const vscan_llm_desc *desc, size_t *bytes) {
@@ -652,7 +718,7 @@ static int run_llm_fused(const vscan_llm_desc *d, const FusedPlan &p, const SeqM
     return VSCAN_OK;
 }
 
-int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q,
+static int llm_prune_fused_impl(const vscan_llm_desc *d, void *hidden, const void *w_q,
                           const void *w_k_t, int32_t *kept_idx, void *hidden_out,
                           float *scores_out, void *workspace, size_t workspace_bytes,
                           void *stream) {
@@ -662,6 +728,13 @@ int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q
     return run_llm_fused(d, p, nullptr, p.S_out, d->in_place ? d->seq_len : p.S_out, hidden, w_q,
                          w_k_t, kept_idx, hidden_out, scores_out, workspace, workspace_bytes,
                          stream);
+}
+
+int vscan_llm_prune_fused(const vscan_llm_desc *d, void *hidden, const void *w_q,
+                          const void *w_k_t, int32_t *kept_idx, void *hidden_out,
+                          float *scores_out, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+    return finish("vscan_llm_prune_fused", llm_prune_fused_impl(d, hidden, w_q, w_k_t, kept_idx, hidden_out, scores_out, workspace, workspace_bytes, stream));
 }
 
 // Validation of a ragged batch's host table against the capacities; *max_out_rows receives the
@@ -683,7 +756,7 @@ static int check_seq_meta(const vscan_llm_desc *d, const vscan_seq_meta *meta_ho
     return VSCAN_OK;
 }
 
-int vscan_llm_prune_fused_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
+static int llm_prune_fused_ragged_impl(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
                                  const vscan_seq_meta *meta_device, void *hidden, const void *w_q,
                                  const void *w_k_t, int32_t *kept_idx, void *hidden_out,
                                  float *scores_out, void *workspace, size_t workspace_bytes,
@@ -701,6 +774,14 @@ int vscan_llm_prune_fused_ragged(const vscan_llm_desc *d, const vscan_seq_meta *
     return run_llm_fused(&caps, p, reinterpret_cast<const SeqMeta *>(meta_device), max_out_rows,
                          d->seq_len, hidden, w_q, w_k_t, kept_idx, hidden_out, scores_out,
                          workspace, workspace_bytes, stream);
+}
+
+int vscan_llm_prune_fused_ragged(const vscan_llm_desc *d, const vscan_seq_meta *meta_host,
+                                 const vscan_seq_meta *meta_device, void *hidden, const void *w_q,
+                                 const void *w_k_t, int32_t *kept_idx, void *hidden_out,
+                                 float *scores_out, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+    return finish("vscan_llm_prune_fused_ragged", llm_prune_fused_ragged_impl(d, meta_host, meta_device, hidden, w_q, w_k_t, kept_idx, hidden_out, scores_out, workspace, workspace_bytes, stream));
 }
 
 int vscan_profile_enable(int on) {
