@@ -155,6 +155,28 @@ int vscan_llm_prune(const vscan_llm_desc *desc, const void *q, void *k, void *v,
                     float *scores_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * vscan_llm_prune for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Arguments, results and errors are those of vscan_llm_prune
+ * without `workspace` / `workspace_bytes`: the scratch is a fixed array of
+ * VSCAN_STATIC_SCRATCH_BYTES inside the library's code object, which every GPU
+ * the library runs on holds until the process ends.  The call allocates and
+ * frees nothing.
+ *   - A descriptor whose vscan_llm_workspace_size exceeds
+ *     VSCAN_STATIC_SCRATCH_BYTES is refused with VSCAN_ERR_WORKSPACE (nothing is
+ *     enqueued).
+ *   - The first call on a device looks the array's device address up (one
+ *     symbol query, no allocation); make that call outside graph capture.
+ *   - All calls on one GPU share the one array, which keeps the last call's
+ *     contents: calls must be ordered (one stream, or events between streams);
+ *     calls that overlap on one GPU race.
+ * ------------------------------------------------------------------------- */
+#define VSCAN_STATIC_SCRATCH_BYTES (16u << 20)
+int vscan_llm_prune_static(const vscan_llm_desc *desc, const void *q, void *k, void *v,
+                           void *hidden, int32_t *kept_idx, void *k_out, void *v_out,
+                           void *hidden_out, float *scores_out, void *stream);
+
+/* ---------------------------------------------------------------------------
  * Measurement aid (not part of the method): per-kernel device time.
  *
  * While enabled, every kernel the two entry points launch is bracketed by a pair

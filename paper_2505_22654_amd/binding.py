@@ -26,7 +26,8 @@ EXPORTS = ("vscan_encoder_workspace_size", "vscan_encoder_reduce", "vscan_llm_wo
            "vscan_version", "vscan_budget", "vscan_budget_solve_r1", "vscan_flops",
            "vscan_llm_prune_ragged", "vscan_llm_fused_workspace_size", "vscan_llm_prune_fused",
            "vscan_encoder_fused_workspace_size", "vscan_encoder_reduce_fused",
-           "vscan_llm_prune_fused_ragged")
+           "vscan_llm_prune_fused_ragged", "vscan_llm_prune_static")
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class EncoderDesc(ctypes.Structure):
@@ -90,6 +91,9 @@ def lib():
         L.vscan_llm_prune.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, vp, i32p, vp, vp, vp,
                                       f32p, vp, ctypes.c_size_t, vp]
         L.vscan_llm_prune.restype = ctypes.c_int
+        L.vscan_llm_prune_static.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, vp, i32p, vp, vp,
+                                             vp, f32p, vp]
+        L.vscan_llm_prune_static.restype = ctypes.c_int
         L.vscan_llm_prune_ragged.argtypes = [ctypes.POINTER(LlmDesc), vp, vp, vp, vp, vp, vp, i32p,
                                              vp, vp, vp, f32p, vp, ctypes.c_size_t, vp]
         L.vscan_llm_prune_ragged.restype = ctypes.c_int
@@ -315,8 +319,9 @@ def encoder_reduce(shape, q, k, x, q_local=None, k_local=None, want_assign: bool
 
 
 def llm_prune(shape, q, k, v, hidden, want_scores: bool = False, workspace=None,
-              out=None) -> Dict[str, object]:
-    """vscan_llm_prune on CUDA tensors q [B,Hq,Tq,dh], k, v [B,Hkv,S,dh], hidden [B,S,Dh].
+              out=None, static_scratch: bool = False) -> Dict[str, object]:
+    """vscan_llm_prune on CUDA tensors q [B,Hq,Tq,dh], k, v [B,Hkv,S,dh], hidden [B,S,Dh]
+    (`static_scratch`: vscan_llm_prune_static, which takes no workspace).
 
     Out of place it returns k, v, hidden of length S_out; in place (shape.in_place) it
     mutates the inputs and returns views of their first S_out rows."""
@@ -330,7 +335,7 @@ def llm_prune(shape, q, k, v, hidden, want_scores: bool = False, workspace=None,
     assert tuple(q.shape) == (B, shape.q_heads, shape.n_query, shape.head_dim)
     assert tuple(k.shape) == (B, shape.kv_heads, S, shape.head_dim) and k.shape == v.shape
     assert tuple(hidden.shape) == (B, S, shape.hidden)
-    if workspace is None:
+    if workspace is None and not static_scratch:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     out = dict(out) if out else {}
     if "kept_idx" not in out:
@@ -349,12 +354,17 @@ def llm_prune(shape, q, k, v, hidden, want_scores: bool = False, workspace=None,
             vo = torch.empty_like(ko)
         if ho is None:
             ho = torch.empty((B, So, shape.hidden), dtype=hidden.dtype, device=dev)
-    rc = lib().vscan_llm_prune(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(hidden),
-                               _ptr(out["kept_idx"]), _ptr(ko), _ptr(vo), _ptr(ho),
-                               _ptr(out.get("scores")), _ptr(workspace), workspace.numel(),
-                               _stream_handle())
+    if static_scratch:
+        rc = lib().vscan_llm_prune_static(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v),
+                                          _ptr(hidden), _ptr(out["kept_idx"]), _ptr(ko), _ptr(vo),
+                                          _ptr(ho), _ptr(out.get("scores")), _stream_handle())
+    else:
+        rc = lib().vscan_llm_prune(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(hidden),
+                                   _ptr(out["kept_idx"]), _ptr(ko), _ptr(vo), _ptr(ho),
+                                   _ptr(out.get("scores")), _ptr(workspace), workspace.numel(),
+                                   _stream_handle())
     if rc != VSCAN_OK:
-        raise VscanError(rc, "vscan_llm_prune")
+        raise VscanError(rc, "vscan_llm_prune_static" if static_scratch else "vscan_llm_prune")
     if shape.in_place:
         out["k"], out["v"], out["hidden"] = k[:, :, :So], v[:, :, :So], hidden[:, :So]
     else:

@@ -11,7 +11,8 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvscan.so")
 
-SOURCES = ["api.cpp", "budget.cpp", "encoder_score.hip", "select.hip", "sim_merge.hip", "llm.hip", "fused.hip"]
+SOURCES = ["api.cpp", "budget.cpp", "encoder_score.hip", "select.hip", "sim_merge.hip", "llm.hip", "fused.hip",
+           "static_entry.hip"]
 HEADERS = ["common.hpp", "launch.hpp", "fused.hpp", os.path.join("..", "..", "include", "vscan.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
