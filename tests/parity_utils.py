@@ -2,7 +2,12 @@
 conversion and the comparison rules.  Nothing here is used by the product path.
 
 Comparison rules (tolerances are stated here once and used by every test):
-  * kept indices: bit-exact.
+  * kept indices: bit-exact wherever the oracle's selection boundary clears MARGIN.  Where it
+    does not (several index sets are then correct for fp32 scores), the complete validity
+    check applies instead of a skip: right count, ascending, unique, every kept candidate's
+    oracle score at least every dropped candidate's up to 2 * SCORE_RTOL, and the lowest index
+    wins wherever two oracle scores are exactly equal; everything downstream (assignment,
+    merge, compaction) is then checked under the kept set the GPU returned.
   * scores: relative error of the fp32 GPU scores against the fp64 oracle must
     stay below SCORE_RTOL on every token whose score is not in the deep tail.
   * selection boundaries: a seed is only used when every top-k boundary of the
@@ -82,8 +87,94 @@ def topk_boundary_gap(scores: np.ndarray, keep: int) -> float:
     return worst
 
 
+def assert_valid_topk(picked, pool, scores, k, what):
+    """Complete validity of a top-k: `picked` (token indices) against the candidate `pool`
+    (token indices) under the oracle `scores` (indexed by token)."""
+    picked = np.asarray(picked, dtype=np.int64)
+    pool = np.asarray(pool, dtype=np.int64)
+    assert picked.size == k, f"{what}: {picked.size} picked, budget {k}"
+    assert np.unique(picked).size == k and np.isin(picked, pool).all(), f"{what}: not a subset"
+    left = np.setdiff1d(pool, picked)
+    if k == 0 or left.size == 0:
+        return
+    sp, sl = scores[picked], scores[left]
+    assert sp.min() >= sl.max() * (1.0 - 2 * SCORE_RTOL), (
+        f"{what}: a dropped candidate scores {sl.max():.9e}, a kept one {sp.min():.9e}")
+    for v in np.intersect1d(sp, sl):   # oracle scores exactly equal on both sides
+        assert picked[sp == v].max() < left[sl == v].min(), f"{what}: exact tie not on the lowest index"
+
+
+def check_topk_rows(kept, ref_kept, scores, keep, what):
+    """Rows of a plain top-k (stage 2): identical to the oracle's, or - only where the oracle's
+    boundary gap is within MARGIN - valid.  Returns the number of rows that differ validly."""
+    differing = 0
+    for b in range(scores.shape[0]):
+        if np.array_equal(kept[b], ref_kept[b]):
+            continue
+        gap = topk_boundary_gap(scores[b:b + 1], keep)
+        assert gap <= MARGIN, f"{what}[{b}]: kept indices differ although the boundary gap is {gap:.3e}"
+        assert np.all(np.diff(kept[b]) > 0), f"{what}[{b}]: not ascending"
+        assert_valid_topk(kept[b], np.arange(scores.shape[1]), scores[b], keep, f"{what}[{b}]")
+        differing += 1
+    return differing
+
+
+def window_ids(shape):
+    gh, gw, wr, wc = shape.grid_h, shape.grid_w, shape.win_rows, shape.win_cols
+    rows = (np.arange(gh) * wr) // gh
+    cols = (np.arange(gw) * wc) // gw
+    return (rows[:, None] * wc + cols[None, :]).reshape(-1)
+
+
+def check_encoder_kept(shape, kept, ref, what):
+    """kept [B,K] against the oracle: identical, or valid per segment (a local top-kw in every
+    window under the local scores, then a global top-kg' of the rest under the global scores).
+    Returns the number of segments that differ validly."""
+    if np.array_equal(kept, ref["kept"]):
+        return 0
+    B, C, N = shape.batch, shape.n_segments, shape.n_tokens
+    W = shape.win_rows * shape.win_cols
+    kw = shape.keep_local // W
+    kg = shape.keep_global + shape.keep_local - kw * W
+    Kseg = shape.keep_global + shape.keep_local
+    win = window_ids(shape)
+    sg = ref["scores"].reshape(B, C, N)
+    sl = ref["scores_local"].reshape(B, C, N)
+    differing = 0
+    for b in range(B):
+        assert np.all(np.diff(kept[b]) > 0), f"{what}[{b}]: not ascending"
+        for c in range(C):
+            got = kept[b, c * Kseg:(c + 1) * Kseg].astype(np.int64) - c * N
+            want = ref["kept"][b, c * Kseg:(c + 1) * Kseg].astype(np.int64) - c * N
+            if np.array_equal(got, want):
+                continue
+            one = type("S", (), dict(grid_h=shape.grid_h, grid_w=shape.grid_w, win_rows=shape.win_rows,
+                                     win_cols=shape.win_cols, keep_local=shape.keep_local,
+                                     keep_global=shape.keep_global))
+            gap = encoder_boundary_gap(one, sl[b:b + 1, c:c + 1], sg[b:b + 1, c:c + 1])
+            assert gap <= MARGIN, f"{what}[{b},{c}]: kept differs although the boundary gap is {gap:.3e}"
+            assert got.min() >= 0 and got.max() < N, f"{what}[{b},{c}]: index outside the segment"
+            local = []
+            for w in range(W):
+                pool = np.nonzero(win == w)[0]
+                mine = got[np.isin(got, pool)]
+                assert mine.size >= kw, f"{what}[{b},{c}]: window {w} holds {mine.size} < {kw}"
+                # the window's local picks: its kw best kept tokens by (local score, lowest index)
+                pick = mine[np.lexsort((mine, -sl[b, c, mine]))][:kw]
+                assert_valid_topk(pick, pool, sl[b, c], kw, f"{what}[{b},{c}] window {w}")
+                local.append(pick)
+            local = np.concatenate(local) if local else np.zeros(0, np.int64)
+            rest = np.setdiff1d(np.arange(N), local)
+            assert_valid_topk(np.setdiff1d(got, local), rest, sg[b, c], kg, f"{what}[{b},{c}] global")
+            differing += 1
+    return differing
+
+
 def screened_encoder_case(shape, seed, logit_gain=1.0, with_local=False, max_tries=16):
-    """Inputs + oracle result for the first seed >= `seed` whose boundaries clear MARGIN."""
+    """Inputs + oracle result for the first seed >= `seed` whose boundaries clear MARGIN; when
+    none of `max_tries` seeds does, the one with the widest gap (the comparison then falls back
+    to the validity check where the GPU's choice differs)."""
+    best = None
     for attempt in range(max_tries):
         inp = wl.encoder_inputs(shape, seed + attempt, logit_gain)
         loc = wl.encoder_inputs(shape, seed + attempt, logit_gain, stream=1) if with_local else None
@@ -96,7 +187,10 @@ def screened_encoder_case(shape, seed, logit_gain=1.0, with_local=False, max_tri
         gap = encoder_boundary_gap(shape, sl, sg)
         if gap > MARGIN:
             return inp, loc, ref, {"seed": seed + attempt, "attempts": attempt + 1, "gap": gap}
-    raise AssertionError(f"no seed in {max_tries} tries clears the boundary margin")
+        if best is None or gap > best[3]["gap"]:
+            best = (inp, loc, ref, {"seed": seed + attempt, "attempts": max_tries, "gap": gap,
+                                    "margin": "not cleared: validity check applies"})
+    return best
 
 
 def screened_encoder_batch(shape, seed, logit_gain=1.0, max_items=None):
@@ -125,13 +219,17 @@ def screened_encoder_batch(shape, seed, logit_gain=1.0, max_items=None):
 
 
 def screened_llm_case(shape, seed, max_tries=16):
+    best = None
     for attempt in range(max_tries):
         inp = wl.llm_inputs(shape, seed + attempt)
         ref = vo.llm_prune(shape, **inp)
         gap = topk_boundary_gap(ref["scores"], shape.keep)
         if gap > MARGIN:
             return inp, ref, {"seed": seed + attempt, "attempts": attempt + 1, "gap": gap}
-    raise AssertionError(f"no seed in {max_tries} tries clears the boundary margin")
+        if best is None or gap > best[2]["gap"]:
+            best = (inp, ref, {"seed": seed + attempt, "attempts": max_tries, "gap": gap,
+                               "margin": "not cleared: validity check applies"})
+    return best
 
 
 def check_scores(got: np.ndarray, want: np.ndarray, what: str):
@@ -165,12 +263,16 @@ def check_assignment(x: np.ndarray, kept: np.ndarray, got: np.ndarray, want: np.
 def check_encoder(shape, inp, ref, out, what=""):
     """Full comparison of one vscan_encoder_reduce result with the oracle."""
     kept = to_host(out["kept_idx"])
-    assert np.array_equal(kept, ref["kept"]), f"{what}: kept indices differ"
     report = {}
     if "scores" in out:
         report["score_rel_err"] = check_scores(to_host(out["scores"]), ref["scores"], what)
+    differing = check_encoder_kept(shape, kept, ref, what)
+    ref_assign = ref["assign"]
+    if differing:  # a valid selection other than the oracle's: the rest is checked under it
+        report["segments_valid_not_identical"] = differing
+        ref_assign = vo.assign(inp["x"], kept)
     assign = to_host(out["assign"])
-    report["ambiguous"] = check_assignment(inp["x"], kept, assign, ref["assign"])
+    report["ambiguous"] = check_assignment(inp["x"], kept, assign, ref_assign)
     merged_ref, _ = vo.merge(inp["x"], kept, assign)
     np.testing.assert_allclose(to_host(out["merged"]).astype(np.float64), merged_ref,
                                err_msg=f"{what}: merged", **MERGE_TOL[shape.dtype])
@@ -179,14 +281,18 @@ def check_encoder(shape, inp, ref, out, what=""):
 
 def check_llm(shape, inp, ref, out, what=""):
     kept = to_host(out["kept_idx"])
-    assert np.array_equal(kept, ref["kept"]), f"{what}: kept indices differ"
     report = {}
     if "scores" in out:
         report["score_rel_err"] = check_scores(to_host(out["scores"]), ref["scores"], what)
+    differing = check_topk_rows(kept, ref["kept"], ref["scores"], shape.keep, what)
+    if differing:  # a valid selection other than the oracle's: compaction is checked under it
+        report["rows_valid_not_identical"] = differing
     for name in ("k", "v", "hidden"):
         got = to_host(out[name])
-        assert got.shape == ref[name].shape, f"{what}: {name} shape"
-        assert np.array_equal(got, ref[name]), f"{what}: compacted {name} differs"
+        want = (vo.compact(inp[name], kept, shape.vis_start, shape.vis_len) if differing
+                else ref[name])
+        assert got.shape == want.shape, f"{what}: {name} shape"
+        assert np.array_equal(got, want), f"{what}: compacted {name} differs"
     return report
 
 
@@ -210,13 +316,16 @@ def ragged_llm_case(base, seqs, seed):
     meta, refs = [], []
     for b, (p, v, t, kp) in enumerate(seqs):
         one = replace(base, batch=1, prefix=p, vis_len=v, text=t, keep=kp)
+        best = None
         for attempt in range(32):
             item = wl.llm_inputs(one, seed + 100 * b + attempt)
             ref = vo.llm_prune(one, **item)
-            if topk_boundary_gap(ref["scores"], kp) > MARGIN:
+            gap = topk_boundary_gap(ref["scores"], kp)
+            if best is None or gap > best[0]:
+                best = (gap, item, ref)
+            if gap > MARGIN:
                 break
-        else:
-            raise AssertionError("no seed clears the boundary margin")
+        _, item, ref = best  # no clear boundary in 32 seeds: the validity check applies
         S = one.seq_len
         inp["q"][b] = item["q"][0]
         inp["k"][b, :, :S] = item["k"][0]
@@ -236,11 +345,14 @@ def check_llm_ragged(caps, meta, inp, refs, out, in_place, what=""):
     worst = 0.0
     for b, (S, vs, V, kp) in enumerate(meta):
         ref = refs[b]
-        assert np.array_equal(kept[b, :kp], ref["kept"][0]), f"{what}[{b}]: kept indices differ"
+        differs = check_topk_rows(kept[b:b + 1, :kp], ref["kept"], ref["scores"], kp, f"{what}[{b}]")
         assert np.all(kept[b, kp:] == -1), f"{what}[{b}]: index padding"
         if scores is not None:
             worst = max(worst, check_scores(scores[b:b + 1, :V], ref["scores"], f"{what}[{b}]"))
         So = S - V + kp
+        if differs:  # valid but not the oracle's: compaction under the returned indices
+            ref = {n: vo.compact(inp[n][b:b + 1, ..., :S, :], kept[b:b + 1, :kp], vs, V)
+                   for n in ("k", "v", "hidden")}
         assert np.array_equal(got["k"][b, :, :So], ref["k"][0]), f"{what}[{b}]: k"
         assert np.array_equal(got["v"][b, :, :So], ref["v"][0]), f"{what}[{b}]: v"
         assert np.array_equal(got["hidden"][b, :So], ref["hidden"][0]), f"{what}[{b}]: hidden"
@@ -258,32 +370,45 @@ def fused_reference(shape, hidden, w_q, w_k):
 
 
 def screened_fused_case(shape, seed, max_tries=16):
-    """Hidden states and projection weights whose oracle selection clears the margin."""
+    """Hidden states and projection weights whose oracle selection clears the margin (else the
+    seed with the widest gap, see screened_encoder_case)."""
+    best = None
     for attempt in range(max_tries):
         hidden = wl.llm_inputs(shape, seed + attempt)["hidden"]
         w = wl.llm_weights(shape, seed + attempt)
         ref = fused_reference(shape, hidden, w["w_q"], w["w_k"])
         gap = topk_boundary_gap(ref["scores"], shape.keep)
+        inp = {"hidden": hidden, "w_q": w["w_q"], "w_k": w["w_k"]}
         if gap > MARGIN:
-            inp = {"hidden": hidden, "w_q": w["w_q"], "w_k": w["w_k"]}
             return inp, ref, {"seed": seed + attempt, "attempts": attempt + 1, "gap": gap}
-    raise AssertionError(f"no seed in {max_tries} tries clears the boundary margin")
+        if best is None or gap > best[2]["gap"]:
+            best = (inp, ref, {"seed": seed + attempt, "attempts": max_tries, "gap": gap,
+                               "margin": "not cleared: validity check applies"})
+    return best
 
 
-def check_fused(shape, ref, out, what=""):
+def check_fused(shape, ref, out, what="", hidden=None):
+    """`hidden`: the input hidden states, needed only when the selection differs validly."""
     kept = to_host(out["kept_idx"])
-    assert np.array_equal(kept, ref["kept"]), f"{what}: kept indices differ"
     report = {}
     if "scores" in out:
         report["score_rel_err"] = check_scores(to_host(out["scores"]), ref["scores"], what)
+    differing = check_topk_rows(kept, ref["kept"], ref["scores"], shape.keep, what)
+    want = ref["hidden"]
+    if differing:
+        report["rows_valid_not_identical"] = differing
+        assert hidden is not None, f"{what}: selection differs and no input was passed"
+        want = vo.compact(hidden, kept, shape.vis_start, shape.vis_len)
     got = to_host(out["hidden"])
-    assert got.shape == ref["hidden"].shape, f"{what}: hidden shape"
-    assert np.array_equal(got, ref["hidden"]), f"{what}: compacted hidden differs"
+    assert got.shape == want.shape, f"{what}: hidden shape"
+    assert np.array_equal(got, want), f"{what}: compacted hidden differs"
     return report
 
 
 def screened_encoder_fused_case(shape, seed, logit_gain=1.0, with_local=False, max_tries=16):
-    """Hidden rows, weights and oracle result for the first seed whose boundaries clear MARGIN."""
+    """Hidden rows, weights and oracle result for the first seed whose boundaries clear MARGIN
+    (else the seed with the widest gap, see screened_encoder_case)."""
+    best = None
     for attempt in range(max_tries):
         inp = wl.encoder_hidden_inputs(shape, seed + attempt, logit_gain)
         loc = (wl.encoder_hidden_inputs(shape, seed + attempt, logit_gain, stream=1)
@@ -296,7 +421,10 @@ def screened_encoder_fused_case(shape, seed, logit_gain=1.0, with_local=False, m
         gap = encoder_boundary_gap(shape, sl, sg)
         if gap > MARGIN:
             return inp, loc, ref, {"seed": seed + attempt, "attempts": attempt + 1, "gap": gap}
-    raise AssertionError(f"no seed in {max_tries} tries clears the boundary margin")
+        if best is None or gap > best[3]["gap"]:
+            best = (inp, loc, ref, {"seed": seed + attempt, "attempts": max_tries, "gap": gap,
+                                    "margin": "not cleared: validity check applies"})
+    return best
 
 
 def ragged_fused_case(base, seqs, seed):
@@ -315,13 +443,16 @@ def ragged_fused_case(base, seqs, seed):
     meta, refs = [], []
     for b, (p, v, t, kp) in enumerate(seqs):
         one = replace(base, batch=1, prefix=p, vis_len=v, text=t, keep=kp)
+        best = None
         for attempt in range(32):
             item = wl.llm_inputs(one, seed + 100 * b + attempt)["hidden"]
             ref = vo.llm_prune_fused(one, item, w["w_q"], w["w_k"])
-            if topk_boundary_gap(ref["scores"], kp) > MARGIN:
+            gap = topk_boundary_gap(ref["scores"], kp)
+            if best is None or gap > best[0]:
+                best = (gap, item, ref)
+            if gap > MARGIN:
                 break
-        else:
-            raise AssertionError("no seed clears the boundary margin")
+        _, item, ref = best  # no clear boundary in 32 seeds: the validity check applies
         hidden[b, :one.seq_len] = item[0]
         meta.append((one.seq_len, p, v, kp))
         refs.append(ref)
@@ -335,11 +466,13 @@ def check_fused_ragged(caps, meta, inp, refs, out, in_place, what=""):
     worst = 0.0
     for b, (S, vs, V, kp) in enumerate(meta):
         ref = refs[b]
-        assert np.array_equal(kept[b, :kp], ref["kept"][0]), f"{what}[{b}]: kept indices differ"
+        differs = check_topk_rows(kept[b:b + 1, :kp], ref["kept"], ref["scores"], kp, f"{what}[{b}]")
         assert np.all(kept[b, kp:] == -1), f"{what}[{b}]: index padding"
         worst = max(worst, check_scores(scores[b:b + 1, :V], ref["scores"], f"{what}[{b}]"))
         So = S - V + kp
-        assert np.array_equal(got[b, :So], ref["hidden"][0]), f"{what}[{b}]: hidden"
+        want = (vo.compact(inp["hidden"][b:b + 1, :S], kept[b:b + 1, :kp], vs, V) if differs
+                else ref["hidden"])
+        assert np.array_equal(got[b, :So], want[0]), f"{what}[{b}]: hidden"
         if in_place:
             assert np.array_equal(got[b, S:], inp["hidden"][b, S:]), f"{what}[{b}]: padding rows"
         else:

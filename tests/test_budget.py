@@ -18,8 +18,10 @@ def _rows(name):
 
 
 FLOPS_ROWS = [(int(r[0]), float(r[1])) for r in _rows("flops_printed.txt")]
+# printed rows first, then the rows derived from printed averages (kept in a file of their own)
 BUDGET_ROWS = [(int(r[0]), int(r[1]), int(r[2]), float(r[3]), float(r[4]), int(r[5]), int(r[6]),
-                float(r[7])) for r in _rows("budget_printed.txt")]
+                float(r[7])) for name in ("budget_printed.txt", "budget_derived.txt")
+               for r in _rows(name)]
 
 
 @pytest.mark.parametrize("n,tflops", FLOPS_ROWS)

@@ -73,7 +73,7 @@ def test_fused_small(name):
     inp, ref, info = pu.screened_fused_case(shape, 9100 + sorted(SMALL_FUSED).index(name) * 31)
     print("case", name, info, flush=True)
     out = _run(shape, inp)
-    print(name, pu.check_fused(shape, ref, out, name))
+    print(name, pu.check_fused(shape, ref, out, name, hidden=inp["hidden"]))
 
 
 def test_fused_fp32_is_rejected():
@@ -121,7 +121,7 @@ def test_fused_config2_shape():
     inp, ref, info = pu.screened_fused_case(shape, 9500, max_tries=4)
     print("case", info, flush=True)
     out = _run(shape, inp)
-    print("cfg2 stage-2 shape", pu.check_fused(shape, ref, out, "cfg2 fused"))
+    print("cfg2 stage-2 shape", pu.check_fused(shape, ref, out, "cfg2 fused", hidden=inp["hidden"]))
 
 
 def test_fused_more_sequences_than_one_row_tile():
@@ -131,18 +131,20 @@ def test_fused_more_sequences_than_one_row_tile():
                    head_dim=16, prefix=3, text=6)
     inp, ref, info = pu.screened_fused_case(shape, 9650)
     print("case", info, flush=True)
-    print(pu.check_fused(shape, ref, _run(shape, inp), "33 sequences"))
+    print(pu.check_fused(shape, ref, _run(shape, inp), "33 sequences", hidden=inp["hidden"]))
     shape = dataclasses.replace(shape, batch=20)      # 80 query rows: the 128-row tile shape
     inp, ref, info = pu.screened_fused_case(shape, 9660)
     print("case", info, flush=True)
-    print(pu.check_fused(shape, ref, _run(shape, inp), "20 sequences"))
+    print(pu.check_fused(shape, ref, _run(shape, inp), "20 sequences", hidden=inp["hidden"]))
 
 
 def test_fused_config5_full():
     """Full-size stage-2 stress shape (32 sequences, 2880 visual tokens, 8 query positions = 256
-    query rows, hidden 4096), in place, all three budgets.  Every sequence is checked on the device
-    against the returned indices; the oracle checks, element by element, the sequences whose
-    selection boundary clears the margin (decided from the oracle's own scores)."""
+    query rows, hidden 4096), in place, all three budgets, every sequence against the oracle:
+    scores element by element, kept indices bit-exact (valid where the oracle's boundary is
+    closer than the margin), hidden states against the order-preserving gather of the original
+    rows under those indices (on the device for all sequences; the oracle's own compaction for
+    the first two)."""
     import torch
     base = wl.config(5)
     shape = base.llm
@@ -152,20 +154,15 @@ def test_fused_config5_full():
     wq = pu.to_device(w["w_q"], wl.BF16)
     wkt = pu.to_device(np.ascontiguousarray(w["w_k"].T), wl.BF16)
     hidden = torch.empty((B, S, shape.hidden), dtype=torch.bfloat16, device="cuda")
-    host, scores, wanted = {}, {}, {k: [] for k in keeps}
+    host, s_ref = {}, np.empty((B, V))
     for b in range(B):
         item = wl.llm_item(shape, base.seed, b)["hidden"]
         hidden[b].copy_(pu.to_device(item, wl.BF16))
-        if all(len(v) >= 2 for v in wanted.values()):
-            continue
-        s_ref = vo.llm_scores_from_hidden(item[None], w["w_q"], w["w_k"], vs, V, shape.n_query,
-                                          shape.q_heads, shape.kv_heads, shape.head_dim)
-        for k in keeps:
-            if len(wanted[k]) < 2 and pu.topk_boundary_gap(s_ref, k) > pu.MARGIN:
-                wanted[k].append(b)
-                host[b], scores[b] = item, s_ref
+        s_ref[b] = vo.llm_scores_from_hidden(item[None], w["w_q"], w["w_k"], vs, V, shape.n_query,
+                                             shape.q_heads, shape.kv_heads, shape.head_dim)[0]
+        if b < 2:
+            host[b] = item
     orig = hidden.clone()
-    print("sequences with a clear boundary per budget:", wanted, flush=True)
 
     for keep in keeps:
         sh = dataclasses.replace(shape, keep=keep)
@@ -173,24 +170,21 @@ def test_fused_config5_full():
         hidden.copy_(orig)
         out = vb.llm_prune_fused(sh, hidden, wq, wkt, want_scores=True)
         torch.cuda.synchronize()
+        err = pu.check_scores(pu.to_host(out["scores"]), s_ref, f"cfg5 fused keep {keep}")
+        kept_h = pu.to_host(out["kept_idx"])
+        differing = pu.check_topk_rows(kept_h, vo.topk(s_ref, keep), s_ref, keep,
+                                       f"cfg5 fused keep {keep}")
         kept = out["kept_idx"].long()
-        assert bool((kept[:, 1:] > kept[:, :-1]).all())
-        assert int(kept.min()) >= 0 and int(kept.max()) < V
         rows = torch.cat([torch.arange(vs, device="cuda").expand(B, vs), vs + kept,
                           torch.arange(vs + V, S, device="cuda").expand(B, S - vs - V)], dim=1)
         assert rows.shape == (B, So)
         want_h = torch.gather(orig, 1, rows[:, :, None].expand(B, So, sh.hidden))
         assert torch.equal(out["hidden"], want_h)
-        np.testing.assert_allclose(pu.to_host(out["scores"]).sum(1), 1.0, rtol=1e-5)
-        assert wanted[keep], "no sequence with a clear boundary for this budget"
-        for b in wanted[keep]:
-            want_kept = vo.topk(scores[b], keep)
-            assert np.array_equal(pu.to_host(out["kept_idx"][b:b + 1]), want_kept), (keep, b)
-            err = pu.check_scores(pu.to_host(out["scores"][b:b + 1]), scores[b],
-                                  f"cfg5 fused keep {keep} sequence {b}")
-            ref_h = vo.compact(host[b][None], want_kept, vs, V)
-            assert np.array_equal(pu.to_host(out["hidden"][b:b + 1]), ref_h)
-            print("cfg5 fused keep", keep, "sequence", b, "score_rel_err", err)
+        for b in host:
+            ref_h = vo.compact(host[b][None], kept_h[b:b + 1], vs, V)
+            assert np.array_equal(pu.to_host(out["hidden"][b:b + 1]), ref_h), (keep, b)
+        print("cfg5 fused keep", keep, {"score_rel_err": err, "rows_valid_not_identical": differing},
+              flush=True)
 
 
 RAGGED_SEQS = [
@@ -234,7 +228,7 @@ def test_fused_ragged_matches_uniform():
     torch.cuda.synchronize()
     assert torch.equal(uni["kept_idx"], rag["kept_idx"]) and torch.equal(uni["scores"], rag["scores"])
     assert torch.equal(uni["hidden"], rag["hidden"][:, :shape.seq_out])
-    print("ragged == uniform", info, pu.check_fused(shape, ref, uni, "uniform"))
+    print("ragged == uniform", info, pu.check_fused(shape, ref, uni, "uniform", hidden=inp["hidden"]))
 
 
 # ---- stage 1 scored from the layer's input rows and projection weights -------------------------

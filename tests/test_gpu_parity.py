@@ -65,7 +65,7 @@ SMALL_ENCODER = {
     "bf16-mean-cls": _enc(has_cls=1, score_mode=1, grid_h=11, grid_w=12, head_dim=48),
     "f32-mean": _enc(wl.F32, has_cls=0, score_mode=1, grid_h=14, grid_w=10, head_dim=40),
     "bf16-mean-wide": _enc(has_cls=0, score_mode=1, grid_h=18, grid_w=9, head_dim=160, heads=2),
-    # more than 1024 tokens per segment: the radix-select path
+    # more than 1024 tokens per segment: the workgroup-wide threshold search
     "bf16-large-grid": _enc(grid_h=40, grid_w=37, heads=2, feat_dim=64, win_rows=5, win_cols=4,
                             keep_global=130, keep_local=100),
     "f32-large-grid-one-window": _enc(wl.F32, batch=1, grid_h=33, grid_w=35, heads=2, feat_dim=64,
@@ -125,7 +125,7 @@ def test_encoder_exact_ties():
 
 
 def test_encoder_exact_ties_large_grid():
-    """All scores tie on a segment that takes the radix-select path."""
+    """All scores tie on a segment large enough for the workgroup-wide threshold search."""
     shape = _enc(wl.F32, batch=1, grid_h=36, grid_w=40, win_rows=3, win_cols=4, keep_global=101,
                  keep_local=50, feat_dim=32, heads=2)
     inp = wl.encoder_inputs(shape, 11)
@@ -168,7 +168,7 @@ SMALL_LLM = {
     "bf16-keep-all-in-place": _llm(keep=50, in_place=1),
     "bf16-keep-none": _llm(keep=0),
     "bf16-no-prefix": _llm(prefix=0, in_place=1),
-    # more than 1024 visual tokens: the radix-select path
+    # more than 1024 visual tokens: the workgroup-wide threshold search
     "bf16-large-span": _llm(vis_len=1500, text=30, keep=700, in_place=1, hidden=128),
     "f32-large-span": _llm(wl.F32, vis_len=1111, text=5, keep=3, hidden=72),
 }
@@ -205,9 +205,7 @@ def test_llm_multi_turn_reselection():
     inp2, ref2, info2 = pu.screened_llm_case(shape, seed=4200)
     # turn 2 = turn 1's pool with turn 2's queries
     turn2 = dict(inp1, q=inp2["q"])
-    ref_t2 = vo.llm_prune(shape, **turn2)
-    if pu.topk_boundary_gap(ref_t2["scores"], shape.keep) <= pu.MARGIN:
-        pytest.skip("second-turn boundary too close for this seed")
+    ref_t2 = vo.llm_prune(shape, **turn2)  # a close boundary falls to check_llm's validity check
     q1, k, v, h = (pu.to_device(inp1[n], shape.dtype) for n in ("q", "k", "v", "hidden"))
     q2 = pu.to_device(inp2["q"], shape.dtype)
     pool = [t.clone() for t in (k, v, h)]
@@ -453,30 +451,27 @@ def test_config4_llm_full():
     print("cfg4 llm", info, pu.check_llm(w.llm, inp, ref, _run_llm(w.llm, inp)))
 
 
-# seed offset found with the oracle alone: the first seeds of configuration 4 put two
-# candidates of some window closer than the margin (each oracle pass takes about a minute,
-# so the screen is not repeated here; the margin itself is still asserted)
-CFG4_SEED_OFFSET = 4
-
-
 def test_config4_encoder_full():
+    """Full size, the configuration's own seed.  64 window boundaries and one global boundary
+    among 16384 flat column means: where one of them is closer than the margin, the validity
+    check of check_encoder decides instead of bit-equality."""
     w = wl.config(4)
     shape = w.encoder
-    inp = wl.encoder_inputs(shape, w.seed + CFG4_SEED_OFFSET)
+    inp = wl.encoder_inputs(shape, w.seed)
     ref = vo.encoder_reduce(shape, inp["q"], inp["k"], inp["x"])
     sg = ref["scores"].reshape(1, 1, -1)
     gap = pu.encoder_boundary_gap(shape, sg, sg)
-    assert gap > pu.MARGIN, gap
     np.testing.assert_allclose(ref["scores"].sum(), 1.0, rtol=1e-9)
     out = _run_encoder(shape, inp)
     print("cfg4 encoder", {"gap": gap}, pu.check_encoder(shape, inp, ref, out, "cfg4"))
 
 
 def test_config5_full():
-    """Full-size stage-2 stress, all three budgets.  Every sequence is checked on the device
-    for consistency with the returned indices (a property that holds at any size); the
-    oracle checks, element by element, the first sequences whose selection boundary clears
-    the margin (decided from the oracle's own scores)."""
+    """Full-size stage-2 stress, all three budgets, every sequence against the oracle: scores
+    element by element, kept indices bit-exact (valid where the oracle's boundary is closer
+    than the margin), and hidden states, K and V against the order-preserving gather of the
+    original rows under those indices (pure copies, evaluated on the device for all 32
+    sequences; the oracle's own compaction is compared for the first two sequences)."""
     import torch
     base = wl.config(5)
     shape = base.llm
@@ -488,16 +483,14 @@ def test_config5_full():
                             device="cuda"),
            "hidden": torch.empty((B, S, shape.hidden), dtype=torch.bfloat16, device="cuda")}
     dev["v"] = torch.empty_like(dev["k"])
-    host, wanted = {}, {k: [] for k in keeps}
+    host, s_ref = {}, np.empty((B, V))
     for b in range(B):
         item = wl.llm_item(shape, base.seed, b)
         for n in dev:
             dev[n][b].copy_(pu.to_device(item[n], shape.dtype))
-        s_ref = vo.llm_scores(item["q"][None], item["k"][None], vs, V)
-        for k in keeps:
-            if len(wanted[k]) < 2 and pu.topk_boundary_gap(s_ref, k) > pu.MARGIN:
-                wanted[k].append(b)
-                host[b] = item
+        s_ref[b] = vo.llm_scores(item["q"][None], item["k"][None], vs, V)[0]
+        if b < 2:
+            host[b] = item
     orig = {n: dev[n].clone() for n in ("k", "v", "hidden")}
 
     for keep in keeps:
@@ -508,9 +501,11 @@ def test_config5_full():
         out = vb.llm_prune(sh, dev["q"], dev["k"], dev["v"], dev["hidden"], want_scores=True)
         torch.cuda.synchronize()
 
+        err = pu.check_scores(pu.to_host(out["scores"]), s_ref, f"cfg5 keep {keep}")
+        kept_h = pu.to_host(out["kept_idx"])
+        differing = pu.check_topk_rows(kept_h, vo.topk(s_ref, keep), s_ref, keep, f"cfg5 keep {keep}")
+
         kept = out["kept_idx"].long()
-        assert bool((kept[:, 1:] > kept[:, :-1]).all())
-        assert int(kept.min()) >= 0 and int(kept.max()) < V
         rows = torch.cat([torch.arange(vs, device="cuda").expand(B, vs), vs + kept,
                           torch.arange(vs + V, S, device="cuda").expand(B, S - vs - V)], dim=1)
         assert rows.shape == (B, So)
@@ -519,13 +514,11 @@ def test_config5_full():
         idx = rows[:, None, :, None].expand(B, sh.kv_heads, So, sh.head_dim)
         assert torch.equal(out["k"], torch.gather(orig["k"], 2, idx))
         assert torch.equal(out["v"], torch.gather(orig["v"], 2, idx))
-        np.testing.assert_allclose(pu.to_host(out["scores"]).sum(1), 1.0, rtol=1e-5)
 
-        assert wanted[keep], "no sequence with a clear boundary for this budget"
         one = dataclasses.replace(sh, batch=1)
-        for b in wanted[keep]:
-            item = {n: a[None] for n, a in host[b].items()}
-            ref = vo.llm_prune(one, **item)
-            got = {n: out[n][b:b + 1] for n in ("kept_idx", "scores", "k", "v", "hidden")}
-            rep = pu.check_llm(one, item, ref, got, f"cfg5 keep {keep} sequence {b}")
-            print("cfg5 keep", keep, "sequence", b, rep)
+        for b in host:
+            for n in ("k", "v", "hidden"):
+                want = vo.compact(host[b][n][None], kept_h[b:b + 1], vs, V)
+                assert np.array_equal(pu.to_host(out[n][b:b + 1]), want), (keep, b, n)
+        print("cfg5 keep", keep, {"score_rel_err": err, "rows_valid_not_identical": differing},
+              flush=True)

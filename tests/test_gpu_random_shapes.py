@@ -1,6 +1,6 @@
 """GPU parity on randomly drawn small shapes (fixed generator seed, so the same shapes every
-run): every entry point against the oracle, within the documented limits of the kernels.  A shape
-whose first seeds leave no clear selection boundary is skipped; most must run."""
+run): every entry point against the oracle, within the documented limits of the kernels.  No shape
+is skipped: without a clear selection boundary the validity check decides."""
 import numpy as np
 import pytest
 
@@ -52,21 +52,17 @@ def _llm_shape(r, fused=False):
 
 
 def _sweep(draw, screen, run, check):
+    """Every drawn shape runs.  A shape whose first seeds leave no clear selection boundary is
+    taken with the widest-gap seed and judged by the validity check (parity_utils)."""
     r = np.random.default_rng(20250522)
-    ran = 0
+    unclear = 0
     for i in range(N_SHAPES):
         shape = draw(r)
-        try:
-            case = screen(shape, 31000 + 97 * i)
-        except AssertionError as e:
-            if "clears the boundary margin" not in str(e):
-                raise
-            print("skipped (flat boundary):", shape, flush=True)
-            continue
-        print("shape", i, shape, flush=True)
+        case = screen(shape, 31000 + 97 * i)
+        unclear += "margin" in case[-1]
+        print("shape", i, shape, case[-1], flush=True)
         check(shape, case, run(shape, case))
-        ran += 1
-    assert ran >= (3 * N_SHAPES) // 4, f"only {ran} of {N_SHAPES} shapes had a usable seed"
+    print(f"{N_SHAPES} shapes run, {unclear} of them without a clear boundary", flush=True)
 
 
 def test_random_encoder_shapes():
@@ -101,7 +97,7 @@ def test_random_fused_llm_shapes():
         return out
     _sweep(lambda r: _llm_shape(r, fused=True),
            lambda s, seed: pu.screened_fused_case(s, seed, max_tries=4), run,
-           lambda s, case, out: pu.check_fused(s, case[1], out, str(s)))
+           lambda s, case, out: pu.check_fused(s, case[1], out, str(s), hidden=case[0]["hidden"]))
 
 
 def test_random_fused_encoder_shapes():

@@ -201,6 +201,51 @@ def test_select_brute_force_with_ties(gh, gw, wr, wc, kl, kg):
         assert len(set(want)) == len(want)
 
 
+def test_select_windows_of_a_grid_that_does_not_divide():
+    """5 x 7 grid, 2 x 3 windows, written out by hand from the partition rule (token (r, c) lies
+    in window (floor(2 r / 5), floor(3 c / 7))): rows 0-2 | 3-4, columns 0-2 | 3-4 | 5-6, i.e.
+
+        0 0 0 1 1 2 2
+        0 0 0 1 1 2 2
+        0 0 0 1 1 2 2
+        3 3 3 4 4 5 5
+        3 3 3 4 4 5 5
+
+    Base scores grow with the token index, so a window's best tokens are its last ones unless a
+    planted score says otherwise.  The planted pairs straddle every boundary of the partition:
+    (2,0) | (3,0) across the row boundary, (0,2) | (0,3) and (0,4) | (0,5) across the column
+    boundaries.  Two per window:
+      window 0: (2,0) = 14 and (0,2) = 2      window 1: (0,3) = 3 and (0,4) = 4
+      window 2: (0,5) = 5 and its last token (2,6) = 20
+      window 3: (3,0) = 21 and its last token (4,2) = 30
+      window 4: last two tokens (4,3) = 31, (4,4) = 32      window 5: (4,5) = 33, (4,6) = 34
+    and one global token, the best of the rest: (4,1) = 29.
+    Any other partition (even splits 2 + 3 rows or 2 + 2 + 3 columns, the window counts of
+    the two axes swapped) puts two of the planted scores into one window or separates a pair
+    the wrong way and picks a different set."""
+    s = 0.001 * np.arange(35, dtype=np.float64)
+    for (r, c), v in {(2, 0): 100.0, (3, 0): 99.0, (0, 2): 98.0, (0, 3): 97.0, (0, 4): 96.0,
+                      (0, 5): 95.0}.items():
+        s[r * 7 + c] = v
+    s = s.reshape(1, 1, 35)
+    kept = vo.select(s, s, 5, 7, 2, 3, 12, 0)
+    assert kept.tolist() == [[2, 3, 4, 5, 14, 20, 21, 30, 31, 32, 33, 34]]
+    kept = vo.select(s, s, 5, 7, 2, 3, 12, 1)
+    assert kept.tolist() == [[2, 3, 4, 5, 14, 20, 21, 29, 30, 31, 32, 33, 34]]
+    # the transposed case (7 x 5 grid, 3 x 2 windows), planted at the mirrored positions
+    t = 0.001 * np.arange(35, dtype=np.float64)
+    for (r, c), v in {(0, 2): 100.0, (0, 3): 99.0, (2, 0): 98.0, (3, 0): 97.0, (4, 0): 96.0,
+                      (5, 0): 95.0}.items():
+        t[r * 5 + c] = v
+    # rows 0-2 | 3-4 | 5-6, columns 0-2 | 3-4:
+    #   window 0 (rows 0-2, cols 0-2): (0,2) = 2, (2,0) = 10     window 1 (rows 0-2, cols 3-4): (0,3) = 3, last (2,4) = 14
+    #   window 2 (rows 3-4, cols 0-2): (3,0) = 15, (4,0) = 20    window 3 (rows 3-4, cols 3-4): (4,3) = 23, (4,4) = 24
+    #   window 4 (rows 5-6, cols 0-2): (5,0) = 25, last (6,2) = 32   window 5 (rows 5-6, cols 3-4): (6,3) = 33, (6,4) = 34
+    t = t.reshape(1, 1, 35)
+    kept = vo.select(t, t, 7, 5, 3, 2, 12, 0)
+    assert kept.tolist() == [[2, 3, 10, 14, 15, 20, 23, 24, 25, 32, 33, 34]]
+
+
 def test_select_rejects_budget_larger_than_window():
     s = np.zeros((1, 1, 16))
     with pytest.raises(ValueError):
