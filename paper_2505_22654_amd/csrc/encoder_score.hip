@@ -9,6 +9,8 @@
 //                (two passes over Q K^T on the matrix cores: row log-sum-exp,
 //                then column sums of exp(s - lse_i); the N x N matrix is never
 //                stored)
+#include <type_traits>
+
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -424,6 +426,331 @@ __global__ __launch_bounds__(256, 2) void mean_colsum_kernel(const T *__restrict
 }
 
 // ---------------------------------------------------------------------------
+// Both passes for bf16 rows of up to 160 bytes, software-pipelined inside each wave.
+//
+// Measured on this GPU (issue rates in core cycles per wave instruction): v_fma / v_mul / v_add
+// 4, v_exp_f32 8, a 32x32x16 matrix instruction occupies the matrix pipe for 32 and takes about
+// 10 from the vector issue port.  A 32 x 32 tile of logits therefore costs 16 x (4 + 8 + 4) = 256
+// cycles of vector work per lane against 160 cycles of matrix work (80-element rows): the
+// vector ALU is the bound, and the matrix instructions have to be hidden under it.  A wave that
+// multiplies, waits and then exponentiates leaves both pipes idle in turn, so here every wave
+// keeps two accumulator sets: the matrix instructions of tile t+1 are issued while the
+// exponentials of tile t run, and the LDS reads of tile t+2's operands are already under way.
+//
+// A workgroup (4 waves) owns 4 x 32 x HALVES resident rows, held in registers as matrix
+// operands (pass 1: query rows, pass 2: key rows).  The other operand streams through LDS in
+// stages of 128 rows (4 tiles), two stages in LDS, the next one in flight in registers: one
+// workgroup barrier per 128 streamed rows.  Accumulator layout as in mma32_chunk: a lane owns
+// resident row (lane % 32) of each half and 16 of the 32 streamed rows of a tile.
+//   PASS 1: lse2[i] = log2 sum_j 2^(sl2 * q_i . k_j)      (resident i, streamed j)
+//   PASS 2: head_scores[j] = sum_i 2^(sl2 * q_i . k_j - lse2[i])   (resident j, streamed i)
+// In pass 2 the subtraction rides on the matrix cores: every streamed row carries one more
+// 32-byte chunk holding -lse2[i] / sl2 as three bf16 pieces (24 significant bits: the fp32 value
+// exactly), the resident operand holds ones against them, so the accumulator comes out as
+// q_i . k_j - lse2[i] / sl2 and a logit costs multiply, exponential, add with no per-row
+// operand to fetch.  Rows past the end carry -inf and contribute 2^-inf = 0.
+// ---------------------------------------------------------------------------
+constexpr int kPipeStageRows = 128;
+
+template <int NC, int HALVES, int PASS>
+__global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
+    const unsigned char *__restrict__ resident, const unsigned char *__restrict__ streamed,
+    const float *__restrict__ lse_in, float *__restrict__ out, int n_heads_total, int S, int dh,
+    int res_first, int n_res, int str_first, int n_str, float sl2) {
+    constexpr int NCX = NC + (PASS == 2 ? 1 : 0);      // chunks per streamed row in LDS
+    constexpr int STRIDE = NCX * 32 + 16;              // LDS row pitch: conflict-free 16-byte reads
+    constexpr int PPR = NC * 2;                        // 16-byte pieces per streamed row in memory
+    constexpr int RB = 4 * 32 * HALVES;                // resident rows per workgroup
+    constexpr int NM = NCX * HALVES;                   // matrix instructions per tile
+    constexpr int NL = 16 * HALVES;                    // logits per lane and tile
+    static_assert(kPipeStageRows * PPR == 256 * NC, "NC pieces per thread and stage");
+    __shared__ __align__(16) unsigned char lds[2][kPipeStageRows * STRIDE];
+
+    const int nblk = (n_res + RB - 1) / RB;
+    const int total = n_heads_total * nblk;
+    const int item = xcd_contiguous_item(total);
+    if (item >= total) return;
+    const int bh = item / nblk, blk = item - bh * nblk;
+    const int row_bytes = dh * 2;
+    const unsigned char *rbase = resident + ((int64_t)bh * S + res_first) * row_bytes;
+    const unsigned char *sbase = streamed + ((int64_t)bh * S + str_first) * row_bytes;
+    const float *lse_h = PASS == 2 ? lse_in + (int64_t)bh * n_str : nullptr;
+
+    const int tid = threadIdx.x, lane = lane_id(), g = lane >> 5, w = wave_id();
+    uint4 kf[HALVES][NC];
+#pragma unroll
+    for (int h = 0; h < HALVES; ++h) {
+        const int row = blk * RB + (w * HALVES + h) * 32 + (lane & 31);
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            kf[h][c] = load16_guard(rbase, (int64_t)row * row_bytes + 32 * c + 16 * g,
+                                    row < n_res && 32 * c + 16 * g < row_bytes);
+    }
+    // pass 2: the resident side of the extra chunk, three ones (bf16 0x3f80) in the lower half
+    const uint4 ones = g == 0 ? make_uint4(0x3f803f80u, 0x00003f80u, 0u, 0u) : zero16();
+
+    const int ntiles = (n_str + 31) >> 5;
+    const int nstages = (n_str + kPipeStageRows - 1) / kPipeStageRows;
+
+    // ---- staging of the streamed operand: thread t carries pieces t, t + 256, ... of a stage
+    uint4 sreg[NC];
+    float lse_reg = 0.f;
+    auto stage_load = [&](int s) {
+#pragma unroll
+        for (int it = 0; it < NC; ++it) {
+            const int p = tid + it * 256;
+            const int r = p / PPR, piece = p - r * PPR;
+            // clamped, not predicated: rows past the end re-read the last row (finite data that
+            // the consumers neutralise), pieces past the end of a row its last piece (the
+            // resident operand is zero there)
+            const int row = min(s * kPipeStageRows + r, n_str - 1);
+            sreg[it] = load16(sbase, (int64_t)row * row_bytes + min(piece * 16, row_bytes - 16));
+        }
+        if (PASS == 2 && tid < kPipeStageRows)
+            lse_reg = lse_h[min(s * kPipeStageRows + tid, n_str - 1)];
+    };
+    const float inv_sl2 = 1.0f / sl2;
+    auto stage_store = [&](int s) {
+        unsigned char *dst = lds[s & 1];
+#pragma unroll
+        for (int it = 0; it < NC; ++it) {
+            const int p = tid + it * 256;
+            const int r = p / PPR, piece = p - r * PPR;
+            *reinterpret_cast<uint4 *>(dst + r * STRIDE + piece * 16) = sreg[it];
+        }
+        if (PASS == 2 && tid < kPipeStageRows) {
+            // -lse / sl2 as hi + mid + lo; each residual is exact in fp32 and the third piece
+            // takes what is left of the 24 bits.  (Decided here, not where the value was
+            // fetched: arithmetic right behind the load would make the wave wait for it.)
+            uint4 x = zero16();
+            if (s * kPipeStageRows + tid < n_str) {
+                const float v = -lse_reg * inv_sl2;
+                const uint32_t hi = f32_to_bf16_rne(v);
+                const float r1 = v - __uint_as_float(hi << 16);
+                const uint32_t mid = f32_to_bf16_rne(r1);
+                const float r2 = r1 - __uint_as_float(mid << 16);
+                x.x = hi | (mid << 16);
+                x.y = f32_to_bf16_rne(r2);
+            } else {
+                x.x = 0xff80u;  // -inf
+            }
+            unsigned char *e = dst + tid * STRIDE + NC * 32;
+            *reinterpret_cast<uint4 *>(e) = x;
+            *reinterpret_cast<uint4 *>(e + 16) = zero16();
+        }
+    };
+
+    u32x4_t fr[NCX];      // streamed operand of one tile in matrix-operand layout, refilled in place
+    f32x16_t acc[2][HALVES];
+    auto frag_ptr = [&](int t) {
+        return lds[(t >> 2) & 1] + ((t & 3) * 32 + (lane & 31)) * STRIDE + 16 * g;
+    };
+    auto resident_frag = [&](int h, int c) {
+        union {
+            uint4 u;
+            bf16x8_t v;
+        } x;
+        x.u = c < NC ? kf[h][c < NC ? c : 0] : ones;
+        return x.v;
+    };
+
+    float m_run[HALVES], l_run[HALVES], colsum[HALVES];
+    bool have_ref[HALVES];
+#pragma unroll
+    for (int h = 0; h < HALVES; ++h) {
+        m_run[h] = -INFINITY;
+        l_run[h] = 0.f;
+        colsum[h] = 0.f;
+        have_ref[h] = false;
+    }
+
+    // One pipeline step: the vector work of tile t (accumulators `cur`); when MULT is set, the
+    // matrix instructions of tile t + 1 (operands in `fr`, accumulators `nxt`) are issued in
+    // between, and every operand chunk is refilled with tile t + 2's (REFILL) right after its
+    // last use.  MASK: tile t is the ragged last tile of pass 1.
+    auto step = [&](int t, f32x16_t(&cur)[HALVES], f32x16_t(&nxt)[HALVES], auto mult_tag,
+                    auto refill_tag, auto mask_tag) {
+        constexpr bool MULT = decltype(mult_tag)::value, REFILL = decltype(refill_tag)::value,
+                       MASK = decltype(mask_tag)::value;
+        float ref[HALVES], part[HALVES];
+        if constexpr (PASS == 1) {
+            if constexpr (MASK) {
+#pragma unroll
+                for (int h = 0; h < HALVES; ++h)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (t * 32 + acc_row(r) >= n_str) cur[h][r] = -INFINITY;
+            }
+            // Lazy reference: exponentials are taken against a per-lane reference that is an
+            // actual logit of the row (so the sum is >= 1 and small terms may underflow
+            // harmlessly) and is only raised when the partial sum threatens to overflow.
+#pragma unroll
+            for (int h = 0; h < HALVES; ++h) {
+                if (!have_ref[h]) {
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, cur[h][r]);
+                    if (mx > -INFINITY) {
+                        m_run[h] = mx * sl2;
+                        have_ref[h] = true;
+                    }
+                }
+                ref[h] = have_ref[h] ? m_run[h] : 0.f;  // without a reference every logit is -inf
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < HALVES; ++h) part[h] = 0.f;
+        if constexpr (MULT) {
+#pragma unroll
+            for (int h = 0; h < HALVES; ++h)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) nxt[h][r] = 0.f;
+        }
+        const unsigned char *next_frags = REFILL ? frag_ptr(t + 2) : nullptr;
+        // Slot by slot: one matrix instruction, the LDS read that refills an operand chunk
+        // after its last use, and a slice of tile t's logits (about three: forty cycles of
+        // vector work, which is what one matrix instruction keeps its pipe busy for).  (Pinning
+        // this order with scheduling groups, or tying the step's inputs to this point with
+        // empty asm statements, measured the same as leaving the order to the compiler.)
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            if constexpr (MULT) {
+                const int c = m / HALVES, h = m % HALVES;
+                nxt[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8_t, fr[c]), resident_frag(h, c), nxt[h], 0, 0, 0);
+                if constexpr (REFILL) {
+                    if (h == HALVES - 1) fr[c] = *reinterpret_cast<const u32x4_t *>(next_frags + 32 * c);
+                }
+            }
+#pragma unroll
+            for (int i = m * NL / NM; i < (m + 1) * NL / NM; ++i) {
+                const int h = i / 16, r = i % 16;
+                if constexpr (PASS == 1)
+                    part[h] += __builtin_amdgcn_exp2f(fmaf(cur[h][r], sl2, -ref[h]));
+                else
+                    part[h] += __builtin_amdgcn_exp2f(cur[h][r] * sl2);
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < HALVES; ++h) {
+            if constexpr (PASS == 2) {
+                colsum[h] += part[h];
+            } else {
+                if (part[h] < 0x1p100f) {
+                    l_run[h] += part[h];
+                } else {  // a logit far above the reference: re-base on this tile's maximum
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, cur[h][r]);
+                    const float m_new = fmaxf(m_run[h], mx * sl2);
+                    float add = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        add += __builtin_amdgcn_exp2f(fmaf(cur[h][r], sl2, -m_new));
+                    l_run[h] = l_run[h] * __builtin_amdgcn_exp2f(m_run[h] - m_new) + add;
+                    m_run[h] = m_new;
+                }
+            }
+        }
+        // keep the steps apart: left alone, the compiler gathers the matrix instructions of
+        // several steps into one burst right behind the LDS reads they wait for
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+
+    // ---- prologue: stage 0 in LDS, stage 1 in flight, tile 0 multiplied, tile 1's operands read
+    stage_load(0);
+    stage_store(0);
+    __syncthreads();
+    if (nstages > 1) stage_load(1);
+    {
+        const unsigned char *f0 = frag_ptr(0);
+#pragma unroll
+        for (int c = 0; c < NCX; ++c) fr[c] = *reinterpret_cast<const u32x4_t *>(f0 + 32 * c);
+#pragma unroll
+        for (int h = 0; h < HALVES; ++h) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[0][h][r] = 0.f;
+#pragma unroll
+            for (int c = 0; c < NCX; ++c)
+                acc[0][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8_t, fr[c]), resident_frag(h, c), acc[0][h], 0, 0, 0);
+        }
+        if (ntiles > 1) {
+            const unsigned char *f1 = frag_ptr(1);
+#pragma unroll
+            for (int c = 0; c < NCX; ++c) fr[c] = *reinterpret_cast<const u32x4_t *>(f1 + 32 * c);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    const bool ragged = PASS == 1 && (n_str & 31) != 0;
+    int t0 = 0;
+    // Steady state, four tiles (one stage) per trip: every step here has a tile t + 2 to fetch
+    // operands for and a tile t + 1 to multiply, so the body is straight-line code.
+    for (; t0 + 6 <= ntiles; t0 += 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = t0 + j;
+            if (j == 2) {
+                // the next stage goes to LDS now (its loads were issued four tiles ago), and
+                // the one after it takes over the staging registers
+                const int s = t >> 2;
+                stage_store(s + 1);
+                __syncthreads();
+                if (s + 2 < nstages) stage_load(s + 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            step(t, acc[j & 1], acc[(j + 1) & 1], yes{}, yes{}, no{});
+        }
+    }
+    // The last tiles: the same steps with their conditions spelled out.
+    for (; t0 < ntiles; t0 += 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = t0 + j;
+            if (t < ntiles) {
+                if (j == 2) {
+                    const int s = t >> 2;
+                    if (s + 1 < nstages) {
+                        stage_store(s + 1);
+                        __syncthreads();
+                        if (s + 2 < nstages) stage_load(s + 2);
+                    }
+                }
+                if (t + 2 < ntiles) {
+                    step(t, acc[j & 1], acc[(j + 1) & 1], yes{}, yes{}, no{});
+                } else if (t + 1 < ntiles) {
+                    step(t, acc[j & 1], acc[(j + 1) & 1], yes{}, no{}, no{});
+                } else if (ragged) {
+                    step(t, acc[j & 1], acc[(j + 1) & 1], no{}, no{}, yes{});
+                } else {
+                    step(t, acc[j & 1], acc[(j + 1) & 1], no{}, no{}, no{});
+                }
+            }
+        }
+    }
+
+    // the two half-waves hold disjoint streamed rows of the same resident row
+#pragma unroll
+    for (int h = 0; h < HALVES; ++h) {
+        const int row = blk * RB + (w * HALVES + h) * 32 + (lane & 31);
+        if constexpr (PASS == 1) {
+            const float m_o = __shfl_xor(m_run[h], 32, kWave), l_o = __shfl_xor(l_run[h], 32, kWave);
+            const float M = fmaxf(m_run[h], m_o);
+            float L = 0.f;
+            if (m_run[h] > -INFINITY) L += l_run[h] * __builtin_amdgcn_exp2f(m_run[h] - M);
+            if (m_o > -INFINITY) L += l_o * __builtin_amdgcn_exp2f(m_o - M);
+            if (g == 0 && row < n_res) out[(int64_t)bh * n_res + row] = M + log2f(L);
+        } else {
+            const float c = colsum[h] + __shfl_xor(colsum[h], 32, kWave);
+            if (g == 0 && row < n_res) out[(int64_t)bh * n_res + row] = c;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 template <typename T>
@@ -501,9 +828,37 @@ static hipError_t launch_score_mean_nc(const ScoreArgs &a, hipStream_t s, int pa
     return hipGetLastError();
 }
 
+// The pipelined form: bf16 rows of up to 160 bytes (head sizes up to 80).
+template <int NC, int HALVES>
+static hipError_t launch_mean_pipe(const ScoreArgs &a, hipStream_t s, int pass) {
+    const int row_first = a.has_cls;
+    const int key_first = a.domain_all ? 0 : a.has_cls;
+    const int n_keys = a.S - key_first;
+    constexpr int RB = 4 * 32 * HALVES;
+    const int total = a.BC * a.H * ((a.N + RB - 1) / RB);
+    const int grid = ((total + 7) / 8) * 8;
+    const float sl2 = a.scale * 1.4426950408889634f;
+    const unsigned char *q = reinterpret_cast<const unsigned char *>(a.q);
+    const unsigned char *k = reinterpret_cast<const unsigned char *>(a.k);
+    if (pass == 1)  // resident query rows (patch rows), streamed keys of the softmax domain
+        hipLaunchKernelGGL((mean_pipe_kernel<NC, HALVES, 1>), dim3(grid), dim3(256), 0, s, q, k,
+                           (const float *)nullptr, a.lse, a.BC * a.H, a.S, a.dh, row_first, a.N,
+                           key_first, n_keys, sl2);
+    else            // resident patch keys, streamed query rows (patch rows) with their lse
+        hipLaunchKernelGGL((mean_pipe_kernel<NC, HALVES, 2>), dim3(grid), dim3(256), 0, s, k, q,
+                           (const float *)a.lse, a.head_scores, a.BC * a.H, a.S, a.dh, row_first,
+                           a.N, row_first, a.N, sl2);
+    return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t launch_score_mean_t(const ScoreArgs &a, hipStream_t s, int pass) {
     const int nc = (a.dh * (int)sizeof(T) + 31) / 32;
+    if constexpr (sizeof(T) == 2) {
+        if (nc <= 2) return launch_mean_pipe<2, 2>(a, s, pass);
+        if (nc <= 4) return launch_mean_pipe<4, 2>(a, s, pass);
+        if (nc <= 5) return launch_mean_pipe<5, 2>(a, s, pass);
+    }
     if (nc <= 2) return launch_score_mean_nc<T, 2>(a, s, pass);
     if (nc <= 4) return launch_score_mean_nc<T, 4>(a, s, pass);
     if (nc <= 5) return launch_score_mean_nc<T, 5>(a, s, pass);
