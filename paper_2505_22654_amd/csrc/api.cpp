@@ -27,7 +27,7 @@ inline int elem_bytes(int dtype) { return dtype == VSCAN_BF16 ? 2 : 4; }
 
 struct EncoderPlan {
     int N, S, BC, T, W, kw, kg, Kseg, K, U;
-    size_t off_head_global, off_head_local, off_lse, off_drop, off_best, bytes;
+    size_t off_head_global, off_head_local, off_lse, off_drop, off_best, off_inv_norm, bytes;
 };
 
 int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
@@ -84,6 +84,8 @@ int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
     off += align_up((size_t)d->batch * p->U * sizeof(int32_t));
     p->off_best = off;
     off += align_up((size_t)d->batch * p->T * sizeof(uint64_t));
+    p->off_inv_norm = off;
+    off += align_up((size_t)d->batch * p->K * sizeof(float));
     p->bytes = off ? off : kAlign;
     return VSCAN_OK;
 }
@@ -309,6 +311,7 @@ int enqueue_encoder_tail(const vscan_encoder_desc *d, const EncoderPlan &p, bool
     ma.best = se.best;
     ma.merged = merged;
     ma.assign_out = assign_out;
+    ma.inv_norm = reinterpret_cast<float *>(ws + p.off_inv_norm);
     ma.B = d->batch;
     ma.T = p.T;
     ma.D = d->feat_dim;

@@ -44,6 +44,7 @@ struct MergeArgs {
     uint64_t *best;            // [B, T]
     void *merged;              // [B, K, D]
     int32_t *assign_out;       // optional [B, T]
+    float *inv_norm;           // [B, K] scratch: 1 / ||x_s|| of the kept rows (large form only)
     int B, T, D, K, is_bf16;
 };
 hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s);

@@ -11,6 +11,8 @@
 //   merge           Eq. 4: one wave per kept slot averages the slot's own token
 //                   and its members in ascending token order (fixed order: no
 //                   floating-point atomics, bit-reproducible).
+#include <atomic>
+
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -208,6 +210,248 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
     __syncthreads();
 
     if (!computes) return;  // no barrier below
+    // epilogue: acc[i][j][r] = x_slot . x_token with
+    //   slot  = m0 + (wm*TM + i)*32 + acc_row(r),  token column = n0 + (wn*TN + j)*32 + lane%32
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        float best_v = -INFINITY;
+        int best_s = -1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rl = (wm * TM + i) * 32 + acc_row(r);
+                if (m0 + rl < K) {
+                    const float v = acc[i][j][r] * inv_s[rl];
+                    // slots are visited in ascending order: strict > keeps the lowest on ties
+                    if (best_s < 0 || v > best_v) {
+                        best_v = v;
+                        best_s = m0 + rl;
+                    }
+                }
+            }
+        unsigned long long packed =
+            best_s < 0 ? 0ull
+                       : (((unsigned long long)float_to_key(best_v)) << 32) |
+                             (unsigned long long)(uint32_t)~(uint32_t)best_s;
+        const unsigned long long other = __shfl_xor(packed, 32, kWave);
+        if (other > packed) packed = other;
+        const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+        if (g == 0 && col < U && packed != 0ull) {
+            const int tok = min(max(col_tok[j], 0), T_img - 1);
+            atomicMax(best + (int64_t)b * T_img + tok, packed);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// 1 / max(||x_s||, eps) of every kept row, for the large form of the similarity kernel below:
+// one wave per kept row.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void kept_inv_norm_kernel(const T *__restrict__ x,
+                                                            const int32_t *__restrict__ kept_idx,
+                                                            float *__restrict__ inv_norm, int T_img,
+                                                            int D, int K, int B) {
+    constexpr int E = ElemTraits<T>::kPer16B;
+    const int row = blockIdx.x * 4 + wave_id();  // b * K + slot
+    if (row >= B * K) return;
+    const int b = row / K;
+    const int tok = min(max(kept_idx[row], 0), T_img - 1);
+    const unsigned char *xr =
+        reinterpret_cast<const unsigned char *>(x) + ((int64_t)b * T_img + tok) * D * (int64_t)sizeof(T);
+    const int npieces = D / E;
+    float ss = 0.f;
+    for (int p0 = 0; p0 < npieces; p0 += 4 * kWave) {
+        uint4 raw[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)  // clamped, not predicated: four independent loads in flight
+            raw[u] = load16(xr, (int64_t)min(p0 + u * kWave + lane_id(), npieces - 1) * 16);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float v[E];
+            unpack16<T>(raw[u], v);
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) part = fmaf(v[e], v[e], part);
+            ss += p0 + u * kWave + lane_id() < npieces ? part : 0.f;
+        }
+    }
+    ss = wave_sum(ss);
+    if (lane_id() == 0) inv_norm[row] = 1.0f / fmaxf(sqrtf(ss), kNormEps);
+}
+
+// ---------------------------------------------------------------------------
+// The large form of the kept x dropped similarity: 128 x 128 workgroup tiles of 2 x 2 waves.
+// Counters on the form above showed fifteen vector instructions per matrix instruction at this
+// size (squared norms of the staged kept rows, 64-bit address arithmetic and clamps for every
+// 16-byte piece and stage), which made the vector ALU, not the matrix cores, the busiest unit.
+// Here the inverse norms come precomputed (kept_inv_norm_kernel) and a stage's loads use buffer
+// addressing - the image in a resource descriptor, per-thread 32-bit offsets fixed for the
+// whole kernel, the stage's column offset in a scalar register: no vector arithmetic per load.
+// ---------------------------------------------------------------------------
+// Workgroup tile (32 TM WM) kept slots x (32 TN WN) dropped tokens, WM x WN waves of TM x TN
+// blocks.  Two shapes are used: 128 x 128 with four waves, two workgroups per CU (kept sets of
+// a few hundred slots, where larger tiles would be mostly padding), and 256 x 256 with eight
+// waves of 128 x 64 (one workgroup per CU), which halves the operand traffic from L2 into LDS
+// per multiply-add and reads 0.75 operand fragments from LDS per matrix instruction instead of 1.
+//
+// Which tile a workgroup takes (`mode`): 0 = in launch order; 1 = images pinned to XCDs (eight
+// or more images: image_affine_decode); 2 = one large image: workgroups are handed to the 8 XCDs
+// round-robin by linear index and every XCD has its own L2, so XCD x works through a compact
+// block of (tiles_m / 4) x (tiles_n / 2) tiles, kept tile fastest - its band of kept rows stays
+// in its L2 and its band of dropped rows streams through once.
+template <typename T, int TM, int TN, int WM, int WN, int KC>
+__global__ __launch_bounds__(64 * WM * WN, WM * WN <= 4 ? 2 : 1) void sim_argmax_large_kernel(
+    const T *__restrict__ x, const int32_t *__restrict__ kept_idx,
+    const int32_t *__restrict__ drop_idx, const float *__restrict__ inv_norm,
+    unsigned long long *__restrict__ best, int T_img, int D, int K, int U, int B, int mode) {
+    constexpr int THREADS = 64 * WM * WN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN, ROWS = BM + BN;
+    constexpr int PPR = KC * 2;                 // 16-byte pieces per row per stage
+    constexpr int STRIDE = KC * 32 + 16;        // LDS row stride in bytes
+    constexpr int PER_THREAD = ROWS * PPR / THREADS;
+    constexpr int A_PIECES = BM * PPR / THREADS;
+    static_assert(ROWS * PPR % THREADS == 0 && BM * PPR % THREADS == 0, "tile must split evenly");
+    static_assert(THREADS % PPR == 0, "a thread keeps its piece column for all its rows");
+    extern __shared__ __align__(16) unsigned char lds_raw[];  // two stages, then BM inverse norms
+    unsigned char(*lds)[ROWS * STRIDE] = reinterpret_cast<unsigned char(*)[ROWS * STRIDE]>(lds_raw);
+    float *inv_s = reinterpret_cast<float *>(lds_raw + 2 * ROWS * STRIDE);
+
+    const int tiles_n = (U + BN - 1) / BN, tiles_m = (K + BM - 1) / BM;
+    int b, tile_m, tile_n;
+    if (mode == 2) {
+        const int id = blockIdx.x % (tiles_m * tiles_n);
+        b = blockIdx.x / (tiles_m * tiles_n);
+        const int xcd = id % kXcds, j = id / kXcds;          // j-th tile of this XCD
+        const int bm = tiles_m / 4, bn = tiles_n / 2;         // the XCD's block of tiles
+        tile_m = (xcd % 4) * bm + j % bm;
+        tile_n = (xcd / 4) * bn + j / bm;
+    } else {
+        int tile;
+        if (!image_affine_decode(B, tiles_m * tiles_n, mode == 1, b, tile)) return;
+        tile_m = tile / tiles_n;
+        tile_n = tile - tile_m * tiles_n;
+    }
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int tid = threadIdx.x, lane = lane_id(), g = lane >> 5;
+    const int wm = wave_id() / WN, wn = wave_id() % WN;
+    const int row_bytes = D * (int)sizeof(T);
+    const unsigned char *xb =
+        reinterpret_cast<const unsigned char *>(x) + (int64_t)b * T_img * row_bytes;
+
+    // Byte offset, inside the image, of the piece column this thread carries in each of its
+    // rows (32 bits: the ABI layer rejects images of 2 GiB or more).  Rows outside the problem
+    // (slots >= K, columns >= U) stage some other row of the image: their results are masked
+    // in the epilogue, and a real row keeps every load unconditional and inside the image.
+    const int piece = tid % PPR;
+    uint32_t src[PER_THREAD];
+    {
+        int tok[PER_THREAD];
+#pragma unroll
+        for (int it = 0; it < PER_THREAD; ++it) {  // clamped positions: all index loads in flight
+            const int r = tid / PPR + it * (THREADS / PPR);
+            tok[it] = it < A_PIECES ? kept_idx[(int64_t)b * K + min(m0 + r, K - 1)]
+                                    : drop_idx[(int64_t)b * U + min(n0 + r - BM, U - 1)];
+        }
+#pragma unroll
+        for (int it = 0; it < PER_THREAD; ++it)  // indices come from device memory: stay inside
+            src[it] = (uint32_t)(min(max(tok[it], 0), T_img - 1) * row_bytes + piece * 16);
+    }
+    int col_tok[TN];  // dropped token of each result column this lane reports in the epilogue
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+        col_tok[j] = drop_idx[(int64_t)b * U + min(col, U - 1)];
+    }
+    for (int i = tid; i < BM; i += THREADS) inv_s[i] = inv_norm[(int64_t)b * K + min(m0 + i, K - 1)];
+
+    const int nstages = (row_bytes + KC * 32 - 1) / (KC * 32);
+    const int nfull = row_bytes / (KC * 32);  // stages that lie inside the row entirely
+    // Buffer resource over this image (untyped 32-bit data format); every offset used with it
+    // lies inside the image by construction, the hardware's range check is not relied upon.
+    const __amdgpu_buffer_rsrc_t image = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(xb), 0, T_img * row_bytes, 0x00020000);
+    auto stage_load = [&](int stage, uint4(&regs)[PER_THREAD]) {
+        if (stage < nfull) {
+            // buffer addressing: image base in the resource, the thread's fixed offset in a
+            // vector register, the stage's column offset in a scalar register
+            const int soff = stage * (KC * 32);
+#pragma unroll
+            for (int it = 0; it < PER_THREAD; ++it) {
+                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(image, (int)src[it], soff, 0);
+                regs[it] = make_uint4(v.x, v.y, v.z, v.w);
+            }
+        } else {
+            // the ragged last stage: a piece past the end of the row re-reads the row's last
+            // piece and is cleared when it is written to LDS
+#pragma unroll
+            for (int it = 0; it < PER_THREAD; ++it) {
+                const int col_byte = min(stage * KC * 32 + piece * 16, row_bytes - 16);
+                regs[it] = load16(xb, (int64_t)(src[it] - piece * 16) + col_byte);
+            }
+        }
+    };
+    unsigned char *const my_lds = lds_raw + (tid / PPR) * STRIDE + piece * 16;
+    auto stage_store = [&](int buf, const uint4(&regs)[PER_THREAD], int stage) {
+        unsigned char *dst = my_lds + buf * (ROWS * STRIDE);
+        if (stage < nfull) {  // uniform: the common case carries no per-piece selects
+#pragma unroll
+            for (int it = 0; it < PER_THREAD; ++it)
+                *reinterpret_cast<uint4 *>(dst + it * (THREADS / PPR) * STRIDE) = regs[it];
+        } else {
+            const bool keep = stage * KC * 32 + piece * 16 < row_bytes;
+#pragma unroll
+            for (int it = 0; it < PER_THREAD; ++it)
+                *reinterpret_cast<uint4 *>(dst + it * (THREADS / PPR) * STRIDE) =
+                    keep ? regs[it] : zero16();
+        }
+    };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // chunks [c0, c1) of the stage in `cur`
+    auto compute = [&](const unsigned char *cur, int c0, int c1) {
+        const unsigned char *arow = cur + (wm * 32 * TM + (lane & 31)) * STRIDE + 16 * g;
+        const unsigned char *brow = cur + (BM + wn * 32 * TN + (lane & 31)) * STRIDE + 16 * g;
+#pragma unroll
+        for (int c = c0; c < c1; ++c) {
+            uint4 af[TM], bf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const uint4 *>(arow + i * 32 * STRIDE + 32 * c);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bf[j] = *reinterpret_cast<const uint4 *>(brow + j * 32 * STRIDE + 32 * c);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) mma32_chunk<T>(acc[i][j], af[i], bf[j]);
+        }
+    };
+
+    // The next stage's loads are issued before the stage is multiplied and written to the other
+    // LDS buffer after the first half of the matrix instructions: the LDS writes then complete
+    // under the second half, and the barrier at the end of the stage finds nothing pending.
+    uint4 ra[PER_THREAD];
+    stage_load(0, ra);
+    stage_store(0, ra, 0);
+    __syncthreads();
+    for (int st = 0; st < nstages; ++st) {
+        const bool more = st + 1 < nstages;
+        if (more) stage_load(st + 1, ra);
+        compute(lds[st & 1], 0, KC / 2);
+        if (more) stage_store((st + 1) & 1, ra, st + 1);
+        compute(lds[st & 1], KC / 2, KC);
+        if (more) __syncthreads();
+    }
+
     // epilogue: acc[i][j][r] = x_slot . x_token with
     //   slot  = m0 + (wm*TM + i)*32 + acc_row(r),  token column = n0 + (wn*TN + j)*32 + lane%32
 #pragma unroll
@@ -498,15 +742,56 @@ static hipError_t sim_t(const MergeArgs &a, hipStream_t s) {
                        a.D, a.K, U, a.B, (int)affine);
     return hipGetLastError();
 }
+template <typename T, int TM, int TN, int WM, int WN, int KC>
+static hipError_t sim_large_launch(const MergeArgs &a, hipStream_t s) {
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    const int U = a.T - a.K;
+    const int tiles_m = (a.K + BM - 1) / BM, tiles_n = (U + BN - 1) / BN;
+    const bool affine = image_affinity(a);
+    const int mode = affine ? 1 : (tiles_m % 4 == 0 && tiles_n % 2 == 0 ? 2 : 0);
+    const size_t smem = (size_t)2 * (BM + BN) * (KC * 32 + 16) + BM * sizeof(float);
+    auto kernel = sim_argmax_large_kernel<T, TM, TN, WM, WN, KC>;
+    static std::atomic<bool> attribute_set{false};  // per instantiation; the value never changes
+    if (smem > 64 * 1024 && !attribute_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attribute_set = true;
+    }
+    dim3 grid(image_affine_grid(a.B, tiles_m * tiles_n, affine));
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN), smem, s, (const T *)a.x, a.kept_idx,
+                       a.drop_idx, (const float *)a.inv_norm, (unsigned long long *)a.best, a.T,
+                       a.D, a.K, U, a.B, mode);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t sim_large_t(const MergeArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(kept_inv_norm_kernel<T>, dim3((a.B * a.K + 3) / 4), dim3(256), 0, s,
+                       (const T *)a.x, a.kept_idx, a.inv_norm, a.T, a.D, a.K, a.B);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // 256 x 256 tiles once both sides fill them and there are enough of them for every CU
+    const int U = a.T - a.K;
+    const long tiles256 = (long)(U / 256) * (a.K / 256) * a.B;
+    if (a.K >= 1024 && U >= 1024 && tiles256 >= 2 * 256)
+        return sim_large_launch<T, 4, 2, 2, 4, 4>(a, s);
+    return sim_large_launch<T, 2, 2, 2, 2, 4>(a, s);
+}
+
+bool sim_argmax_uses_large_form(int B, int T, int K) {
+    const int U = T - K;
+    return (long)((U + 127) / 128) * ((K + 127) / 128) * B >= 400;
+}
+
 hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
     // large problems amortise operand traffic with 128 x 128 tiles; small ones need
     // the workgroup count of 64 x 64 tiles and long stages (few memory round-trips)
-    const int U = a.T - a.K;
-    const long tiles128 = (long)((U + 127) / 128) * ((a.K + 127) / 128) * a.B;
-    const bool big = tiles128 >= 400;
-    if (a.is_bf16)
-        return big ? sim_t<bf16_t, 2, 2, 4, 1, 256>(a, s) : sim_t<bf16_t, 1, 1, 8, 2, 512>(a, s);
-    return big ? sim_t<float, 2, 2, 4, 1, 256>(a, s) : sim_t<float, 1, 1, 8, 2, 512>(a, s);
+    if (a.T - a.K <= 0) return hipSuccess;  // nothing was dropped: every token keeps its own slot
+    if (sim_argmax_uses_large_form(a.B, a.T, a.K))
+        return a.is_bf16 ? sim_large_t<bf16_t>(a, s) : sim_large_t<float>(a, s);
+    if (a.is_bf16) return sim_t<bf16_t, 1, 1, 8, 2, 512>(a, s);
+    return sim_t<float, 1, 1, 8, 2, 512>(a, s);
 }
 
 template <typename T>

@@ -402,6 +402,31 @@ def test_llm_dispatch_coverage(name):
     print(name, info, pu.check_llm(shape, inp, ref, _run_llm(shape, inp), name))
 
 
+# The 256 x 256 tile form of the similarity kernel (kept and dropped sets of a thousand rows
+# and more, enough tiles for every CU), in its three tile orders.
+SIM_LARGE = {
+    # one image: every XCD works through its own block of tiles
+    "one-image-xcd-blocks": _enc(batch=1, grid_h=96, grid_w=128, heads=2, head_dim=16, feat_dim=32,
+                                 win_rows=1, win_cols=1, keep_global=4096, keep_local=0),
+    # eight images: pinned to XCDs
+    "eight-images-pinned": _enc(batch=8, grid_h=64, grid_w=80, heads=2, head_dim=16, feat_dim=40,
+                                win_rows=1, win_cols=1, keep_global=1024, keep_local=0),
+    # five kept tiles: not a multiple of the XCD block grid, tiles in launch order; ragged edges
+    "two-images-launch-order": _enc(batch=2, grid_h=114, grid_w=128, heads=2, head_dim=16,
+                                    feat_dim=32, win_rows=1, win_cols=1, keep_global=1270,
+                                    keep_local=0),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SIM_LARGE))
+def test_encoder_similarity_large_tiles(name):
+    shape = SIM_LARGE[name]
+    inp, _, ref, info = pu.screened_encoder_case(shape, seed=8800 + len(name), logit_gain=1.0,
+                                                 max_tries=2)
+    out = _run_encoder(shape, inp)
+    print(name, info, pu.check_encoder(shape, inp, ref, out, name))
+
+
 def test_encoder_many_slots():
     """Enough kept slots in the batch that the merge gives every wave four slots in turn."""
     shape = _enc(batch=32, grid_h=24, grid_w=24, heads=2, feat_dim=72, win_rows=4, win_cols=4,
