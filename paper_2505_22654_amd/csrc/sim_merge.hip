@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) void kept_inv_norm_kernel(const T *__restrict_
 // block of (tiles_m / 4) x (tiles_n / 2) tiles, kept tile fastest - its band of kept rows stays
 // in its L2 and its band of dropped rows streams through once.
 template <typename T, int TM, int TN, int WM, int WN, int KC>
-__global__ __launch_bounds__(64 * WM * WN, WM * WN <= 4 ? 2 : 1) void sim_argmax_large_kernel(
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 1) void sim_argmax_large_kernel(
     const T *__restrict__ x, const int32_t *__restrict__ kept_idx,
     const int32_t *__restrict__ drop_idx, const float *__restrict__ inv_norm,
     unsigned long long *__restrict__ best, int T_img, int D, int K, int U, int B, int mode) {
@@ -416,23 +416,29 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN <= 4 ? 2 : 1) void sim_argmax
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // chunks [c0, c1) of the stage in `cur`
+    // chunks [c0, c1) of the stage in `cur`; the operand fragments of chunk c + 1 are read from
+    // LDS before the matrix instructions of chunk c are issued, so those never wait for LDS
     auto compute = [&](const unsigned char *cur, int c0, int c1) {
         const unsigned char *arow = cur + (wm * 32 * TM + (lane & 31)) * STRIDE + 16 * g;
         const unsigned char *brow = cur + (BM + wn * 32 * TN + (lane & 31)) * STRIDE + 16 * g;
-#pragma unroll
-        for (int c = c0; c < c1; ++c) {
-            uint4 af[TM], bf[TN];
+        uint4 af[2][TM], bf[2][TN];
+        auto read = [&](int c, uint4(&a)[TM], uint4(&bb)[TN]) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const uint4 *>(arow + i * 32 * STRIDE + 32 * c);
+                a[i] = *reinterpret_cast<const uint4 *>(arow + i * 32 * STRIDE + 32 * c);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                bf[j] = *reinterpret_cast<const uint4 *>(brow + j * 32 * STRIDE + 32 * c);
+                bb[j] = *reinterpret_cast<const uint4 *>(brow + j * 32 * STRIDE + 32 * c);
+        };
+        read(c0, af[0], bf[0]);
+#pragma unroll
+        for (int c = c0; c < c1; ++c) {
+            const int cur_set = (c - c0) & 1;
+            if (c + 1 < c1) read(c + 1, af[cur_set ^ 1], bf[cur_set ^ 1]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) mma32_chunk<T>(acc[i][j], af[i], bf[j]);
+                for (int j = 0; j < TN; ++j) mma32_chunk<T>(acc[i][j], af[cur_set][i], bf[cur_set][j]);
         }
     };
 
@@ -506,6 +512,7 @@ __global__ __launch_bounds__(64 * WM * WN, WM * WN <= 4 ? 2 : 1) void sim_argmax
 // Lane l owns the 16-byte pieces l, l+64, ... of the feature row.
 // ---------------------------------------------------------------------------
 constexpr int kMergeListCap = 128;  // ints of LDS per list
+
 constexpr int kMergeAloneCap = 32;  // longest group that one wave adds alone (a few batches of rows)
 constexpr int kMergeMaxSpw = 4;     // slots a wave handles one after the other, at most
 
@@ -516,10 +523,10 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
                                                     int32_t *__restrict__ assign_out, int T_img,
                                                     int D, int K, int B, int affine, int spw) {
     constexpr int E = ElemTraits<T>::kPer16B;
-    // rows fetched together.  Eight keep the kernel within 128 registers for rows of up to 2 KiB,
-    // so that four workgroups fit a compute unit and a launch of several hundred starts at once
-    // (measured: with 16 the third wave of workgroups started 7 us late).
-    constexpr int BATCH = 8;
+    // rows fetched together: about 24 16-byte loads per lane in flight (96 registers), which is
+    // what it takes for the few workgroups that own the large groups to pull rows at the rate
+    // a compute unit can take them
+    constexpr int BATCH = PIECES <= 3 ? 8 : PIECES <= 6 ? 4 : PIECES <= 12 ? 2 : 1;
     __shared__ int cnt[4 * kMergeMaxSpw];
     __shared__ int lists[4 * kMergeMaxSpw][kMergeListCap];
     __shared__ int scratch_lists[4][kMergeListCap];  // per wave, for the scans of phase 3
@@ -573,20 +580,27 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
             int tok[BATCH];
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) tok[j] = list[min(m + j, n - 1)];
+            // every piece of every row of the batch is requested before anything is added.  The
+            // loads carry no condition (a row past the end of the list re-reads the last
+            // member, a piece past the end of the row its last piece): a load inside a branch
+            // makes the compiler wait for all outstanding loads where the branch joins.
+            uint4 raw[BATCH][PIECES];
 #pragma unroll
-            for (int p = 0; p < PIECES; ++p) {
-                const int piece = lane + p * kWave;
-                uint4 raw[BATCH];
+            for (int j = 0; j < BATCH; ++j)
 #pragma unroll
-                for (int j = 0; j < BATCH; ++j)
-                    raw[j] = load16_guard(xb, tok[j] * row_bytes + (int64_t)piece * 16,
-                                          m + j < n && piece < npieces);
+                for (int p = 0; p < PIECES; ++p)
+                    raw[j][p] = load16(xb, tok[j] * row_bytes +
+                                               (int64_t)min(lane + p * kWave, npieces - 1) * 16);
 #pragma unroll
-                for (int j = 0; j < BATCH; ++j) {
-                    float v[E];
-                    unpack16<T>(raw[j], v);
+            for (int j = 0; j < BATCH; ++j) {
+                if (m + j < n) {  // uniform over the wave; rows are added in list order
 #pragma unroll
-                    for (int e = 0; e < E; ++e) acc[p][e] += v[e];
+                    for (int p = 0; p < PIECES; ++p) {
+                        float v[E];
+                        unpack16<T>(raw[j][p], v);
+#pragma unroll
+                        for (int e = 0; e < E; ++e) acc[p][e] += v[e];
+                    }
                 }
             }
         }
