@@ -27,7 +27,7 @@ inline int elem_bytes(int dtype) { return dtype == VSCAN_BF16 ? 2 : 4; }
 
 struct EncoderPlan {
     int N, S, BC, T, W, kw, kg, Kseg, K, U;
-    size_t off_head_global, off_head_local, off_lse, off_drop, off_best, off_inv_norm, bytes;
+    size_t off_head_global, off_head_local, off_lse, off_drop, off_best, off_inv_norm, off_pre_key, off_pre_flag, bytes;
 };
 
 int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
@@ -86,13 +86,17 @@ int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
     off += align_up((size_t)d->batch * p->T * sizeof(uint64_t));
     p->off_inv_norm = off;
     off += align_up((size_t)d->batch * p->K * sizeof(float));
+    p->off_pre_key = off;
+    off += align_up((size_t)p->BC * p->N * sizeof(uint32_t));
+    p->off_pre_flag = off;
+    off += align_up((size_t)p->BC * p->N);
     p->bytes = off ? off : kAlign;
     return VSCAN_OK;
 }
 
 struct LlmPlan {
     int rows, k0, nk, S_out;
-    size_t off_part, bytes;
+    size_t off_part, off_split_e, off_split_stats, bytes;
 };
 
 int plan_llm(const vscan_llm_desc *d, LlmPlan *p) {
@@ -118,8 +122,15 @@ int plan_llm(const vscan_llm_desc *d, LlmPlan *p) {
     if (!llm_score_supported(p->rows, p->nk, d->head_dim * es)) return VSCAN_ERR_UNSUPPORTED;
     if (llm_select_lds_bytes(d->vis_len) > kLdsBudget) return VSCAN_ERR_UNSUPPORTED;
     p->off_part = 0;
-    p->bytes = align_up((size_t)d->batch * d->kv_heads * d->vis_len * sizeof(float));
-    if (!p->bytes) p->bytes = kAlign;
+    size_t off = align_up((size_t)d->batch * d->kv_heads * d->vis_len * sizeof(float));
+    // few items with long key domains are scored chunk by chunk (uniform batches only; the
+    // space is part of the plan whenever the shape qualifies)
+    const int chunks = llm_score_split_chunks(d->batch, d->kv_heads, p->rows, p->nk, false);
+    p->off_split_e = off;
+    if (chunks > 0) off += align_up((size_t)d->batch * d->kv_heads * p->rows * d->vis_len * sizeof(float));
+    p->off_split_stats = off;
+    if (chunks > 0) off += align_up((size_t)d->batch * d->kv_heads * chunks * p->rows * 2 * sizeof(float));
+    p->bytes = off ? off : kAlign;
     return VSCAN_OK;
 }
 
@@ -302,6 +313,8 @@ int enqueue_encoder_tail(const vscan_encoder_desc *d, const EncoderPlan &p, bool
     se.drop_idx = reinterpret_cast<int32_t *>(ws + p.off_drop);
     se.best = reinterpret_cast<uint64_t *>(ws + p.off_best);
     se.scores_out = scores_out;
+    se.pre_key_ws = reinterpret_cast<uint32_t *>(ws + p.off_pre_key);
+    se.pre_flag_ws = reinterpret_cast<uint8_t *>(ws + p.off_pre_flag);
     VSCAN_LAUNCH("encoder_select", launch_encoder_select(se, s));
 
     MergeArgs ma;
@@ -543,6 +556,8 @@ static int run_llm(const vscan_llm_desc *d, const LlmPlan &p, const SeqMeta *met
     sa.is_bf16 = d->dtype == VSCAN_BF16;
     sa.scale = resolve_scale(d->scale, d->head_dim);
     sa.meta = meta;
+    sa.split_e = reinterpret_cast<float *>(ws + p.off_split_e);
+    sa.split_stats = reinterpret_cast<float *>(ws + p.off_split_stats);
     VSCAN_LAUNCH("llm_score", launch_llm_score(sa, s));
 
     LlmSelectArgs se;

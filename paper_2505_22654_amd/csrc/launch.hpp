@@ -32,6 +32,13 @@ struct EncSelectArgs {
     int32_t *drop_idx;         // [B, C*N - K]
     uint64_t *best;            // [B, C*N] packed (similarity key, ~slot)
     float *scores_out;         // optional [B, C*N]
+    // scratch for large segments, where the local scan runs as a kernel of its own:
+    // global-scan keys [BC, N] and local-scan flags [BC, N]
+    uint32_t *pre_key_ws = nullptr;
+    uint8_t *pre_flag_ws = nullptr;
+    // set by the launcher for the second kernel of that form
+    const uint32_t *pre_key = nullptr;
+    const uint8_t *pre_flag = nullptr;
 };
 hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s);
 size_t encoder_select_lds_bytes(int N, int has_local);
@@ -67,8 +74,12 @@ struct LlmScoreArgs {
     int domain_all, is_bf16;
     float scale;
     const SeqMeta *meta = nullptr;
+    // scratch of the form that cuts long key domains into chunks (llm_score_split_chunks > 0):
+    // e [B*Hkv, rows, V] and per-chunk (maximum, sum) pairs [B*Hkv, chunks, rows, 2]
+    float *split_e = nullptr, *split_stats = nullptr;
 };
 hipError_t launch_llm_score(const LlmScoreArgs &a, hipStream_t s);
+int llm_score_split_chunks(int B, int Hkv, int rows, int nk, bool ragged);
 // rows = (Hq/Hkv)*Tq query rows per kv head, nk = keys in the softmax domain
 bool llm_score_supported(int rows, int nk, int row_bytes);
 

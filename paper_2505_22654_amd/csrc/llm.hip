@@ -359,7 +359,179 @@ static hipError_t llm_score_t(const LlmScoreArgs &a, hipStream_t s) {
     return llm_score_launch<T, 8, 4>(a, s);
 }
 
+// ---------------------------------------------------------------------------
+// Few (sequence, kv head) items with long key domains: one workgroup per item would leave most
+// of the chip idle (a 4096-token span under 4 kv heads: 4 workgroups on 256 CUs), so the key
+// domain is cut into chunks of 256 keys, one workgroup each.
+//   llm_score_split_kernel    thread = key: logits of all R query rows against it, then per
+//                             chunk and row the maximum m_c[r], the sum l_c[r] of
+//                             e = 2^(z - m_c[r]), and e itself for the visual columns
+//   llm_score_combine_kernel  M_r = max_c m_c[r], L_r = sum_c l_c[r] 2^(m_c[r] - M_r) in chunk
+//                             order, part[j] = sum_r e[r][j] 2^(m_c(j)[r] - M_r) / L_r in row
+//                             order: fixed orders throughout, no atomics
+// ---------------------------------------------------------------------------
+constexpr int kSplitChunk = 256;
+
+template <typename T, int RB>
+__global__ __launch_bounds__(256) void llm_score_split_kernel(
+    const T *__restrict__ q, const T *__restrict__ k, float *__restrict__ e_out,
+    float *__restrict__ stats, int Hkv, int R, int Tq, int S, int dh, int vis_start, int V, int k0,
+    int nk, float sl2) {
+    constexpr int E = ElemTraits<T>::kPer16B;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *qs = reinterpret_cast<float *>(smem);   // [R][dh]
+    float *red = qs + RB * dh;                      // [RB][4]: per-wave partial results
+    const int item = blockIdx.y, chunk = blockIdx.x, nchunks = gridDim.x;
+    const int tid = threadIdx.x;
+    const T *qrow = q + (int64_t)item * R * dh;     // the item's query rows are contiguous
+    for (int i = tid; i < R * dh; i += 256) qs[i] = load_elem<T>(qrow + i);
+    for (int i = R * dh + tid; i < RB * dh; i += 256) qs[i] = 0.f;
+    __syncthreads();
+
+    const int kk = chunk * kSplitChunk + tid;       // key inside the domain
+    const unsigned char *krow = reinterpret_cast<const unsigned char *>(
+        k + ((int64_t)item * S + k0 + min(kk, nk - 1)) * dh);   // clamped: always readable
+    float acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
+    const int npieces = dh / E;
+    // sixteen 16-byte pieces of the key row at a time (a 128-element bf16 row in one round trip)
+    constexpr int PB = 16;
+    for (int p0 = 0; p0 < npieces; p0 += PB) {
+        uint4 raw[PB];
+#pragma unroll
+        for (int u = 0; u < PB; ++u) raw[u] = load16_stream(krow, (int64_t)min(p0 + u, npieces - 1) * 16);
+#pragma unroll
+        for (int u = 0; u < PB; ++u) {
+            if (p0 + u < npieces) {  // uniform
+                float v[E];
+                unpack16<T>(raw[u], v);
+#pragma unroll
+                for (int r = 0; r < RB; ++r) {
+                    const float *qr = qs + r * dh + (p0 + u) * E;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[r] = fmaf(v[e], qr[e], acc[r]);
+                }
+            }
+        }
+    }
+    // masking: keys past the domain, and for a causal row the keys behind its query
+    float z[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        const int last_pos = S - Tq + (r < R ? r % Tq : 0);
+        z[r] = (r < R && kk < nk && k0 + kk <= last_pos) ? acc[r] * sl2 : -INFINITY;
+    }
+    // per row: maximum over the chunk, then e and its sum
+    const int lane = lane_id(), w = wave_id();
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        const float m = wave_max(z[r]);
+        if (lane == 0) red[r * 4 + w] = m;
+    }
+    __syncthreads();
+    float mrow[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+        mrow[r] = fmaxf(fmaxf(red[r * 4], red[r * 4 + 1]), fmaxf(red[r * 4 + 2], red[r * 4 + 3]));
+    __syncthreads();
+    const int col = k0 + kk - vis_start;            // visual column of this key
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        const float e = mrow[r] > -INFINITY ? __builtin_amdgcn_exp2f(z[r] - mrow[r]) : 0.f;
+        if (r < R && kk < nk && col >= 0 && col < V) e_out[((int64_t)item * R + r) * V + col] = e;
+        const float sum = wave_sum(e);
+        if (lane == 0) red[r * 4 + w] = sum;
+    }
+    __syncthreads();
+    if (tid < R) {
+        float m = -INFINITY;  // mrow[tid] without indexing registers by a run-time value
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+            if (r == tid) m = mrow[r];
+        float *st = stats + (((int64_t)item * nchunks + chunk) * R + tid) * 2;
+        st[0] = m;
+        st[1] = (red[tid * 4] + red[tid * 4 + 1]) + (red[tid * 4 + 2] + red[tid * 4 + 3]);
+    }
+}
+
+__global__ __launch_bounds__(256) void llm_score_combine_kernel(const float *__restrict__ e_in,
+                                                               const float *__restrict__ stats,
+                                                               float *__restrict__ part, int R,
+                                                               int V, int vis_start, int k0,
+                                                               int nchunks) {
+    extern __shared__ float wgt[];                  // [nchunks][R], then M[R], invL[R], then the pairs
+    float *M = wgt + nchunks * R, *invL = M + R, *st = invL + R;
+    const int item = blockIdx.y, tid = threadIdx.x;
+    // all (maximum, sum) pairs of the item into LDS at once: the row loops below would
+    // otherwise be chains of dependent global loads
+    for (int i = tid; i < nchunks * R * 2; i += 256) st[i] = stats[(int64_t)item * nchunks * R * 2 + i];
+    __syncthreads();
+    if (tid < R) {
+        float m = -INFINITY;
+        for (int c = 0; c < nchunks; ++c) m = fmaxf(m, st[(c * R + tid) * 2]);
+        float l = 0.f;
+        for (int c = 0; c < nchunks; ++c) {
+            const float mc = st[(c * R + tid) * 2];
+            if (mc > -INFINITY) l += st[(c * R + tid) * 2 + 1] * __builtin_amdgcn_exp2f(mc - m);
+        }
+        M[tid] = m;
+        invL[tid] = 1.0f / l;
+    }
+    __syncthreads();
+    for (int i = tid; i < nchunks * R; i += 256) {
+        const int r = i % R;
+        const float mc = st[i * 2];
+        wgt[i] = mc > -INFINITY ? __builtin_amdgcn_exp2f(mc - M[r]) * invL[r] : 0.f;
+    }
+    __syncthreads();
+    const int col = blockIdx.x * 256 + tid;
+    if (col >= V) return;
+    const int c = (vis_start + col - k0) / kSplitChunk;
+    float sum = 0.f;
+    for (int r = 0; r < R; ++r) sum += e_in[((int64_t)item * R + r) * V + col] * wgt[c * R + r];
+    part[(int64_t)item * V + col] = sum;
+}
+
+// chunks the key domain is cut into, 0 when the one-workgroup-per-item kernel is the better fit
+int llm_score_split_chunks(int B, int Hkv, int rows, int nk, bool ragged) {
+    if (ragged || rows > 16 || nk < 4 * kSplitChunk || (int64_t)B * Hkv > kCus / 4) return 0;
+    return (nk + kSplitChunk - 1) / kSplitChunk;
+}
+
+template <typename T>
+static hipError_t llm_score_split_t(const LlmScoreArgs &a, hipStream_t s, int nchunks) {
+    const int R = (a.Hq / a.Hkv) * a.Tq, items = a.B * a.Hkv;
+    const int k0 = a.domain_all ? 0 : a.vis_start, nk = a.domain_all ? a.S : a.V;
+    const float sl2 = a.scale * 1.4426950408889634f;
+    dim3 grid(nchunks, items);
+    if (R <= 8) {
+        const size_t smem = (size_t)(8 * a.dh + 8 * 4) * sizeof(float);
+        hipLaunchKernelGGL((llm_score_split_kernel<T, 8>), grid, dim3(256), smem, s, (const T *)a.q,
+                           (const T *)a.k, a.split_e, a.split_stats, a.Hkv, R, a.Tq, a.S, a.dh,
+                           a.vis_start, a.V, k0, nk, sl2);
+    } else {
+        const size_t smem = (size_t)(16 * a.dh + 16 * 4) * sizeof(float);
+        hipLaunchKernelGGL((llm_score_split_kernel<T, 16>), grid, dim3(256), smem, s, (const T *)a.q,
+                           (const T *)a.k, a.split_e, a.split_stats, a.Hkv, R, a.Tq, a.S, a.dh,
+                           a.vis_start, a.V, k0, nk, sl2);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t smem2 = (size_t)(3 * nchunks * R + 2 * R) * sizeof(float);
+    hipLaunchKernelGGL(llm_score_combine_kernel, dim3((a.V + 255) / 256, items), dim3(256), smem2, s,
+                       (const float *)a.split_e, (const float *)a.split_stats, a.part, R, a.V,
+                       a.vis_start, k0, nchunks);
+    return hipGetLastError();
+}
+
 hipError_t launch_llm_score(const LlmScoreArgs &a, hipStream_t s) {
+    const int rows = (a.Hq / a.Hkv) * a.Tq;
+    const int nchunks = llm_score_split_chunks(a.B, a.Hkv, rows, a.domain_all ? a.S : a.V,
+                                               a.meta != nullptr);
+    if (nchunks > 0 && a.split_e && a.split_stats)
+        return a.is_bf16 ? llm_score_split_t<bf16_t>(a, s, nchunks)
+                         : llm_score_split_t<float>(a, s, nchunks);
     return a.is_bf16 ? llm_score_t<bf16_t>(a, s) : llm_score_t<float>(a, s);
 }
 

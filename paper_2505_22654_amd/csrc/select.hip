@@ -59,6 +59,38 @@ __device__ __forceinline__ int block_excl_count(bool pred, int *wsum, int &total
     return base + pos;
 }
 
+// Rank of every flagged token among the flagged ones, for all rounds of a block-strided walk at
+// once (token j = round * blockDim + thread): per round and wave the flagged count goes to LDS,
+// one barrier, then every thread adds up the counts in front of it.  Two barriers in all where a
+// walk with one prefix count per round takes two per round.  `cnts`: LDS, rounds * waves ints,
+// free for this use.  emit(j, flagged, rank) is called for every j < n in ascending rounds.
+template <typename Emit>
+__device__ __forceinline__ void ranked_walk(const uint8_t *flag, int n, int *cnts, Emit emit) {
+    const int tid = threadIdx.x, nt = blockDim.x, nw = nt / kWave, w = wave_id();
+    const int rounds = (n + nt - 1) / nt;
+    for (int r = 0; r < rounds; ++r) {
+        const int j = r * nt + tid;
+        const uint64_t m = __ballot(j < n && flag[j] != 0);
+        if (lane_id() == 0) cnts[r * nw + w] = __popcll(m);
+    }
+    __syncthreads();
+    int run = 0;
+    for (int r = 0; r < rounds; ++r) {
+        int before = 0, tot = 0;
+        for (int i = 0; i < nw; ++i) {
+            const int c = cnts[r * nw + i];
+            before += i < w ? c : 0;
+            tot += c;
+        }
+        const int j = r * nt + tid;
+        const bool f = j < n && flag[j] != 0;
+        const uint64_t m = __ballot(f);
+        if (j < n) emit(j, f, run + before + __popcll(m & lanemask_lt()));
+        run += tot;
+    }
+    __syncthreads();
+}
+
 __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ---------------------------------------------------------------------------
@@ -297,20 +329,43 @@ __global__ __launch_bounds__(1024) void encoder_select_kernel(EncSelectArgs a, i
     const int tid = threadIdx.x, nt = blockDim.x;
     const int T_img = a.C * N;
 
-    for (int j = tid; j < N; j += nt) {
-        const float sg = head_sum(a.head_global + (int64_t)bc * a.H * N + j, a.H, N) * a.norm;
-        keyg[j] = float_to_key(sg);
-        if (a.scores_out) a.scores_out[(int64_t)b * T_img + (int64_t)c * N + j] = sg;
-        if (a.head_local)
-            keyl[j] = float_to_key(head_sum(a.head_local + (int64_t)bc * a.H * N + j, a.H, N) *
-                                   a.norm);
-        flag[j] = 0;
+    if (a.pre_key) {
+        // large segment: head sums, keys and the local scan were done window by window by
+        // encoder_select_local_kernel; what is left is the global scan and the lists
+        // every thread's values requested at once (clamped positions): a loop of one load per
+        // trip would be a chain of memory round-trips
+        uint32_t kreg[NREG_G];
+        uint8_t freg[NREG_G];
+#pragma unroll
+        for (int r = 0; r < NREG_G; ++r) {
+            const int64_t j = (int64_t)bc * N + min(r * nt + tid, N - 1);
+            kreg[r] = a.pre_key[j];
+            freg[r] = a.pre_flag[j];
+        }
+#pragma unroll
+        for (int r = 0; r < NREG_G; ++r) {
+            const int j = r * nt + tid;
+            if (j < N) {
+                keyg[j] = kreg[r];
+                flag[j] = freg[r];
+            }
+        }
+    } else {
+        for (int j = tid; j < N; j += nt) {
+            const float sg = head_sum(a.head_global + (int64_t)bc * a.H * N + j, a.H, N) * a.norm;
+            keyg[j] = float_to_key(sg);
+            if (a.scores_out) a.scores_out[(int64_t)b * T_img + (int64_t)c * N + j] = sg;
+            if (a.head_local)
+                keyl[j] = float_to_key(head_sum(a.head_local + (int64_t)bc * a.H * N + j, a.H, N) *
+                                       a.norm);
+            flag[j] = 0;
+        }
     }
     __syncthreads();
 
     // ---- local scan (Eq. 3) ----
     const int nW = a.wr * a.wc;
-    if (a.kw > 0) {
+    if (a.kw > 0 && !a.pre_key) {
         if (WIN_MODE == 3) {
             // LDS behind the flags: the window-major keys (`win_pitch` slots per window, unused
             // slots zero: no real key is zero), then per grid row and per grid column the window
@@ -421,25 +476,73 @@ __global__ __launch_bounds__(1024) void encoder_select_kernel(EncSelectArgs a, i
     // ---- ascending kept / dropped lists; seed the assignment words ----
     const int Kseg = nW * a.kw + a.kg;
     const int K = a.C * Kseg, U = T_img - K;
-    int run = 0;
-    for (int base = 0; base < N; base += nt) {
-        const int j = base + tid;
-        const bool kept = j < N && flag[j] != 0;
-        int tot;
-        const int slot = run + block_excl_count(kept, sm.wsum, tot);
-        if (j < N) {
-            const int tok = c * N + j;
-            if (kept) {
-                const int s = c * Kseg + slot;
-                a.kept_idx[(int64_t)b * K + s] = tok;
-                a.best[(int64_t)b * T_img + tok] = (0xffffffffull << 32) | (uint32_t)~(uint32_t)s;
-            } else {
-                a.drop_idx[(int64_t)b * U + (int64_t)c * (N - Kseg) + (j - slot)] = tok;
-                a.best[(int64_t)b * T_img + tok] = 0ull;
-            }
+    // (the keys are no longer needed: their LDS holds the per-round counts of the walk)
+    __syncthreads();
+    ranked_walk(flag, N, reinterpret_cast<int *>(keyg), [&](int j, bool kept, int slot) {
+        const int tok = c * N + j;
+        if (kept) {
+            const int s = c * Kseg + slot;
+            a.kept_idx[(int64_t)b * K + s] = tok;
+            a.best[(int64_t)b * T_img + tok] = (0xffffffffull << 32) | (uint32_t)~(uint32_t)s;
+        } else {
+            a.drop_idx[(int64_t)b * U + (int64_t)c * (N - Kseg) + (j - slot)] = tok;
+            a.best[(int64_t)b * T_img + tok] = 0ull;
         }
-        run += tot;
+    });
+}
+
+// Large segments, first half: one workgroup per window (or per 1024 tokens when there is no local
+// scan).  A single workgroup that walks a 16384-token segment spends most of its time fetching
+// H values per token at the rate one compute unit can take them; here every window's tokens are
+// summed over the heads, turned into keys and ranked inside the window (by counting: window
+// slots in row-major order are ascending token indices, which is what ties are broken by) by a
+// workgroup of its own.  Outputs: the global-scan key and the local-scan flag of every token.
+__global__ __launch_bounds__(1024) void encoder_select_local_kernel(EncSelectArgs a,
+                                                                   uint32_t *__restrict__ key_out,
+                                                                   uint8_t *__restrict__ flag_out) {
+    __shared__ __align__(16) uint32_t wk[1024];
+    const int N = a.gh * a.gw, T_img = a.C * N;
+    const int bc = blockIdx.y, b = bc / a.C, c = bc - b * a.C;
+    const int tid = threadIdx.x;
+    int j = -1, slots = 0;
+    if (a.kw > 0) {
+        const WindowGeom g = window_geom(a, blockIdx.x);
+        slots = g.wh * g.ww;
+        if (tid < slots) {
+            const int rr = tid / g.ww, cc = tid - rr * g.ww;
+            j = (g.r0 + rr) * a.gw + g.c0 + cc;
+        }
+    } else if (blockIdx.x * 1024 + tid < N) {
+        j = blockIdx.x * 1024 + tid;
     }
+    uint32_t kl = 0u;
+    if (j >= 0) {
+        const float sg = head_sum(a.head_global + (int64_t)bc * a.H * N + j, a.H, N) * a.norm;
+        const uint32_t kg = float_to_key(sg);
+        key_out[(int64_t)bc * N + j] = kg;
+        if (a.scores_out) a.scores_out[(int64_t)b * T_img + (int64_t)c * N + j] = sg;
+        kl = a.head_local
+                 ? float_to_key(head_sum(a.head_local + (int64_t)bc * a.H * N + j, a.H, N) * a.norm)
+                 : kg;
+    }
+    if (a.kw <= 0) {
+        if (j >= 0) flag_out[(int64_t)bc * N + j] = 0;
+        return;
+    }
+    wk[tid] = kl;  // threads past the window hold key 0, below every real key
+    __syncthreads();
+    if (j < 0) return;
+    int cnt = 0;
+    const uint4 *row = reinterpret_cast<const uint4 *>(wk);
+    for (int i = 0; i < (slots + 3) / 4; ++i) {
+        const uint4 k4 = row[i];
+        const int s0 = 4 * i;
+        cnt += (k4.x > kl) || (k4.x == kl && s0 < tid);
+        cnt += (k4.y > kl) || (k4.y == kl && s0 + 1 < tid);
+        cnt += (k4.z > kl) || (k4.z == kl && s0 + 2 < tid);
+        cnt += (k4.w > kl) || (k4.w == kl && s0 + 3 < tid);
+    }
+    flag_out[(int64_t)bc * N + j] = cnt < a.kw ? 1 : 0;
 }
 
 // Stage-2 selection, one workgroup per sequence.
@@ -453,11 +556,43 @@ __global__ __launch_bounds__(1024) void llm_select_kernel(LlmSelectArgs a) {
     // ragged batch: this sequence's own span and budget; a.V and a.keep stay the strides
     const int V = a.meta ? a.meta[b].vis_len : a.V;
     const int keep = a.meta ? a.meta[b].keep : a.keep;
-    for (int j = tid; j < V; j += nt) {
-        const float s = head_sum(a.part + (int64_t)b * a.Hkv * a.V + j, a.Hkv, a.V) * a.norm;
-        key[j] = float_to_key(s);
-        flag[j] = 0;
-        if (a.scores_out) a.scores_out[(int64_t)b * a.V + j] = s;
+    if (GLOBAL_WAVE) {
+        for (int j = tid; j < V; j += nt) {  // one token per thread
+            const float s = head_sum(a.part + (int64_t)b * a.Hkv * a.V + j, a.Hkv, a.V) * a.norm;
+            key[j] = float_to_key(s);
+            flag[j] = 0;
+            if (a.scores_out) a.scores_out[(int64_t)b * a.V + j] = s;
+        }
+    } else {
+        // several tokens per thread: the head values of all of them are requested together,
+        // a few heads at a time (clamped positions), and added in head order as head_sum does
+        constexpr int HB = NREG <= 4 ? 8 : NREG <= 16 ? 2 : 1;
+        float acc[NREG];
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) acc[r] = 0.f;
+        const float *pb = a.part + (int64_t)b * a.Hkv * a.V;
+        for (int h0 = 0; h0 < a.Hkv; h0 += HB) {
+            float v[NREG][HB];
+#pragma unroll
+            for (int r = 0; r < NREG; ++r)
+#pragma unroll
+                for (int u = 0; u < HB; ++u)
+                    v[r][u] = pb[(int64_t)min(h0 + u, a.Hkv - 1) * a.V + min(r * nt + tid, V - 1)];
+#pragma unroll
+            for (int r = 0; r < NREG; ++r)
+#pragma unroll
+                for (int u = 0; u < HB; ++u) acc[r] += h0 + u < a.Hkv ? v[r][u] : 0.f;
+        }
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) {
+            const int j = r * nt + tid;
+            if (j < V) {
+                const float s = acc[r] * a.norm;
+                key[j] = float_to_key(s);
+                flag[j] = 0;
+                if (a.scores_out) a.scores_out[(int64_t)b * a.V + j] = s;
+            }
+        }
     }
     if (a.meta)
         for (int i = keep + tid; i < a.keep; i += nt) a.kept_idx[(int64_t)b * a.keep + i] = -1;
@@ -472,15 +607,10 @@ __global__ __launch_bounds__(1024) void llm_select_kernel(LlmSelectArgs a) {
     } else {
         block_topk_regs<NREG>(slot, V, keep, flag, 1, sm);
     }
-    int run = 0;
-    for (int base = 0; base < V; base += nt) {
-        const int j = base + tid;
-        const bool kept = j < V && flag[j] != 0;
-        int tot;
-        const int s = run + block_excl_count(kept, sm.wsum, tot);
+    __syncthreads();  // the keys are no longer needed: their LDS holds the counts of the walk
+    ranked_walk(flag, V, reinterpret_cast<int *>(key), [&](int j, bool kept, int s) {
         if (kept) a.kept_idx[(int64_t)b * a.keep + s] = j;
-        run += tot;
-    }
+    });
 }
 
 // ---------------------------------------------------------------------------
@@ -541,6 +671,23 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
     }
     const int threads = 1024;  // large segment: block-wide global scan, ceil(N/1024) registers
     const int nreg = (N + threads - 1) / threads;
+    const int max_window = ((a.gh + a.wr - 1) / a.wr) * ((a.gw + a.wc - 1) / a.wc);
+    if (N > 4096 && a.pre_key_ws && a.pre_flag_ws && (a.kw <= 0 || max_window <= 1024)) {
+        // windows (and head sums) by a workgroup each, then the global scan by one per segment
+        const int wthreads = a.kw > 0 ? (max_window + kWave - 1) / kWave * kWave : 1024;
+        dim3 grid(a.kw > 0 ? a.wr * a.wc : (N + 1023) / 1024, blocks);
+        hipLaunchKernelGGL(encoder_select_local_kernel, grid, dim3(wthreads), 0, s, a, a.pre_key_ws,
+                           a.pre_flag_ws);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        EncSelectArgs g = a;
+        g.pre_key = a.pre_key_ws;
+        g.pre_flag = a.pre_flag_ws;
+        g.scores_out = nullptr;  // written by the first kernel
+        if (nreg <= 4) return launch_select(encoder_select_kernel<2, 1, false, 4>, blocks, threads, smem, s, g, 0);
+        if (nreg <= 16) return launch_select(encoder_select_kernel<2, 1, false, 16>, blocks, threads, smem, s, g, 0);
+        return launch_select(encoder_select_kernel<2, 1, false, 32>, blocks, threads, smem, s, g, 0);
+    }
     if (win_slots * nreg <= 128) {
         if (nreg <= 4) VSCAN_SEL(0, 1, false, 4);
         if (nreg <= 16) VSCAN_SEL(0, 1, false, 16);

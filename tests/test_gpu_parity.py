@@ -386,9 +386,17 @@ DISPATCH_LLM = {
     # select: 16 candidates per thread
     "span-8000": _llm(batch=2, vis_len=8000, text=6, q_heads=1, kv_heads=1, head_dim=16,
                       hidden=16, keep=90),
-    # scoring: logits of 8 rows x 4500 keys leave no LDS for the staging areas
-    "unstaged-8x4500": _llm(batch=2, vis_len=4500, text=4, q_heads=8, kv_heads=1, head_dim=128,
-                            hidden=16, keep=50),
+    # scoring: few items with a long span are cut into chunks of 256 keys (ragged last chunk)
+    "split-8x4500": _llm(batch=2, vis_len=4500, text=4, q_heads=8, kv_heads=1, head_dim=128,
+                         hidden=16, keep=50),
+    # ... also over the causal domain of several query positions, 12 query rows per kv head
+    "split-causal-12x1500": _llm(batch=3, prefix=7, vis_len=1500, text=9, q_heads=8, kv_heads=2,
+                                 n_query=3, head_dim=40, hidden=16, keep=400, softmax_domain=1),
+    "f32-split-1x3000": _llm(wl.F32, batch=1, vis_len=3000, text=3, q_heads=2, kv_heads=2,
+                             head_dim=24, hidden=16, keep=77),
+    # scoring: logits of 17 rows x 2100 keys leave no LDS for the staging areas
+    "unstaged-17x2100": _llm(batch=2, vis_len=2100, text=4, q_heads=17, kv_heads=1, head_dim=128,
+                             hidden=16, keep=50),
     # scoring: 512-byte key rows with more than 16 query rows
     "f32-wide-many-rows": _llm(wl.F32, batch=2, vis_len=300, text=8, q_heads=8, kv_heads=2,
                                head_dim=128, hidden=16, keep=40, n_query=5),
