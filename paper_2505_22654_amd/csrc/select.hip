@@ -35,9 +35,18 @@ __device__ __forceinline__ float head_sum(const float *p, int heads, int stride)
     return s;
 }
 
+// Sum over the first sixteen lanes of a wave (one DPP row); every lane gets it.
+__device__ __forceinline__ int row0_sum_dpp(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true);  // row_half_mirror
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true);  // row_mirror
+    return __builtin_amdgcn_readlane(v, 0);
+}
+
 struct SelectSmem {
     int wsum[16];
-    int cnt[2][16][4];  // per-wave candidate counts of the block-wide search, double-buffered
+    alignas(16) int cnt[2][16][4];  // per-wave candidate counts of the block-wide search, double-buffered
 };
 
 // Exclusive prefix count of `pred` over the block in thread order; `total` gets
@@ -59,34 +68,31 @@ __device__ __forceinline__ int block_excl_count(bool pred, int *wsum, int &total
     return base + pos;
 }
 
-// Rank of every flagged token among the flagged ones, for all rounds of a block-strided walk at
-// once (token j = round * blockDim + thread): per round and wave the flagged count goes to LDS,
-// one barrier, then every thread adds up the counts in front of it.  Two barriers in all where a
-// walk with one prefix count per round takes two per round.  `cnts`: LDS, rounds * waves ints,
-// free for this use.  emit(j, flagged, rank) is called for every j < n in ascending rounds.
+// Rank of every flagged token among the flagged ones.  Each wave owns one contiguous run of
+// tokens and walks it 64 at a time (consecutive lanes, consecutive tokens: byte reads of the flags
+// without bank conflicts, coalesced writes in `emit`).  A first pass counts the wave's flagged
+// tokens (ballot population counts, on the scalar unit), the totals cross LDS once, and the
+// second pass hands out ranks: two barriers in all, whatever the length.  `cnts`: LDS, one int
+// per wave, free for this use.  emit(j, flagged, rank) is called once for every j < n.
 template <typename Emit>
 __device__ __forceinline__ void ranked_walk(const uint8_t *flag, int n, int *cnts, Emit emit) {
-    const int tid = threadIdx.x, nt = blockDim.x, nw = nt / kWave, w = wave_id();
-    const int rounds = (n + nt - 1) / nt;
+    const int nw = blockDim.x / kWave, w = wave_id(), lane = lane_id();
+    const int rounds = (n + nw * kWave - 1) / (nw * kWave);  // per wave
+    const int first = w * rounds * kWave;
+    int total = 0;
     for (int r = 0; r < rounds; ++r) {
-        const int j = r * nt + tid;
-        const uint64_t m = __ballot(j < n && flag[j] != 0);
-        if (lane_id() == 0) cnts[r * nw + w] = __popcll(m);
+        const int j = first + r * kWave + lane;
+        total += __popcll(__ballot(j < n && flag[j] != 0));
     }
+    if (lane == 0) cnts[w] = total;
     __syncthreads();
-    int run = 0;
+    int run = row0_sum_dpp(lane < w ? cnts[lane] : 0);  // at most 16 waves
     for (int r = 0; r < rounds; ++r) {
-        int before = 0, tot = 0;
-        for (int i = 0; i < nw; ++i) {
-            const int c = cnts[r * nw + i];
-            before += i < w ? c : 0;
-            tot += c;
-        }
-        const int j = r * nt + tid;
+        const int j = first + r * kWave + lane;
         const bool f = j < n && flag[j] != 0;
         const uint64_t m = __ballot(f);
-        if (j < n) emit(j, f, run + before + __popcll(m & lanemask_lt()));
-        run += tot;
+        if (j < n) emit(j, f, run + __popcll(m & lanemask_lt()));
+        run += __popcll(m);
     }
     __syncthreads();
 }
@@ -195,21 +201,17 @@ __device__ __forceinline__ void block_topk_regs(SlotFn slot_fn, int nslots, int 
         const int sl = r * nt + tid;
         if (sl < nslots) key[r] = slot_fn(sl, idx[r]);
     }
+    // a, b, c: this wave's counts, already the same in every lane (ballot population counts,
+    // which the scalar unit adds up beside the vector compares).  One lane posts them; after the
+    // barrier lane i reads wave i's row in one access and a DPP sum over the wave adds the rows.
     auto exchange = [&](int buf, int a, int b, int c, int &ta, int &tb, int &tc) {
-        const int packed = wave_sum_dpp(a | (b << 16));  // per-wave counts are <= 64*NREG
-        const int sc = wave_sum_dpp(c);
-        if (lane_id() == 0) {
-            sm.cnt[buf][w][0] = packed & 0xffff;
-            sm.cnt[buf][w][1] = packed >> 16;
-            sm.cnt[buf][w][2] = sc;
-        }
+        if (lane_id() == 0) *reinterpret_cast<int4 *>(sm.cnt[buf][w]) = make_int4(a, b, c, 0);
         __syncthreads();
-        ta = tb = tc = 0;
-        for (int i = 0; i < nw; ++i) {
-            ta += sm.cnt[buf][i][0];
-            tb += sm.cnt[buf][i][1];
-            tc += sm.cnt[buf][i][2];
-        }
+        int4 row = make_int4(0, 0, 0, 0);
+        if (lane_id() < nw) row = *reinterpret_cast<const int4 *>(sm.cnt[buf][lane_id()]);
+        ta = row0_sum_dpp(row.x);
+        tb = row0_sum_dpp(row.y);
+        tc = row0_sum_dpp(row.z);
     };
     // As in the wave-level search: start at the highest bit in which the largest and the
     // smallest candidate differ (one exchange of per-wave maxima through LDS).
@@ -243,9 +245,9 @@ __device__ __forceinline__ void block_topk_regs(SlotFn slot_fn, int nslots, int 
         int n1 = 0, n2 = 0, n3 = 0;
 #pragma unroll
         for (int r = 0; r < NREG; ++r) {
-            n1 += key[r] >= c1;
-            n2 += key[r] >= c2;
-            n3 += key[r] >= c3;
+            n1 += __popcll(__ballot(key[r] >= c1));
+            n2 += __popcll(__ballot(key[r] >= c2));
+            n3 += __popcll(__ballot(key[r] >= c3));
         }
         int t1, t2, t3;
         exchange(buf, n1, n2, n3, t1, t2, t3);
@@ -264,8 +266,8 @@ __device__ __forceinline__ void block_topk_regs(SlotFn slot_fn, int nslots, int 
     int c_gt = 0, c_eq = 0;
 #pragma unroll
     for (int r = 0; r < NREG; ++r) {
-        c_gt += key[r] > T;
-        c_eq += key[r] == T;
+        c_gt += __popcll(__ballot(key[r] > T));
+        c_eq += __popcll(__ballot(key[r] == T));
     }
     int t_gt, t_eq, unused;
     exchange(buf, c_gt, 0, c_eq, t_gt, unused, t_eq);
