@@ -20,8 +20,12 @@
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream) and the call returns without synchronising.  Calls that
  *     share a workspace must be ordered on one stream.
- *   - Return value: VSCAN_OK or a negative error.  On error nothing is enqueued
- *     and no output is touched.  No exceptions, no abort.
+ *   - Return value: VSCAN_OK or a negative error.  No exceptions, no abort.
+ *     Every argument, shape, budget, alignment and workspace check is made on
+ *     the host before the first launch: with any error other than
+ *     VSCAN_ERR_HIP nothing has been enqueued and no output is touched.
+ *     VSCAN_ERR_HIP reports a launch the runtime refused; kernels enqueued
+ *     before it still run, and the outputs are then unspecified.
  *   - Ties are broken towards the lowest index; index outputs are ascending.
  *   - Floating-point inputs must be finite (NaN ordering is unspecified).
  */
@@ -75,7 +79,7 @@ typedef struct {
     int32_t has_cls;        /* 1: q/k have S = N + 1 rows and [CLS] is row 0 */
     int32_t score_mode;     /* VSCAN_SCORE_* */
     int32_t softmax_domain; /* VSCAN_KEYS_* */
-    int32_t heads;          /* H */
+    int32_t heads;          /* H, 1 .. 1024 */
     int32_t head_dim;       /* dh, multiple of 8, <= 256 */
     int32_t feat_dim;       /* D of x, multiple of 8 */
     int32_t win_rows, win_cols; /* windows per segment along each axis (Eq. 3):
@@ -124,7 +128,7 @@ typedef struct {
     int32_t vis_len;        /* V visual tokens, contiguous */
     int32_t n_query;        /* Tq scoring queries = the last Tq positions; the paper
                                uses the last instruction token only (Tq = 1) */
-    int32_t q_heads;        /* Hq */
+    int32_t q_heads;        /* Hq, 1 .. 1024 */
     int32_t kv_heads;       /* Hkv, divides Hq; query head h reads kv head h/(Hq/Hkv) */
     int32_t head_dim;       /* dh, multiple of 8, <= 256 */
     int32_t hidden;         /* Dh, multiple of 8 */

@@ -7,6 +7,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -60,6 +61,9 @@ int plan_encoder(const vscan_encoder_desc *d, int with_local, EncoderPlan *p) {
     if (p->kw > min_window) return VSCAN_ERR_BUDGET;
     if ((int64_t)d->batch * d->n_segments > (1 << 24)) return VSCAN_ERR_SHAPE;
     if ((int64_t)d->n_segments * p->N > (1 << 24)) return VSCAN_ERR_SHAPE;
+    // (segment, head) pairs index launch grids and 32-bit item counters
+    if (d->heads > 1024 || (int64_t)d->batch * d->n_segments * d->heads > (1 << 24))
+        return VSCAN_ERR_SHAPE;
     p->BC = d->batch * d->n_segments;
     p->T = d->n_segments * p->N;
     p->K = d->n_segments * p->Kseg;
@@ -109,6 +113,7 @@ int plan_llm(const vscan_llm_desc *d, LlmPlan *p) {
         return VSCAN_ERR_SHAPE;
     if ((int64_t)d->vis_start + d->vis_len + d->n_query > d->seq_len) return VSCAN_ERR_SHAPE;
     if (d->q_heads < 1 || d->kv_heads < 1 || d->q_heads % d->kv_heads) return VSCAN_ERR_SHAPE;
+    if (d->q_heads > 1024) return VSCAN_ERR_SHAPE;
     if (d->head_dim < 8 || d->head_dim % 8 || d->head_dim > 256) return VSCAN_ERR_SHAPE;
     if (d->hidden < 8 || d->hidden % 8) return VSCAN_ERR_SHAPE;
     if (d->in_place != 0 && d->in_place != 1) return VSCAN_ERR_SHAPE;
@@ -182,6 +187,7 @@ int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
         return VSCAN_ERR_SHAPE;
     if ((int64_t)d->vis_start + d->vis_len + d->n_query > d->seq_len) return VSCAN_ERR_SHAPE;
     if (d->q_heads < 1 || d->kv_heads < 1 || d->q_heads % d->kv_heads) return VSCAN_ERR_SHAPE;
+    if (d->q_heads > 1024) return VSCAN_ERR_SHAPE;
     if (d->head_dim < 8 || d->head_dim % 8 || d->head_dim > 256) return VSCAN_ERR_SHAPE;
     if (d->hidden < 8 || d->hidden % 8) return VSCAN_ERR_SHAPE;
     if (d->in_place != 0 && d->in_place != 1) return VSCAN_ERR_SHAPE;
@@ -238,14 +244,14 @@ struct ProfRecord {
 };
 std::mutex g_prof_mutex;
 std::vector<ProfRecord> g_prof_records;
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};  // read by every launch, on any thread
 
 struct ProfScope {
     const char *name;
     hipStream_t stream;
     hipEvent_t start = nullptr, stop = nullptr;
     bool on;
-    ProfScope(const char *n, hipStream_t s) : name(n), stream(s), on(g_prof_on) {
+    ProfScope(const char *n, hipStream_t s) : name(n), stream(s), on(g_prof_on.load(std::memory_order_relaxed)) {
         if (!on) return;
         if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess ||
             hipEventRecord(start, stream) != hipSuccess)
@@ -804,7 +810,7 @@ int vscan_llm_prune_fused_ragged(const vscan_llm_desc *d, const vscan_seq_meta *
 
 int vscan_profile_enable(int on) {
     std::lock_guard<std::mutex> lock(g_prof_mutex);
-    g_prof_on = on != 0;
+    g_prof_on.store(on != 0, std::memory_order_relaxed);
     return VSCAN_OK;
 }
 

@@ -759,9 +759,8 @@ static hipError_t launch_score_cls_t(const ScoreArgs &a, hipStream_t s) {
     const int n_keys = a.S - first_key;
     const size_t smem = (16 + 256 + (size_t)n_keys) * sizeof(float);
     if (smem > 64 * 1024) {
-        hipError_t e =
-            hipFuncSetAttribute(reinterpret_cast<const void *>(score_cls_generic_kernel<T>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        static std::atomic<uint64_t> lds_allowed{0};  // one per element type
+        hipError_t e = allow_large_lds(score_cls_generic_kernel<T>, lds_allowed);
         if (e != hipSuccess) return e;
     }
     dim3 grid(a.H, a.BC);
@@ -774,9 +773,8 @@ static hipError_t launch_score_cls_t(const ScoreArgs &a, hipStream_t s) {
 #define VSCAN_CLS_U(L, U)                                                                     \
     {                                                                                         \
         if (smem > 64 * 1024) {                                                               \
-            hipError_t e = hipFuncSetAttribute(                                               \
-                reinterpret_cast<const void *>(score_cls_kernel<T, L, U>),                    \
-                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                       \
+            static std::atomic<uint64_t> lds_allowed{0};                                      \
+            hipError_t e = allow_large_lds(score_cls_kernel<T, L, U>, lds_allowed);           \
             if (e != hipSuccess) return e;                                                    \
         }                                                                                     \
         hipLaunchKernelGGL((score_cls_kernel<T, L, U>), grid, dim3(256), smem, s,             \

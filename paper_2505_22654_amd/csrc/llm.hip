@@ -308,10 +308,9 @@ template <typename T, int NC, int NRB, bool STAGED, int DEPTH>
 static hipError_t llm_score_launch3(const LlmScoreArgs &a, hipStream_t s, size_t smem) {
     const int k0 = a.domain_all ? 0 : a.vis_start;
     const int nk = a.domain_all ? a.S : a.V;
+    static std::atomic<uint64_t> lds_allowed{0};  // one per instantiation
     if (smem > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(llm_score_kernel<T, NC, NRB, STAGED, DEPTH>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipError_t e = allow_large_lds(llm_score_kernel<T, NC, NRB, STAGED, DEPTH>, lds_allowed);
         if (e != hipSuccess) return e;
     }
     // persistent grid: as many workgroups as the CUs hold at once (LDS decides, at most four

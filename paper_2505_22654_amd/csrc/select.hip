@@ -625,12 +625,12 @@ size_t encoder_select_lds_bytes(int N, int has_local) {
 }
 size_t llm_select_lds_bytes(int V) { return sizeof(SelectSmem) + (size_t)V * 4 + round16((size_t)V); }
 
-template <typename Kernel, typename... Args>
-static hipError_t launch_select(Kernel kernel, int blocks, int threads, size_t smem, hipStream_t s,
+template <auto kernel, typename... Args>
+static hipError_t launch_select(int blocks, int threads, size_t smem, hipStream_t s,
                                 const Args &...args) {
+    static std::atomic<uint64_t> lds_allowed{0};  // one per kernel instantiation
     if (smem > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipError_t e = allow_large_lds(kernel, lds_allowed);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), smem, s, args...);
@@ -645,14 +645,14 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
     while (wcols < (a.gw + a.wc - 1) / a.wc) wcols <<= 1;
     const int win_slots = a.kw > 0 ? ((a.gh + a.wr - 1) / a.wr) * wcols : 0;
 #define VSCAN_SEL(...) \
-    return launch_select(encoder_select_kernel<__VA_ARGS__>, blocks, threads, smem, s, a, 0)
+    return launch_select<encoder_select_kernel<__VA_ARGS__>>(blocks, threads, smem, s, a, 0)
     // WIN_MODE 3 keeps, behind the usual state, a window-major copy of the keys (pitch = slots of
     // the largest window, in whole 16-byte reads) and the two geometry tables
     const int win_pitch = ((((a.gh + a.wr - 1) / a.wr) * ((a.gw + a.wc - 1) / a.wc)) + 3) & ~3;
     const size_t smem_wm = round16(sizeof(SelectSmem) + (size_t)N * 4 * (a.head_local ? 2 : 1) + N) +
                            (size_t)a.wr * a.wc * win_pitch * 4 + (size_t)3 * (a.gh + a.gw) * 4;
 #define VSCAN_SEL_WM(...)                                                                      \
-    return launch_select(encoder_select_kernel<__VA_ARGS__>, blocks, threads, smem_wm, s, a, \
+    return launch_select<encoder_select_kernel<__VA_ARGS__>>(blocks, threads, smem_wm, s, a, \
                          win_pitch)
     if (N <= 1024) {
         // small segment: one thread per token, wave 0 does the global scan from registers
@@ -686,9 +686,9 @@ hipError_t launch_encoder_select(const EncSelectArgs &a, hipStream_t s) {
         g.pre_key = a.pre_key_ws;
         g.pre_flag = a.pre_flag_ws;
         g.scores_out = nullptr;  // written by the first kernel
-        if (nreg <= 4) return launch_select(encoder_select_kernel<2, 1, false, 4>, blocks, threads, smem, s, g, 0);
-        if (nreg <= 16) return launch_select(encoder_select_kernel<2, 1, false, 16>, blocks, threads, smem, s, g, 0);
-        return launch_select(encoder_select_kernel<2, 1, false, 32>, blocks, threads, smem, s, g, 0);
+        if (nreg <= 4) return launch_select<encoder_select_kernel<2, 1, false, 4>>(blocks, threads, smem, s, g, 0);
+        if (nreg <= 16) return launch_select<encoder_select_kernel<2, 1, false, 16>>(blocks, threads, smem, s, g, 0);
+        return launch_select<encoder_select_kernel<2, 1, false, 32>>(blocks, threads, smem, s, g, 0);
     }
     if (win_slots * nreg <= 128) {
         if (nreg <= 4) VSCAN_SEL(0, 1, false, 4);
@@ -722,13 +722,13 @@ hipError_t launch_llm_select(const LlmSelectArgs &a, hipStream_t s) {
     if (a.V <= 1024) {
         const int threads = (a.V + kWave - 1) / kWave * kWave;
         if (a.V <= 256)
-            return launch_select(llm_select_kernel<true, 4>, a.B, threads, smem, s, a);
-        return launch_select(llm_select_kernel<true, 16>, a.B, threads, smem, s, a);
+            return launch_select<llm_select_kernel<true, 4>>(a.B, threads, smem, s, a);
+        return launch_select<llm_select_kernel<true, 16>>(a.B, threads, smem, s, a);
     }
     const int nreg = (a.V + 1023) / 1024;
-    if (nreg <= 4) return launch_select(llm_select_kernel<false, 4>, a.B, 1024, smem, s, a);
-    if (nreg <= 16) return launch_select(llm_select_kernel<false, 16>, a.B, 1024, smem, s, a);
-    return launch_select(llm_select_kernel<false, 32>, a.B, 1024, smem, s, a);
+    if (nreg <= 4) return launch_select<llm_select_kernel<false, 4>>(a.B, 1024, smem, s, a);
+    if (nreg <= 16) return launch_select<llm_select_kernel<false, 16>>(a.B, 1024, smem, s, a);
+    return launch_select<llm_select_kernel<false, 32>>(a.B, 1024, smem, s, a);
 }
 
 }  // namespace vscan

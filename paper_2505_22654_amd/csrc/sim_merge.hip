@@ -765,12 +765,10 @@ static hipError_t sim_large_launch(const MergeArgs &a, hipStream_t s) {
     const int mode = affine ? 1 : (tiles_m % 4 == 0 && tiles_n % 2 == 0 ? 2 : 0);
     const size_t smem = (size_t)2 * (BM + BN) * (KC * 32 + 16) + BM * sizeof(float);
     auto kernel = sim_argmax_large_kernel<T, TM, TN, WM, WN, KC>;
-    static std::atomic<bool> attribute_set{false};  // per instantiation; the value never changes
-    if (smem > 64 * 1024 && !attribute_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static std::atomic<uint64_t> lds_allowed{0};
+    if (smem > 64 * 1024) {
+        hipError_t e = allow_large_lds(kernel, lds_allowed);
         if (e != hipSuccess) return e;
-        attribute_set = true;
     }
     dim3 grid(image_affine_grid(a.B, tiles_m * tiles_n, affine));
     hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN), smem, s, (const T *)a.x, a.kept_idx,
