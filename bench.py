@@ -35,18 +35,19 @@ from paper_2505_22654_amd import workloads as wl  # noqa: E402
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # Vector ALU without packed fp32 operations (the build switches them off): 256 compute units x
-# 4 SIMDs x 16 lanes = 16384 lane-operations per cycle at 2.4 GHz.  A transcendental
-# (v_exp_f32) runs at a quarter of that rate and counts as 4 lane-operations.
+# 4 SIMDs x 16 lanes = 16384 lane-operations per cycle at 2.4 GHz.  On this chip a
+# transcendental (v_exp_f32) issues at half that rate (one wave instruction per 8 cycles and SIMD,
+# measured; CDNA4 doubled the transcendental rate of its predecessor) and counts as 2.
 PEAK_ALU_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# lane-operations per logit of the mean-attention passes: one multiply-add (scale and
-# reference), one exponential (4), one accumulation
-MEAN_LANEOPS_PER_LOGIT = 6.0
+# least lane-operations per logit of the mean-attention passes: one multiply (or multiply-add)
+# by the softmax scale, one exponential (2), one accumulation
+MEAN_LANEOPS_PER_LOGIT = 4.0
 
 KERNEL_SOURCE = {
     "score_cls": "encoder_score.hip", "score_mean_lse": "encoder_score.hip",
     "score_mean_colsum": "encoder_score.hip", "encoder_select": "select.hip",
-    "llm_select": "select.hip", "sim_argmax": "sim_merge.hip", "merge_lists": "sim_merge.hip",
-    "merge": "sim_merge.hip", "llm_score": "llm.hip", "llm_score_combine": "llm.hip",
+    "llm_select": "select.hip", "sim_argmax": "sim_merge.hip",
+    "merge": "sim_merge.hip", "llm_score": "llm.hip",
     "compact": "llm.hip",
     "fused_q": "fused.hip", "fused_split_q": "fused.hip", "fused_qt": "fused.hip",
     "fused_logits": "fused.hip", "fused_softmax": "fused.hip",
@@ -103,7 +104,6 @@ def algorithmic_work(w: wl.Workload, inputs: str = "qk"):
             out["score_mean_colsum"] = ("mfma", 2.0 * B * C * H * N * N * dh)
         out["encoder_select"] = ("hbm", B * T * 4 + B * K * 4)
         out["sim_argmax"] = ("mfma", 2.0 * B * U * K * D)
-        out["merge_lists"] = ("hbm", B * T * 8 + B * T * 4 + B * K * 4)
         out["merge"] = ("hbm", B * (T + K) * D * es)
     l = w.llm
     if l is not None:
@@ -116,7 +116,6 @@ def algorithmic_work(w: wl.Workload, inputs: str = "qk"):
         prefix = 0 if l.in_place else l.prefix
         if inputs == "qk":
             out["llm_score"] = ("hbm", l.batch * l.kv_heads * l.vis_len * l.head_dim * es)
-            out["llm_score_combine"] = ("hbm", l.batch * l.kv_heads * l.vis_len * 4 * 2)
             out["compact"] = ("hbm", l.batch * moved * row * 2)
             extra["compact"] = {"prefix_rows_bytes": l.batch * prefix * row * 2}
         else:
@@ -517,7 +516,7 @@ def measure(index: int, steps: int, warmup: int, inputs: str, streams: int, cold
              "frac": round(achieved / peak, 5), "avg_us": round(avg_s * 1e6, 2),
              "launches_per_step": rec["launches"] // steps, "share": rec["total_ms"]}
         if kname in ("score_mean_lse", "score_mean_colsum"):
-            # also against the vector-ALU bound: 6 lane-operations per logit
+            # also against the vector-ALU bound: MEAN_LANEOPS_PER_LOGIT lane-operations per logit
             laneops = MEAN_LANEOPS_PER_LOGIT * (per_launch / (2.0 * _head_dim(points))) / avg_s / 1e12
             k["alu"] = {"bound": "alu", "achieved": round(laneops, 3),
                         "peak": round(PEAK_ALU_TLANEOPS, 3), "unit": "Tlane-op/s",

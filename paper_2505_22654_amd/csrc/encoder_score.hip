@@ -600,12 +600,6 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
         }
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) part[h] = 0.f;
-        if constexpr (MULT) {
-#pragma unroll
-            for (int h = 0; h < HALVES; ++h)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) nxt[h][r] = 0.f;
-        }
         const unsigned char *next_frags = REFILL ? frag_ptr(t + 2) : nullptr;
         // Slot by slot: one matrix instruction, the LDS read that refills an operand chunk
         // after its last use, and a slice of tile t's logits (about three: forty cycles of
@@ -616,8 +610,12 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
         for (int m = 0; m < NM; ++m) {
             if constexpr (MULT) {
                 const int c = m / HALVES, h = m % HALVES;
+                // (the first chunk starts from a constant zero: no registers to clear)
+                const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                                       0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                 nxt[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8_t, fr[c]), resident_frag(h, c), nxt[h], 0, 0, 0);
+                    __builtin_bit_cast(bf16x8_t, fr[c]), resident_frag(h, c), c == 0 ? zero : nxt[h],
+                    0, 0, 0);
                 if constexpr (REFILL) {
                     if (h == HALVES - 1) fr[c] = *reinterpret_cast<const u32x4_t *>(next_frags + 32 * c);
                 }

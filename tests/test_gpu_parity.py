@@ -94,6 +94,17 @@ def test_encoder_local_scan_from_shallow_layer_pair():
     pu.check_encoder(shape, inp, ref, out, "local-pair")
 
 
+def test_encoder_local_pair_on_a_large_segment():
+    """More than 4096 tokens per segment: the local scan runs window by window in a kernel of its
+    own, here on the scores of the shallow-layer pair, and hands keys and flags to the global scan."""
+    shape = _enc(batch=1, n_segments=2, grid_h=80, grid_w=80, heads=2, head_dim=16, feat_dim=32,
+                 win_rows=4, win_cols=4, keep_global=40, keep_local=48)
+    inp, loc, ref, info = pu.screened_encoder_case(shape, seed=78, logit_gain=1.0, with_local=True,
+                                                   max_tries=4)
+    out = _run_encoder(shape, inp, loc)
+    print("local-pair-large", info, pu.check_encoder(shape, inp, ref, out, "local-pair-large"))
+
+
 def test_encoder_keep_everything_is_identity():
     shape = _enc(wl.F32, grid_h=8, grid_w=8, keep_global=32, keep_local=32)
     inp = wl.encoder_inputs(shape, 5)
