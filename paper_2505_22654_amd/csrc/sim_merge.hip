@@ -516,8 +516,8 @@ constexpr int kMergeListCap = 128;  // ints of LDS per list
 constexpr int kMergeAloneCap = 32;  // longest group that one wave adds alone (a few batches of rows)
 constexpr int kMergeMaxSpw = 4;     // slots a wave handles one after the other, at most
 
-template <typename T, int PIECES>
-__global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
+template <typename T, int PIECES, int NW>
+__global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
                                                     const unsigned long long *__restrict__ best,
                                                     T *__restrict__ merged,
                                                     int32_t *__restrict__ assign_out, int T_img,
@@ -526,12 +526,16 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
     // rows fetched together: about 24 16-byte loads per lane in flight (96 registers), which is
     // what it takes for the few workgroups that own the large groups to pull rows at the rate
     // a compute unit can take them
-    constexpr int BATCH = PIECES <= 3 ? 8 : PIECES <= 6 ? 4 : PIECES <= 12 ? 2 : 1;
-    __shared__ int cnt[4 * kMergeMaxSpw];
-    __shared__ int lists[4 * kMergeMaxSpw][kMergeListCap];
-    __shared__ int scratch_lists[4][kMergeListCap];  // per wave, for the scans of phase 3
-    extern __shared__ float part[];  // D floats: partial sums of a shared group
-    const int ns = 4 * spw;  // slots of this workgroup
+    // (sixteen waves share 512 registers per SIMD four ways: 128 each, so fewer rows per wave)
+    constexpr int BATCH = NW == 16 ? (PIECES <= 2 ? 8 : PIECES == 3 ? 5 : 3)
+                                   : (PIECES <= 3 ? 8 : PIECES <= 6 ? 4 : PIECES <= 12 ? 2 : 1);
+    constexpr int NT = 64 * NW;       // threads
+    constexpr int NB = NW / 4;        // partial-sum buffers of a shared group (four waves each)
+    __shared__ int cnt[NW * kMergeMaxSpw];
+    __shared__ int lists[NW * kMergeMaxSpw][kMergeListCap];
+    __shared__ int scratch_lists[NW][kMergeListCap];  // per wave, for the scans of phase 3
+    extern __shared__ float part[];  // NB x D floats: partial sums of a shared group
+    const int ns = NW * spw;  // slots of this workgroup
     int b, group;
     if (!image_affine_decode(B, (K + ns - 1) / ns, affine != 0, b, group)) return;
     const int slot0 = group * ns;
@@ -543,19 +547,19 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
     const int npieces = D / E;
     const int64_t row_bytes = (int64_t)D * sizeof(T);
 
-    if (tid < 4 * kMergeMaxSpw) cnt[tid] = 0;
+    if (tid < NW * kMergeMaxSpw) cnt[tid] = 0;
     __syncthreads();
 
     constexpr int SCAN = 8;  // assignment words fetched ahead per thread
-    for (int base = 0; base < T_img; base += SCAN * 256) {
+    for (int base = 0; base < T_img; base += SCAN * NT) {
         // The index is clamped, not predicated: the loads stay independent of each other and
         // in flight together.
         uint32_t w[SCAN];
 #pragma unroll
-        for (int u = 0; u < SCAN; ++u) w[u] = slot_word[2 * min(base + u * 256 + tid, T_img - 1)];
+        for (int u = 0; u < SCAN; ++u) w[u] = slot_word[2 * min(base + u * NT + tid, T_img - 1)];
 #pragma unroll
         for (int u = 0; u < SCAN; ++u) {
-            const int t = base + u * 256 + tid;
+            const int t = base + u * NT + tid;
             const int s = (int)(~w[u]);
             const unsigned rel = (unsigned)(s - slot0);
             if (t < T_img && rel < (unsigned)ns && s < K) {
@@ -655,7 +659,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
     // ---- phase 2: every wave sorts the lists of its slots and finishes the small groups
     bool any_shared = false;
     for (int i = 0; i < spw; ++i) {
-        const int rel = wave + 4 * i;
+        const int rel = wave + NW * i;
         const int slot = slot0 + rel;
         if (slot >= K) break;
         const int count = __builtin_amdgcn_readfirstlane(cnt[rel]);
@@ -671,9 +675,9 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
     if (!any_shared) return;  // the same decision in every wave: cnt is final since the barrier
     __syncthreads();          // sorted lists visible to all waves
 
-    // ---- phase 3: larger groups, all four waves on one group at a time
-    const int quarter = ((T_img + 4 * kWave - 1) / (4 * kWave)) * kWave;
-    const int t_begin = wave * quarter, t_end = min(T_img, t_begin + quarter);
+    // ---- phase 3: larger groups, all waves on one group at a time
+    const int share = ((T_img + NW * kWave - 1) / (NW * kWave)) * kWave;
+    const int t_begin = min(T_img, wave * share), t_end = min(T_img, t_begin + share);
     int *scan_list = scratch_lists[wave];
     for (int rel = 0; rel < ns; ++rel) {
         const int slot = slot0 + rel;
@@ -681,12 +685,12 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
         if (slot >= K || count <= kMergeAloneCap) continue;  // uniform over the workgroup
         clear();
         if (count <= kMergeListCap) {
-            // the sorted list is complete: wave w takes its w-th quarter
-            const int per = (count + 3) >> 2;
+            // the sorted list is complete: wave w takes its w-th share
+            const int per = (count + NW - 1) / NW;
             const int lo = min(wave * per, count), hi = min(lo + per, count);
             drain(lists[rel] + lo, hi - lo);
         } else {
-            // too long for the list: wave w gathers the members inside the w-th quarter of the
+            // too long for the list: wave w gathers the members inside the w-th share of the
             // token range with an ordered ballot scan
             int nlist = 0;
             for (int base = t_begin; base < t_end; base += SCAN * kWave) {
@@ -709,26 +713,47 @@ __global__ __launch_bounds__(256) void merge_kernel(const T *__restrict__ x,
             }
             drain(scan_list, nlist);
         }
-        // partial sums combined in wave order: part = acc0; part += acc1; part += acc2;
-        // wave 3 adds its own on top and writes the row
+        // Partial sums combined in wave order.  Waves 4g .. 4g+3 share buffer g: wave 4g writes
+        // its sum, 4g+1 and 4g+2 add theirs, 4g+3 adds its own on top (four rounds, all buffers at
+        // once); then the last wave adds the buffers' totals in buffer order and writes the row.
+        float *mine = part + (size_t)(wave >> 2) * D;
         for (int w = 0; w < 4; ++w) {
-            if (wave == w) {
+            if ((wave & 3) == w) {
 #pragma unroll
                 for (int p = 0; p < PIECES; ++p) {
                     const int piece = lane + p * kWave;
                     if (piece < npieces) {
 #pragma unroll
                         for (int e = 0; e < E; ++e) {
-                            float &slot_sum = part[piece * E + e];
+                            float &slot_sum = mine[piece * E + e];
                             if (w == 0) slot_sum = acc[p][e];
-                            else if (w < 3) slot_sum += acc[p][e];
+                            else if (w < 3 || (NB > 1 && wave != NW - 1)) slot_sum += acc[p][e];
                             else acc[p][e] = slot_sum + acc[p][e];
                         }
                     }
                 }
-                if (w == 3) write_row(slot, count);
+                if (NB == 1 && w == 3) write_row(slot, count);
             }
             __syncthreads();
+        }
+        if constexpr (NB > 1) {
+            if (wave == NW - 1) {
+                // acc holds buffer NB-1's total (the last wave kept it in registers)
+#pragma unroll
+                for (int p = 0; p < PIECES; ++p) {
+                    const int piece = lane + p * kWave;
+                    if (piece < npieces) {
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            float sum = part[piece * E + e];
+                            for (int g2 = 1; g2 < NB - 1; ++g2) sum += part[(size_t)g2 * D + piece * E + e];
+                            acc[p][e] = sum + acc[p][e];
+                        }
+                    }
+                }
+                write_row(slot, count);
+            }
+            __syncthreads();  // the buffers are reused by the next shared group
         }
     }
 }
@@ -811,23 +836,36 @@ static hipError_t merge_t(const MergeArgs &a, hipStream_t s) {
     constexpr int E = ElemTraits<T>::kPer16B;
     const int per_lane = (a.D / E + kWave - 1) / kWave;
     const bool affine = image_affinity(a);
-    // slots per wave: one while that still gives every CU two workgroups; more for very many
-    // slots, where the shared scan of the assignment words is what has to be amortised
+    // Sixteen waves per workgroup for long images (from 8192 tokens) when rows are short enough
+    // for four partial-sum buffers in LDS and there are slots for at least half the CUs: every
+    // workgroup scans all assignment words of its image, and the few very large groups of such
+    // an image set the kernel's time; both are then spread over four times as many waves
+    // (config 4: 52.6 -> 39.2 us).  Shorter images measured slower that way (config 3: 28 -> 40
+    // us): fewer, larger workgroups and sixteen-wave barriers for every shared group.
+    const bool wide = per_lane <= 4 && a.T >= 8192 && (int64_t)a.B * a.K >= 16 * 128;
+    const int nw = wide ? 16 : 4;
+    // slots per wave: one while that still gives every CU two workgroups of four waves (one of
+    // sixteen); more for very many slots, where the shared scan is what has to be amortised
     int spw = 1;
-    while (spw < kMergeMaxSpw && (int64_t)a.B * a.K >= (int64_t)4 * 512 * 2 * spw) spw *= 2;
-    const int ns = 4 * spw;
+    while (spw < kMergeMaxSpw && (int64_t)a.B * a.K >= (int64_t)nw * (wide ? 256 : 1024) * 2 * spw) spw *= 2;
+    const int ns = nw * spw;
     dim3 grid(image_affine_grid(a.B, (a.K + ns - 1) / ns, affine));
-    const size_t part_bytes = (size_t)a.D * sizeof(float);  // at most 32 KiB (row <= 16 KiB)
-#define VSCAN_MERGE(P)                                                                          \
-    hipLaunchKernelGGL((merge_kernel<T, P>), grid, dim3(256), part_bytes, s, (const T *)a.x,     \
-                       (const unsigned long long *)a.best, (T *)a.merged, a.assign_out, a.T, a.D, \
-                       a.K, a.B, (int)affine, spw)
-    if (per_lane <= 1) VSCAN_MERGE(1);
-    else if (per_lane <= 2) VSCAN_MERGE(2);
-    else if (per_lane <= 3) VSCAN_MERGE(3);
-    else if (per_lane <= 4) VSCAN_MERGE(4);
-    else if (per_lane <= 8) VSCAN_MERGE(8);
-    else if (per_lane <= 16) VSCAN_MERGE(16);
+    const size_t part_bytes = (size_t)(nw / 4) * a.D * sizeof(float);  // at most 32 KiB
+#define VSCAN_MERGE(P, NW)                                                                      \
+    hipLaunchKernelGGL((merge_kernel<T, P, NW>), grid, dim3(64 * NW), part_bytes, s,            \
+                       (const T *)a.x, (const unsigned long long *)a.best, (T *)a.merged,       \
+                       a.assign_out, a.T, a.D, a.K, a.B, (int)affine, spw)
+    if (wide) {
+        if (per_lane <= 1) VSCAN_MERGE(1, 16);
+        else if (per_lane <= 2) VSCAN_MERGE(2, 16);
+        else if (per_lane <= 3) VSCAN_MERGE(3, 16);
+        else VSCAN_MERGE(4, 16);
+    } else if (per_lane <= 1) VSCAN_MERGE(1, 4);
+    else if (per_lane <= 2) VSCAN_MERGE(2, 4);
+    else if (per_lane <= 3) VSCAN_MERGE(3, 4);
+    else if (per_lane <= 4) VSCAN_MERGE(4, 4);
+    else if (per_lane <= 8) VSCAN_MERGE(8, 4);
+    else if (per_lane <= 16) VSCAN_MERGE(16, 4);
     else return hipErrorInvalidValue;  // wider rows are rejected by the ABI layer
 #undef VSCAN_MERGE
     return hipGetLastError();
