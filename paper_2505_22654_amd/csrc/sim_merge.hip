@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256) void kept_inv_norm_kernel(const T *__restrict_
 // round-robin by linear index and every XCD has its own L2, so XCD x works through a compact
 // block of (tiles_m / 4) x (tiles_n / 2) tiles, kept tile fastest - its band of kept rows stays
 // in its L2 and its band of dropped rows streams through once.
-template <typename T, int TM, int TN, int WM, int WN, int KC>
+template <typename T, int TM, int TN, int WM, int WN, int KC, int NSETS>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 1) void sim_argmax_large_kernel(
     const T *__restrict__ x, const int32_t *__restrict__ kept_idx,
     const int32_t *__restrict__ drop_idx, const float *__restrict__ inv_norm,
@@ -442,20 +442,34 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
         }
     };
 
-    // The next stage's loads are issued before the stage is multiplied and written to the other
-    // LDS buffer after the first half of the matrix instructions: the LDS writes then complete
-    // under the second half, and the barrier at the end of the stage finds nothing pending.
-    uint4 ra[PER_THREAD];
-    stage_load(0, ra);
-    stage_store(0, ra, 0);
+    // Stage s + 1 is written to the other LDS buffer after the first half of stage s's matrix
+    // instructions (the LDS writes then complete under the second half, and the barrier at the
+    // end of the stage finds nothing pending), and the registers it came from are refilled at
+    // once with the loads of stage s + 1 + NSETS: a load has NSETS whole stages to arrive.  With
+    // one register set (the eight-wave form has no registers to spare) that is one stage, about
+    // what a fetch from L2 takes while the chip is busy; the four-wave form keeps three sets in
+    // flight.  Stage i always lives in set i % NSETS, so the loop is unrolled NSETS times.
+    uint4 ra[NSETS][PER_THREAD];
+    stage_load(0, ra[0]);
+    stage_store(0, ra[0], 0);
+#pragma unroll
+    for (int i = 1; i <= NSETS; ++i)
+        if (i < nstages) stage_load(i, ra[i % NSETS]);
     __syncthreads();
-    for (int st = 0; st < nstages; ++st) {
-        const bool more = st + 1 < nstages;
-        if (more) stage_load(st + 1, ra);
-        compute(lds[st & 1], 0, KC / 2);
-        if (more) stage_store((st + 1) & 1, ra, st + 1);
-        compute(lds[st & 1], KC / 2, KC);
-        if (more) __syncthreads();
+    for (int st0 = 0; st0 < nstages; st0 += NSETS) {
+#pragma unroll
+        for (int j = 0; j < NSETS; ++j) {
+            const int st = st0 + j;
+            if (st < nstages) {  // uniform
+                const bool more = st + 1 < nstages;
+                const int next_set = (j + 1) % NSETS;  // a constant once unrolled: st0 is a multiple of NSETS
+                compute(lds[st & 1], 0, KC / 2);
+                if (more) stage_store((st + 1) & 1, ra[next_set], st + 1);
+                if (st + 1 + NSETS < nstages) stage_load(st + 1 + NSETS, ra[next_set]);
+                compute(lds[st & 1], KC / 2, KC);
+                if (more) __syncthreads();
+            }
+        }
     }
 
     // epilogue: acc[i][j][r] = x_slot . x_token with
@@ -493,21 +507,22 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 4.  A workgroup (4 waves) owns 4 * spw consecutive kept slots of one image.
+// Eq. 4.  A workgroup of NW waves (4, or 16 for long images) owns NW * spw consecutive kept
+// slots of one image.
 //
 // Phase 1 (whole workgroup): one pass over the image's assignment words; a token whose slot
 // belongs to the workgroup is appended to that slot's member list in LDS (position from an LDS
 // counter, so the order inside a list is arbitrary at this point).
 // Phase 2 (one wave per slot, spw slots one after the other): the list is sorted by token index
 // (rank by counting); a group of up to kMergeAloneCap members is added up by that wave right
-// away, eight rows in flight at a time (a shared group costs the workgroup about 4 us of
+// away, several rows in flight at a time (a shared group costs the workgroup about 4 us of
 // barriers and serial combination, which is why groups of a few dozen are still added alone).
 // Phase 3 (whole workgroup, one larger group after the other): group sizes are heavy-tailed
 // (many dropped tokens look like the same kept token), and one wave adding dozens or hundreds
-// of rows would set the kernel's time.  The four waves share such a group: each takes a quarter
-// of the sorted list - or, when the group is longer than the list, gathers the members inside
-// its quarter of the token range with an ordered ballot scan - and the four partial sums are
-// combined in wave order through LDS.
+// of rows would set the kernel's time.  All waves share such a group: each takes its share of
+// the sorted list - or, when the group is longer than the list, gathers the members inside its
+// share of the token range with an ordered ballot scan - and the partial sums are combined in
+// wave order through LDS (four waves per buffer, then the buffers in order).
 // Every sum has a fixed order of additions, so results do not depend on scheduling.
 // Lane l owns the 16-byte pieces l, l+64, ... of the feature row.
 // ---------------------------------------------------------------------------
@@ -781,7 +796,7 @@ static hipError_t sim_t(const MergeArgs &a, hipStream_t s) {
                        a.D, a.K, U, a.B, (int)affine);
     return hipGetLastError();
 }
-template <typename T, int TM, int TN, int WM, int WN, int KC>
+template <typename T, int TM, int TN, int WM, int WN, int KC, int NSETS>
 static hipError_t sim_large_launch(const MergeArgs &a, hipStream_t s) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int U = a.T - a.K;
@@ -789,7 +804,7 @@ static hipError_t sim_large_launch(const MergeArgs &a, hipStream_t s) {
     const bool affine = image_affinity(a);
     const int mode = affine ? 1 : (tiles_m % 4 == 0 && tiles_n % 2 == 0 ? 2 : 0);
     const size_t smem = (size_t)2 * (BM + BN) * (KC * 32 + 16) + BM * sizeof(float);
-    auto kernel = sim_argmax_large_kernel<T, TM, TN, WM, WN, KC>;
+    auto kernel = sim_argmax_large_kernel<T, TM, TN, WM, WN, KC, NSETS>;
     static std::atomic<uint64_t> lds_allowed{0};
     if (smem > 64 * 1024) {
         hipError_t e = allow_large_lds(kernel, lds_allowed);
@@ -812,8 +827,8 @@ static hipError_t sim_large_t(const MergeArgs &a, hipStream_t s) {
     const int U = a.T - a.K;
     const long tiles256 = (long)(U / 256) * (a.K / 256) * a.B;
     if (a.K >= 1024 && U >= 1024 && tiles256 >= 2 * 256)
-        return sim_large_launch<T, 4, 2, 2, 4, 4>(a, s);
-    return sim_large_launch<T, 2, 2, 2, 2, 4>(a, s);
+        return sim_large_launch<T, 4, 2, 2, 4, 4, 1>(a, s);
+    return sim_large_launch<T, 2, 2, 2, 2, 4, 3>(a, s);
 }
 
 bool sim_argmax_uses_large_form(int B, int T, int K) {
