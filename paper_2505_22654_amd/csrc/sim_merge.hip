@@ -416,39 +416,37 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // chunks [c0, c1) of the stage in `cur`; the operand fragments of chunk c + 1 are read from
-    // LDS before the matrix instructions of chunk c are issued, so those never wait for LDS
-    auto compute = [&](const unsigned char *cur, int c0, int c1) {
-        const unsigned char *arow = cur + (wm * 32 * TM + (lane & 31)) * STRIDE + 16 * g;
-        const unsigned char *brow = cur + (BM + wn * 32 * TN + (lane & 31)) * STRIDE + 16 * g;
-        uint4 af[2][TM], bf[2][TN];
-        auto read = [&](int c, uint4(&a)[TM], uint4(&bb)[TN]) {
+    // Operand fragments: two register sets, chunk c of a stage in set c & 1 (KC is even).  The
+    // fragments of the next chunk are read from LDS before the matrix instructions of the
+    // current one are issued - across the middle of a stage, and across the barrier at its end:
+    // the first chunk of stage s + 1 is read right after the barrier and arrives under the
+    // matrix instructions of stage s's last chunk.  No matrix instruction waits for LDS.
+    static_assert(KC % 2 == 0, "chunk c lives in fragment set c & 1");
+    const int a_off = (wm * 32 * TM + (lane & 31)) * STRIDE + 16 * g;
+    const int b_off = (BM + wn * 32 * TN + (lane & 31)) * STRIDE + 16 * g;
+    uint4 af[2][TM], bf[2][TN];
+    auto read = [&](const unsigned char *cur, int c, int set) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                a[i] = *reinterpret_cast<const uint4 *>(arow + i * 32 * STRIDE + 32 * c);
+        for (int i = 0; i < TM; ++i)
+            af[set][i] = *reinterpret_cast<const uint4 *>(cur + a_off + i * 32 * STRIDE + 32 * c);
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bb[j] = *reinterpret_cast<const uint4 *>(brow + j * 32 * STRIDE + 32 * c);
-        };
-        read(c0, af[0], bf[0]);
+        for (int j = 0; j < TN; ++j)
+            bf[set][j] = *reinterpret_cast<const uint4 *>(cur + b_off + j * 32 * STRIDE + 32 * c);
+    };
+    auto mma = [&](int set) {
 #pragma unroll
-        for (int c = c0; c < c1; ++c) {
-            const int cur_set = (c - c0) & 1;
-            if (c + 1 < c1) read(c + 1, af[cur_set ^ 1], bf[cur_set ^ 1]);
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) mma32_chunk<T>(acc[i][j], af[cur_set][i], bf[cur_set][j]);
-        }
+            for (int j = 0; j < TN; ++j) mma32_chunk<T>(acc[i][j], af[set][i], bf[set][j]);
     };
 
-    // Stage s + 1 is written to the other LDS buffer after the first half of stage s's matrix
-    // instructions (the LDS writes then complete under the second half, and the barrier at the
-    // end of the stage finds nothing pending), and the registers it came from are refilled at
-    // once with the loads of stage s + 1 + NSETS: a load has NSETS whole stages to arrive.  With
-    // one register set (the eight-wave form has no registers to spare) that is one stage, about
-    // what a fetch from L2 takes while the chip is busy; the four-wave form keeps three sets in
-    // flight.  Stage i always lives in set i % NSETS, so the loop is unrolled NSETS times.
+    // Stage s + 1 is written to the other LDS buffer in the middle of stage s (the LDS writes
+    // complete under the second half of its matrix instructions), and the registers it came
+    // from are refilled at once with the loads of stage s + 1 + NSETS: a load has NSETS whole
+    // stages to arrive.  With one register set (the eight-wave form has no registers to spare)
+    // that is one stage, about what a fetch from L2 takes while the chip is busy; the four-wave
+    // form keeps three sets in flight.  Stage i always lives in set i % NSETS, so the loop is
+    // unrolled NSETS times.
     uint4 ra[NSETS][PER_THREAD];
     stage_load(0, ra[0]);
     stage_store(0, ra[0], 0);
@@ -456,6 +454,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
     for (int i = 1; i <= NSETS; ++i)
         if (i < nstages) stage_load(i, ra[i % NSETS]);
     __syncthreads();
+    read(lds[0], 0, 0);
     for (int st0 = 0; st0 < nstages; st0 += NSETS) {
 #pragma unroll
         for (int j = 0; j < NSETS; ++j) {
@@ -463,11 +462,23 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
             if (st < nstages) {  // uniform
                 const bool more = st + 1 < nstages;
                 const int next_set = (j + 1) % NSETS;  // a constant once unrolled: st0 is a multiple of NSETS
-                compute(lds[st & 1], 0, KC / 2);
-                if (more) stage_store((st + 1) & 1, ra[next_set], st + 1);
-                if (st + 1 + NSETS < nstages) stage_load(st + 1 + NSETS, ra[next_set]);
-                compute(lds[st & 1], KC / 2, KC);
-                if (more) __syncthreads();
+                const unsigned char *cur = lds[st & 1];
+#pragma unroll
+                for (int c = 0; c + 1 < KC; ++c) {
+                    read(cur, c + 1, (c + 1) & 1);
+                    mma(c & 1);
+                    if (c == KC / 2 - 1) {
+                        if (more) stage_store((st + 1) & 1, ra[next_set], st + 1);
+                        if (st + 1 + NSETS < nstages) stage_load(st + 1 + NSETS, ra[next_set]);
+                    }
+                }
+                if (more) {
+                    // every wave has issued its last reads of this buffer and its writes of the
+                    // other one; both are complete when the barrier is passed
+                    __syncthreads();
+                    read(lds[(st + 1) & 1], 0, 0);
+                }
+                mma((KC - 1) & 1);
             }
         }
     }
