@@ -369,7 +369,7 @@ static hipError_t llm_score_t(const LlmScoreArgs &a, hipStream_t s) {
 //                             order, part[j] = sum_r e[r][j] 2^(m_c(j)[r] - M_r) / L_r in row
 //                             order: fixed orders throughout, no atomics
 // ---------------------------------------------------------------------------
-constexpr int kSplitChunk = 256;
+constexpr int kSplitChunk = 64;   // keys per workgroup: four lanes share a key row
 
 template <typename T, int RB>
 __global__ __launch_bounds__(256) void llm_score_split_kernel(
@@ -387,33 +387,42 @@ __global__ __launch_bounds__(256) void llm_score_split_kernel(
     for (int i = R * dh + tid; i < RB * dh; i += 256) qs[i] = 0.f;
     __syncthreads();
 
-    const int kk = chunk * kSplitChunk + tid;       // key inside the domain
+    // Four adjacent lanes share a key: lane `sub` takes the 16-byte pieces sub, sub + 4, ... of
+    // its row (the four lanes read 64 contiguous bytes per request), so the serial chain of
+    // multiply-adds per lane is a quarter of the row, and the chip sees four times the workgroups.
+    const int sub = tid & 3;
+    const int kk = chunk * kSplitChunk + (tid >> 2);  // key inside the domain
     const unsigned char *krow = reinterpret_cast<const unsigned char *>(
         k + ((int64_t)item * S + k0 + min(kk, nk - 1)) * dh);   // clamped: always readable
     float acc[RB];
 #pragma unroll
     for (int r = 0; r < RB; ++r) acc[r] = 0.f;
     const int npieces = dh / E;
-    // sixteen 16-byte pieces of the key row at a time (a 128-element bf16 row in one round trip)
-    constexpr int PB = 16;
-    for (int p0 = 0; p0 < npieces; p0 += PB) {
+    // eight pieces per lane at a time (a 256-element bf16 row in one round trip)
+    constexpr int PB = 8;
+    for (int p0 = 0; p0 < npieces; p0 += 4 * PB) {
         uint4 raw[PB];
 #pragma unroll
-        for (int u = 0; u < PB; ++u) raw[u] = load16_stream(krow, (int64_t)min(p0 + u, npieces - 1) * 16);
+        for (int u = 0; u < PB; ++u)
+            raw[u] = load16_stream(krow, (int64_t)min(p0 + 4 * u + sub, npieces - 1) * 16);
 #pragma unroll
         for (int u = 0; u < PB; ++u) {
-            if (p0 + u < npieces) {  // uniform
+            const int piece = p0 + 4 * u + sub;
+            if (p0 + 4 * u < npieces) {  // uniform; a lane past the end of the row adds zeros
                 float v[E];
                 unpack16<T>(raw[u], v);
+                const bool live = piece < npieces;
 #pragma unroll
                 for (int r = 0; r < RB; ++r) {
-                    const float *qr = qs + r * dh + (p0 + u) * E;
+                    const float *qr = qs + r * dh + min(piece, npieces - 1) * E;
 #pragma unroll
-                    for (int e = 0; e < E; ++e) acc[r] = fmaf(v[e], qr[e], acc[r]);
+                    for (int e = 0; e < E; ++e) acc[r] = fmaf(live ? v[e] : 0.f, qr[e], acc[r]);
                 }
             }
         }
     }
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = group_sum<4>(acc[r]);  // every lane of a key: its logit
     // masking: keys past the domain, and for a causal row the keys behind its query
     float z[RB];
 #pragma unroll
@@ -438,8 +447,9 @@ __global__ __launch_bounds__(256) void llm_score_split_kernel(
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
         const float e = mrow[r] > -INFINITY ? __builtin_amdgcn_exp2f(z[r] - mrow[r]) : 0.f;
-        if (r < R && kk < nk && col >= 0 && col < V) e_out[((int64_t)item * R + r) * V + col] = e;
-        const float sum = wave_sum(e);
+        if (sub == 0 && r < R && kk < nk && col >= 0 && col < V)
+            e_out[((int64_t)item * R + r) * V + col] = e;
+        const float sum = wave_sum(sub == 0 ? e : 0.f);  // one lane per key counts
         if (lane == 0) red[r * 4 + w] = sum;
     }
     __syncthreads();
@@ -466,16 +476,22 @@ __global__ __launch_bounds__(256) void llm_score_combine_kernel(const float *__r
     // otherwise be chains of dependent global loads
     for (int i = tid; i < nchunks * R * 2; i += 256) st[i] = stats[(int64_t)item * nchunks * R * 2 + i];
     __syncthreads();
-    if (tid < R) {
+    // per row: maximum and rescaled sum over the chunks, one wave per row, lanes over chunks
+    // (a fixed reduction tree: the result does not depend on scheduling)
+    for (int r = wave_id(); r < R; r += 4) {
         float m = -INFINITY;
-        for (int c = 0; c < nchunks; ++c) m = fmaxf(m, st[(c * R + tid) * 2]);
+        for (int c = lane_id(); c < nchunks; c += kWave) m = fmaxf(m, st[(c * R + r) * 2]);
+        m = wave_max(m);
         float l = 0.f;
-        for (int c = 0; c < nchunks; ++c) {
-            const float mc = st[(c * R + tid) * 2];
-            if (mc > -INFINITY) l += st[(c * R + tid) * 2 + 1] * __builtin_amdgcn_exp2f(mc - m);
+        for (int c = lane_id(); c < nchunks; c += kWave) {
+            const float mc = st[(c * R + r) * 2];
+            if (mc > -INFINITY) l += st[(c * R + r) * 2 + 1] * __builtin_amdgcn_exp2f(mc - m);
         }
-        M[tid] = m;
-        invL[tid] = 1.0f / l;
+        l = wave_sum(l);
+        if (lane_id() == 0) {
+            M[r] = m;
+            invL[r] = 1.0f / l;
+        }
     }
     __syncthreads();
     for (int i = tid; i < nchunks * R; i += 256) {
@@ -494,7 +510,7 @@ __global__ __launch_bounds__(256) void llm_score_combine_kernel(const float *__r
 
 // chunks the key domain is cut into, 0 when the one-workgroup-per-item kernel is the better fit
 int llm_score_split_chunks(int B, int Hkv, int rows, int nk, bool ragged) {
-    if (ragged || rows > 16 || nk < 4 * kSplitChunk || (int64_t)B * Hkv > kCus / 4) return 0;
+    if (ragged || rows > 16 || nk < 1024 || (int64_t)B * Hkv > kCus / 4) return 0;
     return (nk + kSplitChunk - 1) / kSplitChunk;
 }
 

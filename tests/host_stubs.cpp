@@ -120,7 +120,7 @@ hipError_t launch_merge(const MergeArgs &a, hipStream_t) {
 
 int llm_score_split_chunks(int B, int Hkv, int rows, int nk, bool ragged) {
     if (ragged || rows > 16 || nk < 1024 || (int64_t)B * Hkv > 64) return 0;
-    return (nk + 255) / 256;
+    return (nk + 63) / 64;
 }
 bool llm_score_supported(int rows, int, int row_bytes) { return rows <= 64 && row_bytes <= 512; }
 hipError_t launch_llm_score(const LlmScoreArgs &a, hipStream_t) {
