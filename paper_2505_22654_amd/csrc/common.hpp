@@ -246,6 +246,7 @@ __device__ __forceinline__ void mma16_chunk<float>(f32x4_t &acc, const uint4 &a,
 // Grid size: image_affine_grid().  Returns false for a padding workgroup.
 // ---------------------------------------------------------------------------
 constexpr int kXcds = 8;
+constexpr int kCus = 256;  // compute units of the MI355X
 __host__ __device__ inline int image_affine_grid(int images, int per_image, bool affine) {
     return affine ? kXcds * ((images + kXcds - 1) / kXcds) * per_image : images * per_image;
 }

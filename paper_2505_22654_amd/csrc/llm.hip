@@ -39,7 +39,6 @@ namespace vscan {
 // the smaller register footprint lets a second workgroup share the CU.
 constexpr int kScoreWaves = 8;  // waves per workgroup
 constexpr int kScoreHeader = 128 + kScoreWaves * 64;  // floats of LDS before the logits
-constexpr int kCus = 256;       // compute units of the MI355X
 
 __host__ __device__ inline int score_logit_stride(int nk) {
     // floats per logit row: >= nk rounded up to 16, and = 16 mod 64 so that the 16 query rows

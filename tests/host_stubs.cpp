@@ -17,7 +17,6 @@
 namespace {
 uintptr_t g_lo = 0, g_hi = 0;
 int g_calls = 0, g_regions = 0, g_violations = 0;
-std::vector<std::pair<uintptr_t, uintptr_t>> g_seen;  // regions of the current entry-point call
 
 void region(const char *who, const char *what, const void *p, size_t bytes) {
     ++g_regions;
