@@ -414,8 +414,9 @@ def measure(index: int, steps: int, warmup: int, inputs: str, streams: int, cold
     points = sweep_points(index)
     if inputs == "hidden" and any(w.encoder is not None and w.encoder.score_mode != 0
                                   for w in points):
-        sys.exit("bench.py: --inputs hidden needs a [CLS] encoder (mean-attention scoring has one "
-                 "query per token and is served by the Q/K form only)")
+        sys.exit("bench.py: --inputs hidden is timed on [CLS] encoders only (the mean-attention form of "
+                 "vscan_encoder_reduce_fused projects Q and K of every token and then runs the fp32 "
+                 "kernels of the Q/K entry point; it is covered by the parity tests, not by this bench)")
     hosts = host_inputs(points, inputs)
     in_place = any(w.llm is not None and w.llm.in_place for w in points)
     ring = steps if in_place else 1

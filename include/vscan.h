@@ -284,18 +284,21 @@ int vscan_llm_prune_fused(const vscan_llm_desc *desc, void *hidden, const void *
 
 /* ---------------------------------------------------------------------------
  * Stage 1 for a caller that does not hold the attention layer's queries and
- * keys: the [CLS] scores of Eq. 1-2 computed as written, from the rows the
- * layer sees and its projection weights (Sec. 4.1 "Global Scan": Q = X W_Q^h,
- * K = X W_K^h, the [CLS] row of softmax(Q K^T * scale), mean over heads), then
+ * keys: the scores of Sec. 4.1 "Global Scan" computed as written, from the rows
+ * the layer sees and its projection weights (Q = X W_Q^h, K = X W_K^h), then
  * the same local scan, global scan, assignment and merge as
- * vscan_encoder_reduce.  VSCAN_SCORE_CLS_ROW and bf16 only
+ * vscan_encoder_reduce.  VSCAN_SCORE_CLS_ROW: the [CLS] row of
+ * softmax(Q K^T * scale), mean over heads (Eq. 1-2).  VSCAN_SCORE_MEAN_RECEIVED
+ * (encoders without a [CLS] token, last sentence of "Global Scan"): Q and K of
+ * every token are projected (fp32) and the mean attention each token receives
+ * is computed as in vscan_encoder_reduce; head_dim <= 128 there.  bf16 only
  * (VSCAN_ERR_UNSUPPORTED otherwise); projection biases are not part of the
  * equations and not applied.
  *
  * desc          HOST; as for vscan_encoder_reduce; the hidden size of the layer
  *               is desc->feat_dim
- * hidden        DEVICE [B*C, S, feat_dim], S = 1 + grid_h*grid_w, the [CLS] row
- *               first; read only
+ * hidden        DEVICE [B*C, S, feat_dim], S = has_cls + grid_h*grid_w, the
+ *               [CLS] row first where there is one; read only
  * w_q           DEVICE [H*dh, feat_dim]  (row n: weights of output feature n)
  * w_k_t         DEVICE [feat_dim, H*dh]  (row c: what input feature c
  *               contributes; the paper's W_K with the heads side by side)

@@ -271,15 +271,49 @@ def encoder_scores_from_hidden(hidden, w_q, w_k, heads, head_dim, domain: int = 
     return out / heads
 
 
+def encoder_mean_scores_from_hidden(hidden, w_q, w_k, heads, head_dim, has_cls: int,
+                                    domain: int = 0, scale: float = 0.0):
+    """The encoder without a usable [CLS] row (last sentence of Sec. 4.1 "Global Scan"), written
+    out from the rows the attention layer sees: hidden [B,C,S,D] (S = N + has_cls, the [CLS] row
+    first where there is one), w_q, w_k [H*dh, D],
+        Q = x W_Q^h,  K = x W_K^h,  A^h = row-softmax(Q K^T * scale) for the N patch queries,
+        score_j = mean over heads and over the N queries of A^h_ij  (diagonal included).
+    domain 0: the softmax runs over the patch keys; domain 1: over all S keys, and the [CLS]
+    column is dropped afterwards.  Returns [B,C,N] fp64.  Plain numpy in fp64."""
+    x = np.asarray(hidden, dtype=np.float64)
+    wq = np.asarray(w_q, dtype=np.float64)
+    wk = np.asarray(w_k, dtype=np.float64)
+    B, C, S, D = x.shape
+    N = S - has_cls
+    sc = default_scale(head_dim, scale)
+    k0 = 0 if domain else has_cls
+    out = np.zeros((B, C, N), dtype=np.float64)
+    for b in range(B):
+        for c in range(C):
+            q = (x[b, c, has_cls:, :] @ wq.T).reshape(N, heads, head_dim)
+            k = (x[b, c, k0:, :] @ wk.T).reshape(S - k0, heads, head_dim)
+            for h in range(heads):
+                logit = q[:, h, :] @ k[:, h, :].T * sc              # [N queries, keys]
+                e = np.exp(logit - logit.max(axis=1, keepdims=True))
+                a = e / e.sum(axis=1, keepdims=True)
+                out[b, c] += a[:, has_cls - k0:].sum(axis=0)
+    return out / (heads * N)
+
+
 def encoder_reduce_fused(shape, hidden, w_q, w_k, x, hidden_local=None, w_q_local=None,
                          w_k_local=None) -> Dict[str, np.ndarray]:
     """Sec. 4.1 end to end with the scores taken from hidden states and projection weights
-    ([CLS] scoring only); the optional second triple is the shallow layer of the local scan."""
-    s_global = encoder_scores_from_hidden(hidden, w_q, w_k, shape.heads, shape.head_dim,
+    ([CLS] row or mean attention received, as the shape says); the optional second triple is the
+    shallow layer of the local scan."""
+    def scores(h, wq, wk):
+        if shape.score_mode == 1:
+            return encoder_mean_scores_from_hidden(h, wq, wk, shape.heads, shape.head_dim,
+                                                   shape.has_cls, shape.softmax_domain, shape.scale)
+        return encoder_scores_from_hidden(h, wq, wk, shape.heads, shape.head_dim,
                                           shape.softmax_domain, shape.scale)
+    s_global = scores(hidden, w_q, w_k)
     if hidden_local is not None:
-        s_local = encoder_scores_from_hidden(hidden_local, w_q_local, w_k_local, shape.heads,
-                                             shape.head_dim, shape.softmax_domain, shape.scale)
+        s_local = scores(hidden_local, w_q_local, w_k_local)
     else:
         s_local = s_global
     kept = select(s_local, s_global, shape.grid_h, shape.grid_w, shape.win_rows, shape.win_cols,

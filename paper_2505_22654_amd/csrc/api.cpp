@@ -211,13 +211,37 @@ struct EncoderFusedPlan {
     EncoderPlan e;
     FusedScratch f;
     int k0, nk;
+    // mean-attention scoring: W_K with its rows along the output features, then Q and K of
+    // every token in fp32 [BC, H, S, dh]
+    size_t off_wk, off_qf, off_kf;
     size_t bytes;
 };
 
 int plan_encoder_fused(const vscan_encoder_desc *d, int with_local, EncoderFusedPlan *p) {
     const int rc = plan_encoder(d, with_local, &p->e);
     if (rc != VSCAN_OK) return rc;
-    if (d->dtype != VSCAN_BF16 || d->score_mode != VSCAN_SCORE_CLS_ROW) return VSCAN_ERR_UNSUPPORTED;
+    if (d->dtype != VSCAN_BF16) return VSCAN_ERR_UNSUPPORTED;
+    if (d->score_mode == VSCAN_SCORE_MEAN_RECEIVED) {
+        // Q and K are projected in fp32 and scored by the fp32 mean-attention kernels
+        if (d->head_dim * 4 > 512) return VSCAN_ERR_UNSUPPORTED;
+        const int64_t lim = (int64_t)1 << 32;  // 32-bit row offsets inside the projection
+        const int64_t feat = (int64_t)d->heads * d->head_dim;
+        if ((int64_t)p->e.BC * p->e.S * d->feat_dim * 2 >= lim || feat * d->feat_dim * 2 >= lim ||
+            (int64_t)p->e.BC * p->e.S >= ((int64_t)1 << 31) / 2)
+            return VSCAN_ERR_UNSUPPORTED;
+        p->k0 = p->nk = 0;
+        p->f = FusedScratch{};
+        size_t off = p->e.bytes;
+        p->off_wk = off;
+        off += align_up((size_t)feat * d->feat_dim * 2);
+        p->off_qf = off;
+        off += align_up((size_t)p->e.BC * feat * p->e.S * sizeof(float));
+        p->off_kf = off;
+        off += align_up((size_t)p->e.BC * feat * p->e.S * sizeof(float));
+        p->bytes = off;
+        return VSCAN_OK;
+    }
+    p->off_wk = p->off_qf = p->off_kf = 0;
     p->k0 = d->softmax_domain == VSCAN_KEYS_ALL ? 0 : 1;
     p->nk = d->softmax_domain == VSCAN_KEYS_ALL ? p->e.S : p->e.N;
     const int rc2 = plan_fused_scratch(p->e.BC, p->e.S, d->feat_dim, d->heads, d->heads,
@@ -485,6 +509,46 @@ static int encoder_reduce_fused_impl(const vscan_encoder_desc *d, const void *hi
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+    if (d->score_mode == VSCAN_SCORE_MEAN_RECEIVED) {
+        // every token is a query: project Q and K of all tokens, then the two mean-attention
+        // passes of the Q/K entry point on the fp32 result
+        ScoreArgs sa;
+        sa.q = ws + p.off_qf;
+        sa.k = ws + p.off_kf;
+        sa.lse = reinterpret_cast<float *>(ws + p.e.off_lse);
+        sa.BC = p.e.BC;
+        sa.H = d->heads;
+        sa.S = p.e.S;
+        sa.dh = d->head_dim;
+        sa.N = p.e.N;
+        sa.has_cls = d->has_cls;
+        sa.domain_all = d->softmax_domain == VSCAN_KEYS_ALL;
+        sa.is_bf16 = 0;
+        sa.scale = resolve_scale(d->scale, d->head_dim);
+        for (int pass = 0; pass < (with_local ? 2 : 1); ++pass) {
+            ProjectArgs pa;
+            pa.hidden = pass ? hidden_local : hidden;
+            pa.BC = p.e.BC;
+            pa.S = p.e.S;
+            pa.Dh = d->feat_dim;
+            pa.H = d->heads;
+            pa.dh = d->head_dim;
+            pa.w = pass ? w_q_local : w_q;
+            pa.out = reinterpret_cast<float *>(ws + p.off_qf);
+            VSCAN_LAUNCH("fused_project", launch_fused_project(pa, s));
+            VSCAN_LAUNCH("fused_transpose", launch_transpose16(pass ? w_k_t_local : w_k_t, ws + p.off_wk,
+                                                              d->feat_dim, d->heads * d->head_dim, s));
+            pa.w = ws + p.off_wk;
+            pa.out = reinterpret_cast<float *>(ws + p.off_kf);
+            VSCAN_LAUNCH("fused_project", launch_fused_project(pa, s));
+            sa.head_scores = reinterpret_cast<float *>(ws + (pass ? p.e.off_head_local : p.e.off_head_global));
+            VSCAN_LAUNCH("score_mean_lse", launch_score_mean_lse(sa, s));
+            VSCAN_LAUNCH("score_mean_colsum", launch_score_mean_colsum(sa, s));
+        }
+        return enqueue_encoder_tail(d, p.e, with_local, d->heads,
+                                    1.0f / ((float)d->heads * (float)p.e.N), x, kept_idx, merged,
+                                    assign_out, scores_out, ws, s);
+    }
     for (int pass = 0; pass < (with_local ? 2 : 1); ++pass) {
         FusedArgs fa;
         fa.hidden = pass ? hidden_local : hidden;

@@ -144,6 +144,27 @@ struct ProbLogit {
     }
 };
 
+// Projection of every row of `hidden` with a weight matrix whose rows are output features; the
+// result goes out in fp32 as [bc][head][token][e] (never split along the contraction axis).
+struct ProbProject {
+    static constexpr int PL = 1;
+    static constexpr bool kStreamS = false;
+    GemmDims d;
+    const char *hidden, *w;
+    int S, H, dh, row_bytes;
+    float *out;
+    __device__ int rows_s(int) const { return d.rows_s; }
+    __device__ const char *s_base(int) const { return w; }
+    __device__ uint32_t s_off(int n) const { return (uint32_t)n * (uint32_t)row_bytes; }
+    __device__ const char *p_base(int, int) const { return hidden; }
+    __device__ uint32_t p_off(int m) const { return (uint32_t)m * (uint32_t)row_bytes; }
+    __device__ void emit(int, int, int p, int s_row, float v) const {
+        const int bc = p / S, t = p - bc * S;
+        const int h = s_row / dh, e = s_row - h * dh;
+        out[(((int64_t)bc * H + h) * S + t) * dh + e] = v;
+    }
+};
+
 // One workgroup of WS x WP waves: 32*FS*WS streamed rows x 32*FP*WP plane-operand rows, one
 // share of the contraction axis; a wave owns FS x FP tiles of 32 x 32.  Both operands pass
 // through LDS in CH-byte row chunks: the next chunk is fetched into registers (coalesced,
@@ -562,6 +583,42 @@ hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
                            ks_stride, a.nk, a.scale, a.Tq, a.causal, a.meta);
 #undef VSCAN_SOFTMAX
     return hipGetLastError();
+}
+
+// 64 x 64 tiles of 16-bit elements through LDS (pitch 65: conflict-free both ways)
+__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t *__restrict__ in,
+                                                          uint16_t *__restrict__ out, int rows,
+                                                          int cols) {
+    __shared__ uint16_t tile[64][65];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int r = i >> 6, c = i & 63;
+        if (r0 + r < rows && c0 + c < cols) tile[r][c] = in[(int64_t)(r0 + r) * cols + c0 + c];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int c = i >> 6, r = i & 63;
+        if (r0 + r < rows && c0 + c < cols) out[(int64_t)(c0 + c) * rows + r0 + r] = tile[r][c];
+    }
+}
+
+hipError_t launch_transpose16(const void *in, void *out, int rows, int cols, hipStream_t s) {
+    hipLaunchKernelGGL(transpose16_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, s,
+                       (const uint16_t *)in, (uint16_t *)out, rows, cols);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_project(const ProjectArgs &a, hipStream_t s) {
+    ProbProject pr;
+    pr.d = dims(a.H * a.dh, a.BC * a.S, a.Dh, 1, nullptr);
+    pr.hidden = reinterpret_cast<const char *>(a.hidden);
+    pr.w = reinterpret_cast<const char *>(a.w);
+    pr.S = a.S;
+    pr.H = a.H;
+    pr.dh = a.dh;
+    pr.row_bytes = a.Dh * 2;
+    pr.out = a.out;
+    return launch_gemm(pr, 1, s);
 }
 
 hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s) {

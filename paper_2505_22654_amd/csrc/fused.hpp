@@ -36,4 +36,19 @@ hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s);
 
+// Mean-attention scoring (last sentence of "Global Scan") from hidden states: every token is a
+// query, so Q and K are projected outright - out[bc][h][t][e] = sum_k hidden[bc][t][k] *
+// w[h*dh + e][k], fp32, in the layout the mean-attention kernels read - and those kernels run
+// on the result.  `w` has its rows along the output features; W_K arrives the other way round
+// and is transposed first.
+struct ProjectArgs {
+    const void *hidden;   // [BC, S, Dh] bf16
+    const void *w;        // [H*dh, Dh] bf16
+    float *out;           // [BC, H, S, dh]
+    int BC, S, Dh, H, dh;
+};
+hipError_t launch_fused_project(const ProjectArgs &a, hipStream_t s);
+// out[c][r] = in[r][c], 16-bit elements; rows and cols are multiples of 8
+hipError_t launch_transpose16(const void *in, void *out, int rows, int cols, hipStream_t s);
+
 }  // namespace vscan

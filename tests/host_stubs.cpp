@@ -164,6 +164,16 @@ static hipError_t check_fused(const char *who, const FusedArgs &a) {
                    {a.part, (size_t)a.B * a.V * 4}});
     return hipSuccess;
 }
+hipError_t launch_fused_project(const ProjectArgs &a, hipStream_t) {
+    ++g_calls;
+    region("fused_project", "out", a.out, (size_t)a.BC * a.H * a.S * a.dh * 4);
+    return hipSuccess;
+}
+hipError_t launch_transpose16(const void *, void *out, int rows, int cols, hipStream_t) {
+    ++g_calls;
+    region("fused_transpose", "out", out, (size_t)rows * cols * 2);
+    return hipSuccess;
+}
 hipError_t launch_fused_q(const FusedArgs &a, hipStream_t) { return check_fused("fused_q", a); }
 hipError_t launch_fused_split_q(const FusedArgs &a, hipStream_t) { return check_fused("fused_split_q", a); }
 hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t) { return check_fused("fused_qt", a); }

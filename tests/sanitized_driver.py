@@ -93,7 +93,7 @@ for idx in (1, 2, 3, 4, 5, 6):
             assert L.vscan_encoder_reduce(ctypes.byref(d), FAKE, FAKE, loc, loc, FAKE, FAKE, FAKE, None,
                                           None, WS + 8, n + 8, None) == vb.VSCAN_ERR_ALIGN
             bad += 2
-        if shape.dtype == wl.BF16 and shape.score_mode == 0:
+        if shape.dtype == wl.BF16:       # [CLS] scoring and mean attention from hidden states
             for with_local in (0, 1):
                 rc, n = size(L.vscan_encoder_fused_workspace_size, d, with_local)
                 if rc == vb.VSCAN_ERR_UNSUPPORTED:

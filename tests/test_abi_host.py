@@ -249,8 +249,12 @@ def test_fused_entry_points_validate_on_the_host():
     assert eneed > vb.encoder_workspace_size(edesc)
     assert vb.encoder_fused_workspace_size(edesc, True) > eneed
     assert _fused_enc_call(vb.encoder_desc(_enc_shape())) == vb.VSCAN_ERR_UNSUPPORTED   # fp32
+    # mean-attention scoring is served (Q and K projected in fp32): larger scratch, and heads
+    # wider than 512 bytes in fp32 are refused
     mean = bf(_enc_shape(has_cls=0, score_mode=1))
-    assert _fused_enc_call(vb.encoder_desc(mean)) == vb.VSCAN_ERR_UNSUPPORTED
+    assert vb.encoder_fused_workspace_size(vb.encoder_desc(mean)) > vb.encoder_workspace_size(vb.encoder_desc(mean))
+    wide = bf(_enc_shape(has_cls=0, score_mode=1, head_dim=136))
+    assert _fused_enc_call(vb.encoder_desc(wide)) == vb.VSCAN_ERR_UNSUPPORTED
     assert _fused_enc_call(edesc, local=(FAKE, FAKE, None)) == vb.VSCAN_ERR_NULL       # partial triple
     assert _fused_enc_call(edesc, x=None) == vb.VSCAN_ERR_NULL
     assert _fused_enc_call(edesc, hidden=FAKE + 4) == vb.VSCAN_ERR_ALIGN

@@ -283,11 +283,64 @@ def test_fused_encoder_local_scan_from_shallow_layer():
     print(pu.check_encoder(shape, inp, ref, out, "fused encoder, shallow-layer local scan"))
 
 
-def test_fused_encoder_rejects_mean_mode_and_fp32():
-    for shape in (_enc(has_cls=0, score_mode=1), _enc(dtype=wl.F32)):
+def test_fused_encoder_rejects_fp32_and_wide_mean_heads():
+    for shape in (_enc(dtype=wl.F32), _enc(has_cls=0, score_mode=1, head_dim=136)):
         with pytest.raises(vb.VscanError) as e:
             vb.encoder_fused_workspace_size(vb.encoder_desc(shape))
         assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
+
+
+FUSED_ENCODER_MEAN = {
+    # no [CLS] row (the encoder the mean-attention sentence is about), ragged grid and head size
+    "no-cls": _enc(has_cls=0, score_mode=1, batch=2, n_segments=2, grid_h=13, grid_w=11, heads=3,
+                   head_dim=40, feat_dim=200, win_rows=3, win_cols=2, keep_global=17, keep_local=13),
+    # a [CLS] row that only takes part as a key
+    "cls-all-keys": _enc(has_cls=1, score_mode=1, softmax_domain=1, keep_global=30, keep_local=16),
+    "cls-patch-keys": _enc(has_cls=1, score_mode=1, grid_h=9, grid_w=14, heads=2, head_dim=64),
+    # more tokens than one 256-row tile of the projection, 128-wide heads (the fp32 limit)
+    "many-rows-wide-heads": _enc(has_cls=0, score_mode=1, batch=3, n_segments=2, grid_h=16,
+                                 grid_w=15, heads=2, head_dim=128, feat_dim=256, keep_global=12,
+                                 keep_local=8),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FUSED_ENCODER_MEAN))
+def test_fused_encoder_mean_attention(name):
+    """Stage 1 scored by mean attention received, from hidden states and projection weights."""
+    shape = FUSED_ENCODER_MEAN[name]
+    inp, _, ref, info = pu.screened_encoder_fused_case(
+        shape, 9900 + sorted(FUSED_ENCODER_MEAN).index(name) * 13, max_tries=6)
+    print("case", name, info, flush=True)
+    out = _run_encoder(shape, inp)
+    print(name, pu.check_encoder(shape, inp, ref, out, name))
+
+
+def test_fused_encoder_mean_attention_with_shallow_layer():
+    shape = _enc(has_cls=0, score_mode=1, batch=2, grid_h=12, grid_w=12, keep_global=14, keep_local=12)
+    inp, loc, ref, info = pu.screened_encoder_fused_case(shape, 9950, with_local=True, max_tries=6)
+    print("case", info, flush=True)
+    out = _run_encoder(shape, inp, loc)
+    print(pu.check_encoder(shape, inp, ref, out, "fused encoder, mean attention, shallow-layer local scan"))
+
+
+def test_fused_encoder_mean_attention_agrees_with_projected_path():
+    """The same scores through the other route: Q and K projected on the host (rounded to fp32)
+    and handed to vscan_encoder_reduce in mean mode."""
+    import torch
+    shape = _enc(has_cls=0, score_mode=1, batch=2, grid_h=10, grid_w=9, heads=3, head_dim=24, feat_dim=96)
+    inp = wl.encoder_hidden_inputs(shape, 9960)
+    out = _run_encoder(shape, inp)
+    x = inp["hidden"].astype(np.float64)
+    B, C, S, D = x.shape
+    H, dh = shape.heads, shape.head_dim
+    q = (x @ inp["w_q"].astype(np.float64).T).reshape(B, C, S, H, dh).transpose(0, 1, 3, 2, 4)
+    k = (x @ inp["w_k"].astype(np.float64).T).reshape(B, C, S, H, dh).transpose(0, 1, 3, 2, 4)
+    f32 = dataclasses.replace(shape, dtype=wl.F32)
+    other = vb.encoder_reduce(f32, pu.to_device(np.ascontiguousarray(q, dtype=np.float32), wl.F32),
+                              pu.to_device(np.ascontiguousarray(k, dtype=np.float32), wl.F32),
+                              pu.to_device(inp["x"].astype(np.float32), wl.F32), want_scores=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(pu.to_host(out["scores"]), pu.to_host(other["scores"]), rtol=2e-5)
 
 
 def test_fused_encoder_config2_shape():

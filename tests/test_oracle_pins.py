@@ -580,3 +580,65 @@ def test_encoder_scores_from_hidden_closed_form():
     got = vo.encoder_scores_from_hidden(x, wq, wk, 1, D, 1, scale=1.0)
     np.testing.assert_allclose(got[0, 0], np.arange(1, N + 1) / (np.arange(1, N + 1).sum() + 1.0),
                                rtol=1e-12)
+
+
+# ---- mean attention received, written out from the encoder's hidden states -------------------
+
+@pytest.mark.parametrize("has_cls", [0, 1])
+def test_encoder_mean_scores_from_hidden_agree_with_projected_form(has_cls):
+    """Projecting on the host and calling the C oracle's mean mode gives the same scores (two
+    routes: numpy on hidden states, C loops on Q and K), with and without a [CLS] row, both key
+    domains; every column sum of row-softmaxes adds up to 1 over the patch columns in domain 0."""
+    from paper_2505_22654_amd import workloads as wl
+    shape = wl.EncoderShape(dtype=wl.BF16, batch=2, n_segments=2, grid_h=5, grid_w=4, has_cls=has_cls,
+                            score_mode=1, heads=3, head_dim=8, feat_dim=24, win_rows=1,
+                            win_cols=1, keep_global=4, keep_local=0)
+    inp = wl.encoder_hidden_inputs(shape, 37)
+    x = inp["hidden"].astype(np.float64)
+    B, C, S, D = x.shape
+    q = (x @ inp["w_q"].astype(np.float64).T).reshape(B, C, S, 3, 8).transpose(0, 1, 3, 2, 4)
+    k = (x @ inp["w_k"].astype(np.float64).T).reshape(B, C, S, 3, 8).transpose(0, 1, 3, 2, 4)
+    for domain in ((0, 1) if has_cls else (0,)):
+        got = vo.encoder_mean_scores_from_hidden(inp["hidden"], inp["w_q"], inp["w_k"], 3, 8, has_cls,
+                                                 domain)
+        want = vo.encoder_scores(q.astype(np.float32), k.astype(np.float32), has_cls, 1, domain)
+        np.testing.assert_allclose(got, want, rtol=5e-6)
+    s0 = vo.encoder_mean_scores_from_hidden(inp["hidden"], inp["w_q"], inp["w_k"], 3, 8, has_cls, 0)
+    np.testing.assert_allclose(s0.sum(axis=2), 1.0, rtol=1e-12)
+
+
+def test_encoder_mean_scores_from_hidden_closed_form():
+    """One head; every query reads hidden feature 0 (all ones), every key hidden feature 1 (= a_j)
+    into feature 0: all rows have logits a_j = ln(j+1), so every row-softmax - and their mean - is
+    (j+1)/sum.  With a key weight transposed the logits would not depend on j.  Then a [CLS] row
+    with key logit 0 in the all-keys domain adds 1 to every denominator."""
+    N, D = 5, 4
+    a = np.log(np.arange(1, N + 1))
+    x = np.zeros((1, 1, N, D))
+    x[0, 0, :, 0] = 1.0
+    x[0, 0, :, 1] = a
+    wq = np.zeros((D, D)); wq[0, 0] = 1.0
+    wk = np.zeros((D, D)); wk[0, 1] = 1.0
+    want = np.arange(1, N + 1) / np.arange(1, N + 1).sum()
+    got = vo.encoder_mean_scores_from_hidden(x, wq, wk, 1, D, 0, 0, scale=1.0)
+    np.testing.assert_allclose(got[0, 0], want, rtol=1e-12)
+    xc = np.concatenate([np.zeros((1, 1, 1, D)), x], axis=2)   # [CLS] row of zeros: key logit 0
+    got = vo.encoder_mean_scores_from_hidden(xc, wq, wk, 1, D, 1, 1, scale=1.0)
+    np.testing.assert_allclose(got[0, 0], np.arange(1, N + 1) / (np.arange(1, N + 1).sum() + 1.0),
+                               rtol=1e-12)
+    # patch-only domain with the same [CLS] row present: it takes no part
+    got = vo.encoder_mean_scores_from_hidden(xc, wq, wk, 1, D, 1, 0, scale=1.0)
+    np.testing.assert_allclose(got[0, 0], want, rtol=1e-12)
+
+
+def test_encoder_mean_scores_from_hidden_query_dependence():
+    """Two queries with different logit gains: the mean of two different softmax rows, by hand."""
+    D = 2
+    x = np.array([[[[1.0, 0.0], [2.0, 1.0]]]])          # two patch tokens
+    wq = np.array([[1.0, 0.0], [0.0, 0.0]])              # q_i = (x_i0, 0)
+    wk = np.array([[0.0, 1.0], [0.0, 0.0]])              # k_j = (x_j1, 0)
+    # logits l_ij = x_i0 * x_j1: row 0 = (0, 1), row 1 = (0, 2)
+    r0 = np.exp([0.0, 1.0]) / np.exp([0.0, 1.0]).sum()
+    r1 = np.exp([0.0, 2.0]) / np.exp([0.0, 2.0]).sum()
+    got = vo.encoder_mean_scores_from_hidden(x, wq, wk, 1, D, 0, 0, scale=1.0)
+    np.testing.assert_allclose(got[0, 0], (r0 + r1) / 2, rtol=1e-12)
