@@ -147,6 +147,21 @@ def test_encoder_exact_ties_large_grid():
     pu.check_encoder(shape, inp, ref, out, "ties-large")
 
 
+@pytest.mark.parametrize("win,keep_local,keep_global", [(4, 50, 301), (1, 0, 777)])
+def test_encoder_exact_ties_on_a_segment_split_over_workgroups(win, keep_local, keep_global):
+    """All scores tie on a segment of more than 4096 tokens: the local scan of every window
+    (a kernel of its own there) and the workgroup-wide global search must both fall back on the
+    token order; with one window the segment is cut into runs of 1024 tokens instead."""
+    shape = _enc(wl.F32, batch=1, n_segments=2, grid_h=72, grid_w=64, win_rows=win, win_cols=win,
+                 keep_global=keep_global, keep_local=keep_local, feat_dim=32, heads=2, head_dim=16)
+    inp = wl.encoder_inputs(shape, 12)
+    inp["q"][:] = 0.0
+    ref = vo.encoder_reduce(shape, inp["q"], inp["k"], inp["x"])
+    out = _run_encoder(shape, inp)
+    assert np.array_equal(pu.to_host(out["kept_idx"]), ref["kept"])
+    pu.check_encoder(shape, inp, ref, out, "ties-split")
+
+
 def test_encoder_runs_are_bit_reproducible():
     shape = SMALL_ENCODER["bf16-ragged"]
     inp = wl.encoder_inputs(shape, 3, 0.25)
