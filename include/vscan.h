@@ -258,7 +258,7 @@ int vscan_llm_prune_fused_ragged(const vscan_llm_desc *desc, const vscan_seq_met
  * states only (K and V of this layer do not exist yet; the caller computes them
  * for the tokens that are left).  With VSCAN_KEYS_ALL every query position
  * attends causally, to the keys up to and including its own position.  No positional rotation is applied to Q or K,
- * as in the equation.  bf16 only (VSCAN_ERR_UNSUPPORTED for fp32).
+ * as in the equation.  bf16 or fp32 (hidden states and weights in desc->dtype).
  *
  * desc        HOST; as for vscan_llm_prune.  `hidden` and `head_dim` must be
  *             multiples of 8.
@@ -291,9 +291,9 @@ int vscan_llm_prune_fused(const vscan_llm_desc *desc, void *hidden, const void *
  * softmax(Q K^T * scale), mean over heads (Eq. 1-2).  VSCAN_SCORE_MEAN_RECEIVED
  * (encoders without a [CLS] token, last sentence of "Global Scan"): Q and K of
  * every token are projected (fp32) and the mean attention each token receives
- * is computed as in vscan_encoder_reduce; head_dim <= 128 there.  bf16 only
- * (VSCAN_ERR_UNSUPPORTED otherwise); projection biases are not part of the
- * equations and not applied.
+ * is computed as in vscan_encoder_reduce; head_dim <= 128 there
+ * (VSCAN_ERR_UNSUPPORTED otherwise).  bf16 or fp32 (hidden states and weights in
+ * desc->dtype); projection biases are not part of the equations and not applied.
  *
  * desc          HOST; as for vscan_encoder_reduce; the hidden size of the layer
  *               is desc->feat_dim

@@ -383,7 +383,7 @@ def llm_prune_fused(shape, hidden, w_q, w_k_t, want_scores: bool = False, worksp
     need = llm_fused_workspace_size(desc)
     dev = hidden.device
     for t in (hidden, w_q, w_k_t):
-        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16
+        assert t.is_cuda and t.is_contiguous() and t.dtype == _torch_dtype(shape.dtype)
     B, S, So = shape.batch, shape.seq_len, shape.seq_out
     assert tuple(hidden.shape) == (B, S, shape.hidden)
     assert tuple(w_q.shape) == (shape.q_heads * shape.head_dim, shape.hidden)
@@ -433,7 +433,7 @@ def encoder_reduce_fused(shape, hidden, w_q, w_k_t, x, local=None, want_assign: 
     triples = [(hidden, w_q, w_k_t)] + ([tuple(local)] if local is not None else [])
     for h, a, b in triples:
         for t in (h, a, b):
-            assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16
+            assert t.is_cuda and t.is_contiguous() and t.dtype == _torch_dtype(shape.dtype)
         assert tuple(h.shape) == (B, shape.n_segments, shape.rows, D)
         assert tuple(a.shape) == (hd, D) and tuple(b.shape) == (D, hd)
     assert x.is_cuda and x.is_contiguous() and tuple(x.shape) == (B, T, D)

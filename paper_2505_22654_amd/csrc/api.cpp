@@ -147,24 +147,27 @@ struct FusedScratch {
 };
 
 int plan_fused_scratch(int64_t seqs, int S, int hidden, int q_heads, int kv_heads, int head_dim,
-                       int n_query, int nk, size_t base, FusedScratch *f) {
-    // 32-bit row offsets inside the kernels
+                       int n_query, int nk, int es, size_t base, FusedScratch *f) {
+    // 32-bit row offsets inside the kernels (es = bytes per element of hidden states and weights)
     const int64_t lim = (int64_t)1 << 32;
     const int64_t Dh = hidden, N = (int64_t)q_heads * head_dim, R = (int64_t)q_heads * n_query;
-    if (seqs * S * Dh * 2 >= lim || N * Dh * 2 >= lim || Dh * kv_heads * head_dim * 2 >= lim ||
-        seqs * n_query * N * 2 >= lim || seqs * R * Dh * 2 >= lim || seqs * R > (1 << 24) ||
+    if (seqs * S * Dh * es >= lim || N * Dh * es >= lim || Dh * kv_heads * head_dim * es >= lim ||
+        seqs * n_query * N * es >= lim || seqs * R * Dh * es >= lim || seqs * R > (1 << 24) ||
         R > 65535 || seqs > 65535)  // sequences and query rows index the softmax grid
         return VSCAN_ERR_UNSUPPORTED;
     const int M = (int)(seqs * n_query);
-    f->ks_q = fused_ksplit((int)N, M, 1, hidden);
-    f->ks_l = fused_ksplit(nk, (int)R, (int)seqs, hidden);
+    f->ks_q = fused_ksplit((int)N, M, 1, hidden, es);
+    f->ks_l = fused_ksplit(nk, (int)R, (int)seqs, hidden, es);
+    // q and the hidden-space query: three bf16 planes each for bf16 inputs, the fp32 values
+    // themselves for fp32 inputs
+    const size_t carried = es == 2 ? (size_t)kFusedQtPlanes * 2 : 4;
     size_t off = base;
     f->off_cq = off;
     off += align_up((size_t)f->ks_q * M * N * sizeof(float));
     f->off_qpl = off;
-    off += align_up((size_t)3 * M * N * 2);
+    off += align_up((size_t)M * N * (es == 2 ? 3 * 2 : 4));
     f->off_qtpl = off;
-    off += align_up((size_t)kFusedQtPlanes * seqs * R * Dh * 2);
+    off += align_up(carried * seqs * R * Dh);
     f->off_cl = off;
     off += align_up((size_t)f->ks_l * seqs * R * nk * sizeof(float));
     f->end = off;
@@ -192,14 +195,13 @@ int plan_fused(const vscan_llm_desc *d, FusedPlan *p) {
     if (d->hidden < 8 || d->hidden % 8) return VSCAN_ERR_SHAPE;
     if (d->in_place != 0 && d->in_place != 1) return VSCAN_ERR_SHAPE;
     if (d->keep < 0 || d->keep > d->vis_len) return VSCAN_ERR_BUDGET;
-    if (d->dtype != VSCAN_BF16) return VSCAN_ERR_UNSUPPORTED;
     p->k0 = d->softmax_domain == VSCAN_KEYS_ALL ? 0 : d->vis_start;
     p->nk = d->softmax_domain == VSCAN_KEYS_ALL ? d->seq_len : d->vis_len;
     p->S_out = d->seq_len - d->vis_len + d->keep;
     p->R = d->q_heads * d->n_query;
     if (llm_select_lds_bytes(d->vis_len) > kLdsBudget) return VSCAN_ERR_UNSUPPORTED;
     const int rc = plan_fused_scratch(d->batch, d->seq_len, d->hidden, d->q_heads, d->kv_heads,
-                                      d->head_dim, d->n_query, p->nk, 0, &p->f);
+                                      d->head_dim, d->n_query, p->nk, elem_bytes(d->dtype), 0, &p->f);
     if (rc != VSCAN_OK) return rc;
     p->off_part = p->f.end;
     p->bytes = p->off_part + align_up((size_t)d->batch * d->vis_len * sizeof(float));
@@ -220,20 +222,20 @@ struct EncoderFusedPlan {
 int plan_encoder_fused(const vscan_encoder_desc *d, int with_local, EncoderFusedPlan *p) {
     const int rc = plan_encoder(d, with_local, &p->e);
     if (rc != VSCAN_OK) return rc;
-    if (d->dtype != VSCAN_BF16) return VSCAN_ERR_UNSUPPORTED;
+    const int es = elem_bytes(d->dtype);
     if (d->score_mode == VSCAN_SCORE_MEAN_RECEIVED) {
         // Q and K are projected in fp32 and scored by the fp32 mean-attention kernels
         if (d->head_dim * 4 > 512) return VSCAN_ERR_UNSUPPORTED;
         const int64_t lim = (int64_t)1 << 32;  // 32-bit row offsets inside the projection
         const int64_t feat = (int64_t)d->heads * d->head_dim;
-        if ((int64_t)p->e.BC * p->e.S * d->feat_dim * 2 >= lim || feat * d->feat_dim * 2 >= lim ||
+        if ((int64_t)p->e.BC * p->e.S * d->feat_dim * es >= lim || feat * d->feat_dim * es >= lim ||
             (int64_t)p->e.BC * p->e.S >= ((int64_t)1 << 31) / 2)
             return VSCAN_ERR_UNSUPPORTED;
         p->k0 = p->nk = 0;
         p->f = FusedScratch{};
         size_t off = p->e.bytes;
         p->off_wk = off;
-        off += align_up((size_t)feat * d->feat_dim * 2);
+        off += align_up((size_t)feat * d->feat_dim * es);
         p->off_qf = off;
         off += align_up((size_t)p->e.BC * feat * p->e.S * sizeof(float));
         p->off_kf = off;
@@ -245,7 +247,7 @@ int plan_encoder_fused(const vscan_encoder_desc *d, int with_local, EncoderFused
     p->k0 = d->softmax_domain == VSCAN_KEYS_ALL ? 0 : 1;
     p->nk = d->softmax_domain == VSCAN_KEYS_ALL ? p->e.S : p->e.N;
     const int rc2 = plan_fused_scratch(p->e.BC, p->e.S, d->feat_dim, d->heads, d->heads,
-                                       d->head_dim, 1, p->nk, p->e.bytes, &p->f);
+                                       d->head_dim, 1, p->nk, es, p->e.bytes, &p->f);
     if (rc2 != VSCAN_OK) return rc2;
     p->bytes = p->f.end;
     return VSCAN_OK;
@@ -527,6 +529,7 @@ static int encoder_reduce_fused_impl(const vscan_encoder_desc *d, const void *hi
         sa.scale = resolve_scale(d->scale, d->head_dim);
         for (int pass = 0; pass < (with_local ? 2 : 1); ++pass) {
             ProjectArgs pa;
+            pa.is_bf16 = d->dtype == VSCAN_BF16;
             pa.hidden = pass ? hidden_local : hidden;
             pa.BC = p.e.BC;
             pa.S = p.e.S;
@@ -536,8 +539,9 @@ static int encoder_reduce_fused_impl(const vscan_encoder_desc *d, const void *hi
             pa.w = pass ? w_q_local : w_q;
             pa.out = reinterpret_cast<float *>(ws + p.off_qf);
             VSCAN_LAUNCH("fused_project", launch_fused_project(pa, s));
-            VSCAN_LAUNCH("fused_transpose", launch_transpose16(pass ? w_k_t_local : w_k_t, ws + p.off_wk,
-                                                              d->feat_dim, d->heads * d->head_dim, s));
+            VSCAN_LAUNCH("fused_transpose", launch_transpose(pass ? w_k_t_local : w_k_t, ws + p.off_wk,
+                                                            d->feat_dim, d->heads * d->head_dim,
+                                                            elem_bytes(d->dtype), s));
             pa.w = ws + p.off_wk;
             pa.out = reinterpret_cast<float *>(ws + p.off_kf);
             VSCAN_LAUNCH("fused_project", launch_fused_project(pa, s));
@@ -551,6 +555,7 @@ static int encoder_reduce_fused_impl(const vscan_encoder_desc *d, const void *hi
     }
     for (int pass = 0; pass < (with_local ? 2 : 1); ++pass) {
         FusedArgs fa;
+        fa.is_bf16 = d->dtype == VSCAN_BF16;
         fa.hidden = pass ? hidden_local : hidden;
         fa.w_q = pass ? w_q_local : w_q;
         fa.w_k_t = pass ? w_k_t_local : w_k_t;
@@ -749,6 +754,7 @@ static int run_llm_fused(const vscan_llm_desc *d, const FusedPlan &p, const SeqM
     unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
 
     FusedArgs fa;
+    fa.is_bf16 = d->dtype == VSCAN_BF16;
     fa.hidden = hidden;
     fa.w_q = w_q;
     fa.w_k_t = w_k_t;
@@ -797,7 +803,7 @@ static int run_llm_fused(const vscan_llm_desc *d, const FusedPlan &p, const SeqM
     ca.vis_start = d->vis_start;
     ca.V = d->vis_len;
     ca.keep = d->keep;
-    ca.elem_bytes = 2;
+    ca.elem_bytes = elem_bytes(d->dtype);
     ca.in_place = d->in_place;
     ca.out_rows = out_rows;
     ca.max_out_rows = max_out_rows;

@@ -60,12 +60,14 @@ __device__ __forceinline__ void emit_partial(const GemmDims &d, int ks, int z, i
 // s_base/p_base: wave-uniform base of batch entry z (and plane pl); s_off/p_off: byte offset of a
 // row's first contraction element from that base.
 
+template <typename T>
 struct ProbQ {
+    using Elem = T;
     static constexpr int PL = 1;
     static constexpr bool kStreamS = false;
     GemmDims d;
     const char *hidden, *w_q;
-    int Tq, S, q_row0, row_bytes;  // row_bytes = Dh * 2
+    int Tq, S, q_row0, row_bytes;  // row_bytes = Dh * sizeof(T)
     const SeqMeta *meta;           // ragged batch: the queries are a sequence's own last rows
     __device__ int rows_s(int) const { return d.rows_s; }
     __device__ const char *s_base(int) const { return w_q; }
@@ -81,46 +83,57 @@ struct ProbQ {
     }
 };
 
+// q arrives as bf16 planes (bf16 inputs: three planes carry all 24 bits of the fp32 value) or as
+// the fp32 values themselves (fp32 inputs: one "plane"); the result leaves the same way.
+template <typename T>
 struct ProbQt {
-    static constexpr int PL = 3;
+    using Elem = T;
+    static constexpr int ES = (int)sizeof(T);
+    static constexpr int PL = ES == 2 ? 3 : 1;
     static constexpr bool kStreamS = false;
     GemmDims d;
     const char *q_planes, *w_k_t;
     int Tq, group, dh, Hq, Hkv;
-    int64_t plane_bytes;  // B*Tq*Hq*dh*2
+    int64_t plane_bytes;  // B*Tq*Hq*dh*ES
     __device__ int rows_s(int) const { return d.rows_s; }
-    __device__ const char *s_base(int g) const { return w_k_t + (int64_t)g * dh * 2; }
-    __device__ uint32_t s_off(int c) const { return (uint32_t)c * (uint32_t)(Hkv * dh * 2); }
+    __device__ const char *s_base(int g) const { return w_k_t + (int64_t)g * dh * ES; }
+    __device__ uint32_t s_off(int c) const { return (uint32_t)c * (uint32_t)(Hkv * dh * ES); }
     __device__ const char *p_base(int g, int pl) const {
-        return q_planes + pl * plane_bytes + (int64_t)g * group * dh * 2;
+        return q_planes + pl * plane_bytes + (int64_t)g * group * dh * ES;
     }
     __device__ uint32_t p_off(int m) const {  // m = (b*group + hh)*Tq + t
         const int t = m % Tq, bh = m / Tq;
         const int hh = bh % group, b = bh / group;
-        return (uint32_t)((b * Tq + t) * Hq * dh + hh * dh) * 2u;
+        return (uint32_t)((b * Tq + t) * Hq * dh + hh * dh) * (uint32_t)ES;
     }
-    // the result goes out as bf16 planes right away (this contraction is never split)
-    uint16_t *qt_planes;      // [kFusedQtPlanes][Hkv][rows_p][rows_s]
+    // the result goes out in its final form right away (this contraction is never split)
+    uint16_t *qt_planes;      // bf16: [kFusedQtPlanes][Hkv][rows_p][rows_s]; fp32: [Hkv][rows_p][rows_s] floats
     int64_t qt_plane_elems;   // Hkv*rows_p*rows_s
     __device__ void emit(int, int g, int p, int s_row, float v) const {
-        uint16_t *o = qt_planes + ((int64_t)g * d.rows_p + p) * d.rows_s + s_row;
+        const int64_t at = ((int64_t)g * d.rows_p + p) * d.rows_s + s_row;
+        if constexpr (ES == 4) {
+            reinterpret_cast<float *>(qt_planes)[at] = v;
+        } else {
+            uint16_t *o = qt_planes + at;
 #pragma unroll
-        for (int pl = 0; pl < kFusedQtPlanes; ++pl) {
-            const uint32_t bits = f32_to_bf16_rne(v);
-            o[pl * qt_plane_elems] = (uint16_t)bits;
-            v -= __uint_as_float(bits << 16);
+            for (int pl = 0; pl < kFusedQtPlanes; ++pl) {
+                const uint32_t bits = f32_to_bf16_rne(v);
+                o[pl * qt_plane_elems] = (uint16_t)bits;
+                v -= __uint_as_float(bits << 16);
+            }
         }
     }
 };
 
-template <int PLANES, bool STREAM>
+template <typename T, bool STREAM>
 struct ProbLogit {
-    static constexpr int PL = PLANES;
+    using Elem = T;
+    static constexpr int PL = sizeof(T) == 2 ? kFusedQtPlanes : 1;
     static constexpr bool kStreamS = STREAM;
     GemmDims d;
     const char *hidden, *qt_planes;
     int Tq, group, S, k0, row_bytes, Mg;  // Mg = B*group*Tq rows of qt per kv head
-    int64_t plane_bytes;                  // Hkv*Mg*Dh*2
+    int64_t plane_bytes;                  // Hkv*Mg*Dh*sizeof(T)
     const SeqMeta *meta;                  // ragged batch: key domain of sequence b from meta[b]
     int domain_all;
     __device__ int rows_s(int b) const {
@@ -146,7 +159,9 @@ struct ProbLogit {
 
 // Projection of every row of `hidden` with a weight matrix whose rows are output features; the
 // result goes out in fp32 as [bc][head][token][e] (never split along the contraction axis).
+template <typename T>
 struct ProbProject {
+    using Elem = T;
     static constexpr int PL = 1;
     static constexpr bool kStreamS = false;
     GemmDims d;
@@ -272,7 +287,7 @@ __global__ __launch_bounds__(64 * WS * WP) void nt_gemm_kernel(Prob pr) {
                     const uint4 a = *reinterpret_cast<const uint4 *>(
                         lds_p + (pl * TP + (wp * FP + i) * 32 + (lane & 31)) * kRowPitch + colb);
 #pragma unroll
-                    for (int j = 0; j < FS; ++j) mma32_chunk<bf16_t>(acc[i][j], a, b[j]);
+                    for (int j = 0; j < FS; ++j) mma32_chunk<typename Prob::Elem>(acc[i][j], a, b[j]);
                 }
         }
         __syncthreads();
@@ -472,11 +487,11 @@ __global__ __launch_bounds__(256) void fused_colsum_kernel(const float *__restri
             ((red[0][lane_id()] + red[1][lane_id()]) + red[2][lane_id()]) + red[3][lane_id()];
 }
 
-GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
+GemmDims dims(int rows_s, int rows_p, int k_elems, int es, int ksplit, float *c) {
     GemmDims d;
     d.rows_s = rows_s;
     d.rows_p = rows_p;
-    d.k_bytes = k_elems * 2;
+    d.k_bytes = k_elems * es;
     d.ksplit = ksplit;
     d.Z = d.s_tiles = d.p_tiles = 1;
     d.affine = 0;
@@ -486,40 +501,60 @@ GemmDims dims(int rows_s, int rows_p, int k_elems, int ksplit, float *c) {
 
 }  // namespace
 
-int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems) {
+int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems, int elem_bytes) {
     const TileShape t = tile_shape(rows_p, rows_s, Z);
     const int64_t tiles = std::max<int64_t>(
         1, (int64_t)((rows_s + t.ts - 1) / t.ts) * ((rows_p + t.tp - 1) / t.tp) * Z);  // empty batch: 1
-    const int nchunks = (k_elems * 2 + t.ch - 1) / t.ch;
+    const int nchunks = (k_elems * elem_bytes + t.ch - 1) / t.ch;
     int ks = (int)((kTargetWorkgroups + tiles - 1) / tiles);
     ks = max(1, min(ks, min(16, nchunks / 2)));
     return ks;
 }
 
-hipError_t launch_fused_q(const FusedArgs &a, hipStream_t s) {
-    ProbQ pr;
-    pr.d = dims(a.Hq * a.dh, a.B * a.Tq, a.Dh, a.ks_q, a.c_q);
+template <typename T>
+static hipError_t fused_q_t(const FusedArgs &a, hipStream_t s) {
+    ProbQ<T> pr;
+    pr.d = dims(a.Hq * a.dh, a.B * a.Tq, a.Dh, (int)sizeof(T), a.ks_q, a.c_q);
     pr.hidden = reinterpret_cast<const char *>(a.hidden);
     pr.w_q = reinterpret_cast<const char *>(a.w_q);
     pr.Tq = a.Tq;
     pr.S = a.S;
     pr.q_row0 = a.q_row0;
     pr.meta = a.meta;
-    pr.row_bytes = a.Dh * 2;
+    pr.row_bytes = a.Dh * (int)sizeof(T);
     return launch_gemm(pr, 1, s);
+}
+hipError_t launch_fused_q(const FusedArgs &a, hipStream_t s) {
+    return a.is_bf16 ? fused_q_t<bf16_t>(a, s) : fused_q_t<float>(a, s);
+}
+
+// fp32 inputs: q stays in fp32; the partial sums of the split contraction axis are added in
+// fixed order
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float *__restrict__ c, int ksplit,
+                                                           int64_t n, float *__restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float v = 0.f;
+    for (int ks = 0; ks < ksplit; ++ks) v += c[ks * n + i];
+    out[i] = v;
 }
 
 hipError_t launch_fused_split_q(const FusedArgs &a, hipStream_t s) {
     const int64_t n = (int64_t)a.B * a.Tq * a.Hq * a.dh;
-    hipLaunchKernelGGL(split_planes_kernel<3>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                       a.c_q, a.ks_q, n, a.q_planes);
+    if (a.is_bf16)
+        hipLaunchKernelGGL(split_planes_kernel<3>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                           a.c_q, a.ks_q, n, a.q_planes);
+    else
+        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                           a.c_q, a.ks_q, n, reinterpret_cast<float *>(a.q_planes));
     return hipGetLastError();
 }
 
-hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s) {
+template <typename T>
+static hipError_t fused_qt_t(const FusedArgs &a, hipStream_t s) {
     const int group = a.Hq / a.Hkv;
-    ProbQt pr;
-    pr.d = dims(a.Dh, a.B * group * a.Tq, a.dh, 1, nullptr);
+    ProbQt<T> pr;
+    pr.d = dims(a.Dh, a.B * group * a.Tq, a.dh, (int)sizeof(T), 1, nullptr);
     pr.q_planes = reinterpret_cast<const char *>(a.q_planes);
     pr.w_k_t = reinterpret_cast<const char *>(a.w_k_t);
     pr.Tq = a.Tq;
@@ -527,10 +562,13 @@ hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s) {
     pr.dh = a.dh;
     pr.Hq = a.Hq;
     pr.Hkv = a.Hkv;
-    pr.plane_bytes = (int64_t)a.B * a.Tq * a.Hq * a.dh * 2;
+    pr.plane_bytes = (int64_t)a.B * a.Tq * a.Hq * a.dh * (int64_t)sizeof(T);
     pr.qt_planes = a.qt_planes;
     pr.qt_plane_elems = (int64_t)a.B * a.Hq * a.Tq * a.Dh;
     return launch_gemm(pr, a.Hkv, s);
+}
+hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s) {
+    return a.is_bf16 ? fused_qt_t<bf16_t>(a, s) : fused_qt_t<float>(a, s);
 }
 
 // Hidden states beyond this size cannot stay in the last-level cache between this pass and
@@ -539,28 +577,29 @@ hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s) {
 // cached.
 constexpr int64_t kStreamHiddenBytes = (int64_t)128 << 20;
 
-template <bool STREAM>
+template <typename T, bool STREAM>
 hipError_t launch_logits(const FusedArgs &a, hipStream_t s) {
     const int group = a.Hq / a.Hkv;
-    ProbLogit<kFusedQtPlanes, STREAM> pr;
-    pr.d = dims(a.nk, a.Hq * a.Tq, a.Dh, a.ks_l, a.c_l);
+    ProbLogit<T, STREAM> pr;
+    pr.d = dims(a.nk, a.Hq * a.Tq, a.Dh, (int)sizeof(T), a.ks_l, a.c_l);
     pr.hidden = reinterpret_cast<const char *>(a.hidden);
     pr.qt_planes = reinterpret_cast<const char *>(a.qt_planes);
     pr.Tq = a.Tq;
     pr.group = group;
     pr.S = a.S;
     pr.k0 = a.k0;
-    pr.row_bytes = a.Dh * 2;
+    pr.row_bytes = a.Dh * (int)sizeof(T);
     pr.Mg = a.B * group * a.Tq;
-    pr.plane_bytes = (int64_t)a.Hkv * pr.Mg * a.Dh * 2;
+    pr.plane_bytes = (int64_t)a.Hkv * pr.Mg * a.Dh * (int64_t)sizeof(T);
     pr.meta = a.meta;
     pr.domain_all = a.causal;
     return launch_gemm(pr, a.B, s);
 }
 
 hipError_t launch_fused_logits(const FusedArgs &a, hipStream_t s) {
-    return (int64_t)a.B * a.S * a.Dh * 2 > kStreamHiddenBytes ? launch_logits<true>(a, s)
-                                                             : launch_logits<false>(a, s);
+    const bool stream = (int64_t)a.B * a.S * a.Dh * (a.is_bf16 ? 2 : 4) > kStreamHiddenBytes;
+    if (a.is_bf16) return stream ? launch_logits<bf16_t, true>(a, s) : launch_logits<bf16_t, false>(a, s);
+    return stream ? launch_logits<float, true>(a, s) : launch_logits<float, false>(a, s);
 }
 
 hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
@@ -585,11 +624,11 @@ hipError_t launch_fused_softmax(const FusedArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// 64 x 64 tiles of 16-bit elements through LDS (pitch 65: conflict-free both ways)
-__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t *__restrict__ in,
-                                                          uint16_t *__restrict__ out, int rows,
-                                                          int cols) {
-    __shared__ uint16_t tile[64][65];
+// 64 x 64 tiles of 16- or 32-bit elements through LDS (pitch 65: conflict-free both ways)
+template <typename U>
+__global__ __launch_bounds__(256) void transpose_kernel(const U *__restrict__ in, U *__restrict__ out,
+                                                        int rows, int cols) {
+    __shared__ U tile[64][65];
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     for (int i = threadIdx.x; i < 64 * 64; i += 256) {
         const int r = i >> 6, c = i & 63;
@@ -602,23 +641,33 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t *__rest
     }
 }
 
-hipError_t launch_transpose16(const void *in, void *out, int rows, int cols, hipStream_t s) {
-    hipLaunchKernelGGL(transpose16_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, s,
-                       (const uint16_t *)in, (uint16_t *)out, rows, cols);
+hipError_t launch_transpose(const void *in, void *out, int rows, int cols, int elem_bytes,
+                            hipStream_t s) {
+    const dim3 grid((cols + 63) / 64, (rows + 63) / 64);
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t *)in,
+                           (uint16_t *)out, rows, cols);
+    else
+        hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s, (const uint32_t *)in,
+                           (uint32_t *)out, rows, cols);
     return hipGetLastError();
 }
 
-hipError_t launch_fused_project(const ProjectArgs &a, hipStream_t s) {
-    ProbProject pr;
-    pr.d = dims(a.H * a.dh, a.BC * a.S, a.Dh, 1, nullptr);
+template <typename T>
+static hipError_t fused_project_t(const ProjectArgs &a, hipStream_t s) {
+    ProbProject<T> pr;
+    pr.d = dims(a.H * a.dh, a.BC * a.S, a.Dh, (int)sizeof(T), 1, nullptr);
     pr.hidden = reinterpret_cast<const char *>(a.hidden);
     pr.w = reinterpret_cast<const char *>(a.w);
     pr.S = a.S;
     pr.H = a.H;
     pr.dh = a.dh;
-    pr.row_bytes = a.Dh * 2;
+    pr.row_bytes = a.Dh * (int)sizeof(T);
     pr.out = a.out;
     return launch_gemm(pr, 1, s);
+}
+hipError_t launch_fused_project(const ProjectArgs &a, hipStream_t s) {
+    return a.is_bf16 ? fused_project_t<bf16_t>(a, s) : fused_project_t<float>(a, s);
 }
 
 hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s) {

@@ -1,5 +1,5 @@
 // Host-side launch interface of the score chain that starts from hidden states and projection
-// weights (Eq. 1 / Eq. 5 as written), bf16 only.  Every launcher enqueues on the given stream
+// weights (Eq. 1 / Eq. 5 as written), bf16 or fp32 inputs.  Every launcher enqueues on the given stream
 // and returns hipGetLastError().
 #pragma once
 #include "launch.hpp"
@@ -8,12 +8,14 @@ namespace vscan {
 
 constexpr int kFusedQtPlanes = 3;  // bf16 planes carrying the hidden-space query (all 24 bits)
 struct FusedArgs {
+    int is_bf16 = 1;           // element type of hidden, w_q, w_k_t (else fp32)
     const void *hidden;        // [B, S, Dh]; visual tokens are rows vis_start .. vis_start+V
     const void *w_q;           // [Hq*dh, Dh]   rows = output features
     const void *w_k_t;         // [Dh, Hkv*dh]  rows = input features
     float *c_q;                // [ks_q][B*Tq][Hq*dh] partial sums of q
-    uint16_t *q_planes;        // [3][B*Tq][Hq*dh] bf16
-    uint16_t *qt_planes;       // [kFusedQtPlanes][Hkv][B*(Hq/Hkv)*Tq][Dh] bf16
+    uint16_t *q_planes;        // bf16 inputs: [3][B*Tq][Hq*dh] bf16; fp32 inputs: [B*Tq][Hq*dh] floats
+    uint16_t *qt_planes;       // bf16 inputs: [kFusedQtPlanes][Hkv][B*(Hq/Hkv)*Tq][Dh] bf16; fp32
+                               // inputs: [Hkv][B*(Hq/Hkv)*Tq][Dh] floats
     float *c_l;                // [ks_l][B][Hq*Tq][nk] partial sums of the unscaled logits; the
                                // first slot becomes the softmax weights
     float *part;               // [B][V] sums over the query rows
@@ -28,7 +30,7 @@ struct FusedArgs {
     float scale;
 };
 // shares of the contraction axis for a contraction of Z problems of rows_s x rows_p outputs
-int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems);
+int fused_ksplit(int rows_s, int rows_p, int Z, int k_elems, int elem_bytes);
 hipError_t launch_fused_q(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_split_q(const FusedArgs &a, hipStream_t s);
 hipError_t launch_fused_qt(const FusedArgs &a, hipStream_t s);
@@ -42,13 +44,15 @@ hipError_t launch_fused_colsum(const FusedArgs &a, hipStream_t s);
 // on the result.  `w` has its rows along the output features; W_K arrives the other way round
 // and is transposed first.
 struct ProjectArgs {
-    const void *hidden;   // [BC, S, Dh] bf16
-    const void *w;        // [H*dh, Dh] bf16
+    int is_bf16 = 1;      // element type of hidden and w (else fp32)
+    const void *hidden;   // [BC, S, Dh]
+    const void *w;        // [H*dh, Dh]
     float *out;           // [BC, H, S, dh]
     int BC, S, Dh, H, dh;
 };
 hipError_t launch_fused_project(const ProjectArgs &a, hipStream_t s);
-// out[c][r] = in[r][c], 16-bit elements; rows and cols are multiples of 8
-hipError_t launch_transpose16(const void *in, void *out, int rows, int cols, hipStream_t s);
+// out[c][r] = in[r][c], elements of 2 or 4 bytes
+hipError_t launch_transpose(const void *in, void *out, int rows, int cols, int elem_bytes,
+                            hipStream_t s);
 
 }  // namespace vscan

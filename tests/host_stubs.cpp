@@ -148,12 +148,12 @@ hipError_t launch_compact(const CompactArgs &, hipStream_t) {
     return hipSuccess;
 }
 
-int fused_ksplit(int, int, int, int k_elems) { return k_elems >= 512 ? 2 : 1; }
+int fused_ksplit(int, int, int, int k_elems, int) { return k_elems >= 512 ? 2 : 1; }
 static hipError_t check_fused(const char *who, const FusedArgs &a) {
     ++g_calls;
     const size_t M = (size_t)a.B * a.Tq, N = (size_t)a.Hq * a.dh, R = (size_t)a.Hq * a.Tq;
-    const size_t cq = (size_t)a.ks_q * M * N * 4, qp = 3 * M * N * 2;
-    const size_t qt = (size_t)kFusedQtPlanes * a.B * R * a.Dh * 2;
+    const size_t cq = (size_t)a.ks_q * M * N * 4, qp = a.is_bf16 ? 3 * M * N * 2 : M * N * 4;
+    const size_t qt = (a.is_bf16 ? (size_t)kFusedQtPlanes * 2 : 4) * a.B * R * a.Dh;
     const size_t cl = (size_t)a.ks_l * a.B * R * a.nk * 4;
     region(who, "c_q", a.c_q, cq);
     region(who, "q_planes", a.q_planes, qp);
@@ -169,9 +169,9 @@ hipError_t launch_fused_project(const ProjectArgs &a, hipStream_t) {
     region("fused_project", "out", a.out, (size_t)a.BC * a.H * a.S * a.dh * 4);
     return hipSuccess;
 }
-hipError_t launch_transpose16(const void *, void *out, int rows, int cols, hipStream_t) {
+hipError_t launch_transpose(const void *, void *out, int rows, int cols, int es, hipStream_t) {
     ++g_calls;
-    region("fused_transpose", "out", out, (size_t)rows * cols * 2);
+    region("fused_transpose", "out", out, (size_t)rows * cols * es);
     return hipSuccess;
 }
 hipError_t launch_fused_q(const FusedArgs &a, hipStream_t) { return check_fused("fused_q", a); }

@@ -93,18 +93,18 @@ for idx in (1, 2, 3, 4, 5, 6):
             assert L.vscan_encoder_reduce(ctypes.byref(d), FAKE, FAKE, loc, loc, FAKE, FAKE, FAKE, None,
                                           None, WS + 8, n + 8, None) == vb.VSCAN_ERR_ALIGN
             bad += 2
-        if shape.dtype == wl.BF16:       # [CLS] scoring and mean attention from hidden states
-            for with_local in (0, 1):
-                rc, n = size(L.vscan_encoder_fused_workspace_size, d, with_local)
-                if rc == vb.VSCAN_ERR_UNSUPPORTED:
-                    continue
-                assert rc == 0
-                L.vscan_test_window(WS, n)
-                loc = FAKE if with_local else None
-                rc = L.vscan_encoder_reduce_fused(ctypes.byref(d), FAKE, FAKE, FAKE, loc, loc, loc, FAKE,
-                                                  FAKE, FAKE, FAKE, FAKE, WS, n, None)
-                assert rc == 0, (idx, rc)
-                ok += 1
+        # [CLS] scoring and mean attention from hidden states, both element types
+        for with_local in (0, 1):
+            rc, n = size(L.vscan_encoder_fused_workspace_size, d, with_local)
+            if rc == vb.VSCAN_ERR_UNSUPPORTED:
+                continue
+            assert rc == 0
+            L.vscan_test_window(WS, n)
+            loc = FAKE if with_local else None
+            rc = L.vscan_encoder_reduce_fused(ctypes.byref(d), FAKE, FAKE, FAKE, loc, loc, loc, FAKE,
+                                              FAKE, FAKE, FAKE, FAKE, WS, n, None)
+            assert rc == 0, (idx, rc)
+            ok += 1
     for shape in ((l, dataclasses.replace(l, in_place=1), dataclasses.replace(l, softmax_domain=1),
                    dataclasses.replace(l, keep=0), dataclasses.replace(l, batch=0)) if l is not None else ()):
         d = vb.llm_desc(shape)
@@ -123,18 +123,18 @@ for idx in (1, 2, 3, 4, 5, 6):
                                       FAKE, FAKE, *outs, FAKE, WS, n, None)
         assert rc == 0, (idx, rc)
         ok += 1
-        if shape.dtype == wl.BF16:
-            rc, n = size(L.vscan_llm_fused_workspace_size, d)
-            if rc == 0:
-                L.vscan_test_window(WS, n)
-                ho = None if shape.in_place else FAKE
-                assert L.vscan_llm_prune_fused(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, ho, FAKE, WS, n,
-                                               None) == 0
-                assert L.vscan_llm_prune_fused_ragged(ctypes.byref(d), ctypes.addressof(meta), FAKE, FAKE,
-                                                      FAKE, FAKE, FAKE, ho, FAKE, WS, n, None) == 0
-                ok += 2
-            else:
-                assert rc == vb.VSCAN_ERR_UNSUPPORTED, rc
+        # both element types
+        rc, n = size(L.vscan_llm_fused_workspace_size, d)
+        if rc == 0:
+            L.vscan_test_window(WS, n)
+            ho = None if shape.in_place else FAKE
+            assert L.vscan_llm_prune_fused(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, ho, FAKE, WS, n,
+                                           None) == 0
+            assert L.vscan_llm_prune_fused_ragged(ctypes.byref(d), ctypes.addressof(meta), FAKE, FAKE,
+                                                  FAKE, FAKE, FAKE, ho, FAKE, WS, n, None) == 0
+            ok += 2
+        else:
+            assert rc == vb.VSCAN_ERR_UNSUPPORTED, rc
 
 # descriptors that must be refused: nothing may reach a launcher
 calls0 = ctypes.c_int(0); regions = ctypes.c_int(0); viol = ctypes.c_int(0)

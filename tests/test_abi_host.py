@@ -224,14 +224,15 @@ def _fused_enc_call(desc, hidden=FAKE, wq=FAKE, wkt=FAKE, local=(None, None, Non
 
 
 def test_fused_entry_points_validate_on_the_host():
-    """Scoring from hidden states: bf16 and [CLS] only; the usual pointer, alignment and
-    workspace checks; nothing is launched by any of these calls."""
+    """Scoring from hidden states: the usual pointer, alignment and workspace checks; every
+    call here fails one of them (or has an empty batch), so nothing is launched."""
     bf = lambda sh: dataclasses.replace(sh, dtype=wl.BF16)
     ldesc = vb.llm_desc(bf(_llm_shape()))
     need = vb.llm_fused_workspace_size(ldesc)
     assert need > vb.llm_workspace_size(ldesc)
     assert _fused_llm_call(None) == vb.VSCAN_ERR_NULL
-    assert _fused_llm_call(vb.llm_desc(_llm_shape())) == vb.VSCAN_ERR_UNSUPPORTED     # fp32
+    assert vb.llm_fused_workspace_size(vb.llm_desc(_llm_shape())) > 0                  # fp32 is served
+    assert _fused_llm_call(vb.llm_desc(_llm_shape()), ws_bytes=16) == vb.VSCAN_ERR_WORKSPACE
     assert _fused_llm_call(vb.llm_desc(bf(_llm_shape(head_dim=100)))) == vb.VSCAN_ERR_SHAPE
     assert _fused_llm_call(vb.llm_desc(bf(_llm_shape(keep=65)))) == vb.VSCAN_ERR_BUDGET
     assert _fused_llm_call(ldesc, wq=None) == vb.VSCAN_ERR_NULL
@@ -248,7 +249,8 @@ def test_fused_entry_points_validate_on_the_host():
     eneed = vb.encoder_fused_workspace_size(edesc)
     assert eneed > vb.encoder_workspace_size(edesc)
     assert vb.encoder_fused_workspace_size(edesc, True) > eneed
-    assert _fused_enc_call(vb.encoder_desc(_enc_shape())) == vb.VSCAN_ERR_UNSUPPORTED   # fp32
+    assert vb.encoder_fused_workspace_size(vb.encoder_desc(_enc_shape())) > 0            # fp32 is served
+    assert _fused_enc_call(vb.encoder_desc(_enc_shape()), ws_bytes=16) == vb.VSCAN_ERR_WORKSPACE
     # mean-attention scoring is served (Q and K projected in fp32): larger scratch, and heads
     # wider than 512 bytes in fp32 are refused
     mean = bf(_enc_shape(has_cls=0, score_mode=1))

@@ -15,9 +15,9 @@ pytestmark = pytest.mark.gpu
 
 def _run(shape, inp):
     import torch
-    h = pu.to_device(inp["hidden"], wl.BF16)
-    wq = pu.to_device(inp["w_q"], wl.BF16)
-    wkt = pu.to_device(np.ascontiguousarray(inp["w_k"].T), wl.BF16)
+    h = pu.to_device(inp["hidden"], shape.dtype)
+    wq = pu.to_device(inp["w_q"], shape.dtype)
+    wkt = pu.to_device(np.ascontiguousarray(inp["w_k"].T), shape.dtype)
     out = vb.llm_prune_fused(shape, h, wq, wkt, want_scores=True)
     torch.cuda.synchronize()
     return out
@@ -76,12 +76,28 @@ def test_fused_small(name):
     print(name, pu.check_fused(shape, ref, out, name, hidden=inp["hidden"]))
 
 
-def test_fused_fp32_is_rejected():
-    import torch
-    shape = _shape(dtype=wl.F32)
-    with pytest.raises(vb.VscanError) as e:
-        vb.llm_fused_workspace_size(vb.llm_desc(shape))
-    assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
+FUSED_F32 = {
+    # fp32 hidden states and weights: the same chain on fp32 matrix instructions, q and the
+    # hidden-space query carried as fp32 values instead of bf16 planes
+    "f32": _shape(dtype=wl.F32),
+    "f32-ragged-tiles": _shape(dtype=wl.F32, batch=3, vis_len=300, hidden=520, keep=100),
+    "f32-in-place": _shape(dtype=wl.F32, in_place=1),
+    "f32-all-keys-queries": _shape(dtype=wl.F32, softmax_domain=1, n_query=3, q_heads=8, kv_heads=4,
+                                   text=11),
+    "f32-many-rows": _shape(dtype=wl.F32, q_heads=16, kv_heads=4, n_query=9, head_dim=40, hidden=320,
+                            vis_len=200, text=12, keep=60),
+    "f32-split-axis": _shape(dtype=wl.F32, batch=1, hidden=2048, q_heads=4, kv_heads=2, head_dim=128,
+                             vis_len=70, keep=11),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FUSED_F32))
+def test_fused_fp32(name):
+    shape = FUSED_F32[name]
+    inp, ref, info = pu.screened_fused_case(shape, 9300 + sorted(FUSED_F32).index(name) * 29)
+    print("case", name, info, flush=True)
+    out = _run(shape, inp)
+    print(name, pu.check_fused(shape, ref, out, name, hidden=inp["hidden"]))
 
 
 def test_fused_agrees_with_projected_path():
@@ -235,7 +251,7 @@ def test_fused_ragged_matches_uniform():
 
 def _run_encoder(shape, inp, loc=None):
     import torch
-    dev = lambda a: pu.to_device(a, wl.BF16)
+    dev = lambda a: pu.to_device(a, shape.dtype)
     triple = lambda d: (dev(d["hidden"]), dev(d["w_q"]), dev(np.ascontiguousarray(d["w_k"].T)))
     h, wq, wkt = triple(inp)
     out = vb.encoder_reduce_fused(shape, h, wq, wkt, dev(inp["x"]),
@@ -283,11 +299,25 @@ def test_fused_encoder_local_scan_from_shallow_layer():
     print(pu.check_encoder(shape, inp, ref, out, "fused encoder, shallow-layer local scan"))
 
 
-def test_fused_encoder_rejects_fp32_and_wide_mean_heads():
-    for shape in (_enc(dtype=wl.F32), _enc(has_cls=0, score_mode=1, head_dim=136)):
-        with pytest.raises(vb.VscanError) as e:
-            vb.encoder_fused_workspace_size(vb.encoder_desc(shape))
-        assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
+def test_fused_encoder_rejects_wide_mean_heads():
+    with pytest.raises(vb.VscanError) as e:
+        vb.encoder_fused_workspace_size(vb.encoder_desc(_enc(has_cls=0, score_mode=1, head_dim=136)))
+    assert e.value.status == vb.VSCAN_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("mode", ["cls", "cls-all-keys", "mean", "mean-with-cls"])
+def test_fused_encoder_fp32(mode):
+    shape = {"cls": _enc(dtype=wl.F32),
+             "cls-all-keys": _enc(dtype=wl.F32, softmax_domain=1, batch=3, n_segments=2, grid_h=13,
+                                  grid_w=11, heads=3, head_dim=40, feat_dim=200, win_rows=3, win_cols=2,
+                                  keep_global=17, keep_local=13),
+             "mean": _enc(dtype=wl.F32, has_cls=0, score_mode=1, grid_h=11, grid_w=13, heads=3,
+                          head_dim=24, feat_dim=96),
+             "mean-with-cls": _enc(dtype=wl.F32, has_cls=1, score_mode=1, softmax_domain=1)}[mode]
+    inp, _, ref, info = pu.screened_encoder_fused_case(shape, 9990, max_tries=6)
+    print("case", mode, info, flush=True)
+    out = _run_encoder(shape, inp)
+    print(mode, pu.check_encoder(shape, inp, ref, out, "fused encoder fp32 " + mode))
 
 
 FUSED_ENCODER_MEAN = {

@@ -21,7 +21,7 @@ def _sync():
 def _encoder_shape(r, fused=False):
     mean = r.random() < 0.3      # the entry points that score from hidden states take both modes
     has_cls = 1 if not mean else int(r.integers(0, 2))
-    dtype = wl.BF16 if fused or r.random() < 0.6 else wl.F32
+    dtype = wl.BF16 if r.random() < 0.6 else wl.F32    # every entry point takes both
     gh, gw = int(r.integers(3, 19)), int(r.integers(3, 19))
     wr, wc = int(r.integers(1, min(gh, 4) + 1)), int(r.integers(1, min(gw, 4) + 1))
     n, w = gh * gw, wr * wc
@@ -44,7 +44,7 @@ def _llm_shape(r, fused=False):
     tq = int(r.integers(1, 4))
     vis = int(r.integers(1, 400))
     return wl.LlmShape(
-        dtype=wl.BF16 if fused or r.random() < 0.6 else wl.F32, batch=int(r.integers(1, 6)),
+        dtype=wl.BF16 if r.random() < 0.6 else wl.F32, batch=int(r.integers(1, 6)),
         prefix=int(r.integers(0, 10)), vis_len=vis, text=tq + int(r.integers(0, 20)), n_query=tq,
         q_heads=kv * group, kv_heads=kv, head_dim=8 * int(r.integers(1, 17)),
         hidden=8 * int(r.integers(1, 34)), keep=int(r.integers(0, vis + 1)),
@@ -90,8 +90,8 @@ def test_random_llm_shapes():
 def test_random_fused_llm_shapes():
     def run(shape, case):
         inp = case[0]
-        h, wq = pu.to_device(inp["hidden"], wl.BF16), pu.to_device(inp["w_q"], wl.BF16)
-        wkt = pu.to_device(np.ascontiguousarray(inp["w_k"].T), wl.BF16)
+        h, wq = pu.to_device(inp["hidden"], shape.dtype), pu.to_device(inp["w_q"], shape.dtype)
+        wkt = pu.to_device(np.ascontiguousarray(inp["w_k"].T), shape.dtype)
         out = vb.llm_prune_fused(shape, h, wq, wkt, want_scores=True)
         _sync()
         return out
@@ -103,7 +103,7 @@ def test_random_fused_llm_shapes():
 def test_random_fused_encoder_shapes():
     def run(shape, case):
         inp = case[0]
-        dev = lambda a: pu.to_device(a, wl.BF16)
+        dev = lambda a: pu.to_device(a, shape.dtype)
         out = vb.encoder_reduce_fused(shape, dev(inp["hidden"]), dev(inp["w_q"]),
                                       dev(np.ascontiguousarray(inp["w_k"].T)), dev(inp["x"]),
                                       want_assign=True, want_scores=True)
@@ -148,8 +148,8 @@ def test_random_ragged_batches():
         if fused:
             caps, meta, inp, refs = pu.ragged_fused_case(base, seqs, seed=33000 + 53 * i)
             out = vb.llm_prune_fused_ragged(
-                caps, meta, pu.to_device(inp["hidden"], wl.BF16), pu.to_device(inp["w_q"], wl.BF16),
-                pu.to_device(np.ascontiguousarray(inp["w_k"].T), wl.BF16), want_scores=True)
+                caps, meta, pu.to_device(inp["hidden"], caps.dtype), pu.to_device(inp["w_q"], caps.dtype),
+                pu.to_device(np.ascontiguousarray(inp["w_k"].T), caps.dtype), want_scores=True)
             torch.cuda.synchronize()
             pu.check_fused_ragged(caps, meta, inp, refs, out, caps.in_place, f"ragged {i}")
         else:
