@@ -452,19 +452,47 @@ __global__ __launch_bounds__(256, 2) void mean_colsum_kernel(const T *__restrict
 // ---------------------------------------------------------------------------
 constexpr int kPipeStageRows = 128;
 
+// 16-byte loads from global memory straight into LDS (no pass through vector registers, no LDS
+// write instruction): lane l's data lands 16*l bytes behind the wave-uniform LDS address.  Issued
+// from inline assembly so that the compiler's wait-count bookkeeping does not see them - it would
+// otherwise make every LDS read wait for them, whichever buffer they fill; the kernel waits for
+// them itself (wait_direct_loads) before the barrier that publishes the stage.
+__device__ __forceinline__ unsigned lds_byte_address(const void *p) {
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+__device__ __forceinline__ void direct_load16(const void *src, unsigned lds_address) {
+    // (M0 carries the LDS address.  It is a reserved register that compiler-generated code
+    // loads right before each instruction that reads it, never keeps live across statements,
+    // and that the kernels of this file use for nothing else.)
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_address), "v"(src)
+                 : "memory");
+}
+// every outstanding vector-memory load of this wave has arrived (vmcnt 0, the other counters
+// left alone)
+__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 template <int NC, int HALVES, int PASS>
 __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
     const unsigned char *__restrict__ resident, const unsigned char *__restrict__ streamed,
     const float *__restrict__ lse_in, float *__restrict__ out, int n_heads_total, int S, int dh,
     int res_first, int n_res, int str_first, int n_str, float sl2) {
-    constexpr int NCX = NC + (PASS == 2 ? 1 : 0);      // chunks per streamed row in LDS
-    constexpr int STRIDE = NCX * 32 + 16;              // LDS row pitch: conflict-free 16-byte reads
+    constexpr int NCX = NC + (PASS == 2 ? 1 : 0);      // chunks per streamed row (pass 2: the lse chunk)
+    // With an odd number of 32-byte chunks per row the unpadded row pitch serves the 16-byte
+    // operand reads at 92 % of the LDS rate (measured; 25 % for an even number), and a stage
+    // is then one contiguous block in memory and in LDS alike: it is fetched with direct loads.
+    // The lse chunk of pass 2 lives in an array of its own (32-byte rows).  Otherwise: padded
+    // rows (pitch 32 NCX + 16, conflict-free) staged through registers.
+    constexpr bool DIRECT = (NC & 1) != 0;
+    constexpr int STRIDE = DIRECT ? NC * 32 : NCX * 32 + 16;
     constexpr int PPR = NC * 2;                        // 16-byte pieces per streamed row in memory
     constexpr int RB = 4 * 32 * HALVES;                // resident rows per workgroup
     constexpr int NM = NCX * HALVES;                   // matrix instructions per tile
     constexpr int NL = 16 * HALVES;                    // logits per lane and tile
     static_assert(kPipeStageRows * PPR == 256 * NC, "NC pieces per thread and stage");
     __shared__ __align__(16) unsigned char lds[2][kPipeStageRows * STRIDE];
+    __shared__ __align__(16) unsigned char lse_lds[DIRECT && PASS == 2 ? 2 : 1][DIRECT && PASS == 2 ? kPipeStageRows * 32 : 16];
 
     const int nblk = (n_res + RB - 1) / RB;
     const int total = n_heads_total * nblk;
@@ -493,7 +521,7 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
     const int nstages = (n_str + kPipeStageRows - 1) / kPipeStageRows;
 
     // ---- staging of the streamed operand: thread t carries pieces t, t + 256, ... of a stage
-    uint4 sreg[NC];
+    uint4 sreg[DIRECT ? 1 : NC];
     float lse_reg = 0.f;
     auto stage_load = [&](int s) {
 #pragma unroll
@@ -504,7 +532,15 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
             // the consumers neutralise), pieces past the end of a row its last piece (the
             // resident operand is zero there)
             const int row = min(s * kPipeStageRows + r, n_str - 1);
-            sreg[it] = load16(sbase, (int64_t)row * row_bytes + min(piece * 16, row_bytes - 16));
+            const int64_t off = (int64_t)row * row_bytes + min(piece * 16, row_bytes - 16);
+            if constexpr (DIRECT) {
+                // piece p of the stage goes to byte 16 p of the stage's buffer: the wave's 64
+                // pieces of this round form one contiguous kilobyte
+                direct_load16(sbase + off, __builtin_amdgcn_readfirstlane(lds_byte_address(
+                                               lds[s & 1] + 16 * (it * 256 + w * kWave))));
+            } else {
+                sreg[it] = load16(sbase, off);
+            }
         }
         if (PASS == 2 && tid < kPipeStageRows)
             lse_reg = lse_h[min(s * kPipeStageRows + tid, n_str - 1)];
@@ -512,11 +548,15 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
     const float inv_sl2 = 1.0f / sl2;
     auto stage_store = [&](int s) {
         unsigned char *dst = lds[s & 1];
+        if constexpr (DIRECT) {
+            wait_direct_loads();  // this wave's share of the stage is in LDS
+        } else {
 #pragma unroll
-        for (int it = 0; it < NC; ++it) {
-            const int p = tid + it * 256;
-            const int r = p / PPR, piece = p - r * PPR;
-            *reinterpret_cast<uint4 *>(dst + r * STRIDE + piece * 16) = sreg[it];
+            for (int it = 0; it < NC; ++it) {
+                const int p = tid + it * 256;
+                const int r = p / PPR, piece = p - r * PPR;
+                *reinterpret_cast<uint4 *>(dst + r * STRIDE + piece * 16) = sreg[it];
+            }
         }
         if (PASS == 2 && tid < kPipeStageRows) {
             // -lse / sl2 as hi + mid + lo; each residual is exact in fp32 and the third piece
@@ -534,7 +574,7 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
             } else {
                 x.x = 0xff80u;  // -inf
             }
-            unsigned char *e = dst + tid * STRIDE + NC * 32;
+            unsigned char *e = DIRECT ? lse_lds[s & 1] + tid * 32 : dst + tid * STRIDE + NC * 32;
             *reinterpret_cast<uint4 *>(e) = x;
             *reinterpret_cast<uint4 *>(e + 16) = zero16();
         }
@@ -544,6 +584,13 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
     f32x16_t acc[2][HALVES];
     auto frag_ptr = [&](int t) {
         return lds[(t >> 2) & 1] + ((t & 3) * 32 + (lane & 31)) * STRIDE + 16 * g;
+    };
+    // chunk c of tile t in matrix-operand layout (`base` = frag_ptr(t))
+    auto read_frag = [&](const unsigned char *base, int t, int c) {
+        if (DIRECT && c == NC)  // the lse chunk of pass 2
+            return *reinterpret_cast<const u32x4_t *>(lse_lds[(t >> 2) & 1] +
+                                                      ((t & 3) * 32 + (lane & 31)) * 32 + 16 * g);
+        return *reinterpret_cast<const u32x4_t *>(base + 32 * c);
     };
     auto resident_frag = [&](int h, int c) {
         union {
@@ -617,7 +664,7 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
                     __builtin_bit_cast(bf16x8_t, fr[c]), resident_frag(h, c), c == 0 ? zero : nxt[h],
                     0, 0, 0);
                 if constexpr (REFILL) {
-                    if (h == HALVES - 1) fr[c] = *reinterpret_cast<const u32x4_t *>(next_frags + 32 * c);
+                    if (h == HALVES - 1) fr[c] = read_frag(next_frags, t + 2, c);
                 }
             }
 #pragma unroll
@@ -665,7 +712,7 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
     {
         const unsigned char *f0 = frag_ptr(0);
 #pragma unroll
-        for (int c = 0; c < NCX; ++c) fr[c] = *reinterpret_cast<const u32x4_t *>(f0 + 32 * c);
+        for (int c = 0; c < NCX; ++c) fr[c] = read_frag(f0, 0, c);
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
@@ -678,7 +725,7 @@ __global__ __launch_bounds__(256, 2) void mean_pipe_kernel(
         if (ntiles > 1) {
             const unsigned char *f1 = frag_ptr(1);
 #pragma unroll
-            for (int c = 0; c < NCX; ++c) fr[c] = *reinterpret_cast<const u32x4_t *>(f1 + 32 * c);
+            for (int c = 0; c < NCX; ++c) fr[c] = read_frag(f1, 1, c);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
