@@ -281,6 +281,26 @@ __global__ __launch_bounds__(256) void kept_inv_norm_kernel(const T *__restrict_
     if (lane_id() == 0) inv_norm[row] = 1.0f / fmaxf(sqrtf(ss), kNormEps);
 }
 
+// 16-byte loads from global memory straight into LDS: lane l's data lands 16*l bytes behind the
+// wave-uniform LDS address held in M0; the source is a wave-uniform base plus a per-lane unsigned
+// 32-bit byte offset.  Issued from inline assembly so that the compiler's wait-count bookkeeping
+// does not see them (it would make every LDS read wait for them, whichever buffer they fill); the
+// kernel waits for them itself before the barrier that publishes a stage.  (M0 is a reserved
+// register that compiler-generated code loads right before each instruction that reads it and
+// that these kernels use for nothing else.)
+__device__ __forceinline__ unsigned lds_byte_address(const void *p) {
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+__device__ __forceinline__ void direct_load16(const void *base, uint32_t byte_offset,
+                                              unsigned lds_address) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_address), "v"(byte_offset), "s"(base)
+                 : "memory");
+}
+// every outstanding vector-memory load of this wave has arrived (vmcnt 0, other counters left alone)
+__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // ---------------------------------------------------------------------------
 // The large form of the kept x dropped similarity: 128 x 128 workgroup tiles of 2 x 2 waves.
 // Counters on the form above showed fifteen vector instructions per matrix instruction at this
@@ -301,7 +321,7 @@ __global__ __launch_bounds__(256) void kept_inv_norm_kernel(const T *__restrict_
 // round-robin by linear index and every XCD has its own L2, so XCD x works through a compact
 // block of (tiles_m / 4) x (tiles_n / 2) tiles, kept tile fastest - its band of kept rows stays
 // in its L2 and its band of dropped rows streams through once.
-template <typename T, int TM, int TN, int WM, int WN, int KC, int NSETS>
+template <typename T, int TM, int TN, int WM, int WN, int KC, int NSETS, bool DIRECT>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 1) void sim_argmax_large_kernel(
     const T *__restrict__ x, const int32_t *__restrict__ kept_idx,
     const int32_t *__restrict__ drop_idx, const float *__restrict__ inv_norm,
@@ -309,7 +329,13 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
     constexpr int THREADS = 64 * WM * WN;
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN, ROWS = BM + BN;
     constexpr int PPR = KC * 2;                 // 16-byte pieces per row per stage
-    constexpr int STRIDE = KC * 32 + 16;        // LDS row stride in bytes
+    // LDS row stride in bytes.  Staged through registers: 16 bytes of padding per row make the
+    // 16-byte operand reads conflict-free.  DIRECT (stages fetched straight into LDS, which
+    // writes a wave's 64 pieces contiguously and so leaves no room for padding): 128-byte rows
+    // whose 16-byte columns are XOR-ed with the row's low three bits instead (86 % of the LDS
+    // read rate, measured).
+    static_assert(!DIRECT || KC == 4, "the column swizzle is written for rows of eight pieces");
+    constexpr int STRIDE = DIRECT ? KC * 32 : KC * 32 + 16;
     constexpr int PER_THREAD = ROWS * PPR / THREADS;
     constexpr int A_PIECES = BM * PPR / THREADS;
     static_assert(ROWS * PPR % THREADS == 0 && BM * PPR % THREADS == 0, "tile must split evenly");
@@ -344,7 +370,9 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
     // rows (32 bits: the ABI layer rejects images of 2 GiB or more).  Rows outside the problem
     // (slots >= K, columns >= U) stage some other row of the image: their results are masked
     // in the epilogue, and a real row keeps every load unconditional and inside the image.
-    const int piece = tid % PPR;
+    // this thread's place in its LDS rows is column tid % PPR; the piece of the row that belongs
+    // there is that column, or with the swizzle that column XOR the row's low bits
+    const int piece = DIRECT ? (tid % PPR) ^ ((tid / PPR) & 7) : tid % PPR;
     uint32_t src[PER_THREAD];
     {
         int tok[PER_THREAD];
@@ -392,7 +420,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
             }
         }
     };
-    unsigned char *const my_lds = lds_raw + (tid / PPR) * STRIDE + piece * 16;
+    unsigned char *const my_lds = lds_raw + (tid / PPR) * STRIDE + (tid % PPR) * 16;
     auto stage_store = [&](int buf, const uint4(&regs)[PER_THREAD], int stage) {
         unsigned char *dst = my_lds + buf * (ROWS * STRIDE);
         if (stage < nfull) {  // uniform: the common case carries no per-piece selects
@@ -422,16 +450,20 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
     // the first chunk of stage s + 1 is read right after the barrier and arrives under the
     // matrix instructions of stage s's last chunk.  No matrix instruction waits for LDS.
     static_assert(KC % 2 == 0, "chunk c lives in fragment set c & 1");
-    const int a_off = (wm * 32 * TM + (lane & 31)) * STRIDE + 16 * g;
-    const int b_off = (BM + wn * 32 * TN + (lane & 31)) * STRIDE + 16 * g;
+    const int a_off = (wm * 32 * TM + (lane & 31)) * STRIDE;
+    const int b_off = (BM + wn * 32 * TN + (lane & 31)) * STRIDE;
+    // byte offset of chunk c's 16 bytes inside a row (every row this lane reads has the same
+    // low three bits as the lane: tiles and blocks start at multiples of 32)
+    auto col_off = [&](int c) { return DIRECT ? 16 * ((g + 2 * c) ^ (lane & 7)) : 16 * g + 32 * c; };
     uint4 af[2][TM], bf[2][TN];
     auto read = [&](const unsigned char *cur, int c, int set) {
+        const int co = col_off(c);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            af[set][i] = *reinterpret_cast<const uint4 *>(cur + a_off + i * 32 * STRIDE + 32 * c);
+            af[set][i] = *reinterpret_cast<const uint4 *>(cur + a_off + i * 32 * STRIDE + co);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            bf[set][j] = *reinterpret_cast<const uint4 *>(cur + b_off + j * 32 * STRIDE + 32 * c);
+            bf[set][j] = *reinterpret_cast<const uint4 *>(cur + b_off + j * 32 * STRIDE + co);
     };
     auto mma = [&](int set) {
 #pragma unroll
@@ -447,38 +479,87 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
     // that is one stage, about what a fetch from L2 takes while the chip is busy; the four-wave
     // form keeps three sets in flight.  Stage i always lives in set i % NSETS, so the loop is
     // unrolled NSETS times.
+    if constexpr (DIRECT) {
+        // Two LDS buffers, no staging registers: the loads of stage s + 1 are issued as soon as
+        // the barrier at the end of stage s - 1 has freed its buffer, and have all of stage s
+        // to arrive.  Rows that end inside a stage (the ragged last one) still pass through
+        // registers, which clears what lies past their end; that one stage is fetched where it
+        // is published, so its registers are not live across the matrix instructions.
+        const unsigned lds0 = lds_byte_address(lds_raw);
+        auto fetch = [&](int stage) {
+            if (stage < nfull) {
+                const unsigned char *sbase = xb + (int64_t)stage * (KC * 32);
+#pragma unroll
+                for (int it = 0; it < PER_THREAD; ++it)
+                    direct_load16(sbase, src[it],
+                                  __builtin_amdgcn_readfirstlane(
+                                      lds0 + (unsigned)((stage & 1) * (ROWS * STRIDE) +
+                                                        (it * (THREADS / PPR) + wave_id() * 8) * STRIDE)));
+            }
+        };
+        auto publish = [&](int stage) {  // this wave's share of the stage is in LDS
+            if (stage < nfull) {
+                wait_direct_loads();
+            } else {
+                uint4 ra[PER_THREAD];
+                stage_load(stage, ra);
+                stage_store(stage & 1, ra, stage);
+            }
+        };
+        fetch(0);
+        publish(0);
+        __syncthreads();
+        read(lds[0], 0, 0);
+        for (int st = 0; st < nstages; ++st) {
+            const bool more = st + 1 < nstages;
+            const unsigned char *cur = lds[st & 1];
+            if (more) fetch(st + 1);
+#pragma unroll
+            for (int c = 0; c + 1 < KC; ++c) {
+                read(cur, c + 1, (c + 1) & 1);
+                mma(c & 1);
+            }
+            if (more) {
+                publish(st + 1);
+                __syncthreads();
+                read(lds[(st + 1) & 1], 0, 0);
+            }
+            mma((KC - 1) & 1);
+        }
+    } else {
     uint4 ra[NSETS][PER_THREAD];
-    stage_load(0, ra[0]);
-    stage_store(0, ra[0], 0);
+        stage_load(0, ra[0]);
+        stage_store(0, ra[0], 0);
 #pragma unroll
-    for (int i = 1; i <= NSETS; ++i)
-        if (i < nstages) stage_load(i, ra[i % NSETS]);
-    __syncthreads();
-    read(lds[0], 0, 0);
-    for (int st0 = 0; st0 < nstages; st0 += NSETS) {
+        for (int i = 1; i <= NSETS; ++i)
+            if (i < nstages) stage_load(i, ra[i % NSETS]);
+        __syncthreads();
+        read(lds[0], 0, 0);
+        for (int st0 = 0; st0 < nstages; st0 += NSETS) {
 #pragma unroll
-        for (int j = 0; j < NSETS; ++j) {
-            const int st = st0 + j;
-            if (st < nstages) {  // uniform
-                const bool more = st + 1 < nstages;
-                const int next_set = (j + 1) % NSETS;  // a constant once unrolled: st0 is a multiple of NSETS
-                const unsigned char *cur = lds[st & 1];
+            for (int j = 0; j < NSETS; ++j) {
+                const int st = st0 + j;
+                if (st < nstages) {  // uniform
+                    const bool more = st + 1 < nstages;
+                    const int next_set = (j + 1) % NSETS;  // a constant once unrolled: st0 is a multiple of NSETS
+                    const unsigned char *cur = lds[st & 1];
 #pragma unroll
-                for (int c = 0; c + 1 < KC; ++c) {
-                    read(cur, c + 1, (c + 1) & 1);
-                    mma(c & 1);
-                    if (c == KC / 2 - 1) {
-                        if (more) stage_store((st + 1) & 1, ra[next_set], st + 1);
-                        if (st + 1 + NSETS < nstages) stage_load(st + 1 + NSETS, ra[next_set]);
+                    for (int c = 0; c + 1 < KC; ++c) {
+                        read(cur, c + 1, (c + 1) & 1);
+                        mma(c & 1);
+                        if (c == KC / 2 - 1) {
+                            if (more) stage_store((st + 1) & 1, ra[next_set], st + 1);
+                            if (st + 1 + NSETS < nstages) stage_load(st + 1 + NSETS, ra[next_set]);
+                        }
                     }
+                    if (more) {
+                        // every wave has issued its last reads of this buffer and its writes of the
+                        // other one; both are complete when the barrier is passed
+                        __syncthreads();
+                        read(lds[(st + 1) & 1], 0, 0);
+                    }
+                    mma((KC - 1) & 1);
                 }
-                if (more) {
-                    // every wave has issued its last reads of this buffer and its writes of the
-                    // other one; both are complete when the barrier is passed
-                    __syncthreads();
-                    read(lds[(st + 1) & 1], 0, 0);
-                }
-                mma((KC - 1) & 1);
             }
         }
     }
@@ -807,15 +888,15 @@ static hipError_t sim_t(const MergeArgs &a, hipStream_t s) {
                        a.D, a.K, U, a.B, (int)affine);
     return hipGetLastError();
 }
-template <typename T, int TM, int TN, int WM, int WN, int KC, int NSETS>
+template <typename T, int TM, int TN, int WM, int WN, int KC, int NSETS, bool DIRECT>
 static hipError_t sim_large_launch(const MergeArgs &a, hipStream_t s) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int U = a.T - a.K;
     const int tiles_m = (a.K + BM - 1) / BM, tiles_n = (U + BN - 1) / BN;
     const bool affine = image_affinity(a);
     const int mode = affine ? 1 : (tiles_m % 4 == 0 && tiles_n % 2 == 0 ? 2 : 0);
-    const size_t smem = (size_t)2 * (BM + BN) * (KC * 32 + 16) + BM * sizeof(float);
-    auto kernel = sim_argmax_large_kernel<T, TM, TN, WM, WN, KC, NSETS>;
+    const size_t smem = (size_t)2 * (BM + BN) * (KC * 32 + (DIRECT ? 0 : 16)) + BM * sizeof(float);
+    auto kernel = sim_argmax_large_kernel<T, TM, TN, WM, WN, KC, NSETS, DIRECT>;
     static std::atomic<uint64_t> lds_allowed{0};
     if (smem > 64 * 1024) {
         hipError_t e = allow_large_lds(kernel, lds_allowed);
@@ -838,8 +919,8 @@ static hipError_t sim_large_t(const MergeArgs &a, hipStream_t s) {
     const int U = a.T - a.K;
     const long tiles256 = (long)(U / 256) * (a.K / 256) * a.B;
     if (a.K >= 1024 && U >= 1024 && tiles256 >= 2 * 256)
-        return sim_large_launch<T, 4, 2, 2, 4, 4, 1>(a, s);
-    return sim_large_launch<T, 2, 2, 2, 2, 4, 3>(a, s);
+        return sim_large_launch<T, 4, 2, 2, 4, 4, 1, true>(a, s);
+    return sim_large_launch<T, 2, 2, 2, 2, 4, 3, true>(a, s);
 }
 
 bool sim_argmax_uses_large_form(int B, int T, int K) {

@@ -449,6 +449,13 @@ SIM_LARGE = {
     "two-images-launch-order": _enc(batch=2, grid_h=114, grid_w=128, heads=2, head_dim=16,
                                     feat_dim=32, win_rows=1, win_cols=1, keep_global=1270,
                                     keep_local=0),
+    # rows of several 128-byte stages plus a ragged one (stages fetched straight into LDS, the
+    # last through registers): 128 x 128 tiles, then 256 x 256 tiles, bf16 and fp32
+    "staged-rows-400-bytes": _enc(batch=8, grid_h=64, grid_w=64, heads=2, head_dim=16, feat_dim=200,
+                                  win_rows=1, win_cols=1, keep_global=512, keep_local=0),
+    "staged-rows-288-bytes-f32": _enc(wl.F32, batch=1, grid_h=96, grid_w=128, heads=2, head_dim=16,
+                                      feat_dim=72, win_rows=1, win_cols=1, keep_global=4096,
+                                      keep_local=0),
 }
 
 
