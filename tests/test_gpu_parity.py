@@ -331,6 +331,84 @@ def test_llm_exact_ties_large_span():
     pu.check_llm(shape, inp, ref, _run_llm(shape, inp), "ties-large")
 
 
+def _expected_by_groups(group_of, group_score, keep):
+    """Tokens whose scores tie exactly inside each group: the best groups whole, then the
+    lowest indices of the group the budget ends in."""
+    order = np.argsort(-group_score, kind="stable")
+    picked = []
+    for g in order:
+        members = np.flatnonzero(group_of == g)
+        take = min(len(members), keep - len(picked))
+        picked.extend(members[:take].tolist())
+        if len(picked) == keep:
+            break
+    return sorted(picked)
+
+
+def _group_scores(scores, group_of, n_groups):
+    """Per group score from the oracle; the groups must be far apart next to rounding."""
+    gs = np.array([scores[group_of == g].mean() for g in range(n_groups)])
+    for g in range(n_groups):
+        assert np.ptp(scores[group_of == g]) <= 1e-9 * gs[g]
+    srt = np.sort(gs)
+    return gs, float(np.min(np.diff(srt) / srt[1:])) if n_groups > 1 else 1.0
+
+
+@pytest.mark.parametrize("n_groups", [2, 24, 100])
+def test_llm_tied_groups_go_to_the_lowest_tokens(n_groups):
+    """Visual keys drawn from a few distinct rows: scores tie exactly inside a group, and the
+    budget ends inside one, so the workgroup-wide search has to settle a tie that covers only
+    part of the candidates (2 groups of about 1500 tokens, 24 of about 125, 100 of about 30)
+    by token order."""
+    shape = _llm(wl.F32, batch=2, vis_len=3000, keep=1000, text=5)
+    inp = wl.llm_inputs(shape, 21)
+    rng = np.random.default_rng(100 + n_groups)
+    group_of = rng.integers(0, n_groups, size=shape.vis_len)
+    for attempt in range(20):
+        rows = rng.standard_normal((shape.batch, shape.kv_heads, n_groups, shape.head_dim)).astype(np.float32)
+        inp["k"][:, :, shape.vis_start:shape.vis_start + shape.vis_len] = rows[:, :, group_of]
+        ref = vo.llm_prune(shape, **inp)
+        per_seq = [_group_scores(ref["scores"][b], group_of, n_groups) for b in range(shape.batch)]
+        if min(gap for _, gap in per_seq) > 3e-5:  # fp32 scores are good to about 1e-6
+            break
+    else:
+        pytest.fail("no draw with well separated groups")
+    want = [_expected_by_groups(group_of, gs, shape.keep) for gs, _ in per_seq]
+    out = _run_llm(shape, inp)
+    assert pu.to_host(out["kept_idx"]).tolist() == want
+    pu.check_scores(pu.to_host(out["scores"]), ref["scores"], "tied-groups")
+
+
+@pytest.mark.parametrize("grid,n_groups", [((40, 40), 12), ((72, 64), 40), ((72, 64), 3)])
+def test_encoder_tied_groups_go_to_the_lowest_tokens(grid, n_groups):
+    """The same for the encoder's global scan, on a segment searched by one workgroup (1600
+    tokens) and on one split over workgroups (4608 tokens); no local scan, so the expected
+    selection follows from the groups alone."""
+    shape = _enc(wl.F32, batch=1, n_segments=2, grid_h=grid[0], grid_w=grid[1], win_rows=1,
+                 win_cols=1, keep_local=0, keep_global=grid[0] * grid[1] // 3, feat_dim=32,
+                 heads=2, head_dim=16)
+    N = grid[0] * grid[1]
+    inp = wl.encoder_inputs(shape, 31)
+    rng = np.random.default_rng(200 + n_groups)
+    group_of = rng.integers(0, n_groups, size=N)
+    for attempt in range(20):
+        rows = rng.standard_normal((1, shape.n_segments, shape.heads, n_groups, shape.head_dim)).astype(np.float32)
+        inp["k"][:, :, :, shape.has_cls:] = rows[:, :, :, group_of]
+        ref = vo.encoder_reduce(shape, inp["q"], inp["k"], inp["x"])
+        per_seg = [_group_scores(ref["scores"][0, c * N:(c + 1) * N], group_of, n_groups)
+                   for c in range(shape.n_segments)]
+        if min(gap for _, gap in per_seg) > 3e-5:
+            break
+    else:
+        pytest.fail("no draw with well separated groups")
+    want = []
+    for c, (gs, _) in enumerate(per_seg):
+        want += [c * N + j for j in _expected_by_groups(group_of, gs, shape.keep_global)]
+    out = _run_encoder(shape, inp)
+    assert pu.to_host(out["kept_idx"]).tolist() == [want]
+    pu.check_scores(pu.to_host(out["scores"]), ref["scores"], "tied-groups")
+
+
 # ----------------------------------------------------------------------------
 # The benchmark configurations at full size
 @pytest.mark.parametrize("win,keep_local,keep_global", [(2, 12, 20), (1, 0, 32), (6, 36, 20)])
