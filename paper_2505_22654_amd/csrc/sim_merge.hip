@@ -628,13 +628,14 @@ __global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
                                                     const unsigned long long *__restrict__ best,
                                                     T *__restrict__ merged,
                                                     int32_t *__restrict__ assign_out, int T_img,
-                                                    int D, int K, int B, int affine, int spw) {
+                                                    int D, int K, int B, int affine, int spw,
+                                                    int parts, int part_pieces) {
     constexpr int E = ElemTraits<T>::kPer16B;
     // rows fetched together: about 24 16-byte loads per lane in flight (96 registers), which is
     // what it takes for the few workgroups that own the large groups to pull rows at the rate
     // a compute unit can take them
     // (sixteen waves share 512 registers per SIMD four ways: 128 each, so fewer rows per wave)
-    constexpr int BATCH = NW == 16 ? (PIECES <= 2 ? 8 : PIECES == 3 ? 5 : 3)
+    constexpr int BATCH = NW == 16 ? (PIECES <= 1 ? 8 : PIECES == 2 ? 6 : PIECES == 3 ? 3 : 2)
                                    : (PIECES <= 3 ? 8 : PIECES <= 6 ? 4 : PIECES <= 12 ? 2 : 1);
     constexpr int NT = 64 * NW;       // threads
     constexpr int NB = NW / 4;        // partial-sum buffers of a shared group (four waves each)
@@ -643,16 +644,25 @@ __global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
     __shared__ int scratch_lists[NW][kMergeListCap];  // per wave, for the scans of phase 3
     extern __shared__ float part[];  // NB x D floats: partial sums of a shared group
     const int ns = NW * spw;  // slots of this workgroup
-    int b, group;
-    if (!image_affine_decode(B, (K + ns - 1) / ns, affine != 0, b, group)) return;
+    // `parts` workgroups share a set of slots: each adds the same rows, but only its own
+    // `part_pieces` 16-byte columns of them (the last part may have fewer).  A group's rows are
+    // added by one workgroup, on one compute unit, and the few groups of several hundred members
+    // decide the kernel's time (10-20 us each); cut by columns, such a group is spread over
+    // `parts` compute units with nothing to combine afterwards and the order of additions
+    // untouched.  The price is that every part repeats the scan of the assignment words.
+    int b, item;
+    if (!image_affine_decode(B, ((K + ns - 1) / ns) * parts, affine != 0, b, item)) return;
+    const int group = item / parts, col_part = item - group * parts;
     const int slot0 = group * ns;
     const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
     // low halves of the assignment words: the complemented slot of every token
     const uint32_t *slot_word = reinterpret_cast<const uint32_t *>(best + (int64_t)b * T_img);
     const unsigned char *xb = reinterpret_cast<const unsigned char *>(x) +
                               (int64_t)b * T_img * D * (int64_t)sizeof(T);
-    const int npieces = D / E;
+    const int piece0 = col_part * part_pieces;                   // first 16-byte column of this part
+    const int npieces = min(D / E - piece0, part_pieces);     // and how many it has (>= 1)
     const int64_t row_bytes = (int64_t)D * sizeof(T);
+    const int64_t col_bytes = (int64_t)piece0 * 16;
 
     if (tid < NW * kMergeMaxSpw) cnt[tid] = 0;
     __syncthreads();
@@ -672,7 +682,7 @@ __global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
             if (t < T_img && rel < (unsigned)ns && s < K) {
                 const int pos = atomicAdd(&cnt[rel], 1);
                 if (pos < kMergeListCap) lists[rel][pos] = t;
-                if (assign_out) assign_out[(int64_t)b * T_img + t] = s;
+                if (assign_out && col_part == 0) assign_out[(int64_t)b * T_img + t] = s;
             }
         }
     }
@@ -685,41 +695,53 @@ __global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
     };
-    // adds rows list[0 .. n) to acc, in list order
+    // adds rows list[0 .. n) to acc, in list order.  BATCH rows are in flight all the time: as
+    // soon as a row has been added, the row BATCH places further down the list is requested into
+    // the registers it leaves (a wave that asked for a whole batch, waited, added and only then
+    // asked for the next one spent 2-3 us per batch, a memory round-trip plus the additions).
+    // No load carries a condition (a row past the end of the list re-reads the last member, a
+    // piece past the end of the row its last piece): a load inside a branch makes the compiler
+    // wait for all outstanding loads where the branch joins.
     auto drain = [&](const int *list, int n) {
-        for (int m = 0; m < n; m += BATCH) {
-            int tok[BATCH];
+        if (n <= 0) return;
+        uint4 raw[BATCH][PIECES];
+        auto fetch = [&](int j, int i) {
+            const int64_t row = list[min(i, n - 1)] * row_bytes + col_bytes;
 #pragma unroll
-            for (int j = 0; j < BATCH; ++j) tok[j] = list[min(m + j, n - 1)];
-            // every piece of every row of the batch is requested before anything is added.  The
-            // loads carry no condition (a row past the end of the list re-reads the last
-            // member, a piece past the end of the row its last piece): a load inside a branch
-            // makes the compiler wait for all outstanding loads where the branch joins.
-            uint4 raw[BATCH][PIECES];
+            for (int p = 0; p < PIECES; ++p)
+                raw[j][p] = load16(xb, row + (int64_t)min(lane + p * kWave, npieces - 1) * 16);
+        };
+        auto add = [&](int j) {
 #pragma unroll
-            for (int j = 0; j < BATCH; ++j)
+            for (int p = 0; p < PIECES; ++p) {
+                float v[E];
+                unpack16<T>(raw[j][p], v);
 #pragma unroll
-                for (int p = 0; p < PIECES; ++p)
-                    raw[j][p] = load16(xb, tok[j] * row_bytes +
-                                               (int64_t)min(lane + p * kWave, npieces - 1) * 16);
+                for (int e = 0; e < E; ++e) acc[p][e] += v[e];
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) fetch(j, j);
+        int m = 0;
+        for (; m + BATCH < n; m += BATCH) {  // rows m .. m+BATCH-1 are all members
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
-                if (m + j < n) {  // uniform over the wave; rows are added in list order
-#pragma unroll
-                    for (int p = 0; p < PIECES; ++p) {
-                        float v[E];
-                        unpack16<T>(raw[j][p], v);
-#pragma unroll
-                        for (int e = 0; e < E; ++e) acc[p][e] += v[e];
-                    }
-                }
+                add(j);
+                // the request reuses the registers the addition has just freed: keep the
+                // scheduler from moving it (or a later row's) up, which would need new ones
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(j, m + BATCH + j);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j)
+            if (m + j < n) add(j);  // uniform over the wave
     };
     auto write_row = [&](int slot, int count) {
         const float inv = 1.0f / (float)count;
         unsigned char *out = reinterpret_cast<unsigned char *>(merged) +
-                             ((int64_t)b * K + slot) * row_bytes;
+                             ((int64_t)b * K + slot) * row_bytes + col_bytes;
 #pragma unroll
         for (int p = 0; p < PIECES; ++p) {
             const int piece = lane + p * kWave;
@@ -941,7 +963,13 @@ hipError_t launch_sim_argmax(const MergeArgs &a, hipStream_t s) {
 template <typename T>
 static hipError_t merge_t(const MergeArgs &a, hipStream_t s) {
     constexpr int E = ElemTraits<T>::kPer16B;
-    const int per_lane = (a.D / E + kWave - 1) / kWave;
+    const int all_pieces = a.D / E;
+    // Rows of 128 and more 16-byte pieces are cut into two column halves, each added by a
+    // workgroup of its own (config 3: 24.4 -> 20.9 us, config 4: 36.8 -> 34.5; three and four
+    // parts measured slower: every part repeats the scan of the assignment words).
+    const int parts = all_pieces >= 2 * kWave ? 2 : 1;
+    const int part_pieces = (all_pieces + parts - 1) / parts;  // >= 64: no part is empty
+    const int per_lane = (part_pieces + kWave - 1) / kWave;
     const bool affine = image_affinity(a);
     // Sixteen waves per workgroup for long images (from 8192 tokens) when rows are short enough
     // for four partial-sum buffers in LDS and there are slots for at least half the CUs: every
@@ -956,12 +984,12 @@ static hipError_t merge_t(const MergeArgs &a, hipStream_t s) {
     int spw = 1;
     while (spw < kMergeMaxSpw && (int64_t)a.B * a.K >= (int64_t)nw * (wide ? 256 : 1024) * 2 * spw) spw *= 2;
     const int ns = nw * spw;
-    dim3 grid(image_affine_grid(a.B, (a.K + ns - 1) / ns, affine));
+    dim3 grid(image_affine_grid(a.B, ((a.K + ns - 1) / ns) * parts, affine));
     const size_t part_bytes = (size_t)(nw / 4) * a.D * sizeof(float);  // at most 32 KiB
 #define VSCAN_MERGE(P, NW)                                                                      \
     hipLaunchKernelGGL((merge_kernel<T, P, NW>), grid, dim3(64 * NW), part_bytes, s,            \
                        (const T *)a.x, (const unsigned long long *)a.best, (T *)a.merged,       \
-                       a.assign_out, a.T, a.D, a.K, a.B, (int)affine, spw)
+                       a.assign_out, a.T, a.D, a.K, a.B, (int)affine, spw, parts, part_pieces)
     if (wide) {
         if (per_lane <= 1) VSCAN_MERGE(1, 16);
         else if (per_lane <= 2) VSCAN_MERGE(2, 16);
