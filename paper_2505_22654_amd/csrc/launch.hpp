@@ -11,17 +11,19 @@ namespace vscan {
 
 // Dynamic LDS above 64 KB has to be allowed per kernel.  The limit is raised to the most one
 // workgroup can have, once per kernel instantiation and device: `done` is a static of the
-// calling instantiation, one bit per device.  Later launches only read the bit.
+// calling instantiation, one bit per device.  Later launches only read the bit.  A kernel that
+// also has static LDS passes a `limit` that leaves room for it.
 constexpr int kMaxDynamicLds = 160 * 1024;
 template <typename Kernel>
-inline hipError_t allow_large_lds(Kernel kernel, std::atomic<uint64_t> &done) {
+inline hipError_t allow_large_lds(Kernel kernel, std::atomic<uint64_t> &done,
+                                  int limit = kMaxDynamicLds) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     const uint64_t bit = 1ull << (dev & 63);
     if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
+                            hipFuncAttributeMaxDynamicSharedMemorySize, limit);
     if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
     return e;
 }

@@ -638,11 +638,10 @@ __global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
     constexpr int BATCH = NW == 16 ? (PIECES <= 1 ? 8 : PIECES == 2 ? 6 : PIECES == 3 ? 3 : 2)
                                    : (PIECES <= 3 ? 8 : PIECES <= 6 ? 4 : PIECES <= 12 ? 2 : 1);
     constexpr int NT = 64 * NW;       // threads
-    constexpr int NB = NW / 4;        // partial-sum buffers of a shared group (four waves each)
     __shared__ int cnt[NW * kMergeMaxSpw];
     __shared__ int lists[NW * kMergeMaxSpw][kMergeListCap];
     __shared__ int scratch_lists[NW][kMergeListCap];  // per wave, for the scans of phase 3
-    extern __shared__ float part[];  // NB x D floats: partial sums of a shared group
+    extern __shared__ __align__(16) float part[];  // NW rows of part_pieces * E floats: partial sums
     const int ns = NW * spw;  // slots of this workgroup
     // `parts` workgroups share a set of slots: each adds the same rows, but only its own
     // `part_pieces` 16-byte columns of them (the last part may have fewer).  A group's rows are
@@ -705,8 +704,8 @@ __global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
     auto drain = [&](const int *list, int n) {
         if (n <= 0) return;
         uint4 raw[BATCH][PIECES];
-        auto fetch = [&](int j, int i) {
-            const int64_t row = list[min(i, n - 1)] * row_bytes + col_bytes;
+        auto fetch = [&](int j, int tok) {
+            const int64_t row = tok * row_bytes + col_bytes;
 #pragma unroll
             for (int p = 0; p < PIECES; ++p)
                 raw[j][p] = load16(xb, row + (int64_t)min(lane + p * kWave, npieces - 1) * 16);
@@ -721,16 +720,19 @@ __global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
             }
         };
 #pragma unroll
-        for (int j = 0; j < BATCH; ++j) fetch(j, j);
+        for (int j = 0; j < BATCH; ++j) fetch(j, list[min(j, n - 1)]);
         int m = 0;
         for (; m + BATCH < n; m += BATCH) {  // rows m .. m+BATCH-1 are all members
+            int next[BATCH];  // the next batch's tokens, read from LDS ahead of the additions
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) next[j] = list[min(m + BATCH + j, n - 1)];
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
                 add(j);
                 // the request reuses the registers the addition has just freed: keep the
                 // scheduler from moving it (or a later row's) up, which would need new ones
                 __builtin_amdgcn_sched_barrier(0);
-                fetch(j, m + BATCH + j);
+                fetch(j, next[j]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -842,48 +844,48 @@ __global__ __launch_bounds__(64 * NW) void merge_kernel(const T *__restrict__ x,
             }
             drain(scan_list, nlist);
         }
-        // Partial sums combined in wave order.  Waves 4g .. 4g+3 share buffer g: wave 4g writes
-        // its sum, 4g+1 and 4g+2 add theirs, 4g+3 adds its own on top (four rounds, all buffers at
-        // once); then the last wave adds the buffers' totals in buffer order and writes the row.
-        float *mine = part + (size_t)(wave >> 2) * D;
-        for (int w = 0; w < 4; ++w) {
-            if ((wave & 3) == w) {
+        // Partial sums: every wave leaves its own in LDS (16-byte accesses, a row of
+        // part_pieces * E floats per wave), then the workgroup's threads take four columns each
+        // and add the waves' values in wave order - the same order on every run - scale, convert
+        // and write them out.
+        constexpr int Q = E / 4;  // float4 per 16-byte piece of the input
+        const int wave_stride = part_pieces * Q;
+        float4 *part4 = reinterpret_cast<float4 *>(part);
 #pragma unroll
-                for (int p = 0; p < PIECES; ++p) {
-                    const int piece = lane + p * kWave;
-                    if (piece < npieces) {
+        for (int p = 0; p < PIECES; ++p) {
+            const int piece = lane + p * kWave;
+            if (piece < npieces) {
 #pragma unroll
-                        for (int e = 0; e < E; ++e) {
-                            float &slot_sum = mine[piece * E + e];
-                            if (w == 0) slot_sum = acc[p][e];
-                            else if (w < 3 || (NB > 1 && wave != NW - 1)) slot_sum += acc[p][e];
-                            else acc[p][e] = slot_sum + acc[p][e];
-                        }
-                    }
-                }
-                if (NB == 1 && w == 3) write_row(slot, count);
+                for (int q = 0; q < Q; ++q)
+                    part4[(size_t)wave * wave_stride + piece * Q + q] =
+                        make_float4(acc[p][4 * q], acc[p][4 * q + 1], acc[p][4 * q + 2],
+                                    acc[p][4 * q + 3]);
             }
-            __syncthreads();
         }
-        if constexpr (NB > 1) {
-            if (wave == NW - 1) {
-                // acc holds buffer NB-1's total (the last wave kept it in registers)
-#pragma unroll
-                for (int p = 0; p < PIECES; ++p) {
-                    const int piece = lane + p * kWave;
-                    if (piece < npieces) {
-#pragma unroll
-                        for (int e = 0; e < E; ++e) {
-                            float sum = part[piece * E + e];
-                            for (int g2 = 1; g2 < NB - 1; ++g2) sum += part[(size_t)g2 * D + piece * E + e];
-                            acc[p][e] = sum + acc[p][e];
-                        }
-                    }
-                }
-                write_row(slot, count);
+        __syncthreads();
+        const float inv = 1.0f / (float)count;
+        unsigned char *out = reinterpret_cast<unsigned char *>(merged) +
+                             ((int64_t)b * K + slot) * row_bytes + col_bytes;
+        for (int c = tid; c < npieces * Q; c += NT) {
+            float4 sum = part4[c];
+            for (int w = 1; w < NW; ++w) {
+                const float4 v = part4[(size_t)w * wave_stride + c];
+                sum.x += v.x;
+                sum.y += v.y;
+                sum.z += v.z;
+                sum.w += v.w;
             }
-            __syncthreads();  // the buffers are reused by the next shared group
+            if constexpr (sizeof(T) == 4) {
+                *reinterpret_cast<float4 *>(out + (int64_t)c * 16) =
+                    make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
+            } else {
+                uint2 o;
+                o.x = f32_to_bf16_rne(sum.x * inv) | (f32_to_bf16_rne(sum.y * inv) << 16);
+                o.y = f32_to_bf16_rne(sum.z * inv) | (f32_to_bf16_rne(sum.w * inv) << 16);
+                *reinterpret_cast<uint2 *>(out + (int64_t)c * 8) = o;
+            }
         }
+        __syncthreads();  // the buffers are reused by the next shared group
     }
 }
 
@@ -965,36 +967,48 @@ static hipError_t merge_t(const MergeArgs &a, hipStream_t s) {
     constexpr int E = ElemTraits<T>::kPer16B;
     const int all_pieces = a.D / E;
     // Rows of 128 and more 16-byte pieces are cut into two column halves, each added by a
-    // workgroup of its own (config 3: 24.4 -> 20.9 us, config 4: 36.8 -> 34.5; three and four
-    // parts measured slower: every part repeats the scan of the assignment words).
-    const int parts = all_pieces >= 2 * kWave ? 2 : 1;
-    const int part_pieces = (all_pieces + parts - 1) / parts;  // >= 64: no part is empty
-    const int per_lane = (part_pieces + kWave - 1) / kWave;
+    // workgroup of its own (config 3: 24.4 -> 20.9 us; three and four parts measured slower:
+    // every part repeats the scan of the assignment words).
+    int parts = all_pieces >= 2 * kWave ? 2 : 1;
     const bool affine = image_affinity(a);
     // Sixteen waves per workgroup for long images (from 8192 tokens) when rows are short enough
-    // for four partial-sum buffers in LDS and there are slots for at least half the CUs: every
+    // for sixteen partial-sum rows in LDS and there are slots for at least half the CUs: every
     // workgroup scans all assignment words of its image, and the few very large groups of such
     // an image set the kernel's time; both are then spread over four times as many waves
     // (config 4: 52.6 -> 39.2 us).  Shorter images measured slower that way (config 3: 28 -> 40
-    // us): fewer, larger workgroups and sixteen-wave barriers for every shared group.
-    const bool wide = per_lane <= 4 && a.T >= 8192 && (int64_t)a.B * a.K >= 16 * 128;
+    // us with sixteen waves, no gain with eight): fewer, larger workgroups.
+    // Such a workgroup has a CU to itself, so column halves would make a second round of
+    // workgroups once there are more than the chip has CUs.
+    const bool wide = all_pieces <= 3 * kWave && a.T >= 8192 && (int64_t)a.B * a.K >= 16 * 128;
     const int nw = wide ? 16 : 4;
+    if (wide && (int64_t)a.B * ((a.K + 15) / 16) * parts > kCus) parts = 1;
+    const int part_pieces = (all_pieces + parts - 1) / parts;  // >= 64 when halved: no empty part
+    const int per_lane = (part_pieces + kWave - 1) / kWave;
     // slots per wave: one while that still gives every CU two workgroups of four waves (one of
     // sixteen); more for very many slots, where the shared scan is what has to be amortised
     int spw = 1;
     while (spw < kMergeMaxSpw && (int64_t)a.B * a.K >= (int64_t)nw * (wide ? 256 : 1024) * 2 * spw) spw *= 2;
     const int ns = nw * spw;
     dim3 grid(image_affine_grid(a.B, ((a.K + ns - 1) / ns) * parts, affine));
-    const size_t part_bytes = (size_t)(nw / 4) * a.D * sizeof(float);  // at most 32 KiB
+    // one row of a part's floats per wave: at most 64 KiB (four waves, 512 pieces)
+    const size_t part_bytes = (size_t)nw * part_pieces * E * sizeof(float);
 #define VSCAN_MERGE(P, NW)                                                                      \
-    hipLaunchKernelGGL((merge_kernel<T, P, NW>), grid, dim3(64 * NW), part_bytes, s,            \
-                       (const T *)a.x, (const unsigned long long *)a.best, (T *)a.merged,       \
-                       a.assign_out, a.T, a.D, a.K, a.B, (int)affine, spw, parts, part_pieces)
+    do {                                                                                        \
+        static std::atomic<uint64_t> lds_allowed{0};                                            \
+        if (part_bytes > 32 * 1024) { /* with the lists: more than the default 64 KiB */        \
+            hipError_t e = allow_large_lds(merge_kernel<T, P, NW>, lds_allowed,                 \
+                                           kMaxDynamicLds - NW * 3072 /* its static LDS */);    \
+            if (e != hipSuccess) return e;                                                      \
+        }                                                                                       \
+        hipLaunchKernelGGL((merge_kernel<T, P, NW>), grid, dim3(64 * NW), part_bytes, s,        \
+                           (const T *)a.x, (const unsigned long long *)a.best, (T *)a.merged,   \
+                           a.assign_out, a.T, a.D, a.K, a.B, (int)affine, spw, parts,           \
+                           part_pieces);                                                        \
+    } while (0)
     if (wide) {
         if (per_lane <= 1) VSCAN_MERGE(1, 16);
         else if (per_lane <= 2) VSCAN_MERGE(2, 16);
-        else if (per_lane <= 3) VSCAN_MERGE(3, 16);
-        else VSCAN_MERGE(4, 16);
+        else VSCAN_MERGE(3, 16);
     } else if (per_lane <= 1) VSCAN_MERGE(1, 4);
     else if (per_lane <= 2) VSCAN_MERGE(2, 4);
     else if (per_lane <= 3) VSCAN_MERGE(3, 4);
