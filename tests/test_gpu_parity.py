@@ -105,6 +105,28 @@ def test_encoder_local_pair_on_a_large_segment():
     print("local-pair-large", info, pu.check_encoder(shape, inp, ref, out, "local-pair-large"))
 
 
+@pytest.mark.parametrize("dtype,feat_dim", [(wl.BF16, 1032), (wl.BF16, 2048), (wl.F32, 520)])
+def test_encoder_clustered_features_make_very_large_groups(dtype, feat_dim):
+    """Features drawn around five prototypes: dozens of groups of 33-128 members (shared by the
+    waves of a workgroup) and at least one of more than 128 (longer than a slot's list, gathered
+    by a scan of the token range), on rows wide enough to be added as two column halves."""
+    shape = _enc(dtype, batch=2, n_segments=1, grid_h=40, grid_w=37, heads=2, head_dim=32,
+                 feat_dim=feat_dim, win_rows=2, win_cols=2, keep_global=30, keep_local=20)
+    inp = wl.encoder_inputs(shape, 77)
+    rng = np.random.default_rng(5)
+    T = shape.grid_h * shape.grid_w
+    protos = rng.standard_normal((5, feat_dim)).astype(np.float32)
+    which = rng.integers(0, 5, size=(shape.batch, T))
+    x = protos[which] + 0.05 * rng.standard_normal((shape.batch, T, feat_dim)).astype(np.float32)
+    inp["x"] = wl.round_to_bf16(x) if dtype == wl.BF16 else x
+    ref = vo.encoder_reduce(shape, inp["q"], inp["k"], inp["x"])
+    sizes = np.concatenate([np.bincount(ref["assign"][b], minlength=shape.keep)
+                            for b in range(shape.batch)])
+    assert sizes.max() > 128 and (sizes > 32).sum() >= 10, sizes.max()
+    out = _run_encoder(shape, inp)
+    print("clustered", pu.check_encoder(shape, inp, ref, out, "clustered"))
+
+
 def test_encoder_keep_everything_is_identity():
     shape = _enc(wl.F32, grid_h=8, grid_w=8, keep_global=32, keep_local=32)
     inp = wl.encoder_inputs(shape, 5)
