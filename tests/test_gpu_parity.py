@@ -127,6 +127,26 @@ def test_encoder_clustered_features_make_very_large_groups(dtype, feat_dim):
     print("clustered", pu.check_encoder(shape, inp, ref, out, "clustered"))
 
 
+def test_encoder_long_image_merge_by_sixteen_waves_and_column_halves():
+    """9216 tokens, 2048 kept: the merge runs with sixteen-wave workgroups, and with 128 of them
+    per column half both halves fit one round (config 4 has too many for that); clustered
+    features give it groups of more than 128 members."""
+    shape = _enc(wl.BF16, batch=1, n_segments=1, grid_h=96, grid_w=96, heads=2, head_dim=16,
+                 feat_dim=1024, win_rows=4, win_cols=4, keep_global=1024, keep_local=1024)
+    inp = wl.encoder_inputs(shape, 78)
+    rng = np.random.default_rng(6)
+    T = shape.grid_h * shape.grid_w
+    protos = rng.standard_normal((5, shape.feat_dim)).astype(np.float32)
+    which = rng.integers(0, 5, size=(shape.batch, T))
+    x = protos[which] + 0.05 * rng.standard_normal((shape.batch, T, shape.feat_dim)).astype(np.float32)
+    inp["x"] = wl.round_to_bf16(x)
+    ref = vo.encoder_reduce(shape, inp["q"], inp["k"], inp["x"])
+    sizes = np.bincount(ref["assign"][0], minlength=shape.keep)
+    assert sizes.max() > 128, sizes.max()
+    out = _run_encoder(shape, inp)
+    print("long-image", sizes.max(), pu.check_encoder(shape, inp, ref, out, "long-image"))
+
+
 def test_encoder_keep_everything_is_identity():
     shape = _enc(wl.F32, grid_h=8, grid_w=8, keep_global=32, keep_local=32)
     inp = wl.encoder_inputs(shape, 5)
