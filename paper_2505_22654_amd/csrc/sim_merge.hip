@@ -48,7 +48,7 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
     static_assert(NSETS == 1 || NSETS == 2 || NSETS == 4, "register sets");
     static_assert(PPR <= 64 && (PPR & (PPR - 1)) == 0, "a row's pieces must sit in one wave");
     __shared__ __align__(16) unsigned char lds[2][ROWS * STRIDE];
-    __shared__ float inv_s[BM];
+    __shared__ __align__(16) float inv_s[BM];
 
     const int tiles_n = (U + BN - 1) / BN, tiles_m = (K + BM - 1) / BM;
     int b, tile;
@@ -212,28 +212,49 @@ __global__ __launch_bounds__(THREADS) void sim_argmax_kernel(const T *__restrict
     if (!computes) return;  // no barrier below
     // epilogue: acc[i][j][r] = x_slot . x_token with
     //   slot  = m0 + (wm*TM + i)*32 + acc_row(r),  token column = n0 + (wn*TN + j)*32 + lane%32
+    // (inverse norms 16 bytes at a time and no bound check inside a full tile, as in the large
+    // form below)
+    const bool full = m0 + BM <= K;  // uniform over the workgroup
+    float best_v[TN];
+    int best_s[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        float best_v = -INFINITY;
-        int best_s = -1;
+        best_v[j] = -INFINITY;
+        best_s[j] = -1;
+    }
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        float inv[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rl = (wm * TM + i) * 32 + acc_row(r);
-                if (m0 + rl < K) {
-                    const float v = acc[i][j][r] * inv_s[rl];
-                    // slots are visited in ascending order: strict > keeps the lowest on ties
-                    if (best_s < 0 || v > best_v) {
-                        best_v = v;
-                        best_s = m0 + rl;
-                    }
+        for (int q = 0; q < 4; ++q) {
+            const float4 t =
+                *reinterpret_cast<const float4 *>(inv_s + (wm * TM + i) * 32 + 8 * q + 4 * g);
+            inv[4 * q] = t.x;
+            inv[4 * q + 1] = t.y;
+            inv[4 * q + 2] = t.z;
+            inv[4 * q + 3] = t.w;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rl = (wm * TM + i) * 32 + acc_row(r);
+            const bool valid = full || m0 + rl < K;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float v = acc[i][j][r] * inv[r];
+                // slots are visited in ascending order: strict > keeps the lowest on ties
+                if (valid && v > best_v[j]) {  // (a finite v beats the initial -inf)
+                    best_v[j] = v;
+                    best_s[j] = m0 + rl;
                 }
             }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
         unsigned long long packed =
-            best_s < 0 ? 0ull
-                       : (((unsigned long long)float_to_key(best_v)) << 32) |
-                             (unsigned long long)(uint32_t)~(uint32_t)best_s;
+            best_s[j] < 0 ? 0ull
+                          : (((unsigned long long)float_to_key(best_v[j])) << 32) |
+                                (unsigned long long)(uint32_t)~(uint32_t)best_s[j];
         const unsigned long long other = __shfl_xor(packed, 32, kWave);
         if (other > packed) packed = other;
         const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
@@ -566,28 +587,52 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
 
     // epilogue: acc[i][j][r] = x_slot . x_token with
     //   slot  = m0 + (wm*TM + i)*32 + acc_row(r),  token column = n0 + (wn*TN + j)*32 + lane%32
+    // Registers 4q .. 4q+3 of a block are four consecutive slots, so their inverse norms come
+    // from LDS 16 bytes at a time, once for all TN columns of blocks; a tile that lies wholly
+    // inside the kept rows (every tile but a ragged last one) skips the per-slot bound check.
+    // (With a 4-byte LDS read and a bound check per candidate the epilogue took 10.7 us of a
+    // 256 x 256 tile's 51 us.)
+    const bool full = m0 + BM <= K;  // uniform over the workgroup
+    float best_v[TN];
+    int best_s[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        float best_v = -INFINITY;
-        int best_s = -1;
+        best_v[j] = -INFINITY;
+        best_s[j] = -1;
+    }
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        float inv[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rl = (wm * TM + i) * 32 + acc_row(r);
-                if (m0 + rl < K) {
-                    const float v = acc[i][j][r] * inv_s[rl];
-                    // slots are visited in ascending order: strict > keeps the lowest on ties
-                    if (best_s < 0 || v > best_v) {
-                        best_v = v;
-                        best_s = m0 + rl;
-                    }
+        for (int q = 0; q < 4; ++q) {
+            const float4 t =
+                *reinterpret_cast<const float4 *>(inv_s + (wm * TM + i) * 32 + 8 * q + 4 * g);
+            inv[4 * q] = t.x;
+            inv[4 * q + 1] = t.y;
+            inv[4 * q + 2] = t.z;
+            inv[4 * q + 3] = t.w;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rl = (wm * TM + i) * 32 + acc_row(r);
+            const bool valid = full || m0 + rl < K;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float v = acc[i][j][r] * inv[r];
+                // slots are visited in ascending order: strict > keeps the lowest on ties
+                if (valid && v > best_v[j]) {  // (a finite v beats the initial -inf)
+                    best_v[j] = v;
+                    best_s[j] = m0 + rl;
                 }
             }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
         unsigned long long packed =
-            best_s < 0 ? 0ull
-                       : (((unsigned long long)float_to_key(best_v)) << 32) |
-                             (unsigned long long)(uint32_t)~(uint32_t)best_s;
+            best_s[j] < 0 ? 0ull
+                          : (((unsigned long long)float_to_key(best_v[j])) << 32) |
+                                (unsigned long long)(uint32_t)~(uint32_t)best_s[j];
         const unsigned long long other = __shfl_xor(packed, 32, kWave);
         if (other > packed) packed = other;
         const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
@@ -607,14 +652,14 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && TM * TN <= 4) ? 2 : 
 // counter, so the order inside a list is arbitrary at this point).
 // Phase 2 (one wave per slot, spw slots one after the other): the list is sorted by token index
 // (rank by counting); a group of up to kMergeAloneCap members is added up by that wave right
-// away, several rows in flight at a time (a shared group costs the workgroup about 4 us of
-// barriers and serial combination, which is why groups of a few dozen are still added alone).
+// away, several rows in flight at a time (a shared group costs the workgroup two barriers and a
+// pass over the partial sums, which is why groups of a few dozen are still added alone).
 // Phase 3 (whole workgroup, one larger group after the other): group sizes are heavy-tailed
 // (many dropped tokens look like the same kept token), and one wave adding dozens or hundreds
 // of rows would set the kernel's time.  All waves share such a group: each takes its share of
 // the sorted list - or, when the group is longer than the list, gathers the members inside its
-// share of the token range with an ordered ballot scan - and the partial sums are combined in
-// wave order through LDS (four waves per buffer, then the buffers in order).
+// share of the token range with an ordered ballot scan - and the partial sums, one row per wave
+// in LDS, are added column by column in wave order.
 // Every sum has a fixed order of additions, so results do not depend on scheduling.
 // Lane l owns the 16-byte pieces l, l+64, ... of the feature row.
 // ---------------------------------------------------------------------------
