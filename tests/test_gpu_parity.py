@@ -125,6 +125,9 @@ def test_encoder_clustered_features_make_very_large_groups(dtype, feat_dim):
     assert sizes.max() > 128 and (sizes > 32).sum() >= 10, sizes.max()
     out = _run_encoder(shape, inp)
     print("clustered", pu.check_encoder(shape, inp, ref, out, "clustered"))
+    again = _run_encoder(shape, inp)  # shared groups and column halves add in a fixed order
+    for name in ("kept_idx", "merged", "assign"):
+        assert np.array_equal(pu.to_host(out[name]), pu.to_host(again[name])), name
 
 
 def test_encoder_long_image_merge_by_sixteen_waves_and_column_halves():
@@ -145,6 +148,9 @@ def test_encoder_long_image_merge_by_sixteen_waves_and_column_halves():
     assert sizes.max() > 128, sizes.max()
     out = _run_encoder(shape, inp)
     print("long-image", sizes.max(), pu.check_encoder(shape, inp, ref, out, "long-image"))
+    again = _run_encoder(shape, inp)
+    for name in ("kept_idx", "merged", "assign"):
+        assert np.array_equal(pu.to_host(out[name]), pu.to_host(again[name])), name
 
 
 def test_encoder_keep_everything_is_identity():
