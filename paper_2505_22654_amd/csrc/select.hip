@@ -71,18 +71,32 @@ __device__ __forceinline__ int block_excl_count(bool pred, int *wsum, int &total
 // Rank of every flagged token among the flagged ones.  Each wave owns one contiguous run of
 // tokens and walks it 64 at a time (consecutive lanes, consecutive tokens: byte reads of the flags
 // without bank conflicts, coalesced writes in `emit`).  A first pass counts the wave's flagged
-// tokens (ballot population counts, on the scalar unit), the totals cross LDS once, and the
-// second pass hands out ranks: two barriers in all, whatever the length.  `cnts`: LDS, one int
+// tokens, the totals cross LDS once, and the second pass hands out ranks (ballot population
+// counts, on the scalar unit): two barriers in all, whatever the length.  `cnts`: LDS, one int
 // per wave, free for this use.  emit(j, flagged, rank) is called once for every j < n.
 template <typename Emit>
 __device__ __forceinline__ void ranked_walk(const uint8_t *flag, int n, int *cnts, Emit emit) {
     const int nw = blockDim.x / kWave, w = wave_id(), lane = lane_id();
     const int rounds = (n + nw * kWave - 1) / (nw * kWave);  // per wave
     const int first = w * rounds * kWave;
-    int total = 0;
-    for (int r = 0; r < rounds; ++r) {
-        const int j = first + r * kWave + lane;
-        total += __popcll(__ballot(j < n && flag[j] != 0));
+    int total;
+    if (rounds == 1) {
+        total = __popcll(__ballot(first + lane < n && flag[first + lane] != 0));
+    } else {
+        // the count needs no order: the run's bytes four at a time, lane l taking words l, l + 64,
+        // ... (a handful of independent LDS reads instead of one dependent read per 64 tokens)
+        const uint32_t *words = reinterpret_cast<const uint32_t *>(flag + first);  // first % 64 == 0
+        int mine = 0;
+        for (int d = lane; d < rounds * (kWave / 4); d += kWave) {
+            const int inside = n - (first + 4 * d);  // bytes of this word that belong to the list
+            if (inside > 0) {
+                uint32_t x = words[d];  // the flags' LDS is padded to a multiple of 16 bytes
+                if (inside < 4) x &= (1u << (8 * inside)) - 1u;
+                // flags are 0, 1 or 2: adding 3 sets bit 2 of exactly the non-zero bytes
+                mine += __popc(((x & 0x03030303u) + 0x03030303u) & 0x04040404u);
+            }
+        }
+        total = wave_sum_dpp(mine);
     }
     if (lane == 0) cnts[w] = total;
     __syncthreads();
