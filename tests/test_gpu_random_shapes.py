@@ -114,6 +114,43 @@ def test_random_fused_encoder_shapes():
            lambda s, case, out: pu.check_encoder(s, case[0], case[2], out, str(s)))
 
 
+def test_random_wide_rows_with_clustered_features():
+    """Feature rows of 96 to 300 16-byte pieces (from 128 on the merge adds them as two column
+    halves) drawn around a few prototypes, so that groups of a few dozen to a few hundred members
+    occur: shared groups, groups longer than a slot's list, ragged column halves."""
+    import torch
+    from oracle import vscan_oracle as vo
+    r = np.random.default_rng(20250523)
+    largest = 0
+    for i in range(16):
+        dtype = wl.BF16 if r.random() < 0.6 else wl.F32
+        pieces = int(r.choice([96, 127, 128, 129, 130, 160, 191, 192, 200, 256, 257, 300]))
+        if dtype == wl.F32:
+            pieces += pieces % 2  # feature rows are whole multiples of 8 elements
+        gh, gw = int(r.integers(8, 45)), int(r.integers(8, 45))
+        wr, wc = int(r.integers(1, 4)), int(r.integers(1, 4))
+        shape = wl.EncoderShape(
+            dtype=dtype, batch=int(r.integers(1, 4)), n_segments=int(r.integers(1, 3)), grid_h=gh,
+            grid_w=gw, has_cls=1, score_mode=0, heads=2, head_dim=16,
+            feat_dim=pieces * (8 if dtype == wl.BF16 else 4), win_rows=wr, win_cols=wc,
+            keep_global=int(r.integers(1, max(2, gh * gw // 8))),
+            keep_local=int(r.integers(0, 4)) * wr * wc, softmax_domain=0)
+        inp = wl.encoder_inputs(shape, 9000 + i)
+        T = shape.n_segments * gh * gw
+        protos = r.standard_normal((int(r.integers(2, 9)), shape.feat_dim)).astype(np.float32)
+        which = r.integers(0, len(protos), size=(shape.batch, T))
+        x = protos[which] + 0.05 * r.standard_normal((shape.batch, T, shape.feat_dim)).astype(np.float32)
+        inp["x"] = wl.round_to_bf16(x) if dtype == wl.BF16 else x
+        ref = vo.encoder_reduce(shape, inp["q"], inp["k"], inp["x"])
+        largest = max(largest, max(int(np.bincount(ref["assign"][b], minlength=shape.keep).max())
+                                   for b in range(shape.batch)))
+        q, k, xd = (pu.to_device(inp[n], shape.dtype) for n in ("q", "k", "x"))
+        out = vb.encoder_reduce(shape, q, k, xd, want_assign=True, want_scores=True)
+        torch.cuda.synchronize()
+        print("shape", i, shape, pu.check_encoder(shape, inp, ref, out, str(shape)), flush=True)
+    assert largest > 128, largest  # the draw covers groups longer than a slot's list
+
+
 def test_random_encoder_shapes_with_shallow_layer_pair():
     def run(shape, case):
         inp, loc = case[0], case[1]
